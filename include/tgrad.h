@@ -1,0 +1,179 @@
+/*
+ * tgrad.h - C ABI of the TensorGRaD optimizer hot path for AMD MI355X (gfx950).
+ *
+ * One context (`tgrad_ctx`) serves one complex weight tensor W of an FNO
+ * spectral layer and holds the compressed optimizer state of the paper's
+ * Algorithm 1 ("Adam with Sparse and Low-Rank Gradient Compression", arxiv
+ * 2501.02379): the sparse support Omega, the Tucker factors U^(n), and the Adam
+ * moments on the k sparse values and on the Tucker core.
+ *
+ * Conventions that hold for every call
+ *  - Return value: TGRAD_OK (0) or a negative TGRAD_ERR_* code.  Nothing aborts
+ *    or throws across this boundary.  `tgrad_strerror` names a code.
+ *  - "device pointer" = address in the memory of the GPU that is current when
+ *    `tgrad_init` is called; "host pointer" = ordinary process memory.
+ *  - The library never allocates or frees device memory.  The caller allocates
+ *    `state_dev` and `workspace_dev` with the sizes `tgrad_query_sizes` reports
+ *    (256-byte aligned) and keeps both alive until `tgrad_destroy`.
+ *  - All device work is enqueued on the one HIP stream given at init.  Neither
+ *    `tgrad_step` nor `tgrad_refresh_factors` waits for the device; only
+ *    `tgrad_get_state`, `tgrad_set_state` and `tgrad_get_kernel_times` do.
+ *  - A context is used from one host thread at a time.
+ *  - Tensors are dense, row-major (last mode fastest).  TGRAD_C64 elements are
+ *    interleaved (re, im) float32 pairs (8 bytes); TGRAD_CBF16 elements are
+ *    interleaved (re, im) bfloat16 pairs (4 bytes).
+ *  - The gradient argument is the ordinary gradient dphi/dW.  Algorithm 1 writes
+ *    G = -grad and W <- W + eta * G~; every operation it applies to G is odd, so
+ *    this library computes the same W as  W <- W (1 - lr wd) - lr * D(grad).
+ */
+#ifndef TGRAD_H
+#define TGRAD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TGRAD_MAX_NDIM 6
+#define TGRAD_MAX_EXTENT 256          /* largest I_n the factor refresh accepts */
+
+typedef struct tgrad_ctx tgrad_ctx;   /* opaque; host memory owned by the library */
+
+enum { TGRAD_C64 = 0, TGRAD_CBF16 = 1 };
+enum { TGRAD_SELECT_TOPK_MAG = 0 };
+
+enum {
+  TGRAD_OK = 0,
+  TGRAD_ERR_INVALID_ARG = -1,   /* null pointer, bad shape/rank/k, misaligned buffer, bad selector */
+  TGRAD_ERR_UNSUPPORTED = -2,   /* valid in the paper's terms, but not built (see field comments) */
+  TGRAD_ERR_NOT_READY = -3,     /* step or state read before any refresh / factor injection */
+  TGRAD_ERR_HIP = -4,           /* a HIP runtime call or kernel launch failed */
+  TGRAD_ERR_TOO_SMALL = -5      /* host buffer smaller than the requested item */
+};
+
+/* Items of `tgrad_get_state` / `tgrad_set_state` (host-side formats in the comments). */
+enum {
+  TGRAD_STATE_STEP = 0,         /* int64: t, the number of completed steps */
+  TGRAD_STATE_INDICES = 1,      /* int64[k]: Omega, ascending row-major linear indices */
+  TGRAD_STATE_CORE_M = 2,       /* float32[2*C]: M_L, interleaved complex, C = prod r_n, row-major */
+  TGRAD_STATE_CORE_V = 3,       /* float32[C]:   V_L */
+  TGRAD_STATE_SPARSE_M = 4,     /* float32[2*k]: M_S, aligned with Omega */
+  TGRAD_STATE_SPARSE_V = 5,     /* float32[k]:   V_S */
+  TGRAD_STATE_SPARSE_G = 6,     /* float32[2*k]: values gathered at Omega by the last step (read-only) */
+  TGRAD_STATE_CORE_G = 7,       /* float32[2*C]: compressed gradient of the last step (read-only) */
+  TGRAD_STATE_GRAM0 = 32,       /* + n: float64[2*I_n*I_n] mode-n Gram of the last refresh (read-only) */
+  TGRAD_STATE_FACTOR0 = 64      /* + n: float32[2*I_n*r_n]: U^(n), row-major I_n x r_n, interleaved complex */
+};
+
+/*
+ * Problem statement = the `Require` line of Algorithm 1 (W, eta, alpha, beta1,
+ * beta2, rank r, sparsity rho, sparse scale lambda, refresh period T) plus what
+ * an implementation must fix (eps, decoupled weight decay, storage types).
+ */
+typedef struct {
+  int32_t ndim;                       /* N, 2..TGRAD_MAX_NDIM */
+  int64_t shape[TGRAD_MAX_NDIM];      /* I_n >= 1; I = prod I_n < 2^31; I_n <= TGRAD_MAX_EXTENT */
+  int32_t rank[TGRAD_MAX_NDIM];       /* Tucker rank r_n, 1..I_n.  r_n == I_n: the mode is not
+                                         compressed (identity factor) */
+  int64_t k_sparse;                   /* k = ceil(rho * I), 0..I, computed by the caller exactly */
+  int32_t grad_dtype;                 /* TGRAD_C64 or TGRAD_CBF16 */
+  int32_t weight_dtype;               /* TGRAD_C64 (bf16-stored weights: TGRAD_ERR_UNSUPPORTED) */
+  float lr;                           /* eta */
+  float beta1, beta2, eps;            /* Adam decay rates and epsilon */
+  float alpha;                        /* scale of the reconstructed update */
+  float lambda;                       /* scale of the sparse part inside it */
+  float weight_decay;                 /* decoupled (AdamW) decay; 0 disables */
+  int32_t refresh_every;              /* T >= 1: tgrad_step refreshes first when t % T == 0.
+                                         0: only tgrad_refresh_factors refreshes */
+  int32_t hooi_sweeps;                /* 0 = HOSVD factors.  > 0 (HOOI refinement): UNSUPPORTED */
+  int32_t select_rule;                /* TGRAD_SELECT_TOPK_MAG */
+} tgrad_config;
+
+/*
+ * Bytes of device memory a context needs.  Host-only, touches no GPU.
+ *  cfg             host pointer, read only.
+ *  state_bytes     host pointer, out: persistent optimizer state (Omega as int32, M_S, V_S, M_L,
+ *                  V_L, U^(n); the quantity the paper's memory model counts).
+ *  workspace_bytes host pointer, out: scratch that carries nothing from one step to the next
+ *                  except kernel-ready copies of the factors and the support bitmask.
+ * Errors: INVALID_ARG, UNSUPPORTED.
+ */
+int tgrad_query_sizes(const tgrad_config* cfg, size_t* state_bytes, size_t* workspace_bytes);
+
+/*
+ * Create a context (Algorithm 1, the initialisation lines: t <- 0, all moments <- 0).
+ *  out            host pointer, receives the context.
+ *  cfg            host pointer, copied.
+ *  state_dev      device pointer, >= state_bytes, 256-byte aligned; zeroed asynchronously here.
+ *  workspace_dev  device pointer, >= workspace_bytes, 256-byte aligned.
+ *  hip_stream     a hipStream_t (NULL = the default stream); every later call enqueues on it.
+ * Errors: INVALID_ARG, UNSUPPORTED, HIP.
+ */
+int tgrad_init(tgrad_ctx** out, const tgrad_config* cfg, void* state_dev, void* workspace_dev,
+               void* hip_stream);
+
+/*
+ * Algorithm 1, the `t mod T = 0` branch: Omega <- SparseIndices(G, rho, top-k magnitude);
+ * R_L <- G - Sparse(G, Omega); {U^(n)} <- TuckerFactors(R_L, r) (HOSVD: eigenvectors of the r_n
+ * largest eigenvalues of each mode-n Gram matrix R_L(n) R_L(n)^H, descending, every column
+ * multiplied by the unit phase that makes its largest-modulus entry real and positive).
+ * Selection order: (|g|^2 descending, linear index ascending), |g|^2 evaluated in float32 as
+ * fl(fl(re*re) + fl(im*im)).  Touches neither the moments nor t.
+ *  grad_dev   device pointer to G (cfg.grad_dtype), read only.
+ * Errors: INVALID_ARG, HIP.
+ */
+int tgrad_refresh_factors(tgrad_ctx* ctx, const void* grad_dev);
+
+/*
+ * One pass of Algorithm 1's loop body on (W, G): refresh first if cfg.refresh_every > 0 and
+ * t % refresh_every == 0; g_S <- G[Omega]; g_L <- (G with Omega zeroed) x_1 U1^H ... x_N UN^H;
+ * AdamUpdate on g_S with (M_S, V_S) and on g_L with (M_L, V_L), tau = t + 1 in the bias
+ * correction, N = (M / (1 - beta1^tau)) / (sqrt(V / (1 - beta2^tau)) + eps), V from |x|^2;
+ * D <- alpha * (N_L x_1 U1 ... x_N UN); D[Omega] += lambda * N_S;
+ * W <- W (1 - lr wd) - lr D; t <- t + 1.
+ *  weight_dev  device pointer to W (TGRAD_C64), updated in place.
+ *  grad_dev    device pointer to G (cfg.grad_dtype), read only, must not alias W.
+ * Errors: INVALID_ARG, NOT_READY (refresh_every == 0 and no refresh yet), HIP.
+ */
+int tgrad_step(tgrad_ctx* ctx, void* weight_dev, const void* grad_dev);
+
+/*
+ * Copy one state item to the host (waits for the stream first).
+ *  what      a TGRAD_STATE_* selector (FACTOR0 + n / GRAM0 + n for mode n).
+ *  host_out  host pointer, receives the item in the format listed at the selector.
+ *  cap       bytes available at host_out.
+ * Errors: INVALID_ARG, TOO_SMALL, NOT_READY (indices/factors before any refresh), HIP.
+ */
+int tgrad_get_state(tgrad_ctx* ctx, int what, void* host_out, size_t cap);
+
+/*
+ * Overwrite one state item from the host (checkpoint restore, or injecting externally computed
+ * factors / support).  Read-only selectors are rejected.  INDICES must be strictly ascending and
+ * within [0, I); setting INDICES and every FACTOR marks the context ready.  Waits for the stream.
+ * Errors: INVALID_ARG, HIP.
+ */
+int tgrad_set_state(tgrad_ctx* ctx, int what, const void* host_in, size_t bytes);
+
+/*
+ * Per-kernel timing with HIP events on the context's stream (for roofline reports).
+ * `tgrad_set_profiling(ctx, 1)` makes later calls bracket every kernel launch with events;
+ * `tgrad_get_kernel_times` waits for the stream and returns, for up to `cap` kernels, the name
+ * (pointer to a static string), the summed duration in milliseconds and the launch count since
+ * profiling was last switched on.  Returns the number of kernels written (>= 0) or an error.
+ */
+int tgrad_set_profiling(tgrad_ctx* ctx, int enabled);
+int tgrad_get_kernel_times(tgrad_ctx* ctx, const char** names, double* total_ms, int64_t* launches,
+                           int cap);
+
+/* Release the context (host memory only; device buffers stay the caller's). */
+int tgrad_destroy(tgrad_ctx* ctx);
+
+/* Static description of a status code. */
+const char* tgrad_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TGRAD_H */

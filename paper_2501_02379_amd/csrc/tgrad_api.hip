@@ -1,0 +1,601 @@
+// Host side of the C ABI (include/tgrad.h): argument validation, the launch plan, carving of the
+// caller's state / workspace buffers, and the sequencing of kernels on the caller's stream for
+// the two branches of Algorithm 1 (refresh and step).
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "tgrad_internal.h"
+
+namespace tgrad {
+void zero_u32(hipStream_t s, uint32_t* p, int64_t n);
+void launch_eig_batch(hipStream_t s, int njobs, const double* const* gram, double* const* work_a,
+                      double* const* work_v, const int* In, const int* r, float* const* U);
+void launch_identity_factor(hipStream_t s, float* U, int n);
+}  // namespace tgrad
+
+using namespace tgrad;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+const char* const kKernelNames[KID_COUNT] = {
+    "select_hist", "select_pick", "select_count", "select_scan", "select_emit", "mask_from_indices",
+    "gram", "gram_reduce", "eig_jacobi", "factor_pack",
+    "gather", "project_first", "project", "adam_core", "backproject", "update", "sparse_update"};
+
+struct Plan {
+  int N = 0;
+  int64_t I = 0;                 // elements of W / G
+  int64_t C = 1;                 // elements of the core
+  int64_t k = 0;
+  int64_t shape[kMaxNdim];
+  int rank[kMaxNdim];
+  Stage proj[kMaxNdim];          // proj[s]: s-th projection stage; contracts mode N-1-s
+  Stage back[kMaxNdim];          // back[s]: s-th reconstruction stage; expands mode s
+  int64_t nseg = 0;
+  int64_t mask_words = 0;
+  // byte offsets into state
+  size_t st_omega, st_ms, st_vs, st_ml, st_vl, st_U[kMaxNdim], state_bytes;
+  // byte offsets into workspace
+  size_t ws_sel, ws_hist, ws_seg_gt, ws_seg_eq, ws_mask, ws_partials, ws_gram[kMaxNdim],
+      ws_eig_a[kMaxNdim], ws_eig_v[kMaxNdim], ws_gs, ws_core_g, ws_core_n, ws_buf[2], workspace_bytes;
+  int gram_chunks[kMaxNdim];
+};
+
+int validate(const tgrad_config* c) {
+  if (!c) return TGRAD_ERR_INVALID_ARG;
+  if (c->ndim < 2 || c->ndim > kMaxNdim) return TGRAD_ERR_INVALID_ARG;
+  long double numel = 1;
+  for (int n = 0; n < c->ndim; ++n) {
+    if (c->shape[n] < 1) return TGRAD_ERR_INVALID_ARG;
+    if (c->rank[n] < 1 || c->rank[n] > c->shape[n]) return TGRAD_ERR_INVALID_ARG;
+    numel *= (long double)c->shape[n];
+    if (numel >= 2147483648.0L) return TGRAD_ERR_UNSUPPORTED;
+  }
+  for (int n = 0; n < c->ndim; ++n)
+    if (c->shape[n] > TGRAD_MAX_EXTENT && c->rank[n] != c->shape[n]) return TGRAD_ERR_UNSUPPORTED;
+  if (c->k_sparse < 0 || (long double)c->k_sparse > numel) return TGRAD_ERR_INVALID_ARG;
+  if (c->grad_dtype != TGRAD_C64 && c->grad_dtype != TGRAD_CBF16) return TGRAD_ERR_INVALID_ARG;
+  if (c->weight_dtype == TGRAD_CBF16) return TGRAD_ERR_UNSUPPORTED;
+  if (c->weight_dtype != TGRAD_C64) return TGRAD_ERR_INVALID_ARG;
+  const float fl[] = {c->lr, c->beta1, c->beta2, c->eps, c->alpha, c->lambda, c->weight_decay};
+  for (float f : fl)
+    if (!std::isfinite(f)) return TGRAD_ERR_INVALID_ARG;
+  if (c->beta1 < 0.f || c->beta1 >= 1.f || c->beta2 < 0.f || c->beta2 >= 1.f) return TGRAD_ERR_INVALID_ARG;
+  if (c->eps < 0.f) return TGRAD_ERR_INVALID_ARG;
+  if (c->refresh_every < 0) return TGRAD_ERR_INVALID_ARG;
+  if (c->hooi_sweeps < 0) return TGRAD_ERR_INVALID_ARG;
+  if (c->hooi_sweeps > 0) return TGRAD_ERR_UNSUPPORTED;
+  if (c->select_rule != TGRAD_SELECT_TOPK_MAG) return TGRAD_ERR_UNSUPPORTED;
+  return TGRAD_OK;
+}
+
+void make_plan(const tgrad_config* c, Plan* p) {
+  p->N = c->ndim;
+  p->I = 1;
+  p->C = 1;
+  for (int n = 0; n < p->N; ++n) {
+    p->shape[n] = c->shape[n];
+    p->rank[n] = c->rank[n];
+    p->I *= c->shape[n];
+    p->C *= c->rank[n];
+  }
+  p->k = c->k_sparse;
+  const int N = p->N;
+  // projection: contract the last mode first (it is the contiguous one and the tensor shrinks
+  // before the strided modes are touched); stage s handles mode n = N-1-s
+  for (int s = 0; s < N; ++s) {
+    const int n = N - 1 - s;
+    Stage& st = p->proj[s];
+    st.mode = n;
+    st.A = 1;
+    for (int m = 0; m < n; ++m) st.A *= p->shape[m];
+    st.B = 1;
+    for (int m = n + 1; m < N; ++m) st.B *= p->rank[m];
+    st.K = (int)p->shape[n];
+    st.M = p->rank[n];
+  }
+  // reconstruction: expand the first mode first, the last (contiguous) mode last, fused with W
+  for (int s = 0; s < N; ++s) {
+    Stage& st = p->back[s];
+    st.mode = s;
+    st.A = 1;
+    for (int m = 0; m < s; ++m) st.A *= p->shape[m];
+    st.B = 1;
+    for (int m = s + 1; m < N; ++m) st.B *= p->rank[m];
+    st.K = p->rank[s];
+    st.M = (int)p->shape[s];
+  }
+  p->nseg = (p->I + kSegElems - 1) / kSegElems;
+  p->mask_words = (p->I + 31) / 32;
+
+  size_t o = 0;
+  auto take = [&o](size_t bytes) {
+    size_t at = o;
+    o = align_up(o + (bytes ? bytes : 1));
+    return at;
+  };
+  p->st_omega = take((size_t)p->k * 4);
+  p->st_ms = take((size_t)p->k * 8);
+  p->st_vs = take((size_t)p->k * 4);
+  p->st_ml = take((size_t)p->C * 8);
+  p->st_vl = take((size_t)p->C * 4);
+  for (int n = 0; n < N; ++n) p->st_U[n] = take((size_t)p->shape[n] * p->rank[n] * 8);
+  p->state_bytes = o;
+
+  o = 0;
+  p->ws_sel = take(sizeof(SelectScalars));
+  p->ws_hist = take(3 * kHistBins * 4);
+  p->ws_seg_gt = take((size_t)p->nseg * 4);
+  p->ws_seg_eq = take((size_t)p->nseg * 4);
+  p->ws_mask = take((size_t)p->mask_words * 4);
+  size_t partial_max = 0;
+  for (int n = 0; n < N; ++n) {
+    int64_t A = 1, B = 1;
+    for (int m = 0; m < n; ++m) A *= p->shape[m];
+    for (int m = n + 1; m < N; ++m) B *= p->shape[m];
+    const bool compressed = p->rank[n] < p->shape[n];
+    p->gram_chunks[n] = compressed ? gram_num_chunks(A, (int)p->shape[n], B) : 0;
+    size_t bytes = (size_t)p->gram_chunks[n] * p->shape[n] * p->shape[n] * 16;
+    if (bytes > partial_max) partial_max = bytes;
+  }
+  p->ws_partials = take(partial_max);
+  for (int n = 0; n < N; ++n) {
+    const size_t mat = p->rank[n] < p->shape[n] ? (size_t)p->shape[n] * p->shape[n] * 16 : 0;
+    p->ws_gram[n] = take(mat);
+    p->ws_eig_a[n] = take(mat);
+    p->ws_eig_v[n] = take(mat);
+  }
+  p->ws_gs = take((size_t)p->k * 8);
+  p->ws_core_g = take((size_t)p->C * 8);
+  p->ws_core_n = take((size_t)p->C * 8);
+  size_t buf[2] = {0, 0};
+  for (int s = 0; s + 1 < N; ++s) {
+    size_t bp = (size_t)(p->proj[s].A * p->proj[s].M * p->proj[s].B) * 8;
+    size_t bb = (size_t)(p->back[s].A * p->back[s].M * p->back[s].B) * 8;
+    if (bp > buf[s & 1]) buf[s & 1] = bp;
+    if (bb > buf[s & 1]) buf[s & 1] = bb;
+  }
+  p->ws_buf[0] = take(buf[0]);
+  p->ws_buf[1] = take(buf[1]);
+  p->workspace_bytes = o;
+}
+
+struct EventPair {
+  hipEvent_t a, b;
+  int kid;
+};
+
+}  // namespace
+
+struct tgrad_ctx {
+  tgrad_config cfg;
+  Plan plan;
+  char* state;
+  char* ws;
+  hipStream_t stream;
+  int64_t t;
+  bool have_indices;
+  bool have_factor[kMaxNdim];
+  bool profiling;
+  std::vector<EventPair> events;
+  double total_ms[KID_COUNT];
+  int64_t launches[KID_COUNT];
+
+  template <typename T>
+  T* st(size_t off) { return reinterpret_cast<T*>(state + off); }
+  template <typename T>
+  T* w(size_t off) { return reinterpret_cast<T*>(ws + off); }
+  bool ready() const {
+    if (!have_indices) return false;
+    for (int n = 0; n < plan.N; ++n)
+      if (!have_factor[n]) return false;
+    return true;
+  }
+};
+
+namespace {
+
+// Brackets one kernel launch with events when profiling is on.
+struct Scope {
+  tgrad_ctx* c;
+  int kid;
+  hipEvent_t a = nullptr, b = nullptr;
+  Scope(tgrad_ctx* ctx, int k) : c(ctx), kid(k) {
+    if (c->profiling && c->events.size() < 200000) {
+      if (hipEventCreate(&a) == hipSuccess && hipEventCreate(&b) == hipSuccess) {
+        (void)hipEventRecord(a, c->stream);
+      } else {
+        a = b = nullptr;
+      }
+    }
+  }
+  ~Scope() {
+    if (a && b) {
+      (void)hipEventRecord(b, c->stream);
+      c->events.push_back({a, b, kid});
+    }
+  }
+};
+
+int drain_events(tgrad_ctx* c) {
+  if (hipStreamSynchronize(c->stream) != hipSuccess) return TGRAD_ERR_HIP;
+  for (auto& e : c->events) {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, e.a, e.b) == hipSuccess) {
+      c->total_ms[e.kid] += ms;
+      c->launches[e.kid] += 1;
+    }
+    (void)hipEventDestroy(e.a);
+    (void)hipEventDestroy(e.b);
+  }
+  c->events.clear();
+  return TGRAD_OK;
+}
+
+int check_launch() { return hipGetLastError() == hipSuccess ? TGRAD_OK : TGRAD_ERR_HIP; }
+
+int do_refresh(tgrad_ctx* c, const void* g) {
+  Plan& p = c->plan;
+  hipStream_t s = c->stream;
+  const int dt = c->cfg.grad_dtype;
+  SelectScalars* sc = c->w<SelectScalars>(p.ws_sel);
+  uint32_t* hist = c->w<uint32_t>(p.ws_hist);
+  uint32_t* seg_gt = c->w<uint32_t>(p.ws_seg_gt);
+  uint32_t* seg_eq = c->w<uint32_t>(p.ws_seg_eq);
+  uint32_t* mask = c->w<uint32_t>(p.ws_mask);
+  int32_t* omega = c->st<int32_t>(p.st_omega);
+
+  // --- Omega <- SparseIndices(G, rho, top-k) ---
+  if (p.k > 0) {
+    zero_u32(s, hist, 3 * kHistBins);
+    for (int pass = 0; pass < 3; ++pass) {
+      { Scope sc_(c, KID_SEL_HIST); launch_select_hist(s, g, dt, p.I, pass, sc, hist + pass * kHistBins); }
+      { Scope sc_(c, KID_SEL_PICK); launch_select_pick(s, pass, (uint32_t)p.k, sc, hist + pass * kHistBins); }
+    }
+    { Scope sc_(c, KID_SEL_COUNT); launch_select_count(s, g, dt, p.I, sc, seg_gt, seg_eq, p.nseg); }
+    { Scope sc_(c, KID_SEL_SCAN); launch_select_scan(s, seg_gt, seg_eq, p.nseg); }
+    { Scope sc_(c, KID_SEL_EMIT); launch_select_emit(s, g, dt, p.I, sc, seg_gt, seg_eq, p.nseg, omega, mask); }
+  }
+  c->have_indices = true;
+  const uint32_t* use_mask = p.k > 0 ? mask : nullptr;
+
+  // --- {U^(n)} <- TuckerFactors(G - Sparse(G, Omega), r) ---
+  const double* grams[kMaxNdim];
+  double* wa[kMaxNdim];
+  double* wv[kMaxNdim];
+  int In[kMaxNdim], rr[kMaxNdim];
+  float* Us[kMaxNdim];
+  int njobs = 0;
+  for (int n = 0; n < p.N; ++n) {
+    float* U = c->st<float>(p.st_U[n]);
+    if (p.rank[n] == p.shape[n]) {
+      Scope sc_(c, KID_FACTOR_PACK);
+      launch_identity_factor(s, U, (int)p.shape[n]);
+    } else {
+      int64_t A = 1, B = 1;
+      for (int m = 0; m < n; ++m) A *= p.shape[m];
+      for (int m = n + 1; m < p.N; ++m) B *= p.shape[m];
+      double* partials = c->w<double>(p.ws_partials);
+      double* gram = c->w<double>(p.ws_gram[n]);
+      { Scope sc_(c, KID_GRAM); launch_gram(s, g, dt, use_mask, A, (int)p.shape[n], B, p.gram_chunks[n], partials); }
+      { Scope sc_(c, KID_GRAM_REDUCE); launch_gram_reduce(s, partials, p.gram_chunks[n], (int)p.shape[n], gram); }
+      grams[njobs] = gram;
+      wa[njobs] = c->w<double>(p.ws_eig_a[n]);
+      wv[njobs] = c->w<double>(p.ws_eig_v[n]);
+      In[njobs] = (int)p.shape[n];
+      rr[njobs] = p.rank[n];
+      Us[njobs] = U;
+      ++njobs;
+    }
+    c->have_factor[n] = true;
+  }
+  if (njobs > 0) {
+    Scope sc_(c, KID_EIG);
+    launch_eig_batch(s, njobs, grams, wa, wv, In, rr, Us);
+  }
+  return check_launch();
+}
+
+int do_step(tgrad_ctx* c, void* weight, const void* g) {
+  Plan& p = c->plan;
+  const tgrad_config& cf = c->cfg;
+  hipStream_t s = c->stream;
+  const int N = p.N;
+  const int32_t* omega = c->st<int32_t>(p.st_omega);
+  const uint32_t* mask = p.k > 0 ? c->w<uint32_t>(p.ws_mask) : nullptr;
+  float2* gs = c->w<float2>(p.ws_gs);
+  float2* core_g = c->w<float2>(p.ws_core_g);
+  float2* core_n = c->w<float2>(p.ws_core_n);
+  float2* buf[2] = {c->w<float2>(p.ws_buf[0]), c->w<float2>(p.ws_buf[1])};
+
+  // g_S <- Sparse(G, Omega)
+  { Scope sc_(c, KID_GATHER); launch_gather(s, g, cf.grad_dtype, omega, p.k, gs); }
+
+  // g_L <- (G - g_S) x_N UN^H ... x_1 U1^H
+  const void* src = g;
+  int src_dt = cf.grad_dtype;
+  for (int st = 0; st < N; ++st) {
+    const Stage& sg = p.proj[st];
+    float2* dst = (st == N - 1) ? core_g : buf[st & 1];
+    const float2* U = c->st<float2>(p.st_U[sg.mode]);
+    Scope sc_(c, st == 0 ? KID_PROJECT_FIRST : KID_PROJECT);
+    launch_contract(s, src, src_dt, st == 0 ? mask : nullptr, U, (int)p.shape[sg.mode], p.rank[sg.mode],
+                    true, sg, dst);
+    src = dst;
+    src_dt = TGRAD_C64;
+  }
+
+  // AdamUpdate on the core; tau = t + 1
+  const double tau = (double)(c->t + 1);
+  const float inv_c1 = (float)(1.0 / (1.0 - std::pow((double)cf.beta1, tau)));
+  const float inv_c2 = (float)(1.0 / (1.0 - std::pow((double)cf.beta2, tau)));
+  {
+    Scope sc_(c, KID_ADAM_CORE);
+    launch_adam_core(s, core_g, c->st<float2>(p.st_ml), c->st<float>(p.st_vl), core_n, p.C, cf.beta1,
+                     cf.beta2, inv_c1, inv_c2, cf.eps);
+  }
+
+  // D <- alpha (N_L x_1 U1 ... x_N UN), the last stage fused with W <- W (1 - lr wd) - lr D
+  const float2* zsrc = core_n;
+  for (int st = 0; st + 1 < N; ++st) {
+    const Stage& sg = p.back[st];
+    float2* dst = buf[st & 1];
+    const float2* U = c->st<float2>(p.st_U[sg.mode]);
+    Scope sc_(c, KID_BACKPROJECT);
+    launch_contract(s, zsrc, TGRAD_C64, nullptr, U, (int)p.shape[sg.mode], p.rank[sg.mode], false, sg, dst);
+    zsrc = dst;
+  }
+  {
+    const Stage& sg = p.back[N - 1];
+    const float2* U = c->st<float2>(p.st_U[sg.mode]);
+    const float decay = 1.f - cf.lr * cf.weight_decay;
+    Scope sc_(c, KID_UPDATE);
+    launch_update(s, zsrc, U, (int)p.shape[sg.mode], p.rank[sg.mode], sg, reinterpret_cast<float2*>(weight),
+                  decay, -cf.lr * cf.alpha);
+  }
+  // AdamUpdate on the sparse values; W[Omega] += -lr lambda N_S
+  {
+    Scope sc_(c, KID_SPARSE_UPDATE);
+    launch_sparse_update(s, gs, omega, p.k, c->st<float2>(p.st_ms), c->st<float>(p.st_vs),
+                         reinterpret_cast<float2*>(weight), cf.beta1, cf.beta2, inv_c1, inv_c2, cf.eps,
+                         -cf.lr * cf.lambda);
+  }
+  c->t += 1;
+  return check_launch();
+}
+
+struct Item {
+  char* dev;        // device address
+  size_t bytes;     // bytes on the device == bytes on the host (except INDICES)
+  bool writable;
+  bool needs_indices, needs_factor;
+  int mode;
+};
+
+int locate(tgrad_ctx* c, int what, Item* it) {
+  Plan& p = c->plan;
+  it->writable = true;
+  it->needs_indices = it->needs_factor = false;
+  it->mode = -1;
+  switch (what) {
+    case TGRAD_STATE_CORE_M: it->dev = c->state + p.st_ml; it->bytes = (size_t)p.C * 8; return TGRAD_OK;
+    case TGRAD_STATE_CORE_V: it->dev = c->state + p.st_vl; it->bytes = (size_t)p.C * 4; return TGRAD_OK;
+    case TGRAD_STATE_SPARSE_M: it->dev = c->state + p.st_ms; it->bytes = (size_t)p.k * 8; return TGRAD_OK;
+    case TGRAD_STATE_SPARSE_V: it->dev = c->state + p.st_vs; it->bytes = (size_t)p.k * 4; return TGRAD_OK;
+    case TGRAD_STATE_SPARSE_G: it->dev = c->ws + p.ws_gs; it->bytes = (size_t)p.k * 8; it->writable = false; return TGRAD_OK;
+    case TGRAD_STATE_CORE_G: it->dev = c->ws + p.ws_core_g; it->bytes = (size_t)p.C * 8; it->writable = false; return TGRAD_OK;
+    default: break;
+  }
+  if (what >= TGRAD_STATE_FACTOR0 && what < TGRAD_STATE_FACTOR0 + p.N) {
+    const int n = what - TGRAD_STATE_FACTOR0;
+    it->dev = c->state + p.st_U[n];
+    it->bytes = (size_t)p.shape[n] * p.rank[n] * 8;
+    it->needs_factor = true;
+    it->mode = n;
+    return TGRAD_OK;
+  }
+  if (what >= TGRAD_STATE_GRAM0 && what < TGRAD_STATE_GRAM0 + p.N) {
+    const int n = what - TGRAD_STATE_GRAM0;
+    if (p.rank[n] == p.shape[n]) return TGRAD_ERR_INVALID_ARG;     // no Gram is formed for an uncompressed mode
+    it->dev = c->ws + p.ws_gram[n];
+    it->bytes = (size_t)p.shape[n] * p.shape[n] * 16;
+    it->writable = false;
+    it->needs_factor = true;
+    it->mode = n;
+    return TGRAD_OK;
+  }
+  return TGRAD_ERR_INVALID_ARG;
+}
+
+}  // namespace
+
+extern "C" {
+
+int tgrad_query_sizes(const tgrad_config* cfg, size_t* state_bytes, size_t* workspace_bytes) {
+  if (!state_bytes || !workspace_bytes) return TGRAD_ERR_INVALID_ARG;
+  int rc = validate(cfg);
+  if (rc != TGRAD_OK) return rc;
+  Plan p;
+  make_plan(cfg, &p);
+  *state_bytes = p.state_bytes;
+  *workspace_bytes = p.workspace_bytes;
+  return TGRAD_OK;
+}
+
+int tgrad_init(tgrad_ctx** out, const tgrad_config* cfg, void* state_dev, void* workspace_dev,
+               void* hip_stream) {
+  if (!out) return TGRAD_ERR_INVALID_ARG;
+  *out = nullptr;
+  int rc = validate(cfg);
+  if (rc != TGRAD_OK) return rc;
+  if (!state_dev || !workspace_dev) return TGRAD_ERR_INVALID_ARG;
+  if (((uintptr_t)state_dev % kAlign) || ((uintptr_t)workspace_dev % kAlign)) return TGRAD_ERR_INVALID_ARG;
+  tgrad_ctx* c = new (std::nothrow) tgrad_ctx();
+  if (!c) return TGRAD_ERR_INVALID_ARG;
+  c->cfg = *cfg;
+  make_plan(cfg, &c->plan);
+  c->state = static_cast<char*>(state_dev);
+  c->ws = static_cast<char*>(workspace_dev);
+  c->stream = static_cast<hipStream_t>(hip_stream);
+  c->t = 0;
+  c->have_indices = false;
+  for (int n = 0; n < kMaxNdim; ++n) c->have_factor[n] = false;
+  c->profiling = false;
+  for (int i = 0; i < KID_COUNT; ++i) {
+    c->total_ms[i] = 0.;
+    c->launches[i] = 0;
+  }
+  // moments <- 0 (and everything else in the state block), with a fill kernel
+  zero_u32(c->stream, reinterpret_cast<uint32_t*>(c->state), (int64_t)(c->plan.state_bytes / 4));
+  if (check_launch() != TGRAD_OK) {
+    delete c;
+    return TGRAD_ERR_HIP;
+  }
+  *out = c;
+  return TGRAD_OK;
+}
+
+int tgrad_refresh_factors(tgrad_ctx* ctx, const void* grad_dev) {
+  if (!ctx || !grad_dev) return TGRAD_ERR_INVALID_ARG;
+  if ((uintptr_t)grad_dev % 16) return TGRAD_ERR_INVALID_ARG;
+  return do_refresh(ctx, grad_dev);
+}
+
+int tgrad_step(tgrad_ctx* ctx, void* weight_dev, const void* grad_dev) {
+  if (!ctx || !weight_dev || !grad_dev) return TGRAD_ERR_INVALID_ARG;
+  if (((uintptr_t)grad_dev % 16) || ((uintptr_t)weight_dev % 16) || weight_dev == grad_dev)
+    return TGRAD_ERR_INVALID_ARG;
+  if (ctx->cfg.refresh_every > 0 && ctx->t % ctx->cfg.refresh_every == 0) {
+    int rc = do_refresh(ctx, grad_dev);
+    if (rc != TGRAD_OK) return rc;
+  }
+  if (!ctx->ready()) return TGRAD_ERR_NOT_READY;
+  return do_step(ctx, weight_dev, grad_dev);
+}
+
+int tgrad_get_state(tgrad_ctx* ctx, int what, void* host_out, size_t cap) {
+  if (!ctx || !host_out) return TGRAD_ERR_INVALID_ARG;
+  Plan& p = ctx->plan;
+  if (what == TGRAD_STATE_STEP) {
+    if (cap < sizeof(int64_t)) return TGRAD_ERR_TOO_SMALL;
+    *static_cast<int64_t*>(host_out) = ctx->t;
+    return TGRAD_OK;
+  }
+  if (what == TGRAD_STATE_INDICES) {
+    if (!ctx->have_indices) return TGRAD_ERR_NOT_READY;
+    if (cap < (size_t)p.k * 8) return TGRAD_ERR_TOO_SMALL;
+    if (hipStreamSynchronize(ctx->stream) != hipSuccess) return TGRAD_ERR_HIP;
+    std::vector<int32_t> tmp((size_t)p.k);
+    if (p.k > 0 && hipMemcpy(tmp.data(), ctx->state + p.st_omega, (size_t)p.k * 4, hipMemcpyDeviceToHost) != hipSuccess)
+      return TGRAD_ERR_HIP;
+    int64_t* o = static_cast<int64_t*>(host_out);
+    for (int64_t j = 0; j < p.k; ++j) o[j] = tmp[(size_t)j];
+    return TGRAD_OK;
+  }
+  Item it;
+  int rc = locate(ctx, what, &it);
+  if (rc != TGRAD_OK) return rc;
+  if (it.needs_factor && !ctx->have_factor[it.mode]) return TGRAD_ERR_NOT_READY;
+  if (cap < it.bytes) return TGRAD_ERR_TOO_SMALL;
+  if (hipStreamSynchronize(ctx->stream) != hipSuccess) return TGRAD_ERR_HIP;
+  if (it.bytes && hipMemcpy(host_out, it.dev, it.bytes, hipMemcpyDeviceToHost) != hipSuccess) return TGRAD_ERR_HIP;
+  return TGRAD_OK;
+}
+
+int tgrad_set_state(tgrad_ctx* ctx, int what, const void* host_in, size_t bytes) {
+  if (!ctx || !host_in) return TGRAD_ERR_INVALID_ARG;
+  Plan& p = ctx->plan;
+  if (what == TGRAD_STATE_STEP) {
+    if (bytes != sizeof(int64_t)) return TGRAD_ERR_INVALID_ARG;
+    int64_t t = *static_cast<const int64_t*>(host_in);
+    if (t < 0) return TGRAD_ERR_INVALID_ARG;
+    ctx->t = t;
+    return TGRAD_OK;
+  }
+  if (what == TGRAD_STATE_INDICES) {
+    if (bytes != (size_t)p.k * 8) return TGRAD_ERR_INVALID_ARG;
+    const int64_t* in = static_cast<const int64_t*>(host_in);
+    std::vector<int32_t> tmp((size_t)p.k);
+    for (int64_t j = 0; j < p.k; ++j) {
+      if (in[j] < 0 || in[j] >= p.I) return TGRAD_ERR_INVALID_ARG;
+      if (j > 0 && in[j] <= in[j - 1]) return TGRAD_ERR_INVALID_ARG;
+      tmp[(size_t)j] = (int32_t)in[j];
+    }
+    if (hipStreamSynchronize(ctx->stream) != hipSuccess) return TGRAD_ERR_HIP;
+    if (p.k > 0) {
+      if (hipMemcpy(ctx->state + p.st_omega, tmp.data(), (size_t)p.k * 4, hipMemcpyHostToDevice) != hipSuccess)
+        return TGRAD_ERR_HIP;
+      Scope sc_(ctx, KID_MASK_FROM_IDX);
+      launch_mask_from_indices(ctx->stream, ctx->st<int32_t>(p.st_omega), p.k, ctx->w<uint32_t>(p.ws_mask),
+                               p.mask_words);
+    }
+    if (hipStreamSynchronize(ctx->stream) != hipSuccess) return TGRAD_ERR_HIP;
+    ctx->have_indices = true;
+    return check_launch();
+  }
+  Item it;
+  int rc = locate(ctx, what, &it);
+  if (rc != TGRAD_OK) return rc;
+  if (!it.writable) return TGRAD_ERR_INVALID_ARG;
+  if (bytes != it.bytes) return TGRAD_ERR_INVALID_ARG;
+  if (hipStreamSynchronize(ctx->stream) != hipSuccess) return TGRAD_ERR_HIP;
+  if (it.bytes && hipMemcpy(it.dev, host_in, it.bytes, hipMemcpyHostToDevice) != hipSuccess) return TGRAD_ERR_HIP;
+  if (it.needs_factor) ctx->have_factor[it.mode] = true;
+  return TGRAD_OK;
+}
+
+int tgrad_set_profiling(tgrad_ctx* ctx, int enabled) {
+  if (!ctx) return TGRAD_ERR_INVALID_ARG;
+  int rc = drain_events(ctx);
+  if (rc != TGRAD_OK) return rc;
+  if (enabled && !ctx->profiling) {
+    for (int i = 0; i < KID_COUNT; ++i) {
+      ctx->total_ms[i] = 0.;
+      ctx->launches[i] = 0;
+    }
+  }
+  ctx->profiling = enabled != 0;
+  return TGRAD_OK;
+}
+
+int tgrad_get_kernel_times(tgrad_ctx* ctx, const char** names, double* total_ms, int64_t* launches, int cap) {
+  if (!ctx || !names || !total_ms || !launches || cap < 0) return TGRAD_ERR_INVALID_ARG;
+  int rc = drain_events(ctx);
+  if (rc != TGRAD_OK) return rc;
+  int n = 0;
+  for (int i = 0; i < KID_COUNT && n < cap; ++i) {
+    if (ctx->launches[i] == 0) continue;
+    names[n] = kKernelNames[i];
+    total_ms[n] = ctx->total_ms[i];
+    launches[n] = ctx->launches[i];
+    ++n;
+  }
+  return n;
+}
+
+int tgrad_destroy(tgrad_ctx* ctx) {
+  if (!ctx) return TGRAD_ERR_INVALID_ARG;
+  (void)drain_events(ctx);
+  delete ctx;
+  return TGRAD_OK;
+}
+
+const char* tgrad_strerror(int status) {
+  switch (status) {
+    case TGRAD_OK: return "ok";
+    case TGRAD_ERR_INVALID_ARG: return "invalid argument";
+    case TGRAD_ERR_UNSUPPORTED: return "configuration not supported by this build";
+    case TGRAD_ERR_NOT_READY: return "no sparse support / Tucker factors yet (refresh first)";
+    case TGRAD_ERR_HIP: return "HIP runtime call or kernel launch failed";
+    case TGRAD_ERR_TOO_SMALL: return "host buffer too small";
+    default: return "unknown status";
+  }
+}
+
+}  // extern "C"

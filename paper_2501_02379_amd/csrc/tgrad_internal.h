@@ -1,0 +1,81 @@
+// Internal declarations shared by the host orchestration and the kernel files.
+// Nothing here is part of the ABI (see include/tgrad.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/tgrad.h"
+
+namespace tgrad {
+
+constexpr int kMaxNdim = TGRAD_MAX_NDIM;
+
+// ---- selection (Algorithm 1: SparseIndices) -------------------------------------------------
+// A "segment" is the run of consecutive elements one wavefront counts/emits in order.
+constexpr int kSegElems = 2048;
+constexpr int kHistBins = 4096;            // 12-bit digits; the three digits are 12 + 12 + 8 bits
+
+struct SelectScalars {                     // lives in workspace, written by the pick kernel
+  uint32_t prefix;                         // key bits fixed so far (high-aligned digits)
+  uint32_t remaining;                      // how many entries are still to take inside `prefix`
+  uint32_t threshold;                      // final: key of the k-th largest entry
+  uint32_t need_eq;                        // final: entries with key == threshold to take (lowest indices)
+};
+
+// ---- one mode-n product stage: Out[a, m, b] = sum_k F[m, k] X[a, k, b] ------------------------
+struct Stage {
+  int mode;                                // which tensor mode this stage contracts
+  int64_t A;                               // product of the extents left of the mode
+  int K;                                   // extent being contracted
+  int M;                                   // extent produced
+  int64_t B;                               // product of the extents right of the mode
+};
+
+// Names of the profiled kernels (index into the per-context timing table).
+enum KernelId {
+  KID_SEL_HIST = 0, KID_SEL_PICK, KID_SEL_COUNT, KID_SEL_SCAN, KID_SEL_EMIT, KID_MASK_FROM_IDX,
+  KID_GRAM, KID_GRAM_REDUCE, KID_EIG, KID_FACTOR_PACK,
+  KID_GATHER, KID_PROJECT_FIRST, KID_PROJECT, KID_ADAM_CORE, KID_BACKPROJECT, KID_UPDATE,
+  KID_SPARSE_UPDATE, KID_COUNT
+};
+
+struct Launch {                            // what every launcher needs
+  hipStream_t stream;
+};
+
+// selection
+void launch_select_hist(hipStream_t s, const void* g, int dtype, int64_t I, int pass,
+                        const SelectScalars* sc, uint32_t* hist);
+void launch_select_pick(hipStream_t s, int pass, uint32_t k, SelectScalars* sc, const uint32_t* hist);
+void launch_select_count(hipStream_t s, const void* g, int dtype, int64_t I, const SelectScalars* sc,
+                         uint32_t* seg_gt, uint32_t* seg_eq, int64_t nseg);
+void launch_select_scan(hipStream_t s, uint32_t* seg_gt, uint32_t* seg_eq, int64_t nseg);
+void launch_select_emit(hipStream_t s, const void* g, int dtype, int64_t I, const SelectScalars* sc,
+                        const uint32_t* seg_gt, const uint32_t* seg_eq, int64_t nseg,
+                        int32_t* omega, uint32_t* mask);
+void launch_mask_from_indices(hipStream_t s, const int32_t* omega, int64_t k, uint32_t* mask,
+                              int64_t mask_words);
+
+// factor refresh
+int gram_num_chunks(int64_t A, int In, int64_t B);
+void launch_gram(hipStream_t s, const void* g, int dtype, const uint32_t* mask, int64_t A, int In,
+                 int64_t B, int nchunks, double* partials);
+void launch_gram_reduce(hipStream_t s, const double* partials, int nchunks, int In, double* gram);
+void launch_eig(hipStream_t s, const double* gram, double* work_a, double* work_v, int In, int r,
+                float* U);
+
+// step
+void launch_gather(hipStream_t s, const void* g, int dtype, const int32_t* omega, int64_t k,
+                   float2* out);
+void launch_contract(hipStream_t s, const void* x, int x_dtype, const uint32_t* mask,
+                     const float2* U, int In, int rn, bool project, const Stage& st, float2* out);
+void launch_adam_core(hipStream_t s, const float2* r, float2* m, float* v, float2* n_out, int64_t C,
+                      float beta1, float beta2, float inv_c1, float inv_c2, float eps);
+void launch_update(hipStream_t s, const float2* z, const float2* U, int In, int rn, const Stage& st,
+                   float2* w, float decay, float neg_lr_alpha);
+void launch_sparse_update(hipStream_t s, const float2* gs, const int32_t* omega, int64_t k,
+                          float2* m, float* v, float2* w, float beta1, float beta2, float inv_c1,
+                          float inv_c2, float eps, float neg_lr_lambda);
+
+}  // namespace tgrad

@@ -1,0 +1,98 @@
+"""Host-side checks of the C-ABI library: it loads, exports every symbol the header declares,
+validates arguments and sizes buffers.  No kernel runs here."""
+import ctypes as C
+import os
+import re
+from fractions import Fraction
+
+import pytest
+
+from paper_2501_02379_amd import synth, tgrad as T
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "tgrad.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(tgrad_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = T.load()
+    names = _declared_symbols()
+    assert set(names) == set(T.EXPORTS)
+    for name in names:
+        assert getattr(lib, name) is not None
+
+
+def test_strerror_names_every_status():
+    seen = set()
+    for code in (0, -1, -2, -3, -4, -5):
+        s = T.strerror(code)
+        assert s and s != "unknown status"
+        seen.add(s)
+    assert len(seen) == 6
+    assert T.strerror(-99) == "unknown status"
+
+
+def test_query_sizes_counts_the_compressed_state():
+    w = synth.WORKLOADS["cfg4"]
+    cfg = T.make_config(w.shape, w.ranks, w.k, refresh_every=w.T)
+    rc, sb, wb = T.tgrad_query_sizes(cfg)
+    assert rc == T.TGRAD_OK
+    core = 32 * 32 * 32 * 16
+    factors = 3 * 128 * 32 + 65 * 16
+    exact = core * 12 + w.k * 16 + factors * 8
+    assert exact <= sb <= exact + 16 * 256           # plus alignment padding only
+    dense_adam = w.numel * 12                        # complex64 M + float32 V
+    assert sb / dense_adam < 0.011
+    assert wb > 0
+
+
+@pytest.mark.parametrize("mutate,expected", [
+    (lambda c: setattr(c, "ndim", 1), T.TGRAD_ERR_INVALID_ARG),
+    (lambda c: setattr(c, "ndim", 7), T.TGRAD_ERR_INVALID_ARG),
+    (lambda c: c.shape.__setitem__(0, 0), T.TGRAD_ERR_INVALID_ARG),
+    (lambda c: c.rank.__setitem__(1, 0), T.TGRAD_ERR_INVALID_ARG),
+    (lambda c: c.rank.__setitem__(1, 99), T.TGRAD_ERR_INVALID_ARG),
+    (lambda c: setattr(c, "k_sparse", -1), T.TGRAD_ERR_INVALID_ARG),
+    (lambda c: setattr(c, "k_sparse", 16 * 16 * 8 * 5 + 1), T.TGRAD_ERR_INVALID_ARG),
+    (lambda c: setattr(c, "grad_dtype", 7), T.TGRAD_ERR_INVALID_ARG),
+    (lambda c: setattr(c, "weight_dtype", T.TGRAD_CBF16), T.TGRAD_ERR_UNSUPPORTED),
+    (lambda c: setattr(c, "beta1", 1.0), T.TGRAD_ERR_INVALID_ARG),
+    (lambda c: setattr(c, "lr", float("nan")), T.TGRAD_ERR_INVALID_ARG),
+    (lambda c: setattr(c, "refresh_every", -1), T.TGRAD_ERR_INVALID_ARG),
+    (lambda c: setattr(c, "hooi_sweeps", 2), T.TGRAD_ERR_UNSUPPORTED),
+    (lambda c: setattr(c, "select_rule", 1), T.TGRAD_ERR_UNSUPPORTED),
+    (lambda c: c.shape.__setitem__(0, 1 << 31), T.TGRAD_ERR_UNSUPPORTED),
+])
+def test_bad_configs_are_rejected(mutate, expected):
+    cfg = T.make_config((16, 16, 8, 5), (8, 8, 4, 3), 103)
+    mutate(cfg)
+    rc, _, _ = T.tgrad_query_sizes(cfg)
+    assert rc == expected
+    h = C.c_void_p(None)
+    rc2 = T.load().tgrad_init(C.byref(h), C.byref(cfg), 256, 256, None)
+    assert rc2 == expected and not h
+
+
+def test_null_and_misaligned_pointers():
+    lib = T.load()
+    cfg = T.make_config((16, 16, 8, 5), (8, 8, 4, 3), 103)
+    h = C.c_void_p(None)
+    assert lib.tgrad_init(None, C.byref(cfg), 256, 256, None) == T.TGRAD_ERR_INVALID_ARG
+    assert lib.tgrad_init(C.byref(h), None, 256, 256, None) == T.TGRAD_ERR_INVALID_ARG
+    assert lib.tgrad_init(C.byref(h), C.byref(cfg), None, 256, None) == T.TGRAD_ERR_INVALID_ARG
+    assert lib.tgrad_init(C.byref(h), C.byref(cfg), 256, 264, None) == T.TGRAD_ERR_INVALID_ARG
+    assert lib.tgrad_step(None, 256, 512) == T.TGRAD_ERR_INVALID_ARG
+    assert lib.tgrad_refresh_factors(None, 256) == T.TGRAD_ERR_INVALID_ARG
+    assert lib.tgrad_destroy(None) == T.TGRAD_ERR_INVALID_ARG
+    assert lib.tgrad_query_sizes(C.byref(cfg), None, None) == T.TGRAD_ERR_INVALID_ARG
+
+
+def test_caller_side_sizes():
+    for w in synth.WORKLOADS.values():
+        assert T.sparse_count(Fraction(*w.density), w.numel) == w.k
+        assert tuple(T.rank_from_ratio(Fraction(1, 2) if w.name == "cfg1" else Fraction(1, 4), i)
+                     for i in w.shape) == w.ranks
