@@ -1,0 +1,276 @@
+#!/usr/bin/env python3
+"""Benchmark of the TensorGRaD optimizer hot path on one MI355X.
+
+One "step" = one `tgrad_step` on one synthetic FNO-shaped gradient already resident in HBM
+(refresh of support and factors included whenever t % T == 0 falls in the timed region).
+Prints ONE JSON line: whole-job throughput in Gelem/s, the roofline of the dominant kernel
+(per-kernel durations from HIP events recorded by the library on its own stream), and the CPU
+oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+MFMA_FP32_PEAK_TF = 157.3      # dense fp32 matrix
+MFMA_FP64_PEAK_TF = 78.6       # dense fp64 matrix
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def kernel_model(w, plan_shapes):
+    """Algorithmic bytes and flops per launch of every kernel, from the tensor shapes alone
+    (8 real flops per complex multiply-add; a complex64 element is 8 bytes)."""
+    shape, ranks, k = w.shape, w.ranks, w.k
+    N = len(shape)
+    I = int(np.prod(shape))
+    C = int(np.prod(ranks))
+    gb = 8 if w.grad_dtype == "c64" else 4
+    m = {}
+
+    def stage_dims(project, s):
+        if project:
+            n = N - 1 - s
+            A = int(np.prod(shape[:n])) if n else 1
+            B = int(np.prod(ranks[n + 1:])) if n + 1 < N else 1
+            return A, shape[n], ranks[n], B
+        n = s
+        A = int(np.prod(shape[:n])) if n else 1
+        B = int(np.prod(ranks[n + 1:])) if n + 1 < N else 1
+        return A, ranks[n], shape[n], B
+
+    A, K, M, B = stage_dims(True, 0)
+    m["project_first"] = {"bytes": I * gb + A * M * B * 8, "flops": 8 * A * K * M * B, "bound": "hbm"}
+    by = fl = 0
+    for s in range(1, N):
+        A, K, M, B = stage_dims(True, s)
+        by += (A * K * B + A * M * B) * 8
+        fl += 8 * A * K * M * B
+    m["project"] = {"bytes": by, "flops": fl, "bound": "mfma", "launches_per_step": N - 1}
+    by = fl = 0
+    for s in range(0, N - 1):
+        A, K, M, B = stage_dims(False, s)
+        by += (A * K * B + A * M * B) * 8
+        fl += 8 * A * K * M * B
+    m["backproject"] = {"bytes": by, "flops": fl, "bound": "mfma", "launches_per_step": N - 1}
+    A, K, M, B = stage_dims(False, N - 1)
+    m["update"] = {"bytes": A * K * 8 + 16 * I, "flops": 8 * A * K * M + 4 * I, "bound": "hbm"}
+    m["gather"] = {"bytes": k * (4 + gb + 8), "flops": 0, "bound": "hbm"}
+    m["adam_core"] = {"bytes": C * (8 + 12 + 12 + 8), "flops": 12 * C, "bound": "hbm"}
+    m["sparse_update"] = {"bytes": k * (8 + 4 + 12 + 12 + 16), "flops": 14 * k, "bound": "hbm"}
+    m["select_hist"] = {"bytes": I * gb, "flops": 3 * I, "bound": "hbm"}
+    m["select_count"] = {"bytes": I * gb, "flops": 3 * I, "bound": "hbm"}
+    m["select_emit"] = {"bytes": I * gb + I // 8 + 4 * k, "flops": 3 * I, "bound": "hbm"}
+    gram_fl = sum(8 * I * shape[n] for n in range(N) if ranks[n] < shape[n])
+    ngram = sum(1 for n in range(N) if ranks[n] < shape[n])
+    m["gram"] = {"bytes": ngram * I * gb, "flops": gram_fl, "bound": "mfma64", "launches_per_step": ngram}
+    return m
+
+
+def cpu_baseline(w, budget_hint_s=20.0):
+    """The oracle, as it stands, on a bounded sample of the same workload: the leading
+    channel block of the gradient (all Fourier modes kept), one refresh + 3 steps, amortised
+    over the workload's refresh period exactly like the GPU figure."""
+    from fractions import Fraction
+    from oracle import tgrad_oracle as O
+    from paper_2501_02379_amd import synth
+    shape = list(w.shape)
+    ranks = list(w.ranks)
+    # shrink the two channel modes until the sample is at most ~40M elements (10-30 s of CPU work)
+    while int(np.prod(shape)) > 40_000_000 and shape[0] > 8:
+        shape[0] //= 2
+        shape[1] //= 2
+        ranks[0] = max(1, ranks[0] // 2)
+        ranks[1] = max(1, ranks[1] // 2)
+    shape, ranks = tuple(shape), tuple(ranks)
+    I = int(np.prod(shape))
+    k = O.sparse_count(Fraction(*w.density), I)
+    sl = tuple(slice(0, s) for s in shape)
+    rng = np.random.default_rng(0)
+
+    def sample_grad(t):
+        g = rng.standard_normal(shape + (2,), dtype=np.float32).view(np.complex64).reshape(shape)
+        g *= np.float32(np.sqrt(0.5))
+        pos = synth.outlier_positions(I, w.outlier_frac, 97 + w.config_id)
+        g.reshape(-1)[pos] *= np.float32(20.0)
+        if w.grad_dtype == "cbf16":
+            return synth.complex64_to_bf16_pairs(g)
+        return g
+
+    st = O.State(shape, O.Hyper(ranks=ranks, k=k, lr=w.lr, T=0))
+    W = np.zeros(shape, dtype=np.complex128)
+    g = sample_grad(0)
+    t0 = time.perf_counter()
+    O.refresh(st, g)
+    t_refresh = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    nsteps = 3
+    for t in range(nsteps):
+        W = O.step(st, W, g)
+    t_step = (time.perf_counter() - t0) / nsteps
+    per_step = t_step + t_refresh / max(1, w.T)
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = len(os.sched_getaffinity(0))
+    return {
+        "value": I / per_step / 1e9, "unit": "Gelem/s", "cores": int(threads), "kind": "oracle",
+        "sample": "leading %s block of the %s gradient, ranks %s, k=%d; 1 refresh (%.2f s) + %d steps "
+                  "(%.2f s each), amortised over T=%d" % ("x".join(map(str, shape)), w.name,
+                                                         ",".join(map(str, ranks)), k, t_refresh, nsteps,
+                                                         t_step, w.T),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg4")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--traffic-kib", type=float, default=None,
+                    help="HBM KiB per launch of the dominant kernel from rocprofv3 --pmc (else null)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on ONE GPU (one process, one MI355X); --gpus %d is not supported."
+            % args.gpus)
+        sys.exit(2)
+
+    import torch
+    from paper_2501_02379_amd import synth, tgrad as T
+
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible")
+        sys.exit(2)
+    T.load()                                    # raises if the HIP library is not built
+    w = synth.WORKLOADS[args.workload]
+    K = args.steps if args.steps is not None else w.T
+    Wm = args.warmup
+    dev = "cuda:0"
+    I = w.numel * w.layers
+
+    log("generating inputs for %s %s ..." % (w.name, "x".join(map(str, w.shape))))
+    ctxs, Ws, Gs = [], [], []
+    for layer in range(w.layers):
+        cfg = T.make_config(w.shape, w.ranks, w.k, grad_dtype=T.TGRAD_CBF16 if w.grad_dtype == "cbf16" else 0,
+                            lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps, alpha=w.alpha, lam=w.lam,
+                            weight_decay=w.weight_decay, refresh_every=w.T)
+        ctxs.append(T.Context(cfg, device=dev))
+        Ws.append(T.to_device_weight(synth.initial_weight(w, layer), dev))
+        Gs.append([T.to_device_grad(synth.gradient(w, t, layer), dev) for t in range(2)])
+    torch.cuda.synchronize()
+
+    def run_steps(n, t0):
+        for t in range(t0, t0 + n):
+            for layer in range(w.layers):
+                ctxs[layer].tgrad_step(Ws[layer], Gs[layer][t & 1])
+
+    log("warmup %d steps ..." % Wm)
+    run_steps(Wm, 0)
+    torch.cuda.synchronize()
+
+    # ---- region A: the timed K steps (no per-kernel events) ----
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    run_steps(K, Wm)
+    e1.record()
+    torch.cuda.synchronize()
+    ms_total = e0.elapsed_time(e1)
+    ms_per_step = ms_total / K
+    refreshes = sum(1 for t in range(Wm, Wm + K) if t % w.T == 0)
+    value = I / (ms_per_step * 1e-3) / 1e9
+
+    # ---- region B: the same K steps again with per-kernel HIP events on the library's stream ----
+    for c in ctxs:
+        c.tgrad_set_profiling(True)
+    torch.cuda.synchronize()
+    e0.record()
+    run_steps(K, Wm + K)
+    e1.record()
+    torch.cuda.synchronize()
+    ms_per_step_profiled = e0.elapsed_time(e1) / K
+    refreshes_b = sum(1 for t in range(Wm + K, Wm + 2 * K) if t % w.T == 0)
+    times = {}
+    for c in ctxs:
+        for name, v in c.tgrad_get_kernel_times().items():
+            d = times.setdefault(name, {"total_ms": 0.0, "launches": 0})
+            d["total_ms"] += v["total_ms"]
+            d["launches"] += v["launches"]
+    # one more explicit refresh so refresh kernels are always covered
+    refresh_ms = None
+    if refreshes_b == 0:
+        for c in ctxs:
+            c.tgrad_set_profiling(False)
+        torch.cuda.synchronize()
+        e0.record()
+        for layer in range(w.layers):
+            ctxs[layer].tgrad_refresh_factors(Gs[layer][0])
+        e1.record()
+        torch.cuda.synchronize()
+        refresh_ms = e0.elapsed_time(e1)
+
+    model = kernel_model(w, None)
+    kernels = {}
+    for name, v in sorted(times.items(), key=lambda kv: -kv[1]["total_ms"]):
+        avg = v["total_ms"] / max(1, v["launches"])
+        ent = {"avg_ms": round(avg, 5), "launches": v["launches"], "total_ms": round(v["total_ms"], 3)}
+        mm = model.get(name)
+        if mm:
+            lp = mm.get("launches_per_step", 1)
+            ent["GBps"] = round(mm["bytes"] / lp / (avg * 1e-3) / 1e9, 1)
+            ent["TFLOPs"] = round(mm["flops"] / lp / (avg * 1e-3) / 1e12, 2)
+        kernels[name] = ent
+    step_kernels = [n for n in kernels if not n.startswith(("select", "gram", "eig", "mask", "factor"))]
+    dom = max(step_kernels, key=lambda n: kernels[n]["total_ms"]) if step_kernels else None
+    roofline = None
+    if dom and dom in model:
+        mm = model[dom]
+        lp = mm.get("launches_per_step", 1)
+        avg_s = kernels[dom]["avg_ms"] * 1e-3
+        if mm["bound"] == "hbm":
+            ach, peak, unit = mm["bytes"] / lp / avg_s / 1e9, HBM_PEAK_GBS, "GB/s"
+        else:
+            ach, peak, unit = mm["flops"] / lp / avg_s / 1e12, MFMA_FP32_PEAK_TF, "TFLOP/s"
+        roofline = {"kernel": dom, "bound": "hbm" if mm["bound"] == "hbm" else "mfma",
+                    "achieved": round(ach, 2), "peak": peak, "unit": unit, "frac": round(ach / peak, 4),
+                    "traffic": (args.traffic_kib * 1024.0 if args.traffic_kib is not None else None),
+                    "algorithmic_bytes_per_launch": mm["bytes"] // lp,
+                    "avg_launch_ms": kernels[dom]["avg_ms"]}
+
+    out = {
+        "metric": "gradient elements compressed+updated/sec (Gelem/s) per step; % HBM roofline",
+        "value": round(value, 4), "unit": "Gelem/s", "n_gpus": 1, "steps": K, "warmup": Wm,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s: %d x %s %s gradient, Tucker ranks %s, k=%d sparse, refresh every %d"
+                               % (w.name, w.layers, "x".join(map(str, w.shape)), w.grad_dtype,
+                                  ",".join(map(str, w.ranks)), w.k, w.T),
+                   "refreshes_in_timed_region": refreshes},
+        "roofline": roofline,
+        "ms_per_step_with_kernel_events": round(ms_per_step_profiled, 4),
+        "refresh_ms": refresh_ms,
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        log("timing the CPU oracle on a bounded sample ...")
+        out["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()
