@@ -1,0 +1,594 @@
+// Mode-n products of the per-step path of Algorithm 1 on the fp32 matrix cores
+// (v_mfma_f32_32x32x2f32), for low-rank compression  g_L = (G - Sparse(G, Omega)) x_n U^(n)H
+// and reconstruction  G~_L = N_L x_n U^(n)  (section "Low-rank gradient tensor decomposition",
+// appendix "Tensor Operations and Notation", mode-k product).
+//
+// A complex contraction is run as a real one without padding or wasted flops: a tensor of
+// interleaved (re, im) float32 pairs is used as it lies in memory, and the factor is expanded to
+// its 2 x 2 real blocks.  With F = Fr + i Fi and X = Xr + i Xi,
+//   re(F X) = Fr Xr - Fi Xi,   im(F X) = Fr Xi + Fi Xr,
+// i.e. 4 real multiply-adds per complex multiply-add on either layout below.
+//
+// Three kernels:
+//  k_mid      contracts a mode that is NOT the last one: the tensor is (A, K, B) with B >= 1
+//             contiguous; every lane owns VEC complex columns (a, b) and walks the K rows.
+//  k_lproj    contracts the LAST mode of the gradient itself (first compression stage): a
+//             flat tile of rows is staged in LDS, the entries of the support Omega that fall
+//             in the tile are handed to the sparse branch (gather) and zeroed (this is
+//             G - Sparse(G, Omega) without a second pass over G), then 32 rows per wavefront
+//             go through the matrix cores.
+//  k_lupdate  the last reconstruction stage fused with everything that touches W: expands the
+//             last mode into an LDS tile, runs AdamUpdate on the sparse values of the tile
+//             and adds lambda N_S into it, then streams W <- W (1 - lr wd) - lr tile with
+//             16-byte accesses.
+//
+// Operand layout of v_mfma_f32_32x32x2f32 (D = A B + C, A 32 x 2, B 2 x 32, 64 lanes):
+//   lane l supplies A[l % 32][l / 32] and B[l / 32][l % 32];
+//   register r of lane l receives D[(r % 4) + 8 (r / 4) + 4 (l / 32)][l % 32].
+#include "device_common.h"
+
+namespace tgrad {
+
+namespace {
+
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ v16f mfma32(float a, float b, v16f c) {
+  return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ int d_row(int r, int half) { return (r & 3) + 8 * (r >> 2) + 4 * half; }
+
+// q = n / d, exact for n * d < 2^32 (callers keep n < 2^17, d < 2^10).
+// magic = ceil(2^32 / d); d == 1 is encoded as magic == 0.
+__device__ __forceinline__ uint32_t div_magic(uint32_t n, uint32_t magic) {
+  return magic ? __umulhi(n, magic) : n;
+}
+
+// -------------------------------------------------------------------------------------------
+// k_mid: out[a, m, b] = sum_k F[m, k] x[a, k, b],  F = U^H (PROJECT) or U.
+// Workgroup = 4 wavefronts; a wavefront owns 32 column vectors (VEC complex each) and MT row
+// tiles of 32 output rows; blockIdx.y selects the group of MT row tiles.
+// Per pair of rows (k = 2 j, 2 j + 1): lanes 0..31 load row 2 j, lanes 32..63 row 2 j + 1 of
+// their column; the factor operands (Fr, Fi) for that pair come from LDS.
+constexpr int kMidThreads = 256;
+constexpr int kMidJChunk = 64;            // row pairs of the factor staged in LDS at a time
+constexpr int kMidUnroll = 8;
+
+template <int VEC> struct VecT;
+template <> struct VecT<1> { typedef float2 type; };
+template <> struct VecT<2> { typedef float4 type; };
+
+template <int MT, int VEC, bool PROJECT>
+__global__ __launch_bounds__(kMidThreads) void k_mid(const float* __restrict__ x,
+                                                     const float2* __restrict__ U, int rn, int64_t A,
+                                                     int K, int M, int64_t B, float* __restrict__ out) {
+  typedef typename VecT<VEC>::type V;
+  extern __shared__ float2 sF[];          // [pair][mt][lane] = (Fr, Fi)
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int col = lane & 31, half = lane >> 5;
+  const int64_t BV = B / VEC;             // host guarantees B % VEC == 0
+  const int64_t ncv = A * BV;
+  const int64_t cv = ((int64_t)blockIdx.x * (kMidThreads / 64) + wave) * 32 + col;
+  const bool valid = cv < ncv;
+  const int64_t a = valid ? cv / BV : 0;
+  const int64_t bv = valid ? cv - a * BV : 0;
+  const float* xp = x + ((a * K) * B + bv * VEC) * 2;
+  const int64_t row_stride = B * 2;       // floats between consecutive k
+  const int mbase = blockIdx.y * (32 * MT);
+
+  v16f acc[MT][2 * VEC];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int t = 0; t < 2 * VEC; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[mt][t][r] = 0.f;
+
+  const int J = (K + 1) >> 1;
+  for (int jc0 = 0; jc0 < J; jc0 += kMidJChunk) {
+    const int jn = (J - jc0) < kMidJChunk ? (J - jc0) : kMidJChunk;
+    __syncthreads();                                           // previous chunk fully consumed
+    for (int e = tid; e < jn * MT * 64; e += kMidThreads) {
+      const int l = e & 63;
+      const int mt = (e >> 6) % MT;
+      const int jj = e / (64 * MT);
+      const int m = mbase + 32 * mt + (l & 31);
+      const int k = 2 * (jc0 + jj) + (l >> 5);
+      float2 f = make_float2(0.f, 0.f);
+      if (m < M && k < K) {
+        if (PROJECT) {
+          const float2 u = U[(int64_t)k * rn + m];
+          f = make_float2(u.x, -u.y);
+        } else {
+          f = U[(int64_t)m * rn + k];
+        }
+      }
+      sF[e] = f;
+    }
+    __syncthreads();
+    for (int jj0 = 0; jj0 < jn; jj0 += kMidUnroll) {
+      V v[kMidUnroll];
+#pragma unroll
+      for (int u = 0; u < kMidUnroll; ++u) {
+        const int k = 2 * (jc0 + jj0 + u) + half;
+        if (VEC == 1) {
+          float2 z = make_float2(0.f, 0.f);
+          if (valid && (jj0 + u) < jn && k < K) z = *reinterpret_cast<const float2*>(xp + (int64_t)k * row_stride);
+          *reinterpret_cast<float2*>(&v[u]) = z;
+        } else {
+          float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
+          if (valid && (jj0 + u) < jn && k < K) z = *reinterpret_cast<const float4*>(xp + (int64_t)k * row_stride);
+          *reinterpret_cast<float4*>(&v[u]) = z;
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < kMidUnroll; ++u) {
+        if (jj0 + u < jn) {                                    // uniform over the workgroup
+          float xs[2 * VEC], xj[2 * VEC];
+          if (VEC == 1) {
+            const float2 z = *reinterpret_cast<float2*>(&v[u]);
+            xs[0] = z.x; xs[1] = z.y;
+          } else {
+            const float4 z = *reinterpret_cast<float4*>(&v[u]);
+            xs[0] = z.x; xs[1] = z.y; xs[2] = z.z; xs[3] = z.w;
+          }
+#pragma unroll
+          for (int c = 0; c < VEC; ++c) {                      // (X J): re column <- -im, im column <- re
+            xj[2 * c] = -xs[2 * c + 1];
+            xj[2 * c + 1] = xs[2 * c];
+          }
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) {
+            const float2 f = sF[((jj0 + u) * MT + mt) * 64 + lane];
+#pragma unroll
+            for (int t = 0; t < 2 * VEC; ++t) {
+              acc[mt][t] = mfma32(f.x, xs[t], acc[mt][t]);
+              acc[mt][t] = mfma32(f.y, xj[t], acc[mt][t]);
+            }
+          }
+        }
+      }
+    }
+  }
+  if (!valid) return;
+  float* op = out + ((a * M) * B + bv * VEC) * 2;
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int m = mbase + 32 * mt + d_row(r, half);
+      if (m < M) {
+        float* o = op + (int64_t)m * row_stride;
+        if (VEC == 1) {
+          *reinterpret_cast<float2*>(o) = make_float2(acc[mt][0][r], acc[mt][1][r]);
+        } else {
+          *reinterpret_cast<float4*>(o) = make_float4(acc[mt][0][r], acc[mt][1][r], acc[mt][2][r], acc[mt][3][r]);
+        }
+      }
+    }
+}
+
+// -------------------------------------------------------------------------------------------
+// Shared by the two last-mode kernels: the tensor seen as (A rows, L complex per row) is cut
+// into flat tiles of R = 32 W rows; tile t holds elements [t R L, (t + 1) R L).
+// `tile_start[t]` = number of support entries below t R L (Omega is ascending), so tile t owns
+// Omega[tile_start[t] .. tile_start[t + 1]).
+
+// B-operand table of a last-mode contraction, staged in LDS as [pair j][column tile][lane]
+// = (coefficient of the re part, coefficient of the im part) of input element k = 2 j + lane / 32
+// for output column c = 32 nt + lane % 32 (complex m = c / 2, part p = c % 2).
+//   PROJECT (F[m, k] = conj(U[k, m])):  p = re: (ur, ui),  p = im: (-ui, ur)
+//   expand  (F[m, k] = U[m, k]):        p = re: (ur, -ui), p = im: (ui, ur)
+template <bool PROJECT>
+__device__ __forceinline__ void stage_last_mode_factor(float2* sB, const float2* __restrict__ U, int rn,
+                                                       int K, int M, int J, int NT, int tid, int nthreads) {
+  for (int e = tid; e < J * NT * 64; e += nthreads) {
+    const int l = e & 63;
+    const int nt = (e >> 6) % NT;
+    const int j = e / (64 * NT);
+    const int k = 2 * j + (l >> 5);
+    const int c = 32 * nt + (l & 31);
+    const int m = c >> 1, p = c & 1;
+    float2 b = make_float2(0.f, 0.f);
+    if (k < K && m < M) {
+      const float2 u = PROJECT ? U[(int64_t)k * rn + m] : U[(int64_t)m * rn + k];
+      const float ui = PROJECT ? u.y : -u.y;                   // sign of the (im -> re) coefficient
+      b = p == 0 ? make_float2(u.x, ui) : make_float2(-ui, u.x);
+    }
+    sB[e] = b;
+  }
+}
+
+// k_lproj: out[a, m] = sum_k conj(U[k, m]) (G - Sparse(G, Omega))[a, k];  gs[j] = G[Omega_j].
+template <int DT, int W, int NTB>
+__global__ __launch_bounds__(64 * W) void k_lproj(const void* __restrict__ g,
+                                                  const int32_t* __restrict__ omega,
+                                                  const uint32_t* __restrict__ tile_start,
+                                                  float2* __restrict__ gs, const float2* __restrict__ U,
+                                                  int rn, int64_t A, int K, int M, uint32_t magicK,
+                                                  int64_t ntiles, float* __restrict__ out) {
+  constexpr int T = 64 * W, R = 32 * W;
+  extern __shared__ float smem[];
+  const int stride = 2 * K + ((K & 1) ? 0 : 2);                // floats per LDS row; stride / 2 is odd
+  float* sX = smem;                                            // R * stride floats
+  float2* sB = reinterpret_cast<float2*>(smem + R * stride);   // J * NT * 64 (R * stride is even)
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int col = lane & 31, half = lane >> 5;
+  const int J = (K + 1) >> 1;
+  const int N2 = 2 * M;
+  const int NT = (N2 + 31) >> 5;
+  stage_last_mode_factor<true>(sB, U, rn, K, M, J, NT, tid, T);
+
+  const int64_t I = A * K;
+  const int tile_elems = R * K;
+  for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+    const int64_t e_base = tile * tile_elems;
+    const int n_e = (int)((I - e_base) < tile_elems ? (I - e_base) : tile_elems);
+    __syncthreads();                                           // previous tile consumed (and sB staged)
+    // ---- stage the tile: flat, coalesced 16-byte loads; element e -> sX[row * stride + 2 col] ----
+    for (int p = tid; 2 * p < n_e; p += T) {
+      const int e0 = 2 * p;
+      float2 v0, v1 = make_float2(0.f, 0.f);
+      if (e0 + 1 < n_e) {
+        load_pair<DT>(g, (e_base >> 1) + p, v0, v1);
+      } else {
+        v0 = load_elem<DT>(g, e_base + e0);
+      }
+      const uint32_t r0 = div_magic((uint32_t)e0, magicK);
+      const uint32_t c0 = (uint32_t)e0 - r0 * (uint32_t)K;
+      *reinterpret_cast<float2*>(&sX[r0 * stride + 2 * c0]) = v0;
+      if (e0 + 1 < n_e) {
+        const uint32_t r1 = (c0 + 1 == (uint32_t)K) ? r0 + 1 : r0;
+        const uint32_t c1 = (c0 + 1 == (uint32_t)K) ? 0u : c0 + 1;
+        *reinterpret_cast<float2*>(&sX[r1 * stride + 2 * c1]) = v1;
+      }
+    }
+    __syncthreads();
+    // ---- Sparse(G, Omega) of this tile: hand the values over, then remove them ----
+    {
+      const uint32_t j0 = tile_start[tile], j1 = tile_start[tile + 1];
+      for (uint32_t j = j0 + tid; j < j1; j += T) {
+        const uint32_t e = (uint32_t)((int64_t)omega[j] - e_base);
+        const uint32_t r = div_magic(e, magicK);
+        const uint32_t c = e - r * (uint32_t)K;
+        float2* p = reinterpret_cast<float2*>(&sX[r * stride + 2 * c]);
+        gs[j] = *p;
+        *p = make_float2(0.f, 0.f);
+      }
+    }
+    __syncthreads();
+    // ---- 32 rows per wavefront through the matrix cores ----
+    const int lrow = wave * 32 + col;
+    const float* xrow = sX + lrow * stride;
+    const int64_t grow0 = tile * R + wave * 32;
+    for (int nt0 = 0; nt0 < NT; nt0 += NTB) {
+      v16f acc[NTB];
+#pragma unroll
+      for (int i = 0; i < NTB; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+      for (int j = 0; j < J; ++j) {
+        const int k = 2 * j + half;
+        float2 a2 = *reinterpret_cast<const float2*>(xrow + 2 * (k < K ? k : 0));
+        if (k >= K) a2 = make_float2(0.f, 0.f);
+#pragma unroll
+        for (int i = 0; i < NTB; ++i) {
+          if (nt0 + i < NT) {
+            const float2 b2 = sB[(j * NT + nt0 + i) * 64 + lane];
+            acc[i] = mfma32(a2.x, b2.x, acc[i]);
+            acc[i] = mfma32(a2.y, b2.y, acc[i]);
+          }
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < NTB; ++i) {
+        if (nt0 + i < NT) {
+          const int c = 32 * (nt0 + i) + col;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int64_t grow = grow0 + d_row(r, half);
+            if (grow < A && c < N2) out[grow * N2 + c] = acc[i][r];
+          }
+        }
+      }
+    }
+  }
+}
+
+// k_lupdate: tile = c_alpha * (z x_N U) + c_lambda * scatter(N_S);  W <- decay * W + tile,
+// with c_alpha = -lr alpha, c_lambda = -lr lambda, decay = 1 - lr wd (Algorithm 1: "Reconstruct
+// low-rank part", "Add scaled sparse tensor", weight update; AdamUpdate on the sparse values
+// as in the appendix algorithm "Adam with low-rank tensor decomposition").
+struct SparseAdam {
+  const int32_t* omega;
+  const uint32_t* tile_start;
+  const float2* gs;
+  float2* ms;
+  float* vs;
+  float beta1, beta2, inv_c1, inv_c2, eps, c_lambda;
+};
+
+constexpr int kUpdPrefetch = 18;          // 16-byte pieces of W per thread kept in flight during the MFMA phase
+
+template <int W, int NTB>
+__global__ __launch_bounds__(64 * W) void k_lupdate(const float* __restrict__ z,
+                                                    const float2* __restrict__ U, int64_t A, int K,
+                                                    int M, uint32_t magicK, int64_t ntiles,
+                                                    float* __restrict__ w, float decay, float c_alpha,
+                                                    SparseAdam sp) {
+  constexpr int T = 64 * W, R = 32 * W;
+  extern __shared__ float smem[];
+  const int zstride = 2 * K + ((K & 1) ? 0 : 2);
+  const int J = (K + 1) >> 1;
+  const int N2 = 2 * M;
+  const int NT = (N2 + 31) >> 5;
+  float* sD = smem;                                            // R * N2 floats, flat image of the W tile
+  float* sZ = sD + ((R * N2 + 3) & ~3);                        // R * zstride floats
+  float2* sB = reinterpret_cast<float2*>(sZ + R * zstride);    // J * NT * 64
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int col = lane & 31, half = lane >> 5;
+  stage_last_mode_factor<false>(sB, U, K, K, M, J, NT, tid, T);
+
+  const int64_t Iw = A * M;                                    // complex elements of W
+  const int64_t Iz = A * K;
+  const int tile_w = R * M, tile_z = R * K;
+  for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+    const int64_t w_base = tile * tile_w;                      // complex index of the tile in W
+    const int n_w = (int)((Iw - w_base) < tile_w ? (Iw - w_base) : tile_w);
+    const int64_t z_base = tile * tile_z;
+    const int n_z = (int)((Iz - z_base) < tile_z ? (Iz - z_base) : tile_z);
+    float4* w4 = reinterpret_cast<float4*>(w + 2 * w_base);    // 16-byte aligned: R * M is even
+    const int n4 = n_w >> 1;                                   // whole 16-byte pieces (2 complex each)
+    // ---- W pieces go in flight first; they are consumed after the MFMA phase ----
+    float4 wpre[kUpdPrefetch];
+#pragma unroll
+    for (int i = 0; i < kUpdPrefetch; ++i) {
+      const int q = tid + i * T;
+      wpre[i] = q < n4 ? w4[q] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    __syncthreads();                                           // previous tile's LDS fully consumed
+    // ---- stage z rows of the tile ----
+    {
+      const float2* z2 = reinterpret_cast<const float2*>(z) + z_base;
+      for (int e = tid; e < n_z; e += T) {
+        const uint32_t r = div_magic((uint32_t)e, magicK);
+        const uint32_t c = (uint32_t)e - r * (uint32_t)K;
+        *reinterpret_cast<float2*>(&sZ[r * zstride + 2 * c]) = z2[e];
+      }
+    }
+    __syncthreads();
+    // ---- expand 32 rows per wavefront: sD[row, c] = c_alpha * sum_k ... ----
+    {
+      const int lrow = wave * 32 + col;
+      const float* zrow = sZ + lrow * zstride;
+      const bool row_ok = (tile * R + lrow) < A;
+      for (int nt0 = 0; nt0 < NT; nt0 += NTB) {
+        v16f acc[NTB];
+#pragma unroll
+        for (int i = 0; i < NTB; ++i)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+        for (int j = 0; j < J; ++j) {
+          const int k = 2 * j + half;
+          float2 a2 = *reinterpret_cast<const float2*>(zrow + 2 * (k < K ? k : 0));
+          if (k >= K || !row_ok) a2 = make_float2(0.f, 0.f);
+#pragma unroll
+          for (int i = 0; i < NTB; ++i) {
+            if (nt0 + i < NT) {
+              const float2 b2 = sB[(j * NT + nt0 + i) * 64 + lane];
+              acc[i] = mfma32(a2.x, b2.x, acc[i]);
+              acc[i] = mfma32(a2.y, b2.y, acc[i]);
+            }
+          }
+        }
+#pragma unroll
+        for (int i = 0; i < NTB; ++i) {
+          if (nt0 + i < NT) {
+            const int c = 32 * (nt0 + i) + col;
+            if (c < N2) {
+#pragma unroll
+              for (int r = 0; r < 16; ++r) sD[(wave * 32 + d_row(r, half)) * N2 + c] = c_alpha * acc[i][r];
+            }
+          }
+        }
+      }
+    }
+    __syncthreads();
+    // ---- AdamUpdate on the sparse values that live in this tile; add lambda N_S into the tile ----
+    {
+      const uint32_t j0 = sp.tile_start[tile], j1 = sp.tile_start[tile + 1];
+      for (uint32_t j = j0 + tid; j < j1; j += T) {
+        const float2 x = sp.gs[j];
+        float2 mm = sp.ms[j];
+        mm.x = sp.beta1 * mm.x + (1.f - sp.beta1) * x.x;
+        mm.y = sp.beta1 * mm.y + (1.f - sp.beta1) * x.y;
+        const float vv = sp.beta2 * sp.vs[j] + (1.f - sp.beta2) * (x.x * x.x + x.y * x.y);
+        sp.ms[j] = mm;
+        sp.vs[j] = vv;
+        const float d = sp.c_lambda * sp.inv_c1 / (sqrtf(vv * sp.inv_c2) + sp.eps);
+        const int e = (int)((int64_t)sp.omega[j] - w_base);
+        sD[2 * e] += d * mm.x;
+        sD[2 * e + 1] += d * mm.y;
+      }
+    }
+    __syncthreads();
+    // ---- stream the tile into W ----
+    const float4* d4 = reinterpret_cast<const float4*>(sD);
+#pragma unroll
+    for (int i = 0; i < kUpdPrefetch; ++i) {
+      const int q = tid + i * T;
+      if (q < n4) {
+        const float4 d = d4[q];
+        const float4 o = wpre[i];
+        w4[q] = make_float4(decay * o.x + d.x, decay * o.y + d.y, decay * o.z + d.z, decay * o.w + d.w);
+      }
+    }
+    for (int q = tid + kUpdPrefetch * T; q < n4; q += T) {
+      const float4 d = d4[q];
+      const float4 o = w4[q];
+      w4[q] = make_float4(decay * o.x + d.x, decay * o.y + d.y, decay * o.z + d.z, decay * o.w + d.w);
+    }
+    if ((n_w & 1) && tid == 0) {                               // odd element count: last complex alone
+      float2* w2 = reinterpret_cast<float2*>(w) + w_base + (n_w - 1);
+      const float2 o = *w2;
+      *w2 = make_float2(decay * o.x + sD[2 * (n_w - 1)], decay * o.y + sD[2 * (n_w - 1) + 1]);
+    }
+  }
+}
+
+// tile_start[t] = #{ j : Omega_j < t * tile_elems }, t = 0 .. ntiles (Omega ascending).
+__global__ void k_tile_offsets(const int32_t* __restrict__ omega, int64_t k, int64_t tile_elems,
+                               int64_t ntiles, uint32_t* __restrict__ tile_start) {
+  const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (t > ntiles) return;
+  const int64_t target = t * tile_elems;
+  int64_t lo = 0, hi = k;                                      // first j in [0, k] with Omega_j >= target
+  while (lo < hi) {
+    const int64_t mid = (lo + hi) >> 1;
+    if ((int64_t)omega[mid] < target) lo = mid + 1; else hi = mid;
+  }
+  tile_start[t] = (uint32_t)lo;
+}
+
+inline uint32_t magic_for(int d) {
+  return d <= 1 ? 0u : (uint32_t)((0x100000000ull + (uint64_t)d - 1) / (uint64_t)d);
+}
+
+constexpr size_t kLdsLimit = 160 * 1024;
+
+template <typename Kern>
+bool allow_lds(Kern kern, size_t bytes) {
+  if (bytes <= 48 * 1024) return true;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                             (int)bytes) == hipSuccess;
+}
+
+int grid_for_tiles(int64_t ntiles, int blocks_per_cu) {
+  const int64_t cap = (int64_t)256 * blocks_per_cu;
+  return (int)(ntiles < cap ? ntiles : cap);
+}
+
+}  // namespace
+
+// ---- host side ---------------------------------------------------------------------------------
+
+size_t lproj_lds_bytes(int W, int K, int M) {
+  const int R = 32 * W, stride = 2 * K + ((K & 1) ? 0 : 2), J = (K + 1) / 2, NT = (2 * M + 31) / 32;
+  return (size_t)R * stride * 4 + (size_t)J * NT * 64 * 8;
+}
+
+size_t lupdate_lds_bytes(int W, int K, int M) {
+  const int R = 32 * W, zstride = 2 * K + ((K & 1) ? 0 : 2), J = (K + 1) / 2, NT = (2 * M + 31) / 32;
+  return (size_t)((R * 2 * M + 3) & ~3) * 4 + (size_t)R * zstride * 4 + (size_t)J * NT * 64 * 8;
+}
+
+// Rows per tile (32 * W) that both last-mode kernels can stage in LDS, or 0 if neither W fits.
+// `Klast` / `rlast` are the extent and the rank of the last mode.
+int choose_tile_waves(int Klast, int rlast, int prefer) {
+  const int cand[3] = {4, 2, 1};
+  for (int i = 0; i < 3; ++i) {
+    const int W = cand[i];
+    if (W > prefer) continue;
+    if (lproj_lds_bytes(W, Klast, rlast) <= kLdsLimit && lupdate_lds_bytes(W, rlast, Klast) <= kLdsLimit &&
+        (int64_t)32 * W * Klast < (1 << 17))
+      return W;
+  }
+  return 0;
+}
+
+void launch_tile_offsets(hipStream_t s, const int32_t* omega, int64_t k, int64_t tile_elems,
+                         int64_t ntiles, uint32_t* tile_start) {
+  const int64_t n = ntiles + 1;
+  k_tile_offsets<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(omega, k, tile_elems, ntiles,
+                                                                        tile_start);
+}
+
+void launch_mid(hipStream_t s, const float2* x, const float2* U, int rn, bool project, const Stage& st,
+                float2* out) {
+  const int64_t A = st.A, B = st.B;
+  const int K = st.K, M = st.M;
+  if (A * M * B <= 0) return;
+  const int vec = (B % 2 == 0) ? 2 : 1;
+  const int mt = M > 32 ? 2 : 1;
+  const int64_t ncv = A * (B / vec);
+  const int64_t gx = (ncv + 127) / 128;
+  const int gy = (M + 32 * mt - 1) / (32 * mt);
+  const int J = (K + 1) / 2;
+  const size_t lds = (size_t)(J < kMidJChunk ? J : kMidJChunk) * mt * 64 * 8;
+  dim3 grid((unsigned)gx, (unsigned)gy), block(kMidThreads);
+  const float* xf = reinterpret_cast<const float*>(x);
+  float* of = reinterpret_cast<float*>(out);
+#define TGRAD_MID(MT_, VEC_, P_)                                                          \
+  do {                                                                                    \
+    allow_lds(k_mid<MT_, VEC_, P_>, lds);                                                 \
+    k_mid<MT_, VEC_, P_><<<grid, block, lds, s>>>(xf, U, rn, A, K, M, B, of);             \
+  } while (0)
+  if (project) {
+    if (mt == 1) { if (vec == 2) TGRAD_MID(1, 2, true); else TGRAD_MID(1, 1, true); }
+    else         { if (vec == 2) TGRAD_MID(2, 2, true); else TGRAD_MID(2, 1, true); }
+  } else {
+    if (mt == 1) { if (vec == 2) TGRAD_MID(1, 2, false); else TGRAD_MID(1, 1, false); }
+    else         { if (vec == 2) TGRAD_MID(2, 2, false); else TGRAD_MID(2, 1, false); }
+  }
+#undef TGRAD_MID
+}
+
+void launch_lproj(hipStream_t s, const void* g, int dtype, const int32_t* omega, const uint32_t* tile_start,
+                  float2* gs, const float2* U, int rn, const Stage& st, int W, float2* out) {
+  const int64_t A = st.A;
+  const int K = st.K, M = st.M;
+  if (A * M <= 0) return;
+  const int R = 32 * W;
+  const int64_t ntiles = (A + R - 1) / R;
+  const size_t lds = lproj_lds_bytes(W, K, M);
+  const int NT = (2 * M + 31) / 32;
+  const int ntb = NT >= 4 ? 4 : NT >= 2 ? 2 : 1;
+  const int per_cu = (int)(kLdsLimit / (lds ? lds : 1));
+  dim3 grid((unsigned)grid_for_tiles(ntiles, per_cu < 1 ? 1 : per_cu > 8 ? 8 : per_cu)), block(64 * W);
+  float* of = reinterpret_cast<float*>(out);
+  const uint32_t magic = magic_for(K);
+#define TGRAD_LP(DT_, W_, NTB_)                                                                          \
+  do {                                                                                                   \
+    allow_lds(k_lproj<DT_, W_, NTB_>, lds);                                                              \
+    k_lproj<DT_, W_, NTB_><<<grid, block, lds, s>>>(g, omega, tile_start, gs, U, rn, A, K, M, magic,     \
+                                                    ntiles, of);                                         \
+  } while (0)
+#define TGRAD_LP_W(DT_, NTB_)                                                                            \
+  do {                                                                                                   \
+    if (W == 4) TGRAD_LP(DT_, 4, NTB_); else if (W == 2) TGRAD_LP(DT_, 2, NTB_); else TGRAD_LP(DT_, 1, NTB_); \
+  } while (0)
+  if (dtype == TGRAD_C64) {
+    if (ntb == 4) TGRAD_LP_W(TGRAD_C64, 4); else if (ntb == 2) TGRAD_LP_W(TGRAD_C64, 2); else TGRAD_LP_W(TGRAD_C64, 1);
+  } else {
+    if (ntb == 4) TGRAD_LP_W(TGRAD_CBF16, 4); else if (ntb == 2) TGRAD_LP_W(TGRAD_CBF16, 2); else TGRAD_LP_W(TGRAD_CBF16, 1);
+  }
+#undef TGRAD_LP_W
+#undef TGRAD_LP
+}
+
+void launch_lupdate(hipStream_t s, const float2* z, const float2* U, const Stage& st, int W, float2* w,
+                    float decay, float c_alpha, const int32_t* omega, const uint32_t* tile_start,
+                    const float2* gs, float2* ms, float* vs, float beta1, float beta2, float inv_c1,
+                    float inv_c2, float eps, float c_lambda) {
+  const int64_t A = st.A;
+  const int K = st.K, M = st.M;
+  if (A * M <= 0) return;
+  const int R = 32 * W;
+  const int64_t ntiles = (A + R - 1) / R;
+  const size_t lds = lupdate_lds_bytes(W, K, M);
+  const int per_cu = (int)(kLdsLimit / (lds ? lds : 1));
+  dim3 grid((unsigned)grid_for_tiles(ntiles, per_cu < 1 ? 1 : per_cu > 8 ? 8 : per_cu)), block(64 * W);
+  SparseAdam sp{omega, tile_start, gs, ms, vs, beta1, beta2, inv_c1, inv_c2, eps, c_lambda};
+  const float* zf = reinterpret_cast<const float*>(z);
+  float* wf = reinterpret_cast<float*>(w);
+  const uint32_t magic = magic_for(K);
+#define TGRAD_LU(W_)                                                                                     \
+  do {                                                                                                   \
+    allow_lds(k_lupdate<W_, 4>, lds);                                                                    \
+    k_lupdate<W_, 4><<<grid, block, lds, s>>>(zf, U, A, K, M, magic, ntiles, wf, decay, c_alpha, sp);    \
+  } while (0)
+  if (W == 4) TGRAD_LU(4); else if (W == 2) TGRAD_LU(2); else TGRAD_LU(1);
+#undef TGRAD_LU
+}
+
+}  // namespace tgrad

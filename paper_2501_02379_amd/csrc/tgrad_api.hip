@@ -25,7 +25,7 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 const char* const kKernelNames[KID_COUNT] = {
     "select_hist", "select_pick", "select_count", "select_scan", "select_emit", "mask_from_indices",
-    "gram", "gram_reduce", "eig_jacobi", "factor_pack",
+    "tile_offsets", "gram", "gram_reduce", "eig_jacobi", "factor_pack",
     "gather", "project_first", "project", "adam_core", "backproject", "update", "sparse_update"};
 
 struct Plan {
@@ -39,10 +39,13 @@ struct Plan {
   Stage back[kMaxNdim];          // back[s]: s-th reconstruction stage; expands mode s
   int64_t nseg = 0;
   int64_t mask_words = 0;
+  int tile_waves = 0;            // last-mode kernels: tiles of 32 * tile_waves rows; 0 = generic kernels
+  int64_t ntiles = 0;            // tiles of the tensor seen as (I / I_N rows, I_N)
+  int64_t tile_elems = 0;
   // byte offsets into state
   size_t st_omega, st_ms, st_vs, st_ml, st_vl, st_U[kMaxNdim], state_bytes;
   // byte offsets into workspace
-  size_t ws_sel, ws_hist, ws_seg_gt, ws_seg_eq, ws_mask, ws_partials, ws_gram[kMaxNdim],
+  size_t ws_sel, ws_hist, ws_seg_gt, ws_seg_eq, ws_mask, ws_tile_start, ws_partials, ws_gram[kMaxNdim],
       ws_eig_a[kMaxNdim], ws_eig_v[kMaxNdim], ws_gs, ws_core_g, ws_core_n, ws_buf[2], workspace_bytes;
   int gram_chunks[kMaxNdim];
 };
@@ -113,6 +116,16 @@ void make_plan(const tgrad_config* c, Plan* p) {
   }
   p->nseg = (p->I + kSegElems - 1) / kSegElems;
   p->mask_words = (p->I + 31) / 32;
+  {
+    int prefer = 2;
+    if (const char* e = std::getenv("TGRAD_TILE_WAVES")) prefer = std::atoi(e);   // tuning knob: 0, 1, 2, 4
+    const int last = N - 1;
+    p->tile_waves = prefer > 0 ? choose_tile_waves((int)p->shape[last], p->rank[last], prefer) : 0;
+    const int64_t rows = p->I / p->shape[last];
+    const int R = p->tile_waves > 0 ? 32 * p->tile_waves : 32;
+    p->ntiles = (rows + R - 1) / R;
+    p->tile_elems = (int64_t)R * p->shape[last];
+  }
 
   size_t o = 0;
   auto take = [&o](size_t bytes) {
@@ -134,6 +147,7 @@ void make_plan(const tgrad_config* c, Plan* p) {
   p->ws_seg_gt = take((size_t)p->nseg * 4);
   p->ws_seg_eq = take((size_t)p->nseg * 4);
   p->ws_mask = take((size_t)p->mask_words * 4);
+  p->ws_tile_start = take((size_t)(p->ntiles + 1) * 4);
   size_t partial_max = 0;
   for (int n = 0; n < N; ++n) {
     int64_t A = 1, B = 1;
@@ -262,6 +276,10 @@ int do_refresh(tgrad_ctx* c, const void* g) {
     { Scope sc_(c, KID_SEL_SCAN); launch_select_scan(s, seg_gt, seg_eq, p.nseg); }
     { Scope sc_(c, KID_SEL_EMIT); launch_select_emit(s, g, dt, p.I, sc, seg_gt, seg_eq, p.nseg, omega, mask); }
   }
+  {
+    Scope sc_(c, KID_TILE_OFFSETS);
+    launch_tile_offsets(s, omega, p.k, p.tile_elems, p.ntiles, c->w<uint32_t>(p.ws_tile_start));
+  }
   c->have_indices = true;
   const uint32_t* use_mask = p.k > 0 ? mask : nullptr;
 
@@ -314,21 +332,26 @@ int do_step(tgrad_ctx* c, void* weight, const void* g) {
   float2* core_n = c->w<float2>(p.ws_core_n);
   float2* buf[2] = {c->w<float2>(p.ws_buf[0]), c->w<float2>(p.ws_buf[1])};
 
-  // g_S <- Sparse(G, Omega)
-  { Scope sc_(c, KID_GATHER); launch_gather(s, g, cf.grad_dtype, omega, p.k, gs); }
+  const uint32_t* tile_start = c->w<uint32_t>(p.ws_tile_start);
+  const bool mfma_last = p.tile_waves > 0;
 
-  // g_L <- (G - g_S) x_N UN^H ... x_1 U1^H
-  const void* src = g;
-  int src_dt = cf.grad_dtype;
+  // g_S <- Sparse(G, Omega);  g_L <- (G - g_S) x_N UN^H ... x_1 U1^H
+  if (!mfma_last) { Scope sc_(c, KID_GATHER); launch_gather(s, g, cf.grad_dtype, omega, p.k, gs); }
+  const float2* src = nullptr;
   for (int st = 0; st < N; ++st) {
     const Stage& sg = p.proj[st];
     float2* dst = (st == N - 1) ? core_g : buf[st & 1];
     const float2* U = c->st<float2>(p.st_U[sg.mode]);
     Scope sc_(c, st == 0 ? KID_PROJECT_FIRST : KID_PROJECT);
-    launch_contract(s, src, src_dt, st == 0 ? mask : nullptr, U, (int)p.shape[sg.mode], p.rank[sg.mode],
-                    true, sg, dst);
+    if (st == 0) {
+      if (mfma_last)
+        launch_lproj(s, g, cf.grad_dtype, omega, tile_start, gs, U, p.rank[sg.mode], sg, p.tile_waves, dst);
+      else
+        launch_contract(s, g, cf.grad_dtype, mask, U, (int)p.shape[sg.mode], p.rank[sg.mode], true, sg, dst);
+    } else {
+      launch_mid(s, src, U, p.rank[sg.mode], true, sg, dst);
+    }
     src = dst;
-    src_dt = TGRAD_C64;
   }
 
   // AdamUpdate on the core; tau = t + 1
@@ -341,30 +364,37 @@ int do_step(tgrad_ctx* c, void* weight, const void* g) {
                      cf.beta2, inv_c1, inv_c2, cf.eps);
   }
 
-  // D <- alpha (N_L x_1 U1 ... x_N UN), the last stage fused with W <- W (1 - lr wd) - lr D
+  // D <- alpha (N_L x_1 U1 ... x_N UN); the last stage is fused with AdamUpdate on the sparse values,
+  // D[Omega] += lambda N_S and W <- W (1 - lr wd) - lr D
   const float2* zsrc = core_n;
   for (int st = 0; st + 1 < N; ++st) {
     const Stage& sg = p.back[st];
     float2* dst = buf[st & 1];
     const float2* U = c->st<float2>(p.st_U[sg.mode]);
     Scope sc_(c, KID_BACKPROJECT);
-    launch_contract(s, zsrc, TGRAD_C64, nullptr, U, (int)p.shape[sg.mode], p.rank[sg.mode], false, sg, dst);
+    launch_mid(s, zsrc, U, p.rank[sg.mode], false, sg, dst);
     zsrc = dst;
   }
   {
     const Stage& sg = p.back[N - 1];
     const float2* U = c->st<float2>(p.st_U[sg.mode]);
     const float decay = 1.f - cf.lr * cf.weight_decay;
-    Scope sc_(c, KID_UPDATE);
-    launch_update(s, zsrc, U, (int)p.shape[sg.mode], p.rank[sg.mode], sg, reinterpret_cast<float2*>(weight),
-                  decay, -cf.lr * cf.alpha);
-  }
-  // AdamUpdate on the sparse values; W[Omega] += -lr lambda N_S
-  {
-    Scope sc_(c, KID_SPARSE_UPDATE);
-    launch_sparse_update(s, gs, omega, p.k, c->st<float2>(p.st_ms), c->st<float>(p.st_vs),
-                         reinterpret_cast<float2*>(weight), cf.beta1, cf.beta2, inv_c1, inv_c2, cf.eps,
-                         -cf.lr * cf.lambda);
+    if (mfma_last) {
+      Scope sc_(c, KID_UPDATE);
+      launch_lupdate(s, zsrc, U, sg, p.tile_waves, reinterpret_cast<float2*>(weight), decay, -cf.lr * cf.alpha,
+                     omega, tile_start, gs, c->st<float2>(p.st_ms), c->st<float>(p.st_vs), cf.beta1, cf.beta2,
+                     inv_c1, inv_c2, cf.eps, -cf.lr * cf.lambda);
+    } else {
+      {
+        Scope sc_(c, KID_UPDATE);
+        launch_update(s, zsrc, U, (int)p.shape[sg.mode], p.rank[sg.mode], sg, reinterpret_cast<float2*>(weight),
+                      decay, -cf.lr * cf.alpha);
+      }
+      Scope sc_(c, KID_SPARSE_UPDATE);
+      launch_sparse_update(s, gs, omega, p.k, c->st<float2>(p.st_ms), c->st<float>(p.st_vs),
+                           reinterpret_cast<float2*>(weight), cf.beta1, cf.beta2, inv_c1, inv_c2, cf.eps,
+                           -cf.lr * cf.lambda);
+    }
   }
   c->t += 1;
   return check_launch();
@@ -534,6 +564,11 @@ int tgrad_set_state(tgrad_ctx* ctx, int what, const void* host_in, size_t bytes)
       Scope sc_(ctx, KID_MASK_FROM_IDX);
       launch_mask_from_indices(ctx->stream, ctx->st<int32_t>(p.st_omega), p.k, ctx->w<uint32_t>(p.ws_mask),
                                p.mask_words);
+    }
+    {
+      Scope sc_(ctx, KID_TILE_OFFSETS);
+      launch_tile_offsets(ctx->stream, ctx->st<int32_t>(p.st_omega), p.k, p.tile_elems, p.ntiles,
+                          ctx->w<uint32_t>(p.ws_tile_start));
     }
     if (hipStreamSynchronize(ctx->stream) != hipSuccess) return TGRAD_ERR_HIP;
     ctx->have_indices = true;

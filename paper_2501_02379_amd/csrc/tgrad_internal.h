@@ -35,7 +35,7 @@ struct Stage {
 // Names of the profiled kernels (index into the per-context timing table).
 enum KernelId {
   KID_SEL_HIST = 0, KID_SEL_PICK, KID_SEL_COUNT, KID_SEL_SCAN, KID_SEL_EMIT, KID_MASK_FROM_IDX,
-  KID_GRAM, KID_GRAM_REDUCE, KID_EIG, KID_FACTOR_PACK,
+  KID_TILE_OFFSETS, KID_GRAM, KID_GRAM_REDUCE, KID_EIG, KID_FACTOR_PACK,
   KID_GATHER, KID_PROJECT_FIRST, KID_PROJECT, KID_ADAM_CORE, KID_BACKPROJECT, KID_UPDATE,
   KID_SPARSE_UPDATE, KID_COUNT
 };
@@ -77,5 +77,18 @@ void launch_update(hipStream_t s, const float2* z, const float2* U, int In, int 
 void launch_sparse_update(hipStream_t s, const float2* gs, const int32_t* omega, int64_t k,
                           float2* m, float* v, float2* w, float beta1, float beta2, float inv_c1,
                           float inv_c2, float eps, float neg_lr_lambda);
+
+// matrix-core kernels of the step (contract_mfma.hip)
+int choose_tile_waves(int Klast, int rlast, int prefer);
+void launch_tile_offsets(hipStream_t s, const int32_t* omega, int64_t k, int64_t tile_elems,
+                         int64_t ntiles, uint32_t* tile_start);
+void launch_mid(hipStream_t s, const float2* x, const float2* U, int rn, bool project, const Stage& st,
+                float2* out);
+void launch_lproj(hipStream_t s, const void* g, int dtype, const int32_t* omega, const uint32_t* tile_start,
+                  float2* gs, const float2* U, int rn, const Stage& st, int W, float2* out);
+void launch_lupdate(hipStream_t s, const float2* z, const float2* U, const Stage& st, int W, float2* w,
+                    float decay, float c_alpha, const int32_t* omega, const uint32_t* tile_start,
+                    const float2* gs, float2* ms, float* vs, float beta1, float beta2, float inv_c1,
+                    float inv_c2, float eps, float c_lambda);
 
 }  // namespace tgrad
