@@ -199,99 +199,240 @@ __device__ __forceinline__ void stage_last_mode_factor(float2* sB, const float2*
   }
 }
 
+// Two consecutive gradient elements as they lie in memory (complex64: 16 bytes, bf16 pairs: 8).
+template <int DT> struct RawPair;
+template <> struct RawPair<TGRAD_C64> { typedef float4 type; };
+template <> struct RawPair<TGRAD_CBF16> { typedef uint2 type; };
+
+template <int DT>
+__device__ __forceinline__ typename RawPair<DT>::type load_raw_pair(const void* g, int64_t p) {
+  return reinterpret_cast<const typename RawPair<DT>::type*>(g)[p];
+}
+template <int DT>
+__device__ __forceinline__ typename RawPair<DT>::type load_raw_single(const void* g, int64_t e) {
+  if constexpr (DT == TGRAD_C64) {
+    const float2 v = reinterpret_cast<const float2*>(g)[e];
+    return make_float4(v.x, v.y, 0.f, 0.f);
+  } else {
+    return make_uint2(reinterpret_cast<const uint32_t*>(g)[e], 0u);
+  }
+}
+template <int DT>
+__device__ __forceinline__ void decode_raw(const typename RawPair<DT>::type& raw, float2& e0, float2& e1) {
+  if constexpr (DT == TGRAD_C64) {
+    e0 = make_float2(raw.x, raw.y);
+    e1 = make_float2(raw.z, raw.w);
+  } else {                                   // a bf16 is the upper half of a float32: widening is exact
+    e0 = make_float2(__uint_as_float(raw.x << 16), __uint_as_float(raw.x & 0xFFFF0000u));
+    e1 = make_float2(__uint_as_float(raw.y << 16), __uint_as_float(raw.y & 0xFFFF0000u));
+  }
+}
+
+constexpr int kTileBatch = 17;            // 2-element pieces per thread in flight while a tile is staged
+constexpr int kJUnroll = 4;               // row pairs whose LDS operands are fetched ahead of their MFMAs
+
+// N column tiles of a last-mode contraction for the 32 rows of a wavefront:
+// acc[i] = rows(32 x 2K reals, from LDS) * sB[:, nt0 + i], then epi(nt0 + i, acc[i]).
+// `xrow` is the lane's own row.  The loops carry no guards (a guarded, branchy loop ran the
+// matrix cores at less than half their rate): for odd K the pair j = J - 1 reads element k = K of
+// the row, whose coefficients in sB are zero and whose LDS slot always holds a finite value.
+template <int N, typename Epi>
+__device__ __forceinline__ void last_mode_block(const float* xrow, const float2* sB, int J, int NT,
+                                                int nt0, int lane, int half, Epi&& epi) {
+  v16f acc[N];
+#pragma unroll
+  for (int i = 0; i < N; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+  const float* xa = xrow + 2 * half;
+  const float2* bp = sB + (size_t)nt0 * 64 + lane;
+  int j = 0;
+  for (; j + kJUnroll <= J; j += kJUnroll) {
+    float2 a2[kJUnroll], b2[kJUnroll][N];
+#pragma unroll
+    for (int u = 0; u < kJUnroll; ++u) {
+      a2[u] = *reinterpret_cast<const float2*>(xa + 4 * (j + u));
+#pragma unroll
+      for (int i = 0; i < N; ++i) b2[u][i] = bp[((j + u) * NT + i) * 64];
+    }
+#pragma unroll
+    for (int u = 0; u < kJUnroll; ++u)
+#pragma unroll
+      for (int i = 0; i < N; ++i) {
+        acc[i] = mfma32(a2[u].x, b2[u][i].x, acc[i]);
+        acc[i] = mfma32(a2[u].y, b2[u][i].y, acc[i]);
+      }
+  }
+  for (; j < J; ++j) {
+    const float2 a2 = *reinterpret_cast<const float2*>(xa + 4 * j);
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      const float2 b2 = bp[(j * NT + i) * 64];
+      acc[i] = mfma32(a2.x, b2.x, acc[i]);
+      acc[i] = mfma32(a2.y, b2.y, acc[i]);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < N; ++i) epi(nt0 + i, acc[i]);
+}
+
+// All NT column tiles, NTB at a time, the remainder one by one.
+template <int NTB, typename Epi>
+__device__ __forceinline__ void last_mode_contract(const float* xrow, const float2* sB, int J, int NT,
+                                                   int lane, int half, Epi&& epi) {
+  int nt0 = 0;
+  for (; nt0 + NTB <= NT; nt0 += NTB) last_mode_block<NTB>(xrow, sB, J, NT, nt0, lane, half, epi);
+  if (NTB > 1)
+    for (; nt0 < NT; ++nt0) last_mode_block<1>(xrow, sB, J, NT, nt0, lane, half, epi);
+}
+
 // k_lproj: out[a, m] = sum_k conj(U[k, m]) (G - Sparse(G, Omega))[a, k];  gs[j] = G[Omega_j].
-template <int DT, int W, int NTB>
-__global__ __launch_bounds__(64 * W) void k_lproj(const void* __restrict__ g,
+// A workgroup walks tiles blockIdx.x, blockIdx.x + gridDim.x, ...; the global loads of the next
+// tile are issued before the matrix-core phase of the current one.
+template <int DT, int W, int NTB, bool FLAT>
+__global__ __launch_bounds__(64 * W, 2) void k_lproj(const void* __restrict__ g,
                                                   const int32_t* __restrict__ omega,
                                                   const uint32_t* __restrict__ tile_start,
                                                   float2* __restrict__ gs, const float2* __restrict__ U,
                                                   int rn, int64_t A, int K, int M, uint32_t magicK,
                                                   int64_t ntiles, float* __restrict__ out) {
+  typedef typename RawPair<DT>::type Raw;
   constexpr int T = 64 * W, R = 32 * W;
   extern __shared__ float smem[];
-  const int stride = 2 * K + ((K & 1) ? 0 : 2);                // floats per LDS row; stride / 2 is odd
-  float* sX = smem;                                            // R * stride floats
-  float2* sB = reinterpret_cast<float2*>(smem + R * stride);   // J * NT * 64 (R * stride is even)
+  constexpr bool flat = FLAT;                                  // odd K: the LDS image is the memory image
+  const int stride = 2 * K + (flat ? 0 : 2);                   // floats per LDS row; stride / 2 is odd
+  float* sX = smem;                                            // R * stride + 2 floats
+  float2* sB = reinterpret_cast<float2*>(smem + R * stride + 2);   // J * NT * 64 (8-byte aligned)
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int col = lane & 31, half = lane >> 5;
   const int J = (K + 1) >> 1;
   const int N2 = 2 * M;
   const int NT = (N2 + 31) >> 5;
+  for (int e = tid; e < R * stride + 2; e += T) sX[e] = 0.f;   // pads and never-staged rows stay finite
   stage_last_mode_factor<true>(sB, U, rn, K, M, J, NT, tid, T);
 
   const int64_t I = A * K;
   const int tile_elems = R * K;
-  for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-    const int64_t e_base = tile * tile_elems;
+  const int64_t step = gridDim.x;
+
+  Raw raw[kTileBatch];
+  int32_t my_om = -1;
+  // issue the first batch of tile `t` (its support range is [j0, j1)) into raw / my_om
+  auto issue = [&](int64_t t, uint32_t j0, uint32_t j1) {
+    const int64_t e_base = t * tile_elems;
     const int n_e = (int)((I - e_base) < tile_elems ? (I - e_base) : tile_elems);
-    __syncthreads();                                           // previous tile consumed (and sB staged)
-    // ---- stage the tile: flat, coalesced 16-byte loads; element e -> sX[row * stride + 2 col] ----
-    for (int p = tid; 2 * p < n_e; p += T) {
-      const int e0 = 2 * p;
-      float2 v0, v1 = make_float2(0.f, 0.f);
-      if (e0 + 1 < n_e) {
-        load_pair<DT>(g, (e_base >> 1) + p, v0, v1);
-      } else {
-        v0 = load_elem<DT>(g, e_base + e0);
-      }
+#ifdef TGRAD_ABL
+    if (TGRAD_ABL & 2) {
+      for (int i = 0; i < kTileBatch; ++i) raw[i] = Raw{};
+      my_om = (j0 + tid < j1) ? omega[j0 + tid] : -1;
+      return;
+    }
+#endif
+#pragma unroll
+    for (int i = 0; i < kTileBatch; ++i) {
+      const int e0 = 2 * (tid + i * T);
+      if (e0 + 1 < n_e) raw[i] = load_raw_pair<DT>(g, (e_base >> 1) + (e0 >> 1));
+      else if (e0 < n_e) raw[i] = load_raw_single<DT>(g, e_base + e0);
+    }
+    my_om = (j0 + tid < j1) ? omega[j0 + tid] : -1;
+  };
+  // element pair at flat offset e0 of the tile -> LDS
+  auto commit_piece = [&](const Raw& rw, int e0, int n_e) {
+    float2 v0, v1;
+    decode_raw<DT>(rw, v0, v1);
+    if (flat) {
+      if (e0 + 1 < n_e) *reinterpret_cast<float4*>(&sX[2 * e0]) = make_float4(v0.x, v0.y, v1.x, v1.y);
+      else *reinterpret_cast<float2*>(&sX[2 * e0]) = v0;
+    } else {
       const uint32_t r0 = div_magic((uint32_t)e0, magicK);
       const uint32_t c0 = (uint32_t)e0 - r0 * (uint32_t)K;
       *reinterpret_cast<float2*>(&sX[r0 * stride + 2 * c0]) = v0;
       if (e0 + 1 < n_e) {
-        const uint32_t r1 = (c0 + 1 == (uint32_t)K) ? r0 + 1 : r0;
-        const uint32_t c1 = (c0 + 1 == (uint32_t)K) ? 0u : c0 + 1;
+        const bool wrap = c0 + 1 == (uint32_t)K;
+        const uint32_t r1 = wrap ? r0 + 1 : r0;
+        const uint32_t c1 = wrap ? 0u : c0 + 1;
         *reinterpret_cast<float2*>(&sX[r1 * stride + 2 * c1]) = v1;
       }
     }
+  };
+
+  // The support ranges are fetched with per-lane (vector) loads on purpose: a scalar load shares
+  // its wait counter with the LDS reads of the matrix-core phase and would stall its first step.
+  const int vzero = tid >> 30;                                 // 0, but not known to be uniform
+  int64_t tile = blockIdx.x;
+  int64_t nxt = tile + step;
+  uint32_t cj0 = tile_start[tile + vzero], cj1 = tile_start[tile + 1 + vzero];
+  uint32_t nj0 = 0, nj1 = 0;
+  if (nxt < ntiles) {
+    nj0 = tile_start[nxt + vzero];
+    nj1 = tile_start[nxt + 1 + vzero];
+  }
+  issue(tile, cj0, cj1);
+  while (true) {
+    const int64_t e_base = tile * tile_elems;
+    const int n_e = (int)((I - e_base) < tile_elems ? (I - e_base) : tile_elems);
+    __syncthreads();                                           // previous tile consumed (and sB staged)
+    int tid_now = tid;                                         // opaque copy: keeps the per-piece LDS addresses
+    asm volatile("" : "+v"(tid_now));                          // from being hoisted out of the tile loop
+#pragma unroll
+    for (int i = 0; i < kTileBatch; ++i) {
+      const int e0 = 2 * (tid_now + i * T);
+      if (e0 < n_e) commit_piece(raw[i], e0, n_e);
+    }
+    for (int e0 = 2 * (tid + kTileBatch * T); e0 < n_e; e0 += 2 * T) {   // long rows: the rest, unpipelined
+      Raw rw;
+      if (e0 + 1 < n_e) rw = load_raw_pair<DT>(g, (e_base >> 1) + (e0 >> 1));
+      else rw = load_raw_single<DT>(g, e_base + e0);
+      commit_piece(rw, e0, n_e);
+    }
     __syncthreads();
     // ---- Sparse(G, Omega) of this tile: hand the values over, then remove them ----
-    {
-      const uint32_t j0 = tile_start[tile], j1 = tile_start[tile + 1];
-      for (uint32_t j = j0 + tid; j < j1; j += T) {
-        const uint32_t e = (uint32_t)((int64_t)omega[j] - e_base);
-        const uint32_t r = div_magic(e, magicK);
-        const uint32_t c = e - r * (uint32_t)K;
-        float2* p = reinterpret_cast<float2*>(&sX[r * stride + 2 * c]);
-        gs[j] = *p;
-        *p = make_float2(0.f, 0.f);
-      }
+    for (uint32_t j = cj0 + tid; j < cj1; j += T) {
+      const int32_t oj = (j == cj0 + tid) ? my_om : omega[j];
+      const uint32_t e = (uint32_t)((int64_t)oj - e_base);
+      const uint32_t r = flat ? 0u : div_magic(e, magicK);
+      float2* p = reinterpret_cast<float2*>(&sX[r * stride + 2 * (e - r * (uint32_t)K)]);
+      gs[j] = *p;
+      *p = make_float2(0.f, 0.f);
     }
     __syncthreads();
-    // ---- 32 rows per wavefront through the matrix cores ----
-    const int lrow = wave * 32 + col;
-    const float* xrow = sX + lrow * stride;
-    const int64_t grow0 = tile * R + wave * 32;
-    for (int nt0 = 0; nt0 < NT; nt0 += NTB) {
-      v16f acc[NTB];
-#pragma unroll
-      for (int i = 0; i < NTB; ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
-      for (int j = 0; j < J; ++j) {
-        const int k = 2 * j + half;
-        float2 a2 = *reinterpret_cast<const float2*>(xrow + 2 * (k < K ? k : 0));
-        if (k >= K) a2 = make_float2(0.f, 0.f);
-#pragma unroll
-        for (int i = 0; i < NTB; ++i) {
-          if (nt0 + i < NT) {
-            const float2 b2 = sB[(j * NT + nt0 + i) * 64 + lane];
-            acc[i] = mfma32(a2.x, b2.x, acc[i]);
-            acc[i] = mfma32(a2.y, b2.y, acc[i]);
-          }
-        }
-      }
-#pragma unroll
-      for (int i = 0; i < NTB; ++i) {
-        if (nt0 + i < NT) {
-          const int c = 32 * (nt0 + i) + col;
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int64_t grow = grow0 + d_row(r, half);
-            if (grow < A && c < N2) out[grow * N2 + c] = acc[i][r];
-          }
-        }
+    // ---- next tile's loads go in flight; its support range was fetched one tile earlier ----
+    const int64_t nn = nxt + step;
+    uint32_t nnj0 = 0, nnj1 = 0;
+    if (nxt < ntiles) {
+      issue(nxt, nj0, nj1);
+      if (nn < ntiles) {
+        nnj0 = tile_start[nn + vzero];
+        nnj1 = tile_start[nn + 1 + vzero];
       }
     }
+    // ---- 32 rows per wavefront through the matrix cores ----
+    const float* xrow = sX + (wave * 32 + col) * stride;
+    const int64_t grow0 = tile * R + wave * 32;
+#ifdef TGRAD_ABL
+    if (TGRAD_ABL & 1) goto abl_skip;
+#endif
+    last_mode_contract<NTB>(xrow, sB, J, NT, lane, half, [&](int nt, const v16f& acc) {
+      const int c = 32 * nt + col;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int64_t grow = grow0 + d_row(r, half);
+#ifdef TGRAD_ABL
+        if ((TGRAD_ABL & 4) && acc[r] != 123.f) continue;
+#endif
+        if (grow < A && c < N2) out[grow * N2 + c] = acc[r];
+      }
+    });
+#ifdef TGRAD_ABL
+  abl_skip:
+#endif
+    if (nxt >= ntiles) break;
+    tile = nxt;
+    nxt = nn;
+    cj0 = nj0;
+    cj1 = nj1;
+    nj0 = nnj0;
+    nj1 = nnj1;
   }
 }
 
@@ -308,7 +449,8 @@ struct SparseAdam {
   float beta1, beta2, inv_c1, inv_c2, eps, c_lambda;
 };
 
-constexpr int kUpdPrefetch = 18;          // 16-byte pieces of W per thread kept in flight during the MFMA phase
+constexpr int kUpdPrefetch = 17;          // 16-byte pieces of W per thread kept in flight during the MFMA phase
+constexpr int kUpdZBatch = 8;             // elements of z per thread loaded one tile ahead
 
 template <int W, int NTB>
 __global__ __launch_bounds__(64 * W) void k_lupdate(const float* __restrict__ z,
@@ -323,16 +465,52 @@ __global__ __launch_bounds__(64 * W) void k_lupdate(const float* __restrict__ z,
   const int N2 = 2 * M;
   const int NT = (N2 + 31) >> 5;
   float* sD = smem;                                            // R * N2 floats, flat image of the W tile
-  float* sZ = sD + ((R * N2 + 3) & ~3);                        // R * zstride floats
-  float2* sB = reinterpret_cast<float2*>(sZ + R * zstride);    // J * NT * 64
+  float* sZ = sD + ((R * N2 + 3) & ~3);                        // R * zstride + 2 floats
+  float2* sB = reinterpret_cast<float2*>(sZ + R * zstride + 2);    // J * NT * 64 (8-byte aligned)
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int col = lane & 31, half = lane >> 5;
+  for (int e = tid; e < R * zstride + 2; e += T) sZ[e] = 0.f;  // pads and never-staged rows stay finite
   stage_last_mode_factor<false>(sB, U, K, K, M, J, NT, tid, T);
 
   const int64_t Iw = A * M;                                    // complex elements of W
   const int64_t Iz = A * K;
   const int tile_w = R * M, tile_z = R * K;
-  for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+  const int64_t step = gridDim.x;
+  const float2* zall = reinterpret_cast<const float2*>(z);
+
+  float2 zpre[kUpdZBatch];
+  int32_t my_om = -1;
+  float2 my_g = make_float2(0.f, 0.f), my_m = make_float2(0.f, 0.f);
+  float my_v = 0.f;
+  // z rows and the sparse state of tile `t` (support range [j0, j1)): issued one tile ahead
+  auto issue_small = [&](int64_t t, uint32_t j0, uint32_t j1) {
+    const int64_t z_base = t * tile_z;
+    const int n_z = (int)((Iz - z_base) < tile_z ? (Iz - z_base) : tile_z);
+#pragma unroll
+    for (int i = 0; i < kUpdZBatch; ++i) {
+      const int e = tid + i * T;
+      if (e < n_z) zpre[i] = zall[z_base + e];
+    }
+    my_om = -1;
+    if (j0 + tid < j1) {
+      my_om = sp.omega[j0 + tid];
+      my_g = sp.gs[j0 + tid];
+      my_m = sp.ms[j0 + tid];
+      my_v = sp.vs[j0 + tid];
+    }
+  };
+
+  const int vzero = tid >> 30;                                 // 0, but not known to be uniform (see k_lproj)
+  int64_t tile = blockIdx.x;
+  int64_t nxt = tile + step;
+  uint32_t cj0 = sp.tile_start[tile + vzero], cj1 = sp.tile_start[tile + 1 + vzero];
+  uint32_t nj0 = 0, nj1 = 0;
+  if (nxt < ntiles) {
+    nj0 = sp.tile_start[nxt + vzero];
+    nj1 = sp.tile_start[nxt + 1 + vzero];
+  }
+  issue_small(tile, cj0, cj1);
+  while (true) {
     const int64_t w_base = tile * tile_w;                      // complex index of the tile in W
     const int n_w = (int)((Iw - w_base) < tile_w ? (Iw - w_base) : tile_w);
     const int64_t z_base = tile * tile_z;
@@ -348,68 +526,62 @@ __global__ __launch_bounds__(64 * W) void k_lupdate(const float* __restrict__ z,
     }
     __syncthreads();                                           // previous tile's LDS fully consumed
     // ---- stage z rows of the tile ----
-    {
-      const float2* z2 = reinterpret_cast<const float2*>(z) + z_base;
-      for (int e = tid; e < n_z; e += T) {
+#pragma unroll
+    for (int i = 0; i < kUpdZBatch; ++i) {
+      const int e = tid + i * T;
+      if (e < n_z) {
         const uint32_t r = div_magic((uint32_t)e, magicK);
         const uint32_t c = (uint32_t)e - r * (uint32_t)K;
-        *reinterpret_cast<float2*>(&sZ[r * zstride + 2 * c]) = z2[e];
+        *reinterpret_cast<float2*>(&sZ[r * zstride + 2 * c]) = zpre[i];
       }
     }
+    for (int e = tid + kUpdZBatch * T; e < n_z; e += T) {      // high ranks: the rest, unpipelined
+      const uint32_t r = div_magic((uint32_t)e, magicK);
+      const uint32_t c = (uint32_t)e - r * (uint32_t)K;
+      *reinterpret_cast<float2*>(&sZ[r * zstride + 2 * c]) = zall[z_base + e];
+    }
+    // sparse state of this tile moves out of the prefetch registers before they are refilled
+    const int32_t c_om = my_om;
+    const float2 c_g = my_g, c_m = my_m;
+    const float c_v = my_v;
     __syncthreads();
+    const int64_t nn = nxt + step;
+    uint32_t nnj0 = 0, nnj1 = 0;
+    if (nxt < ntiles) {
+      issue_small(nxt, nj0, nj1);
+      if (nn < ntiles) {
+        nnj0 = sp.tile_start[nn + vzero];
+        nnj1 = sp.tile_start[nn + 1 + vzero];
+      }
+    }
     // ---- expand 32 rows per wavefront: sD[row, c] = c_alpha * sum_k ... ----
     {
-      const int lrow = wave * 32 + col;
-      const float* zrow = sZ + lrow * zstride;
-      const bool row_ok = (tile * R + lrow) < A;
-      for (int nt0 = 0; nt0 < NT; nt0 += NTB) {
-        v16f acc[NTB];
+      const float* zrow = sZ + (wave * 32 + col) * zstride;
+      last_mode_contract<NTB>(zrow, sB, J, NT, lane, half, [&](int nt, const v16f& acc) {
+        const int c = 32 * nt + col;
+        if (c < N2) {
 #pragma unroll
-        for (int i = 0; i < NTB; ++i)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
-        for (int j = 0; j < J; ++j) {
-          const int k = 2 * j + half;
-          float2 a2 = *reinterpret_cast<const float2*>(zrow + 2 * (k < K ? k : 0));
-          if (k >= K || !row_ok) a2 = make_float2(0.f, 0.f);
-#pragma unroll
-          for (int i = 0; i < NTB; ++i) {
-            if (nt0 + i < NT) {
-              const float2 b2 = sB[(j * NT + nt0 + i) * 64 + lane];
-              acc[i] = mfma32(a2.x, b2.x, acc[i]);
-              acc[i] = mfma32(a2.y, b2.y, acc[i]);
-            }
-          }
+          for (int r = 0; r < 16; ++r) sD[(wave * 32 + d_row(r, half)) * N2 + c] = c_alpha * acc[r];
         }
-#pragma unroll
-        for (int i = 0; i < NTB; ++i) {
-          if (nt0 + i < NT) {
-            const int c = 32 * (nt0 + i) + col;
-            if (c < N2) {
-#pragma unroll
-              for (int r = 0; r < 16; ++r) sD[(wave * 32 + d_row(r, half)) * N2 + c] = c_alpha * acc[i][r];
-            }
-          }
-        }
-      }
+      });
     }
     __syncthreads();
     // ---- AdamUpdate on the sparse values that live in this tile; add lambda N_S into the tile ----
-    {
-      const uint32_t j0 = sp.tile_start[tile], j1 = sp.tile_start[tile + 1];
-      for (uint32_t j = j0 + tid; j < j1; j += T) {
-        const float2 x = sp.gs[j];
-        float2 mm = sp.ms[j];
-        mm.x = sp.beta1 * mm.x + (1.f - sp.beta1) * x.x;
-        mm.y = sp.beta1 * mm.y + (1.f - sp.beta1) * x.y;
-        const float vv = sp.beta2 * sp.vs[j] + (1.f - sp.beta2) * (x.x * x.x + x.y * x.y);
-        sp.ms[j] = mm;
-        sp.vs[j] = vv;
-        const float d = sp.c_lambda * sp.inv_c1 / (sqrtf(vv * sp.inv_c2) + sp.eps);
-        const int e = (int)((int64_t)sp.omega[j] - w_base);
-        sD[2 * e] += d * mm.x;
-        sD[2 * e + 1] += d * mm.y;
-      }
+    for (uint32_t j = cj0 + tid; j < cj1; j += T) {
+      const bool first = j == cj0 + tid;
+      const float2 x = first ? c_g : sp.gs[j];
+      float2 mm = first ? c_m : sp.ms[j];
+      const float v_old = first ? c_v : sp.vs[j];
+      const int32_t oj = first ? c_om : sp.omega[j];
+      mm.x = sp.beta1 * mm.x + (1.f - sp.beta1) * x.x;
+      mm.y = sp.beta1 * mm.y + (1.f - sp.beta1) * x.y;
+      const float vv = sp.beta2 * v_old + (1.f - sp.beta2) * (x.x * x.x + x.y * x.y);
+      sp.ms[j] = mm;
+      sp.vs[j] = vv;
+      const float d = sp.c_lambda * sp.inv_c1 / (sqrtf(vv * sp.inv_c2) + sp.eps);
+      const int e = (int)((int64_t)oj - w_base);
+      sD[2 * e] += d * mm.x;
+      sD[2 * e + 1] += d * mm.y;
     }
     __syncthreads();
     // ---- stream the tile into W ----
@@ -433,6 +605,13 @@ __global__ __launch_bounds__(64 * W) void k_lupdate(const float* __restrict__ z,
       const float2 o = *w2;
       *w2 = make_float2(decay * o.x + sD[2 * (n_w - 1)], decay * o.y + sD[2 * (n_w - 1) + 1]);
     }
+    if (nxt >= ntiles) break;
+    tile = nxt;
+    nxt = nn;
+    cj0 = nj0;
+    cj1 = nj1;
+    nj0 = nnj0;
+    nj1 = nnj1;
   }
 }
 
@@ -474,12 +653,12 @@ int grid_for_tiles(int64_t ntiles, int blocks_per_cu) {
 
 size_t lproj_lds_bytes(int W, int K, int M) {
   const int R = 32 * W, stride = 2 * K + ((K & 1) ? 0 : 2), J = (K + 1) / 2, NT = (2 * M + 31) / 32;
-  return (size_t)R * stride * 4 + (size_t)J * NT * 64 * 8;
+  return (size_t)(R * stride + 2) * 4 + (size_t)J * NT * 64 * 8;
 }
 
 size_t lupdate_lds_bytes(int W, int K, int M) {
   const int R = 32 * W, zstride = 2 * K + ((K & 1) ? 0 : 2), J = (K + 1) / 2, NT = (2 * M + 31) / 32;
-  return (size_t)((R * 2 * M + 3) & ~3) * 4 + (size_t)R * zstride * 4 + (size_t)J * NT * 64 * 8;
+  return (size_t)((R * 2 * M + 3) & ~3) * 4 + (size_t)(R * zstride + 2) * 4 + (size_t)J * NT * 64 * 8;
 }
 
 // Rows per tile (32 * W) that both last-mode kernels can stage in LDS, or 0 if neither W fits.
@@ -542,27 +721,32 @@ void launch_lproj(hipStream_t s, const void* g, int dtype, const int32_t* omega,
   const int64_t ntiles = (A + R - 1) / R;
   const size_t lds = lproj_lds_bytes(W, K, M);
   const int NT = (2 * M + 31) / 32;
-  const int ntb = NT >= 4 ? 4 : NT >= 2 ? 2 : 1;
+  const int ntb = NT >= 2 ? 2 : 1;
   const int per_cu = (int)(kLdsLimit / (lds ? lds : 1));
   dim3 grid((unsigned)grid_for_tiles(ntiles, per_cu < 1 ? 1 : per_cu > 8 ? 8 : per_cu)), block(64 * W);
   float* of = reinterpret_cast<float*>(out);
   const uint32_t magic = magic_for(K);
-#define TGRAD_LP(DT_, W_, NTB_)                                                                          \
+#define TGRAD_LP(DT_, W_, NTB_, F_)                                                                     \
   do {                                                                                                   \
-    allow_lds(k_lproj<DT_, W_, NTB_>, lds);                                                              \
-    k_lproj<DT_, W_, NTB_><<<grid, block, lds, s>>>(g, omega, tile_start, gs, U, rn, A, K, M, magic,     \
-                                                    ntiles, of);                                         \
+    allow_lds(k_lproj<DT_, W_, NTB_, F_>, lds);                                                          \
+    k_lproj<DT_, W_, NTB_, F_><<<grid, block, lds, s>>>(g, omega, tile_start, gs, U, rn, A, K, M, magic, \
+                                                        ntiles, of);                                     \
+  } while (0)
+#define TGRAD_LP_F(DT_, W_, NTB_)                                                                        \
+  do {                                                                                                   \
+    if (K & 1) TGRAD_LP(DT_, W_, NTB_, true); else TGRAD_LP(DT_, W_, NTB_, false);                       \
   } while (0)
 #define TGRAD_LP_W(DT_, NTB_)                                                                            \
   do {                                                                                                   \
-    if (W == 4) TGRAD_LP(DT_, 4, NTB_); else if (W == 2) TGRAD_LP(DT_, 2, NTB_); else TGRAD_LP(DT_, 1, NTB_); \
+    if (W == 4) TGRAD_LP_F(DT_, 4, NTB_); else if (W == 2) TGRAD_LP_F(DT_, 2, NTB_); else TGRAD_LP_F(DT_, 1, NTB_); \
   } while (0)
   if (dtype == TGRAD_C64) {
-    if (ntb == 4) TGRAD_LP_W(TGRAD_C64, 4); else if (ntb == 2) TGRAD_LP_W(TGRAD_C64, 2); else TGRAD_LP_W(TGRAD_C64, 1);
+    if (ntb == 2) TGRAD_LP_W(TGRAD_C64, 2); else TGRAD_LP_W(TGRAD_C64, 1);
   } else {
-    if (ntb == 4) TGRAD_LP_W(TGRAD_CBF16, 4); else if (ntb == 2) TGRAD_LP_W(TGRAD_CBF16, 2); else TGRAD_LP_W(TGRAD_CBF16, 1);
+    if (ntb == 2) TGRAD_LP_W(TGRAD_CBF16, 2); else TGRAD_LP_W(TGRAD_CBF16, 1);
   }
 #undef TGRAD_LP_W
+#undef TGRAD_LP_F
 #undef TGRAD_LP
 }
 
