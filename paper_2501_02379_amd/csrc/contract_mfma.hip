@@ -25,6 +25,8 @@
 // Operand layout of v_mfma_f32_32x32x2f32 (D = A B + C, A 32 x 2, B 2 x 32, 64 lanes):
 //   lane l supplies A[l % 32][l / 32] and B[l / 32][l % 32];
 //   register r of lane l receives D[(r % 4) + 8 (r / 4) + 4 (l / 32)][l % 32].
+#include <type_traits>
+
 #include "device_common.h"
 
 namespace tgrad {
@@ -169,34 +171,50 @@ __global__ __launch_bounds__(kMidThreads) void k_mid(const float* __restrict__ x
 }
 
 // -------------------------------------------------------------------------------------------
-// Shared by the two last-mode kernels: the tensor seen as (A rows, L complex per row) is cut
-// into flat tiles of R = 32 W rows; tile t holds elements [t R L, (t + 1) R L).
-// `tile_start[t]` = number of support entries below t R L (Omega is ascending), so tile t owns
+// Shared by the two last-mode kernels.  The tensor seen as (A rows, L complex per row) is cut
+// into flat tiles of 32 rows (one matrix-core tile); tile t holds elements [32 t L, 32 (t + 1) L).
+// `tile_start[t]` = number of support entries below 32 t L (Omega is ascending), so tile t owns
 // Omega[tile_start[t] .. tile_start[t + 1]).
+//
+// A tile belongs to ONE wavefront from its first load to its last store, and the LDS slice it
+// is staged in is private to that wavefront.  The wavefronts of a workgroup therefore never
+// meet at a barrier after the factor table is staged: each runs its own load / matrix-core /
+// store pipeline and the hardware overlaps them.  Workgroups have 4 wavefronts because a
+// workgroup's wavefronts are spread over the 4 SIMDs of a compute unit starting at the first
+// one: smaller workgroups leave the matrix cores of the last SIMDs idle.
+constexpr int kTileRows = 32;
 
-// B-operand table of a last-mode contraction, staged in LDS as [pair j][column tile][lane]
-// = (coefficient of the re part, coefficient of the im part) of input element k = 2 j + lane / 32
-// for output column c = 32 nt + lane % 32 (complex m = c / 2, part p = c % 2).
-//   PROJECT (F[m, k] = conj(U[k, m])):  p = re: (ur, ui),  p = im: (-ui, ur)
-//   expand  (F[m, k] = U[m, k]):        p = re: (ur, -ui), p = im: (ui, ur)
+// Orders the LDS accesses of one wavefront across its lanes (LDS executes a wavefront's
+// instructions in order; this only keeps the compiler from moving them across the point).
+__device__ __forceinline__ void wave_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Factor table in LDS: sF[k * ld + m] = F[m, k] as (fr, fi), ld = 16 NT, zero for k >= K or
+// m >= M.  PROJECT: F[m, k] = conj(U[k, m]); otherwise F[m, k] = U[m, k].
 template <bool PROJECT>
-__device__ __forceinline__ void stage_last_mode_factor(float2* sB, const float2* __restrict__ U, int rn,
-                                                       int K, int M, int J, int NT, int tid, int nthreads) {
-  for (int e = tid; e < J * NT * 64; e += nthreads) {
-    const int l = e & 63;
-    const int nt = (e >> 6) % NT;
-    const int j = e / (64 * NT);
-    const int k = 2 * j + (l >> 5);
-    const int c = 32 * nt + (l & 31);
-    const int m = c >> 1, p = c & 1;
-    float2 b = make_float2(0.f, 0.f);
+__device__ __forceinline__ void stage_factor_table(float2* sF, const float2* __restrict__ U, int rn, int K,
+                                                   int M, int krows, int ld, int tid, int nthreads) {
+  for (int e = tid; e < krows * ld; e += nthreads) {
+    const int k = e / ld, m = e - k * ld;
+    float2 f = make_float2(0.f, 0.f);
     if (k < K && m < M) {
-      const float2 u = PROJECT ? U[(int64_t)k * rn + m] : U[(int64_t)m * rn + k];
-      const float ui = PROJECT ? u.y : -u.y;                   // sign of the (im -> re) coefficient
-      b = p == 0 ? make_float2(u.x, ui) : make_float2(-ui, u.x);
+      if (PROJECT) {
+        const float2 u = U[(int64_t)k * rn + m];
+        f = make_float2(u.x, -u.y);
+      } else {
+        f = U[(int64_t)m * rn + k];
+      }
     }
-    sB[e] = b;
+    sF[e] = f;
   }
+}
+// Coefficients of the (re, im) parts of input element k for real output column (m, p):
+// re(F x) = fr xr - fi xi,  im(F x) = fi xr + fr xi.
+__device__ __forceinline__ float2 column_coef(float2 f, int p) {
+  return p ? make_float2(f.y, f.x) : make_float2(f.x, -f.y);
 }
 
 // Two consecutive gradient elements as they lie in memory (complex64: 16 bytes, bf16 pairs: 8).
@@ -228,92 +246,46 @@ __device__ __forceinline__ void decode_raw(const typename RawPair<DT>::type& raw
   }
 }
 
-constexpr int kTileBatch = 17;            // 2-element pieces per thread in flight while a tile is staged
+constexpr int kTileBatch = 17;            // 2-element pieces per lane in flight while a tile is staged
 constexpr int kJUnroll = 4;               // row pairs whose LDS operands are fetched ahead of their MFMAs
 
-// N column tiles of a last-mode contraction for the 32 rows of a wavefront:
-// acc[i] = rows(32 x 2K reals, from LDS) * sB[:, nt0 + i], then epi(nt0 + i, acc[i]).
-// `xrow` is the lane's own row.  The loops carry no guards (a guarded, branchy loop ran the
-// matrix cores at less than half their rate): for odd K the pair j = J - 1 reads element k = K of
-// the row, whose coefficients in sB are zero and whose LDS slot always holds a finite value.
-template <int N, typename Epi>
-__device__ __forceinline__ void last_mode_block(const float* xrow, const float2* sB, int J, int NT,
-                                                int nt0, int lane, int half, Epi&& epi) {
-  v16f acc[N];
-#pragma unroll
-  for (int i = 0; i < N; ++i)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
-  const float* xa = xrow + 2 * half;
-  const float2* bp = sB + (size_t)nt0 * 64 + lane;
-  int j = 0;
-  for (; j + kJUnroll <= J; j += kJUnroll) {
-    float2 a2[kJUnroll], b2[kJUnroll][N];
-#pragma unroll
-    for (int u = 0; u < kJUnroll; ++u) {
-      a2[u] = *reinterpret_cast<const float2*>(xa + 4 * (j + u));
-#pragma unroll
-      for (int i = 0; i < N; ++i) b2[u][i] = bp[((j + u) * NT + i) * 64];
-    }
-#pragma unroll
-    for (int u = 0; u < kJUnroll; ++u)
-#pragma unroll
-      for (int i = 0; i < N; ++i) {
-        acc[i] = mfma32(a2[u].x, b2[u][i].x, acc[i]);
-        acc[i] = mfma32(a2[u].y, b2[u][i].y, acc[i]);
-      }
-  }
-  for (; j < J; ++j) {
-    const float2 a2 = *reinterpret_cast<const float2*>(xa + 4 * j);
-#pragma unroll
-    for (int i = 0; i < N; ++i) {
-      const float2 b2 = bp[(j * NT + i) * 64];
-      acc[i] = mfma32(a2.x, b2.x, acc[i]);
-      acc[i] = mfma32(a2.y, b2.y, acc[i]);
-    }
-  }
-#pragma unroll
-  for (int i = 0; i < N; ++i) epi(nt0 + i, acc[i]);
-}
-
-// All NT column tiles, NTB at a time, the remainder one by one.
-template <int NTB, typename Epi>
-__device__ __forceinline__ void last_mode_contract(const float* xrow, const float2* sB, int J, int NT,
-                                                   int lane, int half, Epi&& epi) {
-  int nt0 = 0;
-  for (; nt0 + NTB <= NT; nt0 += NTB) last_mode_block<NTB>(xrow, sB, J, NT, nt0, lane, half, epi);
-  if (NTB > 1)
-    for (; nt0 < NT; ++nt0) last_mode_block<1>(xrow, sB, J, NT, nt0, lane, half, epi);
-}
-
 // k_lproj: out[a, m] = sum_k conj(U[k, m]) (G - Sparse(G, Omega))[a, k];  gs[j] = G[Omega_j].
-// A workgroup walks tiles blockIdx.x, blockIdx.x + gridDim.x, ...; the global loads of the next
+// Wavefront w of workgroup b walks tiles b W + w, + gridDim.x W, ...; the global loads of its next
 // tile are issued before the matrix-core phase of the current one.
+// Matrix-core step (j, part): lanes 0..31 feed element k = 2 j, lanes 32..63 element k = 2 j + 1
+// of their row (part = re, then im).  The loops carry no guards (a guarded, branchy loop ran the
+// matrix cores at less than half their rate): for odd K the last pair reads element k = K of the
+// row, whose coefficients are zero and whose LDS slot always holds a finite value.
 template <int DT, int W, int NTB, bool FLAT>
 __global__ __launch_bounds__(64 * W, 2) void k_lproj(const void* __restrict__ g,
-                                                  const int32_t* __restrict__ omega,
-                                                  const uint32_t* __restrict__ tile_start,
-                                                  float2* __restrict__ gs, const float2* __restrict__ U,
-                                                  int rn, int64_t A, int K, int M, uint32_t magicK,
-                                                  int64_t ntiles, float* __restrict__ out) {
+                                                     const int32_t* __restrict__ omega,
+                                                     const uint32_t* __restrict__ tile_start,
+                                                     float2* __restrict__ gs, const float2* __restrict__ U,
+                                                     int rn, int64_t A, int K, int M, uint32_t magicK,
+                                                     int64_t ntiles, float* __restrict__ out) {
   typedef typename RawPair<DT>::type Raw;
-  constexpr int T = 64 * W, R = 32 * W;
+  constexpr int T = 64 * W;
   extern __shared__ float smem[];
   constexpr bool flat = FLAT;                                  // odd K: the LDS image is the memory image
   const int stride = 2 * K + (flat ? 0 : 2);                   // floats per LDS row; stride / 2 is odd
-  float* sX = smem;                                            // R * stride + 2 floats
-  float2* sB = reinterpret_cast<float2*>(smem + R * stride + 2);   // J * NT * 64 (8-byte aligned)
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int col = lane & 31, half = lane >> 5;
+  const int slice = kTileRows * stride + 2;                    // floats per wavefront (even)
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // in a scalar register: tile bookkeeping stays scalar
+  float* sX = smem + wave * slice;
+  float2* sF = reinterpret_cast<float2*>(smem + W * slice);
   const int J = (K + 1) >> 1;
   const int N2 = 2 * M;
   const int NT = (N2 + 31) >> 5;
-  for (int e = tid; e < R * stride + 2; e += T) sX[e] = 0.f;   // pads and never-staged rows stay finite
-  stage_last_mode_factor<true>(sB, U, rn, K, M, J, NT, tid, T);
+  const int ld = 16 * NT;
+  for (int e = lane; e < slice; e += 64) sX[e] = 0.f;          // pads and never-staged rows stay finite
+  stage_factor_table<true>(sF, U, rn, K, M, 2 * J, ld, tid, T);
+  __syncthreads();                                             // the only workgroup barrier
 
   const int64_t I = A * K;
-  const int tile_elems = R * K;
-  const int64_t step = gridDim.x;
+  const int tile_elems = kTileRows * K;
+  const int64_t step = (int64_t)gridDim.x * W;
+  int64_t tile = (int64_t)blockIdx.x * W + wave;
+  if (tile >= ntiles) return;
 
   Raw raw[kTileBatch];
   int32_t my_om = -1;
@@ -321,20 +293,13 @@ __global__ __launch_bounds__(64 * W, 2) void k_lproj(const void* __restrict__ g,
   auto issue = [&](int64_t t, uint32_t j0, uint32_t j1) {
     const int64_t e_base = t * tile_elems;
     const int n_e = (int)((I - e_base) < tile_elems ? (I - e_base) : tile_elems);
-#ifdef TGRAD_ABL
-    if (TGRAD_ABL & 2) {
-      for (int i = 0; i < kTileBatch; ++i) raw[i] = Raw{};
-      my_om = (j0 + tid < j1) ? omega[j0 + tid] : -1;
-      return;
-    }
-#endif
 #pragma unroll
     for (int i = 0; i < kTileBatch; ++i) {
-      const int e0 = 2 * (tid + i * T);
+      const int e0 = 2 * (lane + i * 64);
       if (e0 + 1 < n_e) raw[i] = load_raw_pair<DT>(g, (e_base >> 1) + (e0 >> 1));
       else if (e0 < n_e) raw[i] = load_raw_single<DT>(g, e_base + e0);
     }
-    my_om = (j0 + tid < j1) ? omega[j0 + tid] : -1;
+    my_om = (j0 + lane < j1) ? omega[j0 + lane] : -1;
   };
   // element pair at flat offset e0 of the tile -> LDS
   auto commit_piece = [&](const Raw& rw, int e0, int n_e) {
@@ -359,7 +324,6 @@ __global__ __launch_bounds__(64 * W, 2) void k_lproj(const void* __restrict__ g,
   // The support ranges are fetched with per-lane (vector) loads on purpose: a scalar load shares
   // its wait counter with the LDS reads of the matrix-core phase and would stall its first step.
   const int vzero = tid >> 30;                                 // 0, but not known to be uniform
-  int64_t tile = blockIdx.x;
   int64_t nxt = tile + step;
   uint32_t cj0 = tile_start[tile + vzero], cj1 = tile_start[tile + 1 + vzero];
   uint32_t nj0 = 0, nj1 = 0;
@@ -371,31 +335,38 @@ __global__ __launch_bounds__(64 * W, 2) void k_lproj(const void* __restrict__ g,
   while (true) {
     const int64_t e_base = tile * tile_elems;
     const int n_e = (int)((I - e_base) < tile_elems ? (I - e_base) : tile_elems);
-    __syncthreads();                                           // previous tile consumed (and sB staged)
-    int tid_now = tid;                                         // opaque copy: keeps the per-piece LDS addresses
-    asm volatile("" : "+v"(tid_now));                          // from being hoisted out of the tile loop
+    wave_sync();                                               // previous tile's LDS reads are done
+    // Opaque copy of the lane id: everything addressed through it is recomputed per tile (a few
+    // VALU operations) instead of being hoisted into dozens of long-lived registers, which
+    // would spill - and a spill reload waits for every load in flight.
+    int lane_now = lane;
+    asm volatile("" : "+v"(lane_now));
+    const int col = lane_now & 31, half = lane_now >> 5;
+    const float* xa = sX + col * stride + 2 * half;            // the lane's own row, its half of each pair
+    const float2* fl = sF + half * ld + (col >> 1);
+    const int part = col & 1;
 #pragma unroll
     for (int i = 0; i < kTileBatch; ++i) {
-      const int e0 = 2 * (tid_now + i * T);
+      const int e0 = 2 * (lane_now + i * 64);
       if (e0 < n_e) commit_piece(raw[i], e0, n_e);
     }
-    for (int e0 = 2 * (tid + kTileBatch * T); e0 < n_e; e0 += 2 * T) {   // long rows: the rest, unpipelined
+    for (int e0 = 2 * (lane + kTileBatch * 64); e0 < n_e; e0 += 128) {   // long rows: the rest, unpipelined
       Raw rw;
       if (e0 + 1 < n_e) rw = load_raw_pair<DT>(g, (e_base >> 1) + (e0 >> 1));
       else rw = load_raw_single<DT>(g, e_base + e0);
       commit_piece(rw, e0, n_e);
     }
-    __syncthreads();
+    wave_sync();
     // ---- Sparse(G, Omega) of this tile: hand the values over, then remove them ----
-    for (uint32_t j = cj0 + tid; j < cj1; j += T) {
-      const int32_t oj = (j == cj0 + tid) ? my_om : omega[j];
+    for (uint32_t j = cj0 + lane; j < cj1; j += 64) {
+      const int32_t oj = (j == cj0 + lane) ? my_om : omega[j];
       const uint32_t e = (uint32_t)((int64_t)oj - e_base);
       const uint32_t r = flat ? 0u : div_magic(e, magicK);
       float2* p = reinterpret_cast<float2*>(&sX[r * stride + 2 * (e - r * (uint32_t)K)]);
       gs[j] = *p;
       *p = make_float2(0.f, 0.f);
     }
-    __syncthreads();
+    wave_sync();
     // ---- next tile's loads go in flight; its support range was fetched one tile earlier ----
     const int64_t nn = nxt + step;
     uint32_t nnj0 = 0, nnj1 = 0;
@@ -406,26 +377,59 @@ __global__ __launch_bounds__(64 * W, 2) void k_lproj(const void* __restrict__ g,
         nnj1 = tile_start[nn + 1 + vzero];
       }
     }
-    // ---- 32 rows per wavefront through the matrix cores ----
-    const float* xrow = sX + (wave * 32 + col) * stride;
-    const int64_t grow0 = tile * R + wave * 32;
-#ifdef TGRAD_ABL
-    if (TGRAD_ABL & 1) goto abl_skip;
-#endif
-    last_mode_contract<NTB>(xrow, sB, J, NT, lane, half, [&](int nt, const v16f& acc) {
-      const int c = 32 * nt + col;
+    // ---- the 32 rows through the matrix cores, NTB column tiles at a time ----
+    const int64_t grow0 = tile * kTileRows;
+    auto block = [&](int nt0, auto ntile_count) {
+      constexpr int N = decltype(ntile_count)::value;
+      v16f acc[N];
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int64_t grow = grow0 + d_row(r, half);
-#ifdef TGRAD_ABL
-        if ((TGRAD_ABL & 4) && acc[r] != 123.f) continue;
-#endif
-        if (grow < A && c < N2) out[grow * N2 + c] = acc[r];
+      for (int i = 0; i < N; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+      const float2* fb = fl + 16 * nt0;
+      int j = 0;
+      for (; j + kJUnroll <= J; j += kJUnroll) {
+        float2 a2[kJUnroll], f2[kJUnroll][N];
+#pragma unroll
+        for (int u = 0; u < kJUnroll; ++u) {
+          a2[u] = *reinterpret_cast<const float2*>(xa + 4 * (j + u));
+#pragma unroll
+          for (int i = 0; i < N; ++i) f2[u][i] = fb[2 * (j + u) * ld + 16 * i];
+        }
+#pragma unroll
+        for (int u = 0; u < kJUnroll; ++u)
+#pragma unroll
+          for (int i = 0; i < N; ++i) {
+            const float2 b2 = column_coef(f2[u][i], part);
+            acc[i] = mfma32(a2[u].x, b2.x, acc[i]);
+            acc[i] = mfma32(a2[u].y, b2.y, acc[i]);
+          }
       }
-    });
-#ifdef TGRAD_ABL
-  abl_skip:
-#endif
+      for (; j < J; ++j) {
+        const float2 a2 = *reinterpret_cast<const float2*>(xa + 4 * j);
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+          const float2 b2 = column_coef(fb[2 * j * ld + 16 * i], part);
+          acc[i] = mfma32(a2.x, b2.x, acc[i]);
+          acc[i] = mfma32(a2.y, b2.y, acc[i]);
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < N; ++i) {
+        const int c = 32 * (nt0 + i) + col;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int64_t grow = grow0 + d_row(r, half);
+          if (grow < A && c < N2) out[grow * N2 + c] = acc[i][r];
+        }
+      }
+    };
+    {
+      int nt0 = 0;
+      for (; nt0 + NTB <= NT; nt0 += NTB) block(nt0, std::integral_constant<int, NTB>());
+      if (NTB > 1)
+        for (; nt0 < NT; ++nt0) block(nt0, std::integral_constant<int, 1>());
+    }
     if (nxt >= ntiles) break;
     tile = nxt;
     nxt = nn;
@@ -440,6 +444,9 @@ __global__ __launch_bounds__(64 * W, 2) void k_lproj(const void* __restrict__ g,
 // with c_alpha = -lr alpha, c_lambda = -lr lambda, decay = 1 - lr wd (Algorithm 1: "Reconstruct
 // low-rank part", "Add scaled sparse tensor", weight update; AdamUpdate on the sparse values
 // as in the appendix algorithm "Adam with low-rank tensor decomposition").
+// The rows of z are read straight into matrix-core operand registers: lane (row, half) keeps
+// elements k = half JT .. half JT + JT - 1 of its row (JT = a power of two >= K / 2, zero beyond
+// K), so step (j, part) pairs element j (lanes 0..31) with element JT + j (lanes 32..63).
 struct SparseAdam {
   const int32_t* omega;
   const uint32_t* tile_start;
@@ -449,59 +456,57 @@ struct SparseAdam {
   float beta1, beta2, inv_c1, inv_c2, eps, c_lambda;
 };
 
-constexpr int kUpdPrefetch = 17;          // 16-byte pieces of W per thread kept in flight during the MFMA phase
-constexpr int kUpdZBatch = 8;             // elements of z per thread loaded one tile ahead
+constexpr int kUpdPrefetch = 17;          // 16-byte pieces of W per lane kept in flight during the MFMA phase
 
-template <int W, int NTB>
-__global__ __launch_bounds__(64 * W) void k_lupdate(const float* __restrict__ z,
-                                                    const float2* __restrict__ U, int64_t A, int K,
-                                                    int M, uint32_t magicK, int64_t ntiles,
-                                                    float* __restrict__ w, float decay, float c_alpha,
-                                                    SparseAdam sp) {
-  constexpr int T = 64 * W, R = 32 * W;
+template <int W, int NTB, int JT>
+__global__ __launch_bounds__(64 * W, 2) void k_lupdate(const float* __restrict__ z,
+                                                       const float2* __restrict__ U, int64_t A, int K,
+                                                       int M, int64_t ntiles, float* __restrict__ w,
+                                                       float decay, float c_alpha, SparseAdam sp) {
+  constexpr int T = 64 * W;
   extern __shared__ float smem[];
-  const int zstride = 2 * K + ((K & 1) ? 0 : 2);
-  const int J = (K + 1) >> 1;
   const int N2 = 2 * M;
   const int NT = (N2 + 31) >> 5;
-  float* sD = smem;                                            // R * N2 floats, flat image of the W tile
-  float* sZ = sD + ((R * N2 + 3) & ~3);                        // R * zstride + 2 floats
-  float2* sB = reinterpret_cast<float2*>(sZ + R * zstride + 2);    // J * NT * 64 (8-byte aligned)
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int col = lane & 31, half = lane >> 5;
-  for (int e = tid; e < R * zstride + 2; e += T) sZ[e] = 0.f;  // pads and never-staged rows stay finite
-  stage_last_mode_factor<false>(sB, U, K, K, M, J, NT, tid, T);
+  const int ld = 16 * NT;
+  const int slice = (kTileRows * N2 + 3) & ~3;                 // floats per wavefront: flat image of its W tile
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // in a scalar register: tile bookkeeping stays scalar
+  float* sD = smem + wave * slice;
+  float2* sF = reinterpret_cast<float2*>(smem + W * slice);
+  stage_factor_table<false>(sF, U, K, K, M, 2 * JT, ld, tid, T);
+  __syncthreads();                                             // the only workgroup barrier
 
   const int64_t Iw = A * M;                                    // complex elements of W
-  const int64_t Iz = A * K;
-  const int tile_w = R * M, tile_z = R * K;
-  const int64_t step = gridDim.x;
+  const int tile_w = kTileRows * M;
+  const int64_t step = (int64_t)gridDim.x * W;
+  int64_t tile = (int64_t)blockIdx.x * W + wave;
+  if (tile >= ntiles) return;
   const float2* zall = reinterpret_cast<const float2*>(z);
 
-  float2 zpre[kUpdZBatch];
+  float2 zreg[JT];
   int32_t my_om = -1;
   float2 my_g = make_float2(0.f, 0.f), my_m = make_float2(0.f, 0.f);
   float my_v = 0.f;
-  // z rows and the sparse state of tile `t` (support range [j0, j1)): issued one tile ahead
+  // operand rows and sparse state of tile `t` (support range [j0, j1))
   auto issue_small = [&](int64_t t, uint32_t j0, uint32_t j1) {
-    const int64_t z_base = t * tile_z;
-    const int n_z = (int)((Iz - z_base) < tile_z ? (Iz - z_base) : tile_z);
+    const int col = lane & 31, half = lane >> 5;
+    const int64_t grow = t * kTileRows + col;
+    const float2* zr = zall + grow * K + half * JT;
 #pragma unroll
-    for (int i = 0; i < kUpdZBatch; ++i) {
-      const int e = tid + i * T;
-      if (e < n_z) zpre[i] = zall[z_base + e];
+    for (int j = 0; j < JT; ++j) {
+      zreg[j] = make_float2(0.f, 0.f);
+      if (grow < A && half * JT + j < K) zreg[j] = zr[j];
     }
     my_om = -1;
-    if (j0 + tid < j1) {
-      my_om = sp.omega[j0 + tid];
-      my_g = sp.gs[j0 + tid];
-      my_m = sp.ms[j0 + tid];
-      my_v = sp.vs[j0 + tid];
+    if (j0 + lane < j1) {
+      my_om = sp.omega[j0 + lane];
+      my_g = sp.gs[j0 + lane];
+      my_m = sp.ms[j0 + lane];
+      my_v = sp.vs[j0 + lane];
     }
   };
 
   const int vzero = tid >> 30;                                 // 0, but not known to be uniform (see k_lproj)
-  int64_t tile = blockIdx.x;
   int64_t nxt = tile + step;
   uint32_t cj0 = sp.tile_start[tile + vzero], cj1 = sp.tile_start[tile + 1 + vzero];
   uint32_t nj0 = 0, nj1 = 0;
@@ -511,40 +516,28 @@ __global__ __launch_bounds__(64 * W) void k_lupdate(const float* __restrict__ z,
   }
   issue_small(tile, cj0, cj1);
   while (true) {
+    int lane_now = lane;                                       // opaque per-tile copy (see k_lproj)
+    asm volatile("" : "+v"(lane_now));
+    const int col = lane_now & 31, half = lane_now >> 5;
+    const float2* fl = sF + half * JT * ld + (col >> 1);
+    const int part = col & 1;
     const int64_t w_base = tile * tile_w;                      // complex index of the tile in W
     const int n_w = (int)((Iw - w_base) < tile_w ? (Iw - w_base) : tile_w);
-    const int64_t z_base = tile * tile_z;
-    const int n_z = (int)((Iz - z_base) < tile_z ? (Iz - z_base) : tile_z);
-    float4* w4 = reinterpret_cast<float4*>(w + 2 * w_base);    // 16-byte aligned: R * M is even
+    float4* w4 = reinterpret_cast<float4*>(w + 2 * w_base);    // 16-byte aligned: 32 M is even
     const int n4 = n_w >> 1;                                   // whole 16-byte pieces (2 complex each)
-    // ---- W pieces go in flight first; they are consumed after the MFMA phase ----
-    float4 wpre[kUpdPrefetch];
+    // ---- what was fetched one tile ago is claimed here, while nothing younger is in flight (the
+    //      hardware retires loads in order, so a wait placed after the W loads below would also
+    //      wait for those); then the next tile's small loads and this tile's W pieces are issued ----
+    float2 zcur[JT];
 #pragma unroll
-    for (int i = 0; i < kUpdPrefetch; ++i) {
-      const int q = tid + i * T;
-      wpre[i] = q < n4 ? w4[q] : make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int j = 0; j < JT; ++j) {
+      asm volatile("" : "+v"(zreg[j].x), "+v"(zreg[j].y));
+      zcur[j] = zreg[j];
     }
-    __syncthreads();                                           // previous tile's LDS fully consumed
-    // ---- stage z rows of the tile ----
-#pragma unroll
-    for (int i = 0; i < kUpdZBatch; ++i) {
-      const int e = tid + i * T;
-      if (e < n_z) {
-        const uint32_t r = div_magic((uint32_t)e, magicK);
-        const uint32_t c = (uint32_t)e - r * (uint32_t)K;
-        *reinterpret_cast<float2*>(&sZ[r * zstride + 2 * c]) = zpre[i];
-      }
-    }
-    for (int e = tid + kUpdZBatch * T; e < n_z; e += T) {      // high ranks: the rest, unpipelined
-      const uint32_t r = div_magic((uint32_t)e, magicK);
-      const uint32_t c = (uint32_t)e - r * (uint32_t)K;
-      *reinterpret_cast<float2*>(&sZ[r * zstride + 2 * c]) = zall[z_base + e];
-    }
-    // sparse state of this tile moves out of the prefetch registers before they are refilled
+    asm volatile("" : "+v"(my_om), "+v"(my_g.x), "+v"(my_g.y), "+v"(my_m.x), "+v"(my_m.y), "+v"(my_v));
     const int32_t c_om = my_om;
     const float2 c_g = my_g, c_m = my_m;
     const float c_v = my_v;
-    __syncthreads();
     const int64_t nn = nxt + step;
     uint32_t nnj0 = 0, nnj1 = 0;
     if (nxt < ntiles) {
@@ -554,21 +547,50 @@ __global__ __launch_bounds__(64 * W) void k_lupdate(const float* __restrict__ z,
         nnj1 = sp.tile_start[nn + 1 + vzero];
       }
     }
-    // ---- expand 32 rows per wavefront: sD[row, c] = c_alpha * sum_k ... ----
-    {
-      const float* zrow = sZ + (wave * 32 + col) * zstride;
-      last_mode_contract<NTB>(zrow, sB, J, NT, lane, half, [&](int nt, const v16f& acc) {
-        const int c = 32 * nt + col;
+    float4 wpre[kUpdPrefetch];
+#pragma unroll
+    for (int i = 0; i < kUpdPrefetch; ++i) {
+      const int q = lane_now + i * 64;
+      wpre[i] = q < n4 ? w4[q] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    wave_sync();                                               // previous tile's LDS reads are done
+    // ---- expand the 32 rows: sD[row, c] = c_alpha * sum_k ..., NTB column tiles at a time ----
+    auto block = [&](int nt0, auto ntile_count) {
+      constexpr int N = decltype(ntile_count)::value;
+      v16f acc[N];
+#pragma unroll
+      for (int i = 0; i < N; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+      const float2* fb = fl + 16 * nt0;
+#pragma unroll
+      for (int j = 0; j < JT; ++j) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+          const float2 b2 = column_coef(fb[j * ld + 16 * i], part);
+          acc[i] = mfma32(zcur[j].x, b2.x, acc[i]);
+          acc[i] = mfma32(zcur[j].y, b2.y, acc[i]);
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < N; ++i) {
+        const int c = 32 * (nt0 + i) + col;
         if (c < N2) {
 #pragma unroll
-          for (int r = 0; r < 16; ++r) sD[(wave * 32 + d_row(r, half)) * N2 + c] = c_alpha * acc[r];
+          for (int r = 0; r < 16; ++r) sD[d_row(r, half) * N2 + c] = c_alpha * acc[i][r];
         }
-      });
+      }
+    };
+    {
+      int nt0 = 0;
+      for (; nt0 + NTB <= NT; nt0 += NTB) block(nt0, std::integral_constant<int, NTB>());
+      if (NTB > 1)
+        for (; nt0 < NT; ++nt0) block(nt0, std::integral_constant<int, 1>());
     }
-    __syncthreads();
+    wave_sync();
     // ---- AdamUpdate on the sparse values that live in this tile; add lambda N_S into the tile ----
-    for (uint32_t j = cj0 + tid; j < cj1; j += T) {
-      const bool first = j == cj0 + tid;
+    for (uint32_t j = cj0 + lane; j < cj1; j += 64) {
+      const bool first = j == cj0 + lane;
       const float2 x = first ? c_g : sp.gs[j];
       float2 mm = first ? c_m : sp.ms[j];
       const float v_old = first ? c_v : sp.vs[j];
@@ -583,24 +605,24 @@ __global__ __launch_bounds__(64 * W) void k_lupdate(const float* __restrict__ z,
       sD[2 * e] += d * mm.x;
       sD[2 * e + 1] += d * mm.y;
     }
-    __syncthreads();
+    wave_sync();
     // ---- stream the tile into W ----
     const float4* d4 = reinterpret_cast<const float4*>(sD);
 #pragma unroll
     for (int i = 0; i < kUpdPrefetch; ++i) {
-      const int q = tid + i * T;
+      const int q = lane_now + i * 64;
       if (q < n4) {
         const float4 d = d4[q];
         const float4 o = wpre[i];
         w4[q] = make_float4(decay * o.x + d.x, decay * o.y + d.y, decay * o.z + d.z, decay * o.w + d.w);
       }
     }
-    for (int q = tid + kUpdPrefetch * T; q < n4; q += T) {
+    for (int q = lane + kUpdPrefetch * 64; q < n4; q += 64) {
       const float4 d = d4[q];
       const float4 o = w4[q];
       w4[q] = make_float4(decay * o.x + d.x, decay * o.y + d.y, decay * o.z + d.z, decay * o.w + d.w);
     }
-    if ((n_w & 1) && tid == 0) {                               // odd element count: last complex alone
+    if ((n_w & 1) && lane == 0) {                              // odd element count: last complex alone
       float2* w2 = reinterpret_cast<float2*>(w) + w_base + (n_w - 1);
       const float2 o = *w2;
       *w2 = make_float2(decay * o.x + sD[2 * (n_w - 1)], decay * o.y + sD[2 * (n_w - 1) + 1]);
@@ -652,25 +674,37 @@ int grid_for_tiles(int64_t ntiles, int blocks_per_cu) {
 // ---- host side ---------------------------------------------------------------------------------
 
 size_t lproj_lds_bytes(int W, int K, int M) {
-  const int R = 32 * W, stride = 2 * K + ((K & 1) ? 0 : 2), J = (K + 1) / 2, NT = (2 * M + 31) / 32;
-  return (size_t)(R * stride + 2) * 4 + (size_t)J * NT * 64 * 8;
+  const int stride = 2 * K + ((K & 1) ? 0 : 2), J = (K + 1) / 2, NT = (2 * M + 31) / 32;
+  return (size_t)W * (kTileRows * stride + 2) * 4 + (size_t)2 * J * 16 * NT * 8;
+}
+
+int lupdate_jt(int K) {                         // operand-register pairs per lane: power of two >= K / 2
+  int jt = 1;
+  while (2 * jt < K) jt *= 2;
+  return jt;
 }
 
 size_t lupdate_lds_bytes(int W, int K, int M) {
-  const int R = 32 * W, zstride = 2 * K + ((K & 1) ? 0 : 2), J = (K + 1) / 2, NT = (2 * M + 31) / 32;
-  return (size_t)((R * 2 * M + 3) & ~3) * 4 + (size_t)(R * zstride + 2) * 4 + (size_t)J * NT * 64 * 8;
+  const int NT = (2 * M + 31) / 32;
+  return (size_t)W * ((kTileRows * 2 * M + 3) & ~3) * 4 + (size_t)2 * lupdate_jt(K) * 16 * NT * 8;
 }
 
-// Rows per tile (32 * W) that both last-mode kernels can stage in LDS, or 0 if neither W fits.
-// `Klast` / `rlast` are the extent and the rank of the last mode.
+constexpr int kUpdMaxJT = 16;                   // k_lupdate keeps a row of z in registers: rank of the last mode <= 32
+
+// Wavefronts per workgroup for the two last-mode kernels (each wavefront stages its own 32-row
+// tile in LDS), or 0 if the shape is outside what they cover.  `Klast` / `rlast` are the extent
+// and the rank of the last mode.  Two workgroups per compute unit are preferred.
 int choose_tile_waves(int Klast, int rlast, int prefer) {
+  if (lupdate_jt(rlast) > kUpdMaxJT) return 0;
+  if ((int64_t)kTileRows * Klast >= (1 << 17)) return 0;
   const int cand[3] = {4, 2, 1};
-  for (int i = 0; i < 3; ++i) {
-    const int W = cand[i];
-    if (W > prefer) continue;
-    if (lproj_lds_bytes(W, Klast, rlast) <= kLdsLimit && lupdate_lds_bytes(W, rlast, Klast) <= kLdsLimit &&
-        (int64_t)32 * W * Klast < (1 << 17))
-      return W;
+  for (int pass = 0; pass < 2; ++pass) {
+    const size_t limit = pass == 0 ? kLdsLimit / 2 : kLdsLimit;
+    for (int i = 0; i < 3; ++i) {
+      const int W = cand[i];
+      if (W > prefer) continue;
+      if (lproj_lds_bytes(W, Klast, rlast) <= limit && lupdate_lds_bytes(W, rlast, Klast) <= limit) return W;
+    }
   }
   return 0;
 }
@@ -717,13 +751,12 @@ void launch_lproj(hipStream_t s, const void* g, int dtype, const int32_t* omega,
   const int64_t A = st.A;
   const int K = st.K, M = st.M;
   if (A * M <= 0) return;
-  const int R = 32 * W;
-  const int64_t ntiles = (A + R - 1) / R;
+  const int64_t ntiles = (A + kTileRows - 1) / kTileRows;
   const size_t lds = lproj_lds_bytes(W, K, M);
   const int NT = (2 * M + 31) / 32;
   const int ntb = NT >= 2 ? 2 : 1;
   const int per_cu = (int)(kLdsLimit / (lds ? lds : 1));
-  dim3 grid((unsigned)grid_for_tiles(ntiles, per_cu < 1 ? 1 : per_cu > 8 ? 8 : per_cu)), block(64 * W);
+  dim3 grid((unsigned)grid_for_tiles((ntiles + W - 1) / W, per_cu < 1 ? 1 : per_cu > 2 ? 2 : per_cu)), block(64 * W);
   float* of = reinterpret_cast<float*>(out);
   const uint32_t magic = magic_for(K);
 #define TGRAD_LP(DT_, W_, NTB_, F_)                                                                     \
@@ -757,21 +790,26 @@ void launch_lupdate(hipStream_t s, const float2* z, const float2* U, const Stage
   const int64_t A = st.A;
   const int K = st.K, M = st.M;
   if (A * M <= 0) return;
-  const int R = 32 * W;
-  const int64_t ntiles = (A + R - 1) / R;
+  const int64_t ntiles = (A + kTileRows - 1) / kTileRows;
   const size_t lds = lupdate_lds_bytes(W, K, M);
   const int per_cu = (int)(kLdsLimit / (lds ? lds : 1));
-  dim3 grid((unsigned)grid_for_tiles(ntiles, per_cu < 1 ? 1 : per_cu > 8 ? 8 : per_cu)), block(64 * W);
+  dim3 grid((unsigned)grid_for_tiles((ntiles + W - 1) / W, per_cu < 1 ? 1 : per_cu > 2 ? 2 : per_cu)), block(64 * W);
   SparseAdam sp{omega, tile_start, gs, ms, vs, beta1, beta2, inv_c1, inv_c2, eps, c_lambda};
   const float* zf = reinterpret_cast<const float*>(z);
   float* wf = reinterpret_cast<float*>(w);
-  const uint32_t magic = magic_for(K);
-#define TGRAD_LU(W_)                                                                                     \
+  const int jt = lupdate_jt(K);
+#define TGRAD_LU(W_, JT_)                                                                                \
   do {                                                                                                   \
-    allow_lds(k_lupdate<W_, 4>, lds);                                                                    \
-    k_lupdate<W_, 4><<<grid, block, lds, s>>>(zf, U, A, K, M, magic, ntiles, wf, decay, c_alpha, sp);    \
+    allow_lds(k_lupdate<W_, 2, JT_>, lds);                                                               \
+    k_lupdate<W_, 2, JT_><<<grid, block, lds, s>>>(zf, U, A, K, M, ntiles, wf, decay, c_alpha, sp);      \
   } while (0)
-  if (W == 4) TGRAD_LU(4); else if (W == 2) TGRAD_LU(2); else TGRAD_LU(1);
+#define TGRAD_LU_J(W_)                                                                                   \
+  do {                                                                                                   \
+    if (jt <= 1) TGRAD_LU(W_, 1); else if (jt == 2) TGRAD_LU(W_, 2); else if (jt == 4) TGRAD_LU(W_, 4);  \
+    else if (jt == 8) TGRAD_LU(W_, 8); else TGRAD_LU(W_, 16);                                            \
+  } while (0)
+  if (W == 4) TGRAD_LU_J(4); else if (W == 2) TGRAD_LU_J(2); else TGRAD_LU_J(1);
+#undef TGRAD_LU_J
 #undef TGRAD_LU
 }
 

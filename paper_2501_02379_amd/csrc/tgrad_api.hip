@@ -39,7 +39,7 @@ struct Plan {
   Stage back[kMaxNdim];          // back[s]: s-th reconstruction stage; expands mode s
   int64_t nseg = 0;
   int64_t mask_words = 0;
-  int tile_waves = 0;            // last-mode kernels: tiles of 32 * tile_waves rows; 0 = generic kernels
+  int tile_waves = 0;            // last-mode kernels: wavefronts per workgroup; 0 = generic kernels
   int64_t ntiles = 0;            // tiles of the tensor seen as (I / I_N rows, I_N)
   int64_t tile_elems = 0;
   // byte offsets into state
@@ -117,14 +117,13 @@ void make_plan(const tgrad_config* c, Plan* p) {
   p->nseg = (p->I + kSegElems - 1) / kSegElems;
   p->mask_words = (p->I + 31) / 32;
   {
-    int prefer = 2;
+    int prefer = 4;
     if (const char* e = std::getenv("TGRAD_TILE_WAVES")) prefer = std::atoi(e);   // tuning knob: 0, 1, 2, 4
     const int last = N - 1;
     p->tile_waves = prefer > 0 ? choose_tile_waves((int)p->shape[last], p->rank[last], prefer) : 0;
     const int64_t rows = p->I / p->shape[last];
-    const int R = p->tile_waves > 0 ? 32 * p->tile_waves : 32;
-    p->ntiles = (rows + R - 1) / R;
-    p->tile_elems = (int64_t)R * p->shape[last];
+    p->ntiles = (rows + 31) / 32;                 // last-mode kernels: flat tiles of 32 rows
+    p->tile_elems = (int64_t)32 * p->shape[last];
   }
 
   size_t o = 0;
