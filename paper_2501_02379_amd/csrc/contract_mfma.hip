@@ -246,6 +246,11 @@ __device__ __forceinline__ void decode_raw(const typename RawPair<DT>::type& raw
   }
 }
 
+__device__ __forceinline__ void claim_raw(float4& r) {
+  asm volatile("" : "+v"(r.x), "+v"(r.y), "+v"(r.z), "+v"(r.w));
+}
+__device__ __forceinline__ void claim_raw(uint2& r) { asm volatile("" : "+v"(r.x), "+v"(r.y)); }
+
 constexpr int kTileBatch = 17;            // 2-element pieces per lane in flight while a tile is staged
 constexpr int kJUnroll = 4;               // row pairs whose LDS operands are fetched ahead of their MFMAs
 
@@ -289,35 +294,34 @@ __global__ __launch_bounds__(64 * W, 2) void k_lproj(const void* __restrict__ g,
 
   Raw raw[kTileBatch];
   int32_t my_om = -1;
-  // issue the first batch of tile `t` (its support range is [j0, j1)) into raw / my_om
+  // issue the first batch of tile `t` (its support range is [j0, j1)) into raw / my_om.  The loads
+  // are unconditional (indices past the tile are clamped onto its last pair): a conditional load
+  // would be followed by a wait and a register copy.
   auto issue = [&](int64_t t, uint32_t j0, uint32_t j1) {
     const int64_t e_base = t * tile_elems;
     const int n_e = (int)((I - e_base) < tile_elems ? (I - e_base) : tile_elems);
+    const int npairs = n_e >> 1;                               // >= 1: the host keeps K >= 2 here
 #pragma unroll
     for (int i = 0; i < kTileBatch; ++i) {
-      const int e0 = 2 * (lane + i * 64);
-      if (e0 + 1 < n_e) raw[i] = load_raw_pair<DT>(g, (e_base >> 1) + (e0 >> 1));
-      else if (e0 < n_e) raw[i] = load_raw_single<DT>(g, e_base + e0);
+      const int pi = lane + i * 64;
+      raw[i] = load_raw_pair<DT>(g, (e_base >> 1) + (pi < npairs ? pi : npairs - 1));
     }
     my_om = (j0 + lane < j1) ? omega[j0 + lane] : -1;
   };
   // element pair at flat offset e0 of the tile -> LDS
-  auto commit_piece = [&](const Raw& rw, int e0, int n_e) {
+  auto commit_pair = [&](const Raw& rw, int e0) {
     float2 v0, v1;
     decode_raw<DT>(rw, v0, v1);
     if (flat) {
-      if (e0 + 1 < n_e) *reinterpret_cast<float4*>(&sX[2 * e0]) = make_float4(v0.x, v0.y, v1.x, v1.y);
-      else *reinterpret_cast<float2*>(&sX[2 * e0]) = v0;
+      *reinterpret_cast<float4*>(&sX[2 * e0]) = make_float4(v0.x, v0.y, v1.x, v1.y);
     } else {
       const uint32_t r0 = div_magic((uint32_t)e0, magicK);
       const uint32_t c0 = (uint32_t)e0 - r0 * (uint32_t)K;
+      const bool wrap = c0 + 1 == (uint32_t)K;
+      const uint32_t r1 = wrap ? r0 + 1 : r0;
+      const uint32_t c1 = wrap ? 0u : c0 + 1;
       *reinterpret_cast<float2*>(&sX[r0 * stride + 2 * c0]) = v0;
-      if (e0 + 1 < n_e) {
-        const bool wrap = c0 + 1 == (uint32_t)K;
-        const uint32_t r1 = wrap ? r0 + 1 : r0;
-        const uint32_t c1 = wrap ? 0u : c0 + 1;
-        *reinterpret_cast<float2*>(&sX[r1 * stride + 2 * c1]) = v1;
-      }
+      *reinterpret_cast<float2*>(&sX[r1 * stride + 2 * c1]) = v1;
     }
   };
 
@@ -345,16 +349,23 @@ __global__ __launch_bounds__(64 * W, 2) void k_lproj(const void* __restrict__ g,
     const float* xa = sX + col * stride + 2 * half;            // the lane's own row, its half of each pair
     const float2* fl = sF + half * ld + (col >> 1);
     const int part = col & 1;
+    // one wait for the whole batch (the only memory operations issued after it were loads)
+    asm volatile("" : "+v"(my_om));
+#pragma unroll
+    for (int i = 0; i < kTileBatch; ++i) claim_raw(raw[i]);
+    const int npairs = n_e >> 1;
 #pragma unroll
     for (int i = 0; i < kTileBatch; ++i) {
-      const int e0 = 2 * (lane_now + i * 64);
-      if (e0 < n_e) commit_piece(raw[i], e0, n_e);
+      const int pi = lane_now + i * 64;
+      if (pi < npairs) commit_pair(raw[i], 2 * pi);
     }
-    for (int e0 = 2 * (lane + kTileBatch * 64); e0 < n_e; e0 += 128) {   // long rows: the rest, unpipelined
-      Raw rw;
-      if (e0 + 1 < n_e) rw = load_raw_pair<DT>(g, (e_base >> 1) + (e0 >> 1));
-      else rw = load_raw_single<DT>(g, e_base + e0);
-      commit_piece(rw, e0, n_e);
+    for (int pi = lane + kTileBatch * 64; pi < npairs; pi += 64)          // long rows: the rest, unpipelined
+      commit_pair(load_raw_pair<DT>(g, (e_base >> 1) + pi), 2 * pi);
+    if ((n_e & 1) && lane == 0) {                              // odd element count: the last one alone
+      const int e = n_e - 1;
+      const float2 v = load_elem<DT>(g, e_base + e);
+      const uint32_t r = div_magic((uint32_t)e, magicK);
+      *reinterpret_cast<float2*>(&sX[r * stride + 2 * ((uint32_t)e - r * (uint32_t)K)]) = v;
     }
     wave_sync();
     // ---- Sparse(G, Omega) of this tile: hand the values over, then remove them ----
@@ -514,7 +525,16 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate(const float* __restrict__
     nj0 = sp.tile_start[nxt + vzero];
     nj1 = sp.tile_start[nxt + 1 + vzero];
   }
+  // Every wait for loads sits at ONE point per tile (claim_loads, before the stream-out), where the
+  // only younger memory operations are loads that are needed right after anyway.  Loads retire
+  // in order, so a wait anywhere else would also wait for stores or loads issued after it.
+  auto claim_small = [&]() {
+#pragma unroll
+    for (int j = 0; j < JT; ++j) asm volatile("" : "+v"(zreg[j].x), "+v"(zreg[j].y));
+    asm volatile("" : "+v"(my_om), "+v"(my_g.x), "+v"(my_g.y), "+v"(my_m.x), "+v"(my_m.y), "+v"(my_v));
+  };
   issue_small(tile, cj0, cj1);
+  claim_small();
   while (true) {
     int lane_now = lane;                                       // opaque per-tile copy (see k_lproj)
     asm volatile("" : "+v"(lane_now));
@@ -525,16 +545,11 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate(const float* __restrict__
     const int n_w = (int)((Iw - w_base) < tile_w ? (Iw - w_base) : tile_w);
     float4* w4 = reinterpret_cast<float4*>(w + 2 * w_base);    // 16-byte aligned: 32 M is even
     const int n4 = n_w >> 1;                                   // whole 16-byte pieces (2 complex each)
-    // ---- what was fetched one tile ago is claimed here, while nothing younger is in flight (the
-    //      hardware retires loads in order, so a wait placed after the W loads below would also
-    //      wait for those); then the next tile's small loads and this tile's W pieces are issued ----
+    // ---- what was fetched one tile ago moves out of the prefetch registers; the next tile's small
+    //      loads and this tile's W pieces go in flight ----
     float2 zcur[JT];
 #pragma unroll
-    for (int j = 0; j < JT; ++j) {
-      asm volatile("" : "+v"(zreg[j].x), "+v"(zreg[j].y));
-      zcur[j] = zreg[j];
-    }
-    asm volatile("" : "+v"(my_om), "+v"(my_g.x), "+v"(my_g.y), "+v"(my_m.x), "+v"(my_m.y), "+v"(my_v));
+    for (int j = 0; j < JT; ++j) zcur[j] = zreg[j];
     const int32_t c_om = my_om;
     const float2 c_g = my_g, c_m = my_m;
     const float c_v = my_v;
@@ -547,11 +562,11 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate(const float* __restrict__
         nnj1 = sp.tile_start[nn + 1 + vzero];
       }
     }
-    float4 wpre[kUpdPrefetch];
-#pragma unroll
+    float4 wpre[kUpdPrefetch];                                 // unconditional loads, clamped onto the last
+#pragma unroll                                                 // piece (n4 >= 1: the host keeps M >= 2 here)
     for (int i = 0; i < kUpdPrefetch; ++i) {
       const int q = lane_now + i * 64;
-      wpre[i] = q < n4 ? w4[q] : make_float4(0.f, 0.f, 0.f, 0.f);
+      wpre[i] = w4[q < n4 ? q : n4 - 1];
     }
     wave_sync();                                               // previous tile's LDS reads are done
     // ---- expand the 32 rows: sD[row, c] = c_alpha * sum_k ..., NTB column tiles at a time ----
@@ -607,11 +622,15 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate(const float* __restrict__
     }
     wave_sync();
     // ---- stream the tile into W ----
+    claim_small();
+#pragma unroll
+    for (int i = 0; i < kUpdPrefetch; ++i) claim_raw(wpre[i]);
     const float4* d4 = reinterpret_cast<const float4*>(sD);
+    const int nfull = n4 >> 6;                                 // pieces every lane owns: no per-lane branch
 #pragma unroll
     for (int i = 0; i < kUpdPrefetch; ++i) {
       const int q = lane_now + i * 64;
-      if (q < n4) {
+      if (i < nfull || q < n4) {
         const float4 d = d4[q];
         const float4 o = wpre[i];
         w4[q] = make_float4(decay * o.x + d.x, decay * o.y + d.y, decay * o.z + d.z, decay * o.w + d.w);
@@ -696,6 +715,7 @@ constexpr int kUpdMaxJT = 16;                   // k_lupdate keeps a row of z in
 // and the rank of the last mode.  Two workgroups per compute unit are preferred.
 int choose_tile_waves(int Klast, int rlast, int prefer) {
   if (lupdate_jt(rlast) > kUpdMaxJT) return 0;
+  if (Klast < 2) return 0;                      // the tile loaders assume at least one 2-element piece per tile
   if ((int64_t)kTileRows * Klast >= (1 << 17)) return 0;
   const int cand[3] = {4, 2, 1};
   for (int pass = 0; pass < 2; ++pass) {
