@@ -52,7 +52,9 @@ def kernel_model(w, plan_shapes):
         return A, ranks[n], shape[n], B
 
     A, K, M, B = stage_dims(True, 0)
-    m["project_first"] = {"bytes": I * gb + A * M * B * 8, "flops": 8 * A * K * M * B, "bound": "hbm"}
+    # first compression stage (contracts the last mode of G itself) fused with the sparse gather
+    m["project_first"] = {"bytes": I * gb + A * M * B * 8 + k * (4 + 8), "flops": 8 * A * K * M * B,
+                          "bound": "hbm"}
     by = fl = 0
     for s in range(1, N):
         A, K, M, B = stage_dims(True, s)
@@ -66,7 +68,11 @@ def kernel_model(w, plan_shapes):
         fl += 8 * A * K * M * B
     m["backproject"] = {"bytes": by, "flops": fl, "bound": "mfma", "launches_per_step": N - 1}
     A, K, M, B = stage_dims(False, N - 1)
-    m["update"] = {"bytes": A * K * 8 + 16 * I, "flops": 8 * A * K * M + 4 * I, "bound": "hbm"}
+    # last reconstruction stage fused with the sparse AdamUpdate, the scatter-add and the weight
+    # update: reads the mode-(N-1)-compressed tensor and W, writes W; per sparse entry its index,
+    # gathered value and both moments are read and the moments written back
+    m["update"] = {"bytes": A * K * 8 + 16 * I + k * (4 + 8 + 12 + 12), "flops": 8 * A * K * M + 4 * I + 14 * k,
+                   "bound": "hbm"}
     m["gather"] = {"bytes": k * (4 + gb + 8), "flops": 0, "bound": "hbm"}
     m["adam_core"] = {"bytes": C * (8 + 12 + 12 + 8), "flops": 12 * C, "bound": "hbm"}
     m["sparse_update"] = {"bytes": k * (8 + 4 + 12 + 12 + 16), "flops": 14 * k, "bound": "hbm"}
@@ -77,6 +83,20 @@ def kernel_model(w, plan_shapes):
     ngram = sum(1 for n in range(N) if ranks[n] < shape[n])
     m["gram"] = {"bytes": ngram * I * gb, "flops": gram_fl, "bound": "mfma64", "launches_per_step": ngram}
     return m
+
+
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel`, measured with rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE,
+    scaled by the calibration copy) and recorded in the text summary under profiles/; None when no
+    such measurement is recorded for this workload."""
+    import re
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_%s.txt" % workload)
+    try:
+        text = open(path).read()
+    except OSError:
+        return None
+    m = re.search(r"^%s\s+traffic_bytes_per_launch\s*=\s*(\d+)" % re.escape(kernel), text, flags=re.M)
+    return int(m.group(1)) if m else None
 
 
 def cpu_baseline(w, budget_hint_s=20.0):
@@ -142,8 +162,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--traffic-kib", type=float, default=None,
-                    help="HBM KiB per launch of the dominant kernel from rocprofv3 --pmc (else null)")
+    ap.add_argument("--calibrate-copy", type=int, default=0,
+                    help="also launch the library's plain copy kernel this many times on a gradient-sized "
+                         "buffer (a known number of HBM bytes, for scaling rocprofv3 --pmc counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU (one process, one MI355X); --gpus %d is not supported."
@@ -178,6 +199,16 @@ def main():
         for t in range(t0, t0 + n):
             for layer in range(w.layers):
                 ctxs[layer].tgrad_step(Ws[layer], Gs[layer][t & 1])
+
+    if args.calibrate_copy > 0:
+        src = torch.empty(w.numel * 8, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        src.zero_()
+        for _ in range(args.calibrate_copy):
+            T.tgrad_calibration_copy(dst, src)
+        torch.cuda.synchronize()
+        log("calibration copy: %d launches of %d bytes read + %d bytes written" % (args.calibrate_copy, src.numel(), src.numel()))
+        del src, dst
 
     log("warmup %d steps ..." % Wm)
     run_steps(Wm, 0)
@@ -248,7 +279,7 @@ def main():
             ach, peak, unit = mm["flops"] / lp / avg_s / 1e12, MFMA_FP32_PEAK_TF, "TFLOP/s"
         roofline = {"kernel": dom, "bound": "hbm" if mm["bound"] == "hbm" else "mfma",
                     "achieved": round(ach, 2), "peak": peak, "unit": unit, "frac": round(ach / peak, 4),
-                    "traffic": (args.traffic_kib * 1024.0 if args.traffic_kib is not None else None),
+                    "traffic": measured_traffic(w.name, dom),
                     "algorithmic_bytes_per_launch": mm["bytes"] // lp,
                     "avg_launch_ms": kernels[dom]["avg_ms"]}
 

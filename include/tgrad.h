@@ -167,6 +167,17 @@ int tgrad_set_profiling(tgrad_ctx* ctx, int enabled);
 int tgrad_get_kernel_times(tgrad_ctx* ctx, const char** names, double* total_ms, int64_t* launches,
                            int cap);
 
+/*
+ * Plain device-to-device copy kernel of a known size, for calibrating hardware counters: a
+ * profiler's HBM read / write counters for this launch correspond to exactly `bytes` read and
+ * `bytes` written, which fixes the scale of the same counters on the optimizer's kernels.
+ *  dst_dev, src_dev  device pointers, 16-byte aligned, non-overlapping, `bytes` long each.
+ *  bytes             a multiple of 16.
+ *  hip_stream        stream to enqueue on (NULL = the default stream).  Does not wait.
+ * Errors: INVALID_ARG, HIP.
+ */
+int tgrad_calibration_copy(void* dst_dev, const void* src_dev, size_t bytes, void* hip_stream);
+
 /* Release the context (host memory only; device buffers stay the caller's). */
 int tgrad_destroy(tgrad_ctx* ctx);
 

@@ -227,15 +227,6 @@ __device__ __forceinline__ typename RawPair<DT>::type load_raw_pair(const void* 
   return reinterpret_cast<const typename RawPair<DT>::type*>(g)[p];
 }
 template <int DT>
-__device__ __forceinline__ typename RawPair<DT>::type load_raw_single(const void* g, int64_t e) {
-  if constexpr (DT == TGRAD_C64) {
-    const float2 v = reinterpret_cast<const float2*>(g)[e];
-    return make_float4(v.x, v.y, 0.f, 0.f);
-  } else {
-    return make_uint2(reinterpret_cast<const uint32_t*>(g)[e], 0u);
-  }
-}
-template <int DT>
 __device__ __forceinline__ void decode_raw(const typename RawPair<DT>::type& raw, float2& e0, float2& e1) {
   if constexpr (DT == TGRAD_C64) {
     e0 = make_float2(raw.x, raw.y);

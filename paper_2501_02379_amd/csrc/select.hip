@@ -244,12 +244,27 @@ __global__ void k_mask_from_indices(const int32_t* __restrict__ omega, int64_t k
   }
 }
 
+// Plain streaming copy (16 bytes per lane per step), the reference point for memory counters.
+__global__ __launch_bounds__(256) void k_copy16(float4* __restrict__ dst, const float4* __restrict__ src,
+                                                int64_t n16) {
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
 __global__ void k_zero_u32(uint32_t* p, int64_t n) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = 0u;
 }
 
 }  // namespace
+
+void launch_copy16(hipStream_t s, void* dst, const void* src, int64_t n16) {
+  if (n16 <= 0) return;
+  const int64_t want = (n16 + 255) / 256;
+  const unsigned grid = (unsigned)(want < 256 * 16 ? want : 256 * 16);
+  k_copy16<<<dim3(grid), dim3(256), 0, s>>>(reinterpret_cast<float4*>(dst), reinterpret_cast<const float4*>(src),
+                                            n16);
+}
 
 void zero_u32(hipStream_t s, uint32_t* p, int64_t n) {
   if (n <= 0) return;

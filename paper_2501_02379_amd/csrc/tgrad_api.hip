@@ -11,6 +11,7 @@
 
 namespace tgrad {
 void zero_u32(hipStream_t s, uint32_t* p, int64_t n);
+void launch_copy16(hipStream_t s, void* dst, const void* src, int64_t n16);
 void launch_eig_batch(hipStream_t s, int njobs, const double* const* gram, double* const* work_a,
                       double* const* work_v, const int* In, const int* r, float* const* U);
 void launch_identity_factor(hipStream_t s, float* U, int n);
@@ -611,6 +612,16 @@ int tgrad_get_kernel_times(tgrad_ctx* ctx, const char** names, double* total_ms,
     ++n;
   }
   return n;
+}
+
+int tgrad_calibration_copy(void* dst_dev, const void* src_dev, size_t bytes, void* hip_stream) {
+  if (!dst_dev || !src_dev || (bytes % 16) || ((uintptr_t)dst_dev % 16) || ((uintptr_t)src_dev % 16))
+    return TGRAD_ERR_INVALID_ARG;
+  const char* a = static_cast<const char*>(dst_dev);
+  const char* b = static_cast<const char*>(src_dev);
+  if (a < b + bytes && b < a + bytes) return TGRAD_ERR_INVALID_ARG;
+  launch_copy16(static_cast<hipStream_t>(hip_stream), dst_dev, src_dev, (int64_t)(bytes / 16));
+  return check_launch();
 }
 
 int tgrad_destroy(tgrad_ctx* ctx) {

@@ -33,8 +33,8 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libtgrad.so
 
 EXPORTS = (
     "tgrad_query_sizes", "tgrad_init", "tgrad_refresh_factors", "tgrad_step", "tgrad_get_state",
-    "tgrad_set_state", "tgrad_set_profiling", "tgrad_get_kernel_times", "tgrad_destroy",
-    "tgrad_strerror",
+    "tgrad_set_state", "tgrad_set_profiling", "tgrad_get_kernel_times", "tgrad_calibration_copy",
+    "tgrad_destroy", "tgrad_strerror",
 )
 
 
@@ -88,6 +88,7 @@ def load():
     lib.tgrad_set_profiling.argtypes = [vp, i32]
     lib.tgrad_get_kernel_times.argtypes = [vp, C.POINTER(C.c_char_p), C.POINTER(C.c_double),
                                            C.POINTER(C.c_int64), i32]
+    lib.tgrad_calibration_copy.argtypes = [vp, vp, sz, vp]
     lib.tgrad_destroy.argtypes = [vp]
     lib.tgrad_strerror.argtypes = [i32]
     lib.tgrad_strerror.restype = C.c_char_p
@@ -248,6 +249,18 @@ class Context:
             self.tgrad_destroy()
         except Exception:
             pass
+
+
+def tgrad_calibration_copy(dst, src, stream=None) -> None:
+    """Plain copy kernel of known size (dst, src: torch tensors of equal byte length)."""
+    import torch
+    nbytes = dst.numel() * dst.element_size()
+    if nbytes != src.numel() * src.element_size():
+        raise TgradError(TGRAD_ERR_INVALID_ARG, "tgrad_calibration_copy")
+    st = stream if stream is not None else torch.cuda.current_stream(dst.device)
+    rc = load().tgrad_calibration_copy(_ptr(dst), _ptr(src), nbytes, C.c_void_p(st.cuda_stream))
+    if rc != TGRAD_OK:
+        raise TgradError(rc, "tgrad_calibration_copy")
 
 
 def to_device_grad(g: np.ndarray, device="cuda:0"):
