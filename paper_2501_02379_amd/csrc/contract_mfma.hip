@@ -70,10 +70,11 @@ __global__ __launch_bounds__(kMidThreads) void k_mid(const float* __restrict__ x
   const int col = lane & 31, half = lane >> 5;
   const int64_t BV = B / VEC;             // host guarantees B % VEC == 0
   const int64_t ncv = A * BV;
-  const int64_t cv = ((int64_t)blockIdx.x * (kMidThreads / 64) + wave) * 32 + col;
-  const bool valid = cv < ncv;
-  const int64_t a = valid ? cv / BV : 0;
-  const int64_t bv = valid ? cv - a * BV : 0;
+  const int64_t cv_raw = ((int64_t)blockIdx.x * (kMidThreads / 64) + wave) * 32 + col;
+  const bool valid = cv_raw < ncv;
+  const int64_t cv = valid ? cv_raw : ncv - 1;   // lanes past the end load a real column, store nothing
+  const int64_t a = cv / BV;
+  const int64_t bv = cv - a * BV;
   const float* xp = x + ((a * K) * B + bv * VEC) * 2;
   const int64_t row_stride = B * 2;       // floats between consecutive k
   const int mbase = blockIdx.y * (32 * MT);
@@ -85,6 +86,36 @@ __global__ __launch_bounds__(kMidThreads) void k_mid(const float* __restrict__ x
     for (int t = 0; t < 2 * VEC; ++t)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[mt][t][r] = 0.f;
+
+  // One row pair: lanes 0..31 hold row 2 j, lanes 32..63 row 2 j + 1 of their column.  The loads are
+  // unconditional (a row index past K is clamped to the last row: its factor operands are zero), and
+  // the loops below carry no guards: predicated loads and guarded MFMAs both stall the pipeline.
+  auto load_pair_row = [&](int j) -> V {
+    const int k = 2 * j + half;
+    return *reinterpret_cast<const V*>(xp + (int64_t)(k < K ? k : K - 1) * row_stride);
+  };
+  auto mfma_pair_row = [&](const V& v, int jj) {
+    float xs[2 * VEC], xj[2 * VEC];
+    if constexpr (VEC == 1) {
+      xs[0] = v.x; xs[1] = v.y;
+    } else {
+      xs[0] = v.x; xs[1] = v.y; xs[2] = v.z; xs[3] = v.w;
+    }
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) {                            // (X J): re column <- -im, im column <- re
+      xj[2 * c] = -xs[2 * c + 1];
+      xj[2 * c + 1] = xs[2 * c];
+    }
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const float2 f = sF[(jj * MT + mt) * 64 + lane];
+#pragma unroll
+      for (int t = 0; t < 2 * VEC; ++t) {
+        acc[mt][t] = mfma32(f.x, xs[t], acc[mt][t]);
+        acc[mt][t] = mfma32(f.y, xj[t], acc[mt][t]);
+      }
+    }
+  };
 
   const int J = (K + 1) >> 1;
   for (int jc0 = 0; jc0 < J; jc0 += kMidJChunk) {
@@ -108,49 +139,15 @@ __global__ __launch_bounds__(kMidThreads) void k_mid(const float* __restrict__ x
       sF[e] = f;
     }
     __syncthreads();
-    for (int jj0 = 0; jj0 < jn; jj0 += kMidUnroll) {
+    int jj = 0;
+    for (; jj + kMidUnroll <= jn; jj += kMidUnroll) {
       V v[kMidUnroll];
 #pragma unroll
-      for (int u = 0; u < kMidUnroll; ++u) {
-        const int k = 2 * (jc0 + jj0 + u) + half;
-        if (VEC == 1) {
-          float2 z = make_float2(0.f, 0.f);
-          if (valid && (jj0 + u) < jn && k < K) z = *reinterpret_cast<const float2*>(xp + (int64_t)k * row_stride);
-          *reinterpret_cast<float2*>(&v[u]) = z;
-        } else {
-          float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
-          if (valid && (jj0 + u) < jn && k < K) z = *reinterpret_cast<const float4*>(xp + (int64_t)k * row_stride);
-          *reinterpret_cast<float4*>(&v[u]) = z;
-        }
-      }
+      for (int u = 0; u < kMidUnroll; ++u) v[u] = load_pair_row(jc0 + jj + u);
 #pragma unroll
-      for (int u = 0; u < kMidUnroll; ++u) {
-        if (jj0 + u < jn) {                                    // uniform over the workgroup
-          float xs[2 * VEC], xj[2 * VEC];
-          if (VEC == 1) {
-            const float2 z = *reinterpret_cast<float2*>(&v[u]);
-            xs[0] = z.x; xs[1] = z.y;
-          } else {
-            const float4 z = *reinterpret_cast<float4*>(&v[u]);
-            xs[0] = z.x; xs[1] = z.y; xs[2] = z.z; xs[3] = z.w;
-          }
-#pragma unroll
-          for (int c = 0; c < VEC; ++c) {                      // (X J): re column <- -im, im column <- re
-            xj[2 * c] = -xs[2 * c + 1];
-            xj[2 * c + 1] = xs[2 * c];
-          }
-#pragma unroll
-          for (int mt = 0; mt < MT; ++mt) {
-            const float2 f = sF[((jj0 + u) * MT + mt) * 64 + lane];
-#pragma unroll
-            for (int t = 0; t < 2 * VEC; ++t) {
-              acc[mt][t] = mfma32(f.x, xs[t], acc[mt][t]);
-              acc[mt][t] = mfma32(f.y, xj[t], acc[mt][t]);
-            }
-          }
-        }
-      }
+      for (int u = 0; u < kMidUnroll; ++u) mfma_pair_row(v[u], jj + u);
     }
+    for (; jj < jn; ++jj) mfma_pair_row(load_pair_row(jc0 + jj), jj);
   }
   if (!valid) return;
   float* op = out + ((a * M) * B + bv * VEC) * 2;
@@ -161,7 +158,7 @@ __global__ __launch_bounds__(kMidThreads) void k_mid(const float* __restrict__ x
       const int m = mbase + 32 * mt + d_row(r, half);
       if (m < M) {
         float* o = op + (int64_t)m * row_stride;
-        if (VEC == 1) {
+        if constexpr (VEC == 1) {
           *reinterpret_cast<float2*>(o) = make_float2(acc[mt][0][r], acc[mt][1][r]);
         } else {
           *reinterpret_cast<float4*>(o) = make_float4(acc[mt][0][r], acc[mt][1][r], acc[mt][2][r], acc[mt][3][r]);
