@@ -249,13 +249,29 @@ constexpr int kJUnroll = 4;               // row pairs whose LDS operands are fe
 // of their row (part = re, then im).  The loops carry no guards (a guarded, branchy loop ran the
 // matrix cores at less than half their rate): for odd K the last pair reads element k = K of the
 // row, whose coefficients are zero and whose LDS slot always holds a finite value.
-template <int DT, int W, int NTB, bool FLAT>
+//
+// FUSE: the next compression stage (mode N-1, extent 32 S, rank M2 <= 32) runs on the matrix-core
+// result while it is still in registers.  A wavefront then walks whole slabs (the S consecutive
+// tiles that share all leading indices): the 32 x 32 result tile of stage one is, as it lies in the
+// accumulator registers, the B operand of  D2[m2, (m3, p)] += F2[m2, i2] Y[i2, (m3, p)]  (register r
+// holds rows d_row(r, 0) / d_row(r, 1) of the tile in the two lane halves = one row pair); the
+// re/im swap of Y for the imaginary part of F2 is a swap of neighbouring lanes (DPP).  D2 is
+// stored once per slab; the intermediate tensor between the two stages never exists.
+struct FusedNext {
+  const float2* fpad;   // [32 S][32]: conj(U^(N-1)[i2, m2]) as (re, im), zero for m2 >= M2
+  float* out;           // (slabs, M2, M) complex, row-major
+  int S;                // tiles per slab; 1 when nothing is fused
+  int M2;
+};
+
+template <int DT, int W, int NTB, bool FLAT, bool FUSE>
 __global__ __launch_bounds__(64 * W, 2) void k_lproj(const void* __restrict__ g,
                                                      const int32_t* __restrict__ omega,
                                                      const uint32_t* __restrict__ tile_start,
                                                      float2* __restrict__ gs, const float2* __restrict__ U,
                                                      int rn, int64_t A, int K, int M, uint32_t magicK,
-                                                     int64_t ntiles, float* __restrict__ out) {
+                                                     int64_t ntiles, float* __restrict__ out,
+                                                     FusedNext fz) {
   typedef typename RawPair<DT>::type Raw;
   constexpr int T = 64 * W;
   extern __shared__ float smem[];
@@ -276,9 +292,17 @@ __global__ __launch_bounds__(64 * W, 2) void k_lproj(const void* __restrict__ g,
 
   const int64_t I = A * K;
   const int tile_elems = kTileRows * K;
-  const int64_t step = (int64_t)gridDim.x * W;
-  int64_t tile = (int64_t)blockIdx.x * W + wave;
-  if (tile >= ntiles) return;
+  // Tile sequence of this wavefront: slabs wg, wg + nw, ... and inside a slab its S tiles in order
+  // (S = 1 without fusion, where a slab is a tile).
+  const int S = FUSE ? fz.S : 1;
+  const int64_t nslabs = (ntiles + S - 1) / S;
+  const int64_t nw = (int64_t)gridDim.x * W;
+  int64_t slab = (int64_t)blockIdx.x * W + wave;
+  int ts = 0;
+  if (slab >= nslabs) return;
+  auto advance = [&](int64_t& sl, int& t) {                    // next position of the sequence
+    if (t + 1 < S) { t += 1; } else { t = 0; sl += nw; }
+  };
 
   Raw raw[kTileBatch];
   int32_t my_om = -1;
@@ -316,14 +340,18 @@ __global__ __launch_bounds__(64 * W, 2) void k_lproj(const void* __restrict__ g,
   // The support ranges are fetched with per-lane (vector) loads on purpose: a scalar load shares
   // its wait counter with the LDS reads of the matrix-core phase and would stall its first step.
   const int vzero = tid >> 30;                                 // 0, but not known to be uniform
-  int64_t nxt = tile + step;
+  int64_t tile = slab * S;
+  int64_t nslab = slab;
+  int nts = ts;
+  advance(nslab, nts);
+  bool have_next = nslab < nslabs;
+  int64_t nxt = have_next ? nslab * S + nts : tile;            // past the end: reload the current tile (unused)
   uint32_t cj0 = tile_start[tile + vzero], cj1 = tile_start[tile + 1 + vzero];
-  uint32_t nj0 = 0, nj1 = 0;
-  if (nxt < ntiles) {
-    nj0 = tile_start[nxt + vzero];
-    nj1 = tile_start[nxt + 1 + vzero];
-  }
+  uint32_t nj0 = tile_start[nxt + vzero], nj1 = tile_start[nxt + 1 + vzero];
   issue(tile, cj0, cj1);
+  v16f acc2;                                                   // FUSE: second-stage accumulator of the slab
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc2[r] = 0.f;
   while (true) {
     const int64_t e_base = tile * tile_elems;
     const int n_e = (int)((I - e_base) < tile_elems ? (I - e_base) : tile_elems);
@@ -366,16 +394,21 @@ __global__ __launch_bounds__(64 * W, 2) void k_lproj(const void* __restrict__ g,
       *p = make_float2(0.f, 0.f);
     }
     wave_sync();
-    // ---- next tile's loads go in flight; its support range was fetched one tile earlier ----
-    const int64_t nn = nxt + step;
-    uint32_t nnj0 = 0, nnj1 = 0;
-    if (nxt < ntiles) {
-      issue(nxt, nj0, nj1);
-      if (nn < ntiles) {
-        nnj0 = tile_start[nn + vzero];
-        nnj1 = tile_start[nn + 1 + vzero];
-      }
+    // ---- second-stage factor operands of this tile (FUSE), then the next tile's loads go in flight;
+    //      its support range was fetched one tile earlier.  All unconditional: see `issue`. ----
+    float2 f2s[FUSE ? 16 : 1];
+    if constexpr (FUSE) {
+      const float2* fp = fz.fpad + (size_t)(32 * ts + 4 * half) * 32 + col;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) f2s[r] = fp[((r & 3) + 8 * (r >> 2)) * 32];
     }
+    int64_t nnslab = nslab;
+    int nnts = nts;
+    advance(nnslab, nnts);
+    const bool have_nn = have_next && nnslab < nslabs;
+    const int64_t nn = have_nn ? nnslab * S + nnts : nxt;
+    issue(nxt, nj0, nj1);
+    const uint32_t nnj0 = tile_start[nn + vzero], nnj1 = tile_start[nn + 1 + vzero];
     // ---- the 32 rows through the matrix cores, NTB column tiles at a time ----
     const int64_t grow0 = tile * kTileRows;
     auto block = [&](int nt0, auto ntile_count) {
@@ -413,25 +446,53 @@ __global__ __launch_bounds__(64 * W, 2) void k_lproj(const void* __restrict__ g,
           acc[i] = mfma32(a2.y, b2.y, acc[i]);
         }
       }
-#pragma unroll
-      for (int i = 0; i < N; ++i) {
-        const int c = 32 * (nt0 + i) + col;
+      if constexpr (FUSE) {                                    // NT == 1, N == 1
+        asm volatile("" : "+v"(f2s[0].x));                     // the factor operands are claimed here
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const int64_t grow = grow0 + d_row(r, half);
-          if (grow < A && c < N2) out[grow * N2 + c] = acc[i][r];
+          const float y = acc[0][r];
+          const float sw = __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(y), 0xB1, 0xF, 0xF, true));
+          const float yj = part ? sw : -sw;                    // (Y J): re column <- -im, im column <- re
+          acc2 = mfma32(f2s[r].x, y, acc2);
+          acc2 = mfma32(f2s[r].y, yj, acc2);
+        }
+        if (ts == S - 1) {                                     // slab complete: D2 -> out[slab, m2, c]
+          float* o = fz.out + (size_t)slab * fz.M2 * N2 + col;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int m2 = d_row(r, half);
+            if (m2 < fz.M2 && col < N2) o[m2 * N2] = acc2[r];
+            acc2[r] = 0.f;
+          }
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+          const int c = 32 * (nt0 + i) + col;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int64_t grow = grow0 + d_row(r, half);
+            if (grow < A && c < N2) out[grow * N2 + c] = acc[i][r];
+          }
         }
       }
     };
-    {
+    if constexpr (FUSE) {
+      block(0, std::integral_constant<int, 1>());              // exactly one column tile (and no loop around the
+    } else {                                                   // claim of f2s: a loop preheader would drain all loads)
       int nt0 = 0;
       for (; nt0 + NTB <= NT; nt0 += NTB) block(nt0, std::integral_constant<int, NTB>());
       if (NTB > 1)
         for (; nt0 < NT; ++nt0) block(nt0, std::integral_constant<int, 1>());
     }
-    if (nxt >= ntiles) break;
+    if (!have_next) break;
     tile = nxt;
+    slab = nslab;
+    ts = nts;
     nxt = nn;
+    nslab = nnslab;
+    nts = nnts;
+    have_next = have_nn;
     cj0 = nj0;
     cj1 = nj1;
     nj0 = nnj0;
@@ -453,6 +514,7 @@ struct SparseAdam {
   float2* ms;
   float* vs;
   float beta1, beta2, inv_c1, inv_c2, eps, c_lambda;
+  int k_last;           // max(k, 1) - 1: a support position that is always safe to read
 };
 
 constexpr int kUpdPrefetch = 17;          // 16-byte pieces of W per lane kept in flight during the MFMA phase
@@ -644,6 +706,244 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate(const float* __restrict__
   }
 }
 
+// k_lupdate_fused: k_lupdate with the reconstruction stage of mode N-1 (extent 32 S, rank K2 <= 32)
+// in front of it, so the tensor between the two stages never exists.  A wavefront walks whole
+// slabs; per tile (32 rows i2 of the slab):
+//   stage A   D'[(m3, p), i2] = sum_m2 Y1[m2, m3] U2[i2, m2]            (rows = interleaved (m3, p))
+//             A operand: lane (rho = 2 m3 + p, half) holds Y1[2 jj + half][m3] (parts chosen per p and
+//             per factor part: re(u y) = ur yr - ui yi, im(u y) = ur yi + ui yr),
+//             B operand: U2[i2, 2 jj + half] from the transposed copy `ut` (coalesced over i2);
+//   stage B   the accumulator registers of D' ARE the operand rows of the last-mode expansion: in lane
+//             (i2, half) registers (2 u, 2 u + 1) hold (re, im) of element k = (u & 1) + 4 (u >> 1) + 2 half
+//             of row i2, so step (u, part) pairs elements k(u, 0) and k(u, 1) and the coefficient
+//             table is read at those rows.  Everything after that is k_lupdate.
+struct FusedPrev {
+  const float2* y1;     // (slabs, K2, K) complex: input of the fused stage
+  const float2* ut;     // [32][32 S]: ut[m2][i2] = U^(N-1)[i2, m2], zero for m2 >= K2
+  int S;                // tiles per slab
+  int K2;               // rank of mode N-1
+};
+
+template <int W, int NTB, int JT2>
+__global__ __launch_bounds__(64 * W, 2) void k_lupdate_fused(const float2* __restrict__ U, int64_t A, int K,
+                                                             int M, int64_t ntiles, float* __restrict__ w,
+                                                             float decay, float c_alpha, SparseAdam sp,
+                                                             FusedPrev fz) {
+  constexpr int T = 64 * W;
+  extern __shared__ float smem[];
+  const int N2 = 2 * M;
+  const int NT = (N2 + 31) >> 5;
+  const int ld = 16 * NT;
+  const int slice = (kTileRows * N2 + 3) & ~3;                 // floats per wavefront: flat image of its W tile
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  float* sD = smem + wave * slice;
+  float2* sF = reinterpret_cast<float2*>(smem + W * slice);
+  stage_factor_table<false>(sF, U, K, K, M, 16, ld, tid, T);   // 16 rows: K <= 16 here
+  __syncthreads();                                             // the only workgroup barrier
+
+  const int64_t Iw = A * M;
+  const int tile_w = kTileRows * M;
+  const int S = fz.S;
+  const int I2 = 32 * S;
+  const int64_t nslabs = ntiles / S;                           // A = slabs * 32 S exactly
+  const int64_t nw = (int64_t)gridDim.x * W;
+  int64_t slab = (int64_t)blockIdx.x * W + wave;
+  int ts = 0;
+  if (slab >= nslabs) return;
+  auto advance = [&](int64_t& sl, int& t) {
+    if (t + 1 < S) { t += 1; } else { t = 0; sl += nw; }
+  };
+
+  int32_t my_om = -1;
+  float2 my_g = make_float2(0.f, 0.f), my_m = make_float2(0.f, 0.f);
+  float my_v = 0.f;
+  const int om_last = sp.k_last;
+  // sparse state of a tile with support range [j0, j1): fetched one tile ahead; unconditional loads
+  // (lanes without an entry read a clamped, valid position and ignore it)
+  auto issue_sparse = [&](uint32_t j0, uint32_t j1) {
+    const uint32_t j = j0 + lane;
+    const uint32_t jc = j < j1 ? j : (uint32_t)om_last;
+    my_om = j < j1 ? sp.omega[jc] : -1;
+    my_g = sp.gs[jc];
+    my_m = sp.ms[jc];
+    my_v = sp.vs[jc];
+  };
+  auto claim_sparse = [&]() {
+    asm volatile("" : "+v"(my_om), "+v"(my_g.x), "+v"(my_g.y), "+v"(my_m.x), "+v"(my_m.y), "+v"(my_v));
+  };
+
+  const int vzero = tid >> 30;
+  int64_t tile = slab * S;
+  int64_t nslab = slab;
+  int nts = ts;
+  advance(nslab, nts);
+  bool have_next = nslab < nslabs;
+  int64_t nxt = have_next ? nslab * S + nts : tile;
+  uint32_t cj0 = sp.tile_start[tile + vzero], cj1 = sp.tile_start[tile + 1 + vzero];
+  uint32_t nj0 = sp.tile_start[nxt + vzero], nj1 = sp.tile_start[nxt + 1 + vzero];
+  issue_sparse(cj0, cj1);
+  claim_sparse();
+  while (true) {
+    int lane_now = lane;                                       // opaque per-tile copy (see k_lproj)
+    asm volatile("" : "+v"(lane_now));
+    const int col = lane_now & 31, half = lane_now >> 5;
+    const int part = col & 1;
+    const int64_t w_base = tile * tile_w;
+    const int n_w = (int)((Iw - w_base) < tile_w ? (Iw - w_base) : tile_w);
+    float4* w4 = reinterpret_cast<float4*>(w + 2 * w_base);
+    const int n4 = n_w >> 1;
+    const int32_t c_om = my_om;
+    const float2 c_g = my_g, c_m = my_m;
+    const float c_v = my_v;
+    // ---- stage-A operands of this tile (small, cache-resident: the slab's Y1 and 32 columns of the
+    //      factor copy), issued BEFORE the W pieces so that waiting for them leaves those in flight.
+    //      Unconditional loads with clamped indices: clamped rows / columns meet zero coefficients. ----
+    float2 y1[JT2], u2[JT2];
+    {
+      const int m3 = (col >> 1) < K ? (col >> 1) : K - 1;
+      const float2* yp = fz.y1 + (size_t)slab * fz.K2 * K + m3;
+      const float2* up = fz.ut + (size_t)half * I2 + 32 * ts + col;
+#pragma unroll
+      for (int jj = 0; jj < JT2; ++jj) {
+        const int m2 = 2 * jj + half;
+        y1[jj] = yp[(size_t)(m2 < fz.K2 ? m2 : fz.K2 - 1) * K];
+        u2[jj] = up[(size_t)(2 * jj) * I2];
+      }
+    }
+    // ---- this tile's W pieces go in flight ----
+    float4 wpre[kUpdPrefetch];
+#pragma unroll
+    for (int i = 0; i < kUpdPrefetch; ++i) {
+      const int q = lane_now + i * 64;
+      wpre[i] = w4[q < n4 ? q : n4 - 1];
+    }
+    // The stage-A operands are claimed here: the asm statements pin every load above them (memory
+    // clobber) and every use below them, so the scheduler cannot interleave load - wait - MFMA.
+#pragma unroll
+    for (int jj = 0; jj < JT2; ++jj)
+      asm volatile("" : "+v"(y1[jj].x), "+v"(y1[jj].y), "+v"(u2[jj].x), "+v"(u2[jj].y) : : "memory");
+    // ---- stage A: D' = rows of the mode-(N-1) expansion for the 32 rows of the tile ----
+    v16f dz;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) dz[r] = 0.f;
+#pragma unroll
+    for (int jj = 0; jj < JT2; ++jj) {
+      const float a1 = part ? y1[jj].y : y1[jj].x;
+      const float a2 = part ? y1[jj].x : -y1[jj].y;
+      dz = mfma32(a1, u2[jj].x, dz);
+      dz = mfma32(a2, u2[jj].y, dz);
+    }
+    // ---- the next tile's sparse state goes in flight ----
+    int64_t nnslab = nslab;
+    int nnts = nts;
+    advance(nnslab, nnts);
+    const bool have_nn = have_next && nnslab < nslabs;
+    const int64_t nn = have_nn ? nnslab * S + nnts : nxt;
+    issue_sparse(nj0, nj1);
+    const uint32_t nnj0 = sp.tile_start[nn + vzero], nnj1 = sp.tile_start[nn + 1 + vzero];
+    wave_sync();                                               // previous tile's LDS reads are done
+    // ---- stage B: expand the last mode: sD[row, c] = c_alpha * sum_k ..., NTB column tiles at a time ----
+    const float2* fl = sF + (2 * half) * ld + (col >> 1);      // row k(u, half) = (u & 1) + 4 (u >> 1) + 2 half
+    auto block = [&](int nt0, auto ntile_count) {
+      constexpr int N = decltype(ntile_count)::value;
+      v16f acc[N];
+#pragma unroll
+      for (int i = 0; i < N; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+      const float2* fb = fl + 16 * nt0;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+          const float2 b2 = column_coef(fb[((u & 1) + 4 * (u >> 1)) * ld + 16 * i], part);
+          acc[i] = mfma32(dz[2 * u], b2.x, acc[i]);
+          acc[i] = mfma32(dz[2 * u + 1], b2.y, acc[i]);
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < N; ++i) {
+        const int c = 32 * (nt0 + i) + col;
+        if (c < N2) {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) sD[d_row(r, half) * N2 + c] = c_alpha * acc[i][r];
+        }
+      }
+    };
+    {
+      int nt0 = 0;
+      for (; nt0 + NTB <= NT; nt0 += NTB) block(nt0, std::integral_constant<int, NTB>());
+      if (NTB > 1)
+        for (; nt0 < NT; ++nt0) block(nt0, std::integral_constant<int, 1>());
+    }
+    wave_sync();
+    // ---- AdamUpdate on the sparse values that live in this tile; add lambda N_S into the tile ----
+    for (uint32_t j = cj0 + lane; j < cj1; j += 64) {
+      const bool first = j == cj0 + lane;
+      const float2 x = first ? c_g : sp.gs[j];
+      float2 mm = first ? c_m : sp.ms[j];
+      const float v_old = first ? c_v : sp.vs[j];
+      const int32_t oj = first ? c_om : sp.omega[j];
+      mm.x = sp.beta1 * mm.x + (1.f - sp.beta1) * x.x;
+      mm.y = sp.beta1 * mm.y + (1.f - sp.beta1) * x.y;
+      const float vv = sp.beta2 * v_old + (1.f - sp.beta2) * (x.x * x.x + x.y * x.y);
+      sp.ms[j] = mm;
+      sp.vs[j] = vv;
+      const float d = sp.c_lambda * sp.inv_c1 / (sqrtf(vv * sp.inv_c2) + sp.eps);
+      const int e = (int)((int64_t)oj - w_base);
+      sD[2 * e] += d * mm.x;
+      sD[2 * e + 1] += d * mm.y;
+    }
+    wave_sync();
+    // ---- the wait point for everything still in flight, then stream the tile into W ----
+    claim_sparse();
+#pragma unroll
+    for (int i = 0; i < kUpdPrefetch; ++i) claim_raw(wpre[i]);
+    const float4* d4 = reinterpret_cast<const float4*>(sD);
+    const int nfull = n4 >> 6;
+#pragma unroll
+    for (int i = 0; i < kUpdPrefetch; ++i) {
+      const int q = lane_now + i * 64;
+      if (i < nfull || q < n4) {
+        const float4 d = d4[q];
+        const float4 o = wpre[i];
+        w4[q] = make_float4(decay * o.x + d.x, decay * o.y + d.y, decay * o.z + d.z, decay * o.w + d.w);
+      }
+    }
+    for (int q = lane + kUpdPrefetch * 64; q < n4; q += 64) {
+      const float4 d = d4[q];
+      const float4 o = w4[q];
+      w4[q] = make_float4(decay * o.x + d.x, decay * o.y + d.y, decay * o.z + d.z, decay * o.w + d.w);
+    }
+    if (!have_next) break;
+    tile = nxt;
+    slab = nslab;
+    ts = nts;
+    nxt = nn;
+    nslab = nnslab;
+    nts = nnts;
+    have_next = have_nn;
+    cj0 = nj0;
+    cj1 = nj1;
+    nj0 = nnj0;
+    nj1 = nnj1;
+  }
+}
+
+// Kernel-ready copies of the mode-(N-1) factor for the fused stages:
+//   fpad[i2][m2] = conj(U[i2, m2]) (m2 < r, else 0), 32 columns  -> second compression stage in k_lproj
+//   ut[m2][i2]   = U[i2, m2]       (m2 < r, else 0), 32 rows     -> first reconstruction stage in k_lupdate
+__global__ void k_pack_fused_factor(const float2* __restrict__ U, int I2, int r, float2* __restrict__ fpad,
+                                    float2* __restrict__ ut) {
+  const int e = blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= I2 * 32) return;
+  const int i2 = e >> 5, m2 = e & 31;
+  const float2 u = m2 < r ? U[(int64_t)i2 * r + m2] : make_float2(0.f, 0.f);
+  fpad[e] = make_float2(u.x, -u.y);
+  ut[(int64_t)m2 * I2 + i2] = u;
+}
+
 // tile_start[t] = #{ j : Omega_j < t * tile_elems }, t = 0 .. ntiles (Omega ascending).
 __global__ void k_tile_offsets(const int32_t* __restrict__ omega, int64_t k, int64_t tile_elems,
                                int64_t ntiles, uint32_t* __restrict__ tile_start) {
@@ -754,8 +1054,15 @@ void launch_mid(hipStream_t s, const float2* x, const float2* U, int rn, bool pr
 #undef TGRAD_MID
 }
 
+void launch_pack_fused_factor(hipStream_t s, const float2* U, int I2, int r, float2* fpad, float2* ut) {
+  k_pack_fused_factor<<<dim3((unsigned)((I2 * 32 + 255) / 256)), dim3(256), 0, s>>>(U, I2, r, fpad, ut);
+}
+
+// `fused_I2` > 0: also contract the next mode (extent fused_I2 = 32 S, rank fused_M2, factor copy
+// `fpad`) and write its result to `out` (slabs, fused_M2, M); otherwise `out` is (A, M).
 void launch_lproj(hipStream_t s, const void* g, int dtype, const int32_t* omega, const uint32_t* tile_start,
-                  float2* gs, const float2* U, int rn, const Stage& st, int W, float2* out) {
+                  float2* gs, const float2* U, int rn, const Stage& st, int W, float2* out, int fused_I2,
+                  int fused_M2, const float2* fpad) {
   const int64_t A = st.A;
   const int K = st.K, M = st.M;
   if (A * M <= 0) return;
@@ -763,25 +1070,35 @@ void launch_lproj(hipStream_t s, const void* g, int dtype, const int32_t* omega,
   const size_t lds = lproj_lds_bytes(W, K, M);
   const int NT = (2 * M + 31) / 32;
   const int ntb = NT >= 2 ? 2 : 1;
+  const bool fuse = fused_I2 > 0;
+  const int S = fuse ? fused_I2 / kTileRows : 1;
+  const int64_t nslabs = (ntiles + S - 1) / S;
   const int per_cu = (int)(kLdsLimit / (lds ? lds : 1));
-  dim3 grid((unsigned)grid_for_tiles((ntiles + W - 1) / W, per_cu < 1 ? 1 : per_cu > 2 ? 2 : per_cu)), block(64 * W);
+  dim3 grid((unsigned)grid_for_tiles((nslabs + W - 1) / W, per_cu < 1 ? 1 : per_cu > 2 ? 2 : per_cu)), block(64 * W);
   float* of = reinterpret_cast<float*>(out);
   const uint32_t magic = magic_for(K);
-#define TGRAD_LP(DT_, W_, NTB_, F_)                                                                     \
+  FusedNext fz{fpad, of, S, fused_M2};
+#define TGRAD_LP(DT_, W_, NTB_, F_, Z_)                                                                  \
   do {                                                                                                   \
-    allow_lds(k_lproj<DT_, W_, NTB_, F_>, lds);                                                          \
-    k_lproj<DT_, W_, NTB_, F_><<<grid, block, lds, s>>>(g, omega, tile_start, gs, U, rn, A, K, M, magic, \
-                                                        ntiles, of);                                     \
+    allow_lds(k_lproj<DT_, W_, NTB_, F_, Z_>, lds);                                                      \
+    k_lproj<DT_, W_, NTB_, F_, Z_><<<grid, block, lds, s>>>(g, omega, tile_start, gs, U, rn, A, K, M,    \
+                                                            magic, ntiles, of, fz);                      \
   } while (0)
 #define TGRAD_LP_F(DT_, W_, NTB_)                                                                        \
   do {                                                                                                   \
-    if (K & 1) TGRAD_LP(DT_, W_, NTB_, true); else TGRAD_LP(DT_, W_, NTB_, false);                       \
+    if (K & 1) TGRAD_LP(DT_, W_, NTB_, true, false); else TGRAD_LP(DT_, W_, NTB_, false, false);         \
   } while (0)
 #define TGRAD_LP_W(DT_, NTB_)                                                                            \
   do {                                                                                                   \
     if (W == 4) TGRAD_LP_F(DT_, 4, NTB_); else if (W == 2) TGRAD_LP_F(DT_, 2, NTB_); else TGRAD_LP_F(DT_, 1, NTB_); \
   } while (0)
-  if (dtype == TGRAD_C64) {
+  if (fuse) {                                   // the host only fuses with W == 4 and one column tile
+    if (dtype == TGRAD_C64) {
+      if (K & 1) TGRAD_LP(TGRAD_C64, 4, 1, true, true); else TGRAD_LP(TGRAD_C64, 4, 1, false, true);
+    } else {
+      if (K & 1) TGRAD_LP(TGRAD_CBF16, 4, 1, true, true); else TGRAD_LP(TGRAD_CBF16, 4, 1, false, true);
+    }
+  } else if (dtype == TGRAD_C64) {
     if (ntb == 2) TGRAD_LP_W(TGRAD_C64, 2); else TGRAD_LP_W(TGRAD_C64, 1);
   } else {
     if (ntb == 2) TGRAD_LP_W(TGRAD_CBF16, 2); else TGRAD_LP_W(TGRAD_CBF16, 1);
@@ -802,7 +1119,7 @@ void launch_lupdate(hipStream_t s, const float2* z, const float2* U, const Stage
   const size_t lds = lupdate_lds_bytes(W, K, M);
   const int per_cu = (int)(kLdsLimit / (lds ? lds : 1));
   dim3 grid((unsigned)grid_for_tiles((ntiles + W - 1) / W, per_cu < 1 ? 1 : per_cu > 2 ? 2 : per_cu)), block(64 * W);
-  SparseAdam sp{omega, tile_start, gs, ms, vs, beta1, beta2, inv_c1, inv_c2, eps, c_lambda};
+  SparseAdam sp{omega, tile_start, gs, ms, vs, beta1, beta2, inv_c1, inv_c2, eps, c_lambda, 0};
   const float* zf = reinterpret_cast<const float*>(z);
   float* wf = reinterpret_cast<float*>(w);
   const int jt = lupdate_jt(K);
@@ -819,6 +1136,36 @@ void launch_lupdate(hipStream_t s, const float2* z, const float2* U, const Stage
   if (W == 4) TGRAD_LU_J(4); else if (W == 2) TGRAD_LU_J(2); else TGRAD_LU_J(1);
 #undef TGRAD_LU_J
 #undef TGRAD_LU
+}
+
+// k_lupdate with the reconstruction stage of mode N-1 in front (see k_lupdate_fused): `y1` is the
+// tensor before that stage, (slabs, K2, K) complex; `ut` the transposed factor copy; I2 = 32 S.
+void launch_lupdate_fused(hipStream_t s, const float2* y1, const float2* ut, int I2, int K2, const float2* U,
+                          const Stage& st, float2* w, float decay, float c_alpha, const int32_t* omega,
+                          const uint32_t* tile_start, int64_t k, const float2* gs, float2* ms, float* vs,
+                          float beta1, float beta2, float inv_c1, float inv_c2, float eps, float c_lambda) {
+  const int64_t A = st.A;
+  const int K = st.K, M = st.M;
+  if (A * M <= 0) return;
+  constexpr int W = 4;
+  const int64_t ntiles = A / kTileRows;
+  const int S = I2 / kTileRows;
+  const int64_t nslabs = ntiles / S;
+  const int NT = (2 * M + 31) / 32;
+  const size_t lds = (size_t)W * ((kTileRows * 2 * M + 3) & ~3) * 4 + (size_t)16 * 16 * NT * 8;
+  const int per_cu = (int)(kLdsLimit / (lds ? lds : 1));
+  dim3 grid((unsigned)grid_for_tiles((nslabs + W - 1) / W, per_cu < 1 ? 1 : per_cu > 2 ? 2 : per_cu)), block(64 * W);
+  SparseAdam sp{omega, tile_start, gs, ms, vs, beta1, beta2, inv_c1, inv_c2, eps, c_lambda,
+                (int)(k > 0 ? k - 1 : 0)};
+  FusedPrev fz{y1, ut, S, K2};
+  float* wf = reinterpret_cast<float*>(w);
+#define TGRAD_LUF(JT2_)                                                                                  \
+  do {                                                                                                   \
+    allow_lds(k_lupdate_fused<W, 1, JT2_>, lds);                                                         \
+    k_lupdate_fused<W, 1, JT2_><<<grid, block, lds, s>>>(U, A, K, M, ntiles, wf, decay, c_alpha, sp, fz); \
+  } while (0)
+  if (K2 <= 8) TGRAD_LUF(4); else if (K2 <= 16) TGRAD_LUF(8); else TGRAD_LUF(16);
+#undef TGRAD_LUF
 }
 
 }  // namespace tgrad

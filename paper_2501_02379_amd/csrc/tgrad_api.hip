@@ -43,10 +43,11 @@ struct Plan {
   int tile_waves = 0;            // last-mode kernels: wavefronts per workgroup; 0 = generic kernels
   int64_t ntiles = 0;            // tiles of the tensor seen as (I / I_N rows, I_N)
   int64_t tile_elems = 0;
+  bool fuse_next = false;        // the last-mode kernels also handle mode N-1 (see make_plan)
   // byte offsets into state
   size_t st_omega, st_ms, st_vs, st_ml, st_vl, st_U[kMaxNdim], state_bytes;
   // byte offsets into workspace
-  size_t ws_sel, ws_hist, ws_seg_gt, ws_seg_eq, ws_mask, ws_tile_start, ws_partials, ws_gram[kMaxNdim],
+  size_t ws_sel, ws_hist, ws_seg_gt, ws_seg_eq, ws_mask, ws_tile_start, ws_fpad, ws_ut, ws_partials, ws_gram[kMaxNdim],
       ws_eig_a[kMaxNdim], ws_eig_v[kMaxNdim], ws_gs, ws_core_g, ws_core_n, ws_buf[2], workspace_bytes;
   int gram_chunks[kMaxNdim];
 };
@@ -125,6 +126,16 @@ void make_plan(const tgrad_config* c, Plan* p) {
     const int64_t rows = p->I / p->shape[last];
     p->ntiles = (rows + 31) / 32;                 // last-mode kernels: flat tiles of 32 rows
     p->tile_elems = (int64_t)32 * p->shape[last];
+    // Fusion of the mode-(N-1) stages into the last-mode kernels: needs whole 32-row tiles per slab,
+    // one column tile of the last mode (r_N <= 16), r_(N-1) <= 32, and enough slabs to fill the chip.
+    bool fuse = p->tile_waves == 4 && N >= 3;
+    if (const char* e = std::getenv("TGRAD_FUSE")) fuse = fuse && std::atoi(e) != 0;       // tuning knob
+    if (fuse) {
+      const int64_t I2 = p->shape[last - 1];
+      fuse = (I2 % 32 == 0) && I2 <= TGRAD_MAX_EXTENT && p->rank[last - 1] <= 32 && 2 * p->rank[last] <= 32 &&
+             rows / I2 >= 512;
+    }
+    p->fuse_next = fuse;
   }
 
   size_t o = 0;
@@ -148,6 +159,8 @@ void make_plan(const tgrad_config* c, Plan* p) {
   p->ws_seg_eq = take((size_t)p->nseg * 4);
   p->ws_mask = take((size_t)p->mask_words * 4);
   p->ws_tile_start = take((size_t)(p->ntiles + 1) * 4);
+  p->ws_fpad = take(p->fuse_next ? (size_t)p->shape[N - 2] * 32 * 8 : 0);
+  p->ws_ut = take(p->fuse_next ? (size_t)p->shape[N - 2] * 32 * 8 : 0);
   size_t partial_max = 0;
   for (int n = 0; n < N; ++n) {
     int64_t A = 1, B = 1;
@@ -337,15 +350,30 @@ int do_step(tgrad_ctx* c, void* weight, const void* g) {
 
   // g_S <- Sparse(G, Omega);  g_L <- (G - g_S) x_N UN^H ... x_1 U1^H
   if (!mfma_last) { Scope sc_(c, KID_GATHER); launch_gather(s, g, cf.grad_dtype, omega, p.k, gs); }
+  if (p.fuse_next) {
+    Scope sc_(c, KID_FACTOR_PACK);
+    launch_pack_fused_factor(s, c->st<float2>(p.st_U[N - 2]), (int)p.shape[N - 2], p.rank[N - 2],
+                             c->w<float2>(p.ws_fpad), c->w<float2>(p.ws_ut));
+  }
   const float2* src = nullptr;
   for (int st = 0; st < N; ++st) {
     const Stage& sg = p.proj[st];
     float2* dst = (st == N - 1) ? core_g : buf[st & 1];
     const float2* U = c->st<float2>(p.st_U[sg.mode]);
+    if (st == 0 && mfma_last && p.fuse_next) {                 // stages 0 and 1 in one kernel
+      float2* dst1 = (N == 2) ? core_g : buf[1];
+      Scope sc_(c, KID_PROJECT_FIRST);
+      launch_lproj(s, g, cf.grad_dtype, omega, tile_start, gs, U, p.rank[sg.mode], sg, p.tile_waves, dst1,
+                   (int)p.shape[N - 2], p.rank[N - 2], c->w<float2>(p.ws_fpad));
+      src = dst1;
+      st = 1;
+      continue;
+    }
     Scope sc_(c, st == 0 ? KID_PROJECT_FIRST : KID_PROJECT);
     if (st == 0) {
       if (mfma_last)
-        launch_lproj(s, g, cf.grad_dtype, omega, tile_start, gs, U, p.rank[sg.mode], sg, p.tile_waves, dst);
+        launch_lproj(s, g, cf.grad_dtype, omega, tile_start, gs, U, p.rank[sg.mode], sg, p.tile_waves, dst, 0, 0,
+                     nullptr);
       else
         launch_contract(s, g, cf.grad_dtype, mask, U, (int)p.shape[sg.mode], p.rank[sg.mode], true, sg, dst);
     } else {
@@ -367,7 +395,8 @@ int do_step(tgrad_ctx* c, void* weight, const void* g) {
   // D <- alpha (N_L x_1 U1 ... x_N UN); the last stage is fused with AdamUpdate on the sparse values,
   // D[Omega] += lambda N_S and W <- W (1 - lr wd) - lr D
   const float2* zsrc = core_n;
-  for (int st = 0; st + 1 < N; ++st) {
+  const int nmid = (mfma_last && p.fuse_next) ? N - 2 : N - 1;   // reconstruction stages run by k_mid
+  for (int st = 0; st < nmid; ++st) {
     const Stage& sg = p.back[st];
     float2* dst = buf[st & 1];
     const float2* U = c->st<float2>(p.st_U[sg.mode]);
@@ -379,7 +408,13 @@ int do_step(tgrad_ctx* c, void* weight, const void* g) {
     const Stage& sg = p.back[N - 1];
     const float2* U = c->st<float2>(p.st_U[sg.mode]);
     const float decay = 1.f - cf.lr * cf.weight_decay;
-    if (mfma_last) {
+    if (mfma_last && p.fuse_next) {
+      Scope sc_(c, KID_UPDATE);
+      launch_lupdate_fused(s, zsrc, c->w<float2>(p.ws_ut), (int)p.shape[N - 2], p.rank[N - 2], U, sg,
+                           reinterpret_cast<float2*>(weight), decay, -cf.lr * cf.alpha, omega, tile_start, p.k, gs,
+                           c->st<float2>(p.st_ms), c->st<float>(p.st_vs), cf.beta1, cf.beta2, inv_c1, inv_c2,
+                           cf.eps, -cf.lr * cf.lambda);
+    } else if (mfma_last) {
       Scope sc_(c, KID_UPDATE);
       launch_lupdate(s, zsrc, U, sg, p.tile_waves, reinterpret_cast<float2*>(weight), decay, -cf.lr * cf.alpha,
                      omega, tile_start, gs, c->st<float2>(p.st_ms), c->st<float>(p.st_vs), cf.beta1, cf.beta2,

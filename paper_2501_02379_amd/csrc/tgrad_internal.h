@@ -84,11 +84,18 @@ void launch_tile_offsets(hipStream_t s, const int32_t* omega, int64_t k, int64_t
                          int64_t ntiles, uint32_t* tile_start);
 void launch_mid(hipStream_t s, const float2* x, const float2* U, int rn, bool project, const Stage& st,
                 float2* out);
+void launch_pack_fused_factor(hipStream_t s, const float2* U, int I2, int r, float2* fpad, float2* ut);
 void launch_lproj(hipStream_t s, const void* g, int dtype, const int32_t* omega, const uint32_t* tile_start,
-                  float2* gs, const float2* U, int rn, const Stage& st, int W, float2* out);
+                  float2* gs, const float2* U, int rn, const Stage& st, int W, float2* out, int fused_I2,
+                  int fused_M2, const float2* fpad);
 void launch_lupdate(hipStream_t s, const float2* z, const float2* U, const Stage& st, int W, float2* w,
                     float decay, float c_alpha, const int32_t* omega, const uint32_t* tile_start,
                     const float2* gs, float2* ms, float* vs, float beta1, float beta2, float inv_c1,
                     float inv_c2, float eps, float c_lambda);
+
+void launch_lupdate_fused(hipStream_t s, const float2* y1, const float2* ut, int I2, int K2, const float2* U,
+                          const Stage& st, float2* w, float decay, float c_alpha, const int32_t* omega,
+                          const uint32_t* tile_start, int64_t k, const float2* gs, float2* ms, float* vs,
+                          float beta1, float beta2, float inv_c1, float inv_c2, float eps, float c_lambda);
 
 }  // namespace tgrad
