@@ -383,25 +383,17 @@ __global__ __launch_bounds__(64 * W, 2) void k_lproj(const void* __restrict__ g,
       const uint32_t r = div_magic((uint32_t)e, magicK);
       *reinterpret_cast<float2*>(&sX[r * stride + 2 * ((uint32_t)e - r * (uint32_t)K)]) = v;
     }
-    wave_sync();
-    // ---- Sparse(G, Omega) of this tile: hand the values over, then remove them ----
-    for (uint32_t j = cj0 + lane; j < cj1; j += 64) {
-      const int32_t oj = (j == cj0 + lane) ? my_om : omega[j];
-      const uint32_t e = (uint32_t)((int64_t)oj - e_base);
-      const uint32_t r = flat ? 0u : div_magic(e, magicK);
-      float2* p = reinterpret_cast<float2*>(&sX[r * stride + 2 * (e - r * (uint32_t)K)]);
-      gs[j] = *p;
-      *p = make_float2(0.f, 0.f);
-    }
-    wave_sync();
-    // ---- second-stage factor operands of this tile (FUSE), then the next tile's loads go in flight;
-    //      its support range was fetched one tile earlier.  All unconditional: see `issue`. ----
+    // ---- second-stage factor operands of this tile (FUSE): small, cache-resident; issued before
+    //      the next tile's loads so that waiting for them leaves those in flight ----
     float2 f2s[FUSE ? 16 : 1];
     if constexpr (FUSE) {
       const float2* fp = fz.fpad + (size_t)(32 * ts + 4 * half) * 32 + col;
 #pragma unroll
       for (int r = 0; r < 16; ++r) f2s[r] = fp[((r & 3) + 8 * (r >> 2)) * 32];
     }
+    // ---- the staging registers are free: the next tile's loads go in flight right away (its
+    //      support range was fetched one tile earlier).  All unconditional: see `issue`. ----
+    const int32_t cur_om = my_om;
     int64_t nnslab = nslab;
     int nnts = nts;
     advance(nnslab, nnts);
@@ -409,6 +401,21 @@ __global__ __launch_bounds__(64 * W, 2) void k_lproj(const void* __restrict__ g,
     const int64_t nn = have_nn ? nnslab * S + nnts : nxt;
     issue(nxt, nj0, nj1);
     const uint32_t nnj0 = tile_start[nn + vzero], nnj1 = tile_start[nn + 1 + vzero];
+    wave_sync();
+    // ---- Sparse(G, Omega) of this tile: hand the values over, then remove them ----
+    // (the first 64 entries of the tile were prefetched with it: the common path loads nothing, so
+    // it never waits for the loads just issued; longer ranges take the rare second loop)
+    auto take_entry = [&](uint32_t j, int32_t oj) {
+      const uint32_t e = (uint32_t)((int64_t)oj - e_base);
+      const uint32_t r = flat ? 0u : div_magic(e, magicK);
+      float2* p = reinterpret_cast<float2*>(&sX[r * stride + 2 * (e - r * (uint32_t)K)]);
+      gs[j] = *p;
+      *p = make_float2(0.f, 0.f);
+    };
+    if (cj0 + lane < cj1) take_entry(cj0 + lane, cur_om);
+    if (cj1 - cj0 > 64u)
+      for (uint32_t j = cj0 + 64u + lane; j < cj1; j += 64) take_entry(j, omega[j]);
+    wave_sync();
     // ---- the 32 rows through the matrix cores, NTB column tiles at a time ----
     const int64_t grow0 = tile * kTileRows;
     auto block = [&](int nt0, auto ntile_count) {
@@ -516,6 +523,21 @@ struct SparseAdam {
   float beta1, beta2, inv_c1, inv_c2, eps, c_lambda;
   int k_last;           // max(k, 1) - 1: a support position that is always safe to read
 };
+
+// AdamUpdate on sparse entry j (value x at support position oj, moments mm / v_old) and
+// tile[oj] += (-lr lambda) N_S[j]; `sD` is the flat LDS image of the W tile that starts at w_base.
+__device__ __forceinline__ void sparse_adam_entry(const SparseAdam& sp, uint32_t j, int32_t oj, float2 x,
+                                                  float2 mm, float v_old, int64_t w_base, float* sD) {
+  mm.x = sp.beta1 * mm.x + (1.f - sp.beta1) * x.x;
+  mm.y = sp.beta1 * mm.y + (1.f - sp.beta1) * x.y;
+  const float vv = sp.beta2 * v_old + (1.f - sp.beta2) * (x.x * x.x + x.y * x.y);
+  sp.ms[j] = mm;
+  sp.vs[j] = vv;
+  const float d = sp.c_lambda * sp.inv_c1 / (sqrtf(vv * sp.inv_c2) + sp.eps);
+  const int e = (int)((int64_t)oj - w_base);
+  sD[2 * e] += d * mm.x;
+  sD[2 * e + 1] += d * mm.y;
+}
 
 constexpr int kUpdPrefetch = 17;          // 16-byte pieces of W per lane kept in flight during the MFMA phase
 
@@ -654,22 +676,10 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate(const float* __restrict__
     }
     wave_sync();
     // ---- AdamUpdate on the sparse values that live in this tile; add lambda N_S into the tile ----
-    for (uint32_t j = cj0 + lane; j < cj1; j += 64) {
-      const bool first = j == cj0 + lane;
-      const float2 x = first ? c_g : sp.gs[j];
-      float2 mm = first ? c_m : sp.ms[j];
-      const float v_old = first ? c_v : sp.vs[j];
-      const int32_t oj = first ? c_om : sp.omega[j];
-      mm.x = sp.beta1 * mm.x + (1.f - sp.beta1) * x.x;
-      mm.y = sp.beta1 * mm.y + (1.f - sp.beta1) * x.y;
-      const float vv = sp.beta2 * v_old + (1.f - sp.beta2) * (x.x * x.x + x.y * x.y);
-      sp.ms[j] = mm;
-      sp.vs[j] = vv;
-      const float d = sp.c_lambda * sp.inv_c1 / (sqrtf(vv * sp.inv_c2) + sp.eps);
-      const int e = (int)((int64_t)oj - w_base);
-      sD[2 * e] += d * mm.x;
-      sD[2 * e + 1] += d * mm.y;
-    }
+    if (cj0 + lane < cj1) sparse_adam_entry(sp, cj0 + lane, c_om, c_g, c_m, c_v, w_base, sD);
+    if (cj1 - cj0 > 64u)                                       // rare: more than 64 entries in one tile
+      for (uint32_t j = cj0 + 64u + lane; j < cj1; j += 64)
+        sparse_adam_entry(sp, j, sp.omega[j], sp.gs[j], sp.ms[j], sp.vs[j], w_base, sD);
     wave_sync();
     // ---- stream the tile into W ----
     claim_small();
@@ -879,22 +889,10 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate_fused(const float2* __res
     }
     wave_sync();
     // ---- AdamUpdate on the sparse values that live in this tile; add lambda N_S into the tile ----
-    for (uint32_t j = cj0 + lane; j < cj1; j += 64) {
-      const bool first = j == cj0 + lane;
-      const float2 x = first ? c_g : sp.gs[j];
-      float2 mm = first ? c_m : sp.ms[j];
-      const float v_old = first ? c_v : sp.vs[j];
-      const int32_t oj = first ? c_om : sp.omega[j];
-      mm.x = sp.beta1 * mm.x + (1.f - sp.beta1) * x.x;
-      mm.y = sp.beta1 * mm.y + (1.f - sp.beta1) * x.y;
-      const float vv = sp.beta2 * v_old + (1.f - sp.beta2) * (x.x * x.x + x.y * x.y);
-      sp.ms[j] = mm;
-      sp.vs[j] = vv;
-      const float d = sp.c_lambda * sp.inv_c1 / (sqrtf(vv * sp.inv_c2) + sp.eps);
-      const int e = (int)((int64_t)oj - w_base);
-      sD[2 * e] += d * mm.x;
-      sD[2 * e + 1] += d * mm.y;
-    }
+    if (cj0 + lane < cj1) sparse_adam_entry(sp, cj0 + lane, c_om, c_g, c_m, c_v, w_base, sD);
+    if (cj1 - cj0 > 64u)                                       // rare: more than 64 entries in one tile
+      for (uint32_t j = cj0 + 64u + lane; j < cj1; j += 64)
+        sparse_adam_entry(sp, j, sp.omega[j], sp.gs[j], sp.ms[j], sp.vs[j], w_base, sD);
     wave_sync();
     // ---- the wait point for everything still in flight, then stream the tile into W ----
     claim_sparse();
