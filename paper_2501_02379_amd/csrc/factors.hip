@@ -151,11 +151,80 @@ struct EigJobs {
 constexpr int kEigThreads = 1024;
 constexpr int kEigMaxN = TGRAD_MAX_EXTENT;
 constexpr int kEigMaxSweeps = 30;
+constexpr int kEigBatch = 4;           // rotations per thread whose loads are in flight together
 
 __device__ __forceinline__ double2 cmuld(double2 a, double2 b) {
   return make_double2(a.x * b.x - a.y * b.y, a.x * b.y + a.y * b.x);
 }
 __device__ __forceinline__ double2 conjd(double2 a) { return make_double2(a.x, -a.y); }
+
+// Shared tail of the eigensolvers: order the eigenvalues in `lam` descending (ties: lower index
+// first), keep the first r, give every kept column of V the unit phase that makes its
+// largest-modulus entry (first on ties) real and positive, and write U (n x r, float32).
+__device__ void eig_finish(int n, int r, int tid, const double* lam, int* col_of, double2* phase,
+                           const double2* V, float2* U) {
+  for (int i = tid; i < n; i += kEigThreads) {
+    int rank = 0;
+    const double li = lam[i];
+    for (int j = 0; j < n; ++j) rank += (lam[j] > li || (lam[j] == li && j < i)) ? 1 : 0;
+    if (rank < r) col_of[rank] = i;
+  }
+  __syncthreads();
+  for (int cidx = tid; cidx < r; cidx += kEigThreads) {
+    const int src = col_of[cidx];
+    double best = -1.;
+    double2 vb = make_double2(1., 0.);
+    for (int i = 0; i < n; ++i) {
+      const double2 v = V[i * n + src];
+      const double a2 = v.x * v.x + v.y * v.y;
+      if (a2 > best) {
+        best = a2;
+        vb = v;
+      }
+    }
+    const double mag = sqrt(best);
+    phase[cidx] = mag > 0. ? make_double2(vb.x / mag, -vb.y / mag) : make_double2(1., 0.);
+  }
+  __syncthreads();
+  for (int e = tid; e < n * r; e += kEigThreads) {
+    const int i = e / r, cidx = e - i * r;
+    const double2 v = cmuld(V[i * n + col_of[cidx]], phase[cidx]);
+    U[e] = make_float2((float)v.x, (float)v.y);
+  }
+}
+
+// Pair (p, q), p < q, of round `round` for slot `slot` of the round-robin tournament on m players.
+__device__ __forceinline__ void jacobi_pair(int slot, int round, int m, int& p, int& q) {
+  if (slot == 0) {
+    p = m - 1;
+    q = round;
+  } else {
+    p = (round + slot) % (m - 1);
+    q = (round - slot + (m - 1)) % (m - 1);
+  }
+  if (p > q) {
+    const int t = p;
+    p = q;
+    q = t;
+  }
+}
+
+// Rotation that annihilates a_pq of the Hermitian 2 x 2 pivot [[app, apq], [conj(apq), aqq]]:
+// c = cos, s = sin e^{i phi}.  Returns false (c = 1, s = 0) when a_pq is already negligible.
+__device__ __forceinline__ bool jacobi_rotation(double app, double aqq, double2 apq, double eps2, double floor2,
+                                                double& c, double2& s) {
+  c = 1.;
+  s = make_double2(0., 0.);
+  const double mag2 = apq.x * apq.x + apq.y * apq.y;
+  if (!(mag2 > eps2 * fabs(app * aqq) && mag2 > floor2)) return false;
+  const double mag = sqrt(mag2);
+  const double tau = (aqq - app) / (2. * mag);
+  const double t = (tau >= 0. ? 1. : -1.) / (fabs(tau) + sqrt(1. + tau * tau));
+  c = 1. / sqrt(1. + t * t);
+  const double sn = t * c;
+  s = make_double2(sn * apq.x / mag, sn * apq.y / mag);
+  return true;
+}
 
 __global__ __launch_bounds__(kEigThreads) void k_eig(EigJobs jobs) {
   const EigJob jb = jobs.job[blockIdx.x];
@@ -203,35 +272,12 @@ __global__ __launch_bounds__(kEigThreads) void k_eig(EigJobs jobs) {
       // ---- phase 1: pairs of this round and their rotations ----
       if (tid < half) {
         int p, q;
-        if (tid == 0) {
-          p = m - 1;
-          q = round;
-        } else {
-          p = (round + tid) % (m - 1);
-          q = (round - tid + (m - 1)) % (m - 1);
-        }
-        if (p > q) {
-          int t = p;
-          p = q;
-          q = t;
-        }
+        jacobi_pair(tid, round, m, p, q);
         int rot = 0;
         double c = 1.;
         double2 s = make_double2(0., 0.);
-        if (q < n) {                                   // q == n is the padding player of an odd n
-          const double2 apq = A[p * n + q];
-          const double app = A[p * n + p].x, aqq = A[q * n + q].x;
-          const double mag2 = apq.x * apq.x + apq.y * apq.y;
-          if (mag2 > eps2 * fabs(app * aqq) && mag2 > floor2) {
-            const double mag = sqrt(mag2);
-            const double tau = (aqq - app) / (2. * mag);
-            const double t = (tau >= 0. ? 1. : -1.) / (fabs(tau) + sqrt(1. + tau * tau));
-            c = 1. / sqrt(1. + t * t);
-            const double sn = t * c;
-            s = make_double2(sn * apq.x / mag, sn * apq.y / mag);   // s e^{i phi}
-            rot = 1;
-          }
-        }
+        if (q < n)                                     // q == n is the padding player of an odd n
+          rot = jacobi_rotation(A[p * n + p].x, A[q * n + q].x, A[p * n + q], eps2, floor2, c, s) ? 1 : 0;
         sp[tid] = p;
         sq[tid] = q;
         sc[tid] = c;
@@ -242,33 +288,72 @@ __global__ __launch_bounds__(kEigThreads) void k_eig(EigJobs jobs) {
       __syncthreads();
       // ---- phase 2: column rotations  X[:, p] <- c X[:, p] - conj(s) X[:, q],
       //                                 X[:, q] <- s X[:, p] + c X[:, q]   for X in {A, V} ----
-      for (int e = tid; e < 2 * n * half; e += kEigThreads) {
-        const int which = e / (n * half);
-        const int e2 = e - which * (n * half);
-        const int i = e2 / half, pr = e2 - i * half;
-        if (!srot[pr]) continue;
-        double2* X = which ? V : A;
-        const int p = sp[pr], q = sq[pr];
-        const double c = sc[pr];
-        const double2 s = ss[pr];
-        const double2 xp = X[i * n + p], xq = X[i * n + q];
-        const double2 t1 = cmuld(conjd(s), xq), t2 = cmuld(s, xp);
-        X[i * n + p] = make_double2(c * xp.x - t1.x, c * xp.y - t1.y);
-        X[i * n + q] = make_double2(t2.x + c * xq.x, t2.y + c * xq.y);
+      // (loads of a batch are all issued before the first use: one memory round trip per batch)
+      for (int e0 = tid; e0 < 2 * n * half; e0 += kEigThreads * kEigBatch) {
+        double2 xp[kEigBatch], xq[kEigBatch];
+        int off_p[kEigBatch], off_q[kEigBatch], prs[kEigBatch];      // prs: pair | (matrix << 16), -1 = idle
+#pragma unroll
+        for (int u = 0; u < kEigBatch; ++u) {
+          const int e = e0 + u * kEigThreads;
+          prs[u] = -1;
+          if (e < 2 * n * half) {
+            const int which = e / (n * half);
+            const int e2 = e - which * (n * half);
+            const int i = e2 / half, pr = e2 - i * half;
+            if (srot[pr]) {
+              const double2* X = which ? V : A;
+              prs[u] = pr | (which << 16);
+              off_p[u] = i * n + sp[pr];
+              off_q[u] = i * n + sq[pr];
+              xp[u] = X[off_p[u]];
+              xq[u] = X[off_q[u]];
+            }
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < kEigBatch; ++u) {
+          if (prs[u] >= 0) {
+            double2* X = (prs[u] >> 16) ? V : A;
+            const int pr = prs[u] & 0xFFFF;
+            const double c = sc[pr];
+            const double2 s = ss[pr];
+            const double2 t1 = cmuld(conjd(s), xq[u]), t2 = cmuld(s, xp[u]);
+            X[off_p[u]] = make_double2(c * xp[u].x - t1.x, c * xp[u].y - t1.y);
+            X[off_q[u]] = make_double2(t2.x + c * xq[u].x, t2.y + c * xq[u].y);
+          }
+        }
       }
       __syncthreads();
       // ---- phase 3: row rotations  A[p, :] <- c A[p, :] - s A[q, :],
       //                              A[q, :] <- conj(s) A[p, :] + c A[q, :] ----
-      for (int e = tid; e < half * n; e += kEigThreads) {
-        const int pr = e / n, j = e - pr * n;
-        if (!srot[pr]) continue;
-        const int p = sp[pr], q = sq[pr];
-        const double c = sc[pr];
-        const double2 s = ss[pr];
-        const double2 xp = A[p * n + j], xq = A[q * n + j];
-        const double2 t1 = cmuld(s, xq), t2 = cmuld(conjd(s), xp);
-        A[p * n + j] = make_double2(c * xp.x - t1.x, c * xp.y - t1.y);
-        A[q * n + j] = make_double2(t2.x + c * xq.x, t2.y + c * xq.y);
+      for (int e0 = tid; e0 < half * n; e0 += kEigThreads * kEigBatch) {
+        double2 xp[kEigBatch], xq[kEigBatch];
+        int off_p[kEigBatch], off_q[kEigBatch], prs[kEigBatch];
+#pragma unroll
+        for (int u = 0; u < kEigBatch; ++u) {
+          const int e = e0 + u * kEigThreads;
+          prs[u] = -1;
+          if (e < half * n) {
+            const int pr = e / n, j = e - pr * n;
+            if (srot[pr]) {
+              prs[u] = pr;
+              off_p[u] = sp[pr] * n + j;
+              off_q[u] = sq[pr] * n + j;
+              xp[u] = A[off_p[u]];
+              xq[u] = A[off_q[u]];
+            }
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < kEigBatch; ++u) {
+          if (prs[u] >= 0) {
+            const double c = sc[prs[u]];
+            const double2 s = ss[prs[u]];
+            const double2 t1 = cmuld(s, xq[u]), t2 = cmuld(conjd(s), xp[u]);
+            A[off_p[u]] = make_double2(c * xp[u].x - t1.x, c * xp[u].y - t1.y);
+            A[off_q[u]] = make_double2(t2.x + c * xq[u].x, t2.y + c * xq[u].y);
+          }
+        }
       }
       __syncthreads();
     }
@@ -277,39 +362,178 @@ __global__ __launch_bounds__(kEigThreads) void k_eig(EigJobs jobs) {
     if (done) break;
   }
 
-  // ---- order eigenvalues descending (ties: lower index first), keep the first r ----
   for (int i = tid; i < n; i += kEigThreads) lam[i] = A[i * n + i].x;
   __syncthreads();
-  for (int i = tid; i < n; i += kEigThreads) {
-    int rank = 0;
-    const double li = lam[i];
-    for (int j = 0; j < n; ++j) rank += (lam[j] > li || (lam[j] == li && j < i)) ? 1 : 0;
-    if (rank < r) col_of[rank] = i;
+  eig_finish(n, r, tid, lam, col_of, phase, V, reinterpret_cast<float2*>(jb.U));
+}
+
+// The same solver for n <= 128 with the Hermitian work matrix held in LDS (lower triangle,
+// n (n + 1) / 2 complex doubles <= 132 KB): a round is then one barrier-separated pair of phases
+// on LDS - rotations from the pivots, then every 2 x 2 block (pair a, pair b), a >= b, updated in one
+// step as  L_a B R_b  (the column and the row rotation of the two-pass form fused) - and only the
+// eigenvector accumulator V goes through memory, once per round.
+constexpr int kEigTriMaxN = 128;
+
+__device__ __forceinline__ int tri_idx(int i, int j) { return i * (i + 1) / 2 + j; }           // i >= j
+__device__ __forceinline__ double2 tri_get(const double2* T, int i, int j) {
+  return i >= j ? T[tri_idx(i, j)] : conjd(T[tri_idx(j, i)]);
+}
+__device__ __forceinline__ void tri_put(double2* T, int i, int j, double2 v) {
+  if (i >= j) T[tri_idx(i, j)] = v; else T[tri_idx(j, i)] = conjd(v);
+}
+
+__global__ __launch_bounds__(kEigThreads) void k_eig_tri(EigJobs jobs) {
+  extern __shared__ double2 T[];                // lower triangle of the work matrix
+  const EigJob jb = jobs.job[blockIdx.x];
+  const int n = jb.n, r = jb.r;
+  const int tid = threadIdx.x;
+  double2* V = reinterpret_cast<double2*>(jb.V);
+  const double2* G = reinterpret_cast<const double2*>(jb.gram);
+
+  __shared__ int sp[kEigTriMaxN / 2 + 1], sq[kEigTriMaxN / 2 + 1];
+  __shared__ double sc[kEigTriMaxN / 2 + 1];
+  __shared__ double2 ss[kEigTriMaxN / 2 + 1];
+  __shared__ int srot[kEigTriMaxN / 2 + 1];
+  __shared__ int nrot;
+  __shared__ double red[kEigThreads];
+  __shared__ double lam[kEigTriMaxN];
+  __shared__ int col_of[kEigTriMaxN];
+  __shared__ double2 phase[kEigTriMaxN];
+
+  double tr = 0.;
+  for (int e = tid; e < n * n; e += kEigThreads) {
+    const int i = e / n, j = e - i * n;
+    const double2 g = G[e];
+    if (i >= j) T[tri_idx(i, j)] = g;
+    V[e] = make_double2(i == j ? 1. : 0., 0.);
+    if (i == j) tr += g.x;
   }
+  red[tid] = tr;
   __syncthreads();
-  // ---- unit phase per kept column: largest-modulus entry (first on ties) becomes real > 0 ----
-  for (int cidx = tid; cidx < r; cidx += kEigThreads) {
-    const int src = col_of[cidx];
-    double best = -1.;
-    double2 vb = make_double2(1., 0.);
-    for (int i = 0; i < n; ++i) {
-      const double2 v = V[i * n + src];
-      const double a2 = v.x * v.x + v.y * v.y;
-      if (a2 > best) {
-        best = a2;
-        vb = v;
+  for (int off = kEigThreads / 2; off > 0; off >>= 1) {
+    if (tid < off) red[tid] += red[tid + off];
+    __syncthreads();
+  }
+  const double trace = red[0];
+  const double floor2 = (2.2e-18 * trace / n) * (2.2e-18 * trace / n);
+  const double eps2 = 4.93e-32;
+  const int m = n + (n & 1);
+  const int half = m / 2;
+  const int nblocks = half * (half + 1) / 2;
+
+  for (int sweep = 0; sweep < kEigMaxSweeps; ++sweep) {
+    if (tid == 0) nrot = 0;
+    __syncthreads();
+    for (int round = 0; round < m - 1; ++round) {
+      // ---- phase 1: pairs of this round and their rotations ----
+      if (tid < half) {
+        int p, q;
+        jacobi_pair(tid, round, m, p, q);
+        int rot = 0;
+        double c = 1.;
+        double2 s = make_double2(0., 0.);
+        if (q < n)                                     // a_pq = conj(T[q, p]) since p < q
+          rot = jacobi_rotation(T[tri_idx(p, p)].x, T[tri_idx(q, q)].x, conjd(T[tri_idx(q, p)]), eps2, floor2,
+                                c, s) ? 1 : 0;
+        sp[tid] = p;
+        sq[tid] = q;
+        sc[tid] = c;
+        ss[tid] = s;
+        srot[tid] = rot;
+        if (rot) atomicAdd(&nrot, 1);
       }
+      __syncthreads();
+      // ---- phase 2a: V[:, p] <- c V[:, p] - conj(s) V[:, q],  V[:, q] <- s V[:, p] + c V[:, q]
+      //      (memory; loads of a batch issued together) ----
+      for (int e0 = tid; e0 < n * half; e0 += kEigThreads * kEigBatch) {
+        double2 xp[kEigBatch], xq[kEigBatch];
+        int off_p[kEigBatch], off_q[kEigBatch], prs[kEigBatch];
+#pragma unroll
+        for (int u = 0; u < kEigBatch; ++u) {
+          const int e = e0 + u * kEigThreads;
+          prs[u] = -1;
+          if (e < n * half) {
+            const int i = e / half, pr = e - i * half;
+            if (srot[pr]) {
+              prs[u] = pr;
+              off_p[u] = i * n + sp[pr];
+              off_q[u] = i * n + sq[pr];
+              xp[u] = V[off_p[u]];
+              xq[u] = V[off_q[u]];
+            }
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < kEigBatch; ++u) {
+          if (prs[u] >= 0) {
+            const double c = sc[prs[u]];
+            const double2 s = ss[prs[u]];
+            const double2 t1 = cmuld(conjd(s), xq[u]), t2 = cmuld(s, xp[u]);
+            V[off_p[u]] = make_double2(c * xp[u].x - t1.x, c * xp[u].y - t1.y);
+            V[off_q[u]] = make_double2(t2.x + c * xq[u].x, t2.y + c * xq[u].y);
+          }
+        }
+      }
+      // ---- phase 2b: every block (pair a, pair b), a >= b:  B <- L_a B R_b  with
+      //      L = [[c, -s], [conj(s), c]] on the rows (p_a, q_a), R = [[c, s], [-conj(s), c]] on the
+      //      columns (p_b, q_b) ----
+      for (int e = tid; e < nblocks; e += kEigThreads) {
+        int a = (int)((sqrtf(8.f * (float)e + 1.f) - 1.f) * 0.5f);
+        while (a * (a + 1) / 2 > e) --a;
+        while ((a + 1) * (a + 2) / 2 <= e) ++a;
+        const int b = e - a * (a + 1) / 2;
+        if (!srot[a] && !srot[b]) continue;
+        const int pa = sp[a], qa = sq[a], pb = sp[b], qb = sq[b];
+        const bool qa_ok = qa < n, qb_ok = qb < n;     // padding player of an odd n: no such row / column
+        const double ca = sc[a], cb = sc[b];
+        const double2 sa = ss[a], sb = ss[b];
+        const double2 zero = make_double2(0., 0.);
+        double2 b00 = tri_get(T, pa, pb);
+        double2 b01 = qb_ok ? tri_get(T, pa, qb) : zero;
+        double2 b10 = qa_ok ? tri_get(T, qa, pb) : zero;
+        double2 b11 = (qa_ok && qb_ok) ? tri_get(T, qa, qb) : zero;
+        // rows: [r_p; r_q] <- [c r_p - s r_q; conj(s) r_p + c r_q]
+        {
+          const double2 t00 = cmuld(sa, b10), t01 = cmuld(sa, b11);
+          const double2 u00 = cmuld(conjd(sa), b00), u01 = cmuld(conjd(sa), b01);
+          const double2 n00 = make_double2(ca * b00.x - t00.x, ca * b00.y - t00.y);
+          const double2 n01 = make_double2(ca * b01.x - t01.x, ca * b01.y - t01.y);
+          const double2 n10 = make_double2(u00.x + ca * b10.x, u00.y + ca * b10.y);
+          const double2 n11 = make_double2(u01.x + ca * b11.x, u01.y + ca * b11.y);
+          b00 = n00; b01 = n01; b10 = n10; b11 = n11;
+        }
+        // columns: [x_p, x_q] <- [c x_p - conj(s) x_q, s x_p + c x_q]
+        {
+          const double2 t00 = cmuld(conjd(sb), b01), t10 = cmuld(conjd(sb), b11);
+          const double2 u00 = cmuld(sb, b00), u10 = cmuld(sb, b10);
+          const double2 n00 = make_double2(cb * b00.x - t00.x, cb * b00.y - t00.y);
+          const double2 n10 = make_double2(cb * b10.x - t10.x, cb * b10.y - t10.y);
+          const double2 n01 = make_double2(u00.x + cb * b01.x, u00.y + cb * b01.y);
+          const double2 n11 = make_double2(u10.x + cb * b11.x, u10.y + cb * b11.y);
+          b00 = n00; b01 = n01; b10 = n10; b11 = n11;
+        }
+        if (a == b) {                                  // pivot block: keep its lower triangle
+          T[tri_idx(pa, pa)] = b00;
+          if (qa_ok) {
+            T[tri_idx(qa, qa)] = b11;
+            T[tri_idx(qa, pa)] = b10;
+          }
+        } else {
+          tri_put(T, pa, pb, b00);
+          if (qb_ok) tri_put(T, pa, qb, b01);
+          if (qa_ok) tri_put(T, qa, pb, b10);
+          if (qa_ok && qb_ok) tri_put(T, qa, qb, b11);
+        }
+      }
+      __syncthreads();
     }
-    const double mag = sqrt(best);
-    phase[cidx] = mag > 0. ? make_double2(vb.x / mag, -vb.y / mag) : make_double2(1., 0.);
+    const int done = (nrot == 0);
+    __syncthreads();
+    if (done) break;
   }
+  for (int i = tid; i < n; i += kEigThreads) lam[i] = T[tri_idx(i, i)].x;
   __syncthreads();
-  float2* U = reinterpret_cast<float2*>(jb.U);
-  for (int e = tid; e < n * r; e += kEigThreads) {
-    const int i = e / r, cidx = e - i * r;
-    const double2 v = cmuld(V[i * n + col_of[cidx]], phase[cidx]);
-    U[e] = make_float2((float)v.x, (float)v.y);
-  }
+  eig_finish(n, r, tid, lam, col_of, phase, V, reinterpret_cast<float2*>(jb.U));
 }
 
 __global__ void k_identity_factor(float2* U, int n) {
@@ -348,16 +572,34 @@ void launch_gram_reduce(hipStream_t s, const double* partials, int nchunks, int 
 void launch_eig_batch(hipStream_t s, int njobs, const double* const* gram, double* const* work_a,
                       double* const* work_v, const int* In, const int* r, float* const* U) {
   if (njobs <= 0) return;
-  EigJobs jobs;
+  EigJobs small, large;                          // n <= 128: work matrix in LDS; larger: in memory
+  int nsmall = 0, nlarge = 0, nmax = 0;
   for (int i = 0; i < njobs; ++i) {
-    jobs.job[i].gram = gram[i];
-    jobs.job[i].A = work_a[i];
-    jobs.job[i].V = work_v[i];
-    jobs.job[i].U = U[i];
-    jobs.job[i].n = In[i];
-    jobs.job[i].r = r[i];
+    EigJob jb;
+    jb.gram = gram[i];
+    jb.A = work_a[i];
+    jb.V = work_v[i];
+    jb.U = U[i];
+    jb.n = In[i];
+    jb.r = r[i];
+    if (In[i] <= kEigTriMaxN) {
+      small.job[nsmall++] = jb;
+      if (In[i] > nmax) nmax = In[i];
+    } else {
+      large.job[nlarge++] = jb;
+    }
   }
-  k_eig<<<dim3((unsigned)njobs), dim3(kEigThreads), 0, s>>>(jobs);
+  if (nsmall > 0) {
+    const size_t lds = (size_t)nmax * (nmax + 1) / 2 * sizeof(double2);
+    static bool attr_set = false;
+    if (!attr_set) {
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_eig_tri), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                kEigTriMaxN * (kEigTriMaxN + 1) / 2 * (int)sizeof(double2));
+      attr_set = true;
+    }
+    k_eig_tri<<<dim3((unsigned)nsmall), dim3(kEigThreads), lds, s>>>(small);
+  }
+  if (nlarge > 0) k_eig<<<dim3((unsigned)nlarge), dim3(kEigThreads), 0, s>>>(large);
 }
 
 void launch_identity_factor(hipStream_t s, float* U, int n) {
