@@ -29,7 +29,13 @@ constexpr int kGramThreads = 1024;   // 16 wavefronts: a 4 x 4 grid of 32 x 32 o
 //   Im[i, j] = sum xi_i xr_j - xr_i xi_j      -> A operand (xi_i | -xr_i), B operand (xr_j | xi_j)
 // Operand lanes: A[i = lane % 16][k = lane / 16], B[k = lane / 16][j = lane % 16];
 // result: register r of lane l holds D[4 r + l / 16][l % 16].
-// Workgroup (chunk, super-tile pair) writes its 128 x 128 block of partials[chunk].
+// The matrix is Hermitian, so only its lower triangle is computed: a workgroup owns one 128 x 128
+// super block (si >= sj) of one chunk of tensor columns, cut into 16 x 16 matrix-core tiles - all 64
+// of them off the diagonal, the 36 on or below it on the diagonal - dealt round-robin to its 16
+// wavefronts (tile t to wavefront t % 16: 9 tiles per SIMD in the diagonal case).  The next
+// 16 columns are fetched into registers while the current ones are in the matrix cores.
+constexpr int kGramMaxTiles = 4;     // tiles per wavefront: 64 / 16
+
 template <int DT>
 __global__ __launch_bounds__(kGramThreads) void k_gram(const void* __restrict__ x,
                                                         const uint32_t* __restrict__ mask, int64_t A,
@@ -39,7 +45,9 @@ __global__ __launch_bounds__(kGramThreads) void k_gram(const void* __restrict__ 
   __shared__ float2 sJ[kSuper * kLd];
   const int nsup = (In + kSuper - 1) / kSuper;
   const int si = blockIdx.y / nsup, sj = blockIdx.y % nsup;
-  const float2* sJp = (si == sj) ? sI : sJ;
+  if (si < sj) return;                                // upper super blocks: mirrored by the reduction
+  const bool diag = si == sj;
+  const float2* sJp = diag ? sI : sJ;
   const int64_t J = A * B;
   const int64_t c_begin = (int64_t)blockIdx.x * cols_per_chunk;
   const int64_t c_end = c_begin + cols_per_chunk < J ? c_begin + cols_per_chunk : J;
@@ -47,90 +55,139 @@ __global__ __launch_bounds__(kGramThreads) void k_gram(const void* __restrict__ 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
-  const int ri0 = (wave >> 2) * 32, rj0 = (wave & 3) * 32;
-  const bool active = (si * kSuper + ri0 < In) && (sj * kSuper + rj0 < In);
   const int part = (lane >> 4) & 1;
   const int ccol = lane >> 5;
   const int lrow = lane & 15;
+  const int rows_i = In - si * kSuper < kSuper ? In - si * kSuper : kSuper;   // rows present in the two
+  const int rows_j = In - sj * kSuper < kSuper ? In - sj * kSuper : kSuper;   // super blocks
 
-  v4d accRe[2][2], accIm[2][2];
-  for (int a = 0; a < 2; ++a)
-    for (int b = 0; b < 2; ++b) {
-      accRe[a][b] = (v4d){0., 0., 0., 0.};
-      accIm[a][b] = (v4d){0., 0., 0., 0.};
+  // this wavefront's tiles: slot k holds tile t = wave + 16 k (static slots: no dynamic indexing)
+  int ti[kGramMaxTiles], tj[kGramMaxTiles];
+  bool mine[kGramMaxTiles];
+  const int ntl = diag ? 36 : 64;
+#pragma unroll
+  for (int k = 0; k < kGramMaxTiles; ++k) {
+    const int t = wave + 16 * k;
+    int a = 0, b = 0;
+    if (diag) {
+      a = (int)((sqrtf(8.f * (float)t + 1.f) - 1.f) * 0.5f);
+      while (a * (a + 1) / 2 > t) --a;
+      while ((a + 1) * (a + 2) / 2 <= t) ++a;
+      b = t - a * (a + 1) / 2;
+    } else {
+      a = t >> 3;
+      b = t & 7;
     }
+    mine[k] = t < ntl && 16 * a < rows_i && 16 * b < rows_j;   // tiles of absent rows hold zeros: skipped
+    ti[k] = mine[k] ? a : 0;
+    tj[k] = mine[k] ? b : 0;
+  }
+
+  v4d accRe[kGramMaxTiles], accIm[kGramMaxTiles];
+#pragma unroll
+  for (int k = 0; k < kGramMaxTiles; ++k) {
+    accRe[k] = (v4d){0., 0., 0., 0.};
+    accIm[k] = (v4d){0., 0., 0., 0.};
+  }
+
+  // element e (0 .. 2047) of a staged tile: (row il, column cl) and the value at tensor column c0 + cl
+  constexpr int kPer = kSuper * kTC / kGramThreads;   // 2 elements per thread and side
+  auto locate = [&](int e, int& il, int& cl) {
+    if (B == 1) {                                     // rows are the fastest index in memory
+      il = e % kSuper;
+      cl = e / kSuper;
+    } else {                                          // columns b are the fastest index
+      il = e / kTC;
+      cl = e % kTC;
+    }
+  };
+  auto fetch = [&](int s, int64_t c0, int e) -> float2 {
+    int il, cl;
+    locate(e, il, cl);
+    const int i = s * kSuper + il;
+    const int64_t c = c0 + cl;
+    float2 v = make_float2(0.f, 0.f);
+    if (i < In && c < c_end) {
+      const int64_t a = c / B, b = c - a * B;
+      const int64_t idx = (a * In + i) * B + b;
+      bool drop = false;
+      if (mask) drop = (mask[idx >> 5] >> (idx & 31)) & 1u;
+      if (!drop) v = load_elem<DT>(x, idx);
+    }
+    return v;
+  };
+
+  float2 preI[kPer], preJ[kPer];                      // next tile of the row side / the column side
+#pragma unroll
+  for (int u = 0; u < kPer; ++u) {
+    preI[u] = fetch(si, c_begin, tid + u * kGramThreads);
+    preJ[u] = diag ? make_float2(0.f, 0.f) : fetch(sj, c_begin, tid + u * kGramThreads);
+  }
 
   for (int64_t c0 = c_begin; c0 < c_end; c0 += kTC) {
     __syncthreads();                                  // previous tile fully consumed
-    // ---- stage rows [s*128, s*128+128) x columns [c0, c0+16) for both sides ----
-    for (int side = 0; side < ((si == sj) ? 1 : 2); ++side) {
-      float2* dst = side == 0 ? sI : sJ;
-      const int s = side == 0 ? si : sj;
-      for (int e = tid; e < kSuper * kTC; e += kGramThreads) {
-        int il, cl;
-        if (B == 1) {                                 // rows are the fastest index in memory
-          il = e % kSuper;
-          cl = e / kSuper;
-        } else {                                      // columns b are the fastest index
-          il = e / kTC;
-          cl = e % kTC;
-        }
-        const int i = s * kSuper + il;
-        const int64_t c = c0 + cl;
-        float2 v = make_float2(0.f, 0.f);
-        if (i < In && c < c_end) {
-          const int64_t a = c / B, b = c - a * B;
-          const int64_t idx = (a * In + i) * B + b;
-          bool drop = false;
-          if (mask) drop = (mask[idx >> 5] >> (idx & 31)) & 1u;
-          if (!drop) v = load_elem<DT>(x, idx);
-        }
-        dst[il * kLd + cl] = v;
-      }
+#pragma unroll
+    for (int u = 0; u < kPer; ++u) {
+      int il, cl;
+      locate(tid + u * kGramThreads, il, cl);
+      sI[il * kLd + cl] = preI[u];
+      if (!diag) sJ[il * kLd + cl] = preJ[u];
     }
     __syncthreads();
-    if (active) {
+    if (c0 + kTC < c_end) {                           // next 16 columns go in flight
 #pragma unroll
-      for (int s2 = 0; s2 < kTC / 2; ++s2) {
-        const int cc = 2 * s2 + ccol;
-        double aRe[2], aIm[2], bop[2];
+      for (int u = 0; u < kPer; ++u) {
+        preI[u] = fetch(si, c0 + kTC, tid + u * kGramThreads);
+        if (!diag) preJ[u] = fetch(sj, c0 + kTC, tid + u * kGramThreads);
+      }
+    }
+#pragma unroll 1
+    for (int s2 = 0; s2 < kTC / 2; ++s2) {
+      const int cc = 2 * s2 + ccol;
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-          float2 xa = sI[(ri0 + t * 16 + lrow) * kLd + cc];
-          float2 xb = sJp[(rj0 + t * 16 + lrow) * kLd + cc];
-          aRe[t] = part ? (double)xa.y : (double)xa.x;
-          aIm[t] = part ? -(double)xa.x : (double)xa.y;
-          bop[t] = part ? (double)xb.y : (double)xb.x;
+      for (int k = 0; k < kGramMaxTiles; ++k) {
+        if (mine[k]) {
+          const float2 xa = sI[(16 * ti[k] + lrow) * kLd + cc];
+          const float2 xb = sJp[(16 * tj[k] + lrow) * kLd + cc];
+          const double aRe = part ? (double)xa.y : (double)xa.x;
+          const double aIm = part ? -(double)xa.x : (double)xa.y;
+          const double bop = part ? (double)xb.y : (double)xb.x;
+          accRe[k] = __builtin_amdgcn_mfma_f64_16x16x4f64(aRe, bop, accRe[k], 0, 0, 0);
+          accIm[k] = __builtin_amdgcn_mfma_f64_16x16x4f64(aIm, bop, accIm[k], 0, 0, 0);
         }
-#pragma unroll
-        for (int ti = 0; ti < 2; ++ti)
-#pragma unroll
-          for (int tj = 0; tj < 2; ++tj) {
-            accRe[ti][tj] = __builtin_amdgcn_mfma_f64_16x16x4f64(aRe[ti], bop[tj], accRe[ti][tj], 0, 0, 0);
-            accIm[ti][tj] = __builtin_amdgcn_mfma_f64_16x16x4f64(aIm[ti], bop[tj], accIm[ti][tj], 0, 0, 0);
-          }
       }
     }
   }
-  if (!active) return;
   double2* out = reinterpret_cast<double2*>(partials) + (int64_t)blockIdx.x * In * In;
-  for (int ti = 0; ti < 2; ++ti)
-    for (int tj = 0; tj < 2; ++tj)
+#pragma unroll
+  for (int k = 0; k < kGramMaxTiles; ++k) {
+    if (mine[k]) {
       for (int r = 0; r < 4; ++r) {
-        const int i = si * kSuper + ri0 + ti * 16 + 4 * r + (lane >> 4);
-        const int j = sj * kSuper + rj0 + tj * 16 + (lane & 15);
-        if (i < In && j < In) out[(int64_t)i * In + j] = make_double2(accRe[ti][tj][r], accIm[ti][tj][r]);
+        const int i = si * kSuper + 16 * ti[k] + 4 * r + (lane >> 4);
+        const int j = sj * kSuper + 16 * tj[k] + (lane & 15);
+        if (i < In && j < In) out[(int64_t)i * In + j] = make_double2(accRe[k][r], accIm[k][r]);
       }
+    }
+  }
 }
 
-// gram[e] = sum over chunks of partials[chunk][e], in chunk order (deterministic).
-__global__ void k_gram_reduce(const double* __restrict__ partials, int nchunks, int64_t n2,
+// gram[i, j] = sum over chunks of partials[chunk][i, j] for i >= j, in chunk order (deterministic);
+// the upper triangle is the conjugate mirror (k_gram leaves it unwritten).
+__global__ void k_gram_reduce(const double* __restrict__ partials, int nchunks, int In,
                               double* __restrict__ gram) {
-  int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t n2 = (int64_t)In * In;
   if (e >= n2) return;
-  double acc = 0.;
-  for (int c = 0; c < nchunks; ++c) acc += partials[(int64_t)c * n2 + e];
-  gram[e] = acc;
+  const int i = (int)(e / In), j = (int)(e - (int64_t)i * In);
+  const int64_t src = i >= j ? e : (int64_t)j * In + i;
+  const double2* p2 = reinterpret_cast<const double2*>(partials);
+  double re = 0., im = 0.;
+  for (int c = 0; c < nchunks; ++c) {
+    const double2 v = p2[(int64_t)c * n2 + src];
+    re += v.x;
+    im += v.y;
+  }
+  reinterpret_cast<double2*>(gram)[e] = make_double2(re, i >= j ? im : -im);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -565,8 +622,8 @@ void launch_gram(hipStream_t s, const void* g, int dtype, const uint32_t* mask, 
 }
 
 void launch_gram_reduce(hipStream_t s, const double* partials, int nchunks, int In, double* gram) {
-  const int64_t n2 = (int64_t)In * In * 2;
-  k_gram_reduce<<<dim3((unsigned)((n2 + 255) / 256)), dim3(256), 0, s>>>(partials, nchunks, n2, gram);
+  const int64_t n2 = (int64_t)In * In;
+  k_gram_reduce<<<dim3((unsigned)((n2 + 255) / 256)), dim3(256), 0, s>>>(partials, nchunks, In, gram);
 }
 
 void launch_eig_batch(hipStream_t s, int njobs, const double* const* gram, double* const* work_a,
