@@ -60,24 +60,33 @@ template <int VEC> struct VecT;
 template <> struct VecT<1> { typedef float2 type; };
 template <> struct VecT<2> { typedef float4 type; };
 
-template <int MT, int VEC, bool PROJECT>
+// MODE 0: every wavefront of a workgroup owns its own 32 column vectors and all MT row tiles.
+// MODE 1 (split-K, MT = 1): the 4 wavefronts share 32 column vectors and deal the row pairs
+//         round-robin; their partial tiles are summed through LDS in a fixed order.  For stages
+//         with few columns, where MODE 0 would leave most of the chip idle.
+// MODE 2 (MT = 1): the 4 wavefronts share 32 column vectors and own one 32-row output tile each
+//         (128 output rows per workgroup).  For reconstruction stages with few columns.
+template <int MT, int VEC, bool PROJECT, int MODE>
 __global__ __launch_bounds__(kMidThreads) void k_mid(const float* __restrict__ x,
                                                      const float2* __restrict__ U, int rn, int64_t A,
                                                      int K, int M, int64_t B, float* __restrict__ out) {
   typedef typename VecT<VEC>::type V;
-  extern __shared__ float2 sF[];          // [pair][mt][lane] = (Fr, Fi)
+  constexpr int TL = MODE == 2 ? 4 : MT;  // row tiles whose factor operands a workgroup stages
+  extern __shared__ float2 sF[];          // [pair][tile][lane] = (Fr, Fi)
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int col = lane & 31, half = lane >> 5;
   const int64_t BV = B / VEC;             // host guarantees B % VEC == 0
   const int64_t ncv = A * BV;
-  const int64_t cv_raw = ((int64_t)blockIdx.x * (kMidThreads / 64) + wave) * 32 + col;
+  const int64_t cv_raw = MODE == 0 ? ((int64_t)blockIdx.x * (kMidThreads / 64) + wave) * 32 + col
+                                   : (int64_t)blockIdx.x * 32 + col;
   const bool valid = cv_raw < ncv;
   const int64_t cv = valid ? cv_raw : ncv - 1;   // lanes past the end load a real column, store nothing
   const int64_t a = cv / BV;
   const int64_t bv = cv - a * BV;
   const float* xp = x + ((a * K) * B + bv * VEC) * 2;
   const int64_t row_stride = B * 2;       // floats between consecutive k
-  const int mbase = blockIdx.y * (32 * MT);
+  const int mbase = blockIdx.y * (32 * TL);
+  const int my_tile0 = MODE == 2 ? wave : 0;   // first of this wavefront's MT tiles among the staged TL
 
   v16f acc[MT][2 * VEC];
 #pragma unroll
@@ -108,7 +117,7 @@ __global__ __launch_bounds__(kMidThreads) void k_mid(const float* __restrict__ x
     }
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-      const float2 f = sF[(jj * MT + mt) * 64 + lane];
+      const float2 f = sF[(jj * TL + my_tile0 + mt) * 64 + lane];
 #pragma unroll
       for (int t = 0; t < 2 * VEC; ++t) {
         acc[mt][t] = mfma32(f.x, xs[t], acc[mt][t]);
@@ -117,14 +126,16 @@ __global__ __launch_bounds__(kMidThreads) void k_mid(const float* __restrict__ x
     }
   };
 
+  constexpr int JSTEP = MODE == 1 ? 4 : 1;                     // split-K: wavefront w takes pairs w, w + 4, ...
+  const int jfirst = MODE == 1 ? wave : 0;
   const int J = (K + 1) >> 1;
   for (int jc0 = 0; jc0 < J; jc0 += kMidJChunk) {
     const int jn = (J - jc0) < kMidJChunk ? (J - jc0) : kMidJChunk;
     __syncthreads();                                           // previous chunk fully consumed
-    for (int e = tid; e < jn * MT * 64; e += kMidThreads) {
+    for (int e = tid; e < jn * TL * 64; e += kMidThreads) {
       const int l = e & 63;
-      const int mt = (e >> 6) % MT;
-      const int jj = e / (64 * MT);
+      const int mt = (e >> 6) % TL;
+      const int jj = e / (64 * TL);
       const int m = mbase + 32 * mt + (l & 31);
       const int k = 2 * (jc0 + jj) + (l >> 5);
       float2 f = make_float2(0.f, 0.f);
@@ -139,15 +150,34 @@ __global__ __launch_bounds__(kMidThreads) void k_mid(const float* __restrict__ x
       sF[e] = f;
     }
     __syncthreads();
-    int jj = 0;
-    for (; jj + kMidUnroll <= jn; jj += kMidUnroll) {
+    int jj = jfirst;
+    for (; jj + (kMidUnroll - 1) * JSTEP < jn; jj += kMidUnroll * JSTEP) {
       V v[kMidUnroll];
 #pragma unroll
-      for (int u = 0; u < kMidUnroll; ++u) v[u] = load_pair_row(jc0 + jj + u);
+      for (int u = 0; u < kMidUnroll; ++u) v[u] = load_pair_row(jc0 + jj + u * JSTEP);
 #pragma unroll
-      for (int u = 0; u < kMidUnroll; ++u) mfma_pair_row(v[u], jj + u);
+      for (int u = 0; u < kMidUnroll; ++u) mfma_pair_row(v[u], jj + u * JSTEP);
     }
-    for (; jj < jn; ++jj) mfma_pair_row(load_pair_row(jc0 + jj), jj);
+    for (; jj < jn; jj += JSTEP) mfma_pair_row(load_pair_row(jc0 + jj), jj);
+  }
+  if constexpr (MODE == 1) {
+    // partial tiles of wavefronts 1..3 -> LDS, summed by wavefront 0 in a fixed order
+    __syncthreads();                                           // factor operands no longer needed
+    float* red = reinterpret_cast<float*>(sF);                 // [wave - 1][t][r][lane]
+    if (wave > 0) {
+#pragma unroll
+      for (int t = 0; t < 2 * VEC; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) red[(((wave - 1) * 2 * VEC + t) * 16 + r) * 64 + lane] = acc[0][t][r];
+    }
+    __syncthreads();
+    if (wave > 0) return;
+#pragma unroll 1
+    for (int w = 0; w < 3; ++w)
+#pragma unroll
+      for (int t = 0; t < 2 * VEC; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[0][t][r] += red[((w * 2 * VEC + t) * 16 + r) * 64 + lane];
   }
   if (!valid) return;
   float* op = out + ((a * M) * B + bv * VEC) * 2;
@@ -155,7 +185,7 @@ __global__ __launch_bounds__(kMidThreads) void k_mid(const float* __restrict__ x
   for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      const int m = mbase + 32 * mt + d_row(r, half);
+      const int m = mbase + 32 * (my_tile0 + mt) + d_row(r, half);
       if (m < M) {
         float* o = op + (int64_t)m * row_stride;
         if constexpr (VEC == 1) {
@@ -1028,27 +1058,46 @@ void launch_mid(hipStream_t s, const float2* x, const float2* U, int rn, bool pr
   const int K = st.K, M = st.M;
   if (A * M * B <= 0) return;
   const int vec = (B % 2 == 0) ? 2 : 1;
-  const int mt = M > 32 ? 2 : 1;
   const int64_t ncv = A * (B / vec);
-  const int64_t gx = (ncv + 127) / 128;
-  const int gy = (M + 32 * mt - 1) / (32 * mt);
   const int J = (K + 1) / 2;
-  const size_t lds = (size_t)(J < kMidJChunk ? J : kMidJChunk) * mt * 64 * 8;
+  const int jn = J < kMidJChunk ? J : kMidJChunk;
+  // Fewer workgroups than compute units: share 32 columns between the 4 wavefronts of a workgroup
+  // (MODE 1 / 2) so that the stage still spreads over the chip; otherwise every wavefront owns 32
+  // columns (MODE 0; measured faster as soon as it yields at least one workgroup per compute unit).
+  const int mt0 = M > 32 ? 2 : 1;
+  const int64_t wgs0 = ((ncv + 127) / 128) * ((M + 32 * mt0 - 1) / (32 * mt0));
+  int mode = 0;
+  if (wgs0 < 256) mode = M > 32 ? 2 : 1;
+  const int mt = mode == 0 ? mt0 : 1;
+  const int tl = mode == 2 ? 4 : mt;
+  const int64_t gx = mode == 0 ? (ncv + 127) / 128 : (ncv + 31) / 32;
+  const int gy = (M + 32 * tl - 1) / (32 * tl);
+  size_t lds = (size_t)jn * tl * 64 * 8;
+  if (mode == 1) {
+    const size_t red = (size_t)3 * 2 * vec * 16 * 64 * 4;
+    if (red > lds) lds = red;
+  }
   dim3 grid((unsigned)gx, (unsigned)gy), block(kMidThreads);
   const float* xf = reinterpret_cast<const float*>(x);
   float* of = reinterpret_cast<float*>(out);
-#define TGRAD_MID(MT_, VEC_, P_)                                                          \
+#define TGRAD_MID(MT_, VEC_, P_, MODE_)                                                   \
   do {                                                                                    \
-    allow_lds(k_mid<MT_, VEC_, P_>, lds);                                                 \
-    k_mid<MT_, VEC_, P_><<<grid, block, lds, s>>>(xf, U, rn, A, K, M, B, of);             \
+    allow_lds(k_mid<MT_, VEC_, P_, MODE_>, lds);                                          \
+    k_mid<MT_, VEC_, P_, MODE_><<<grid, block, lds, s>>>(xf, U, rn, A, K, M, B, of);      \
   } while (0)
-  if (project) {
-    if (mt == 1) { if (vec == 2) TGRAD_MID(1, 2, true); else TGRAD_MID(1, 1, true); }
-    else         { if (vec == 2) TGRAD_MID(2, 2, true); else TGRAD_MID(2, 1, true); }
+#define TGRAD_MID_P(MT_, VEC_, MODE_)                                                     \
+  do {                                                                                    \
+    if (project) TGRAD_MID(MT_, VEC_, true, MODE_); else TGRAD_MID(MT_, VEC_, false, MODE_); \
+  } while (0)
+  if (mode == 0) {
+    if (mt == 1) { if (vec == 2) TGRAD_MID_P(1, 2, 0); else TGRAD_MID_P(1, 1, 0); }
+    else         { if (vec == 2) TGRAD_MID_P(2, 2, 0); else TGRAD_MID_P(2, 1, 0); }
+  } else if (mode == 1) {
+    if (vec == 2) TGRAD_MID_P(1, 2, 1); else TGRAD_MID_P(1, 1, 1);
   } else {
-    if (mt == 1) { if (vec == 2) TGRAD_MID(1, 2, false); else TGRAD_MID(1, 1, false); }
-    else         { if (vec == 2) TGRAD_MID(2, 2, false); else TGRAD_MID(2, 1, false); }
+    if (vec == 2) TGRAD_MID_P(1, 2, 2); else TGRAD_MID_P(1, 1, 2);
   }
+#undef TGRAD_MID_P
 #undef TGRAD_MID
 }
 
