@@ -483,10 +483,10 @@ __global__ __launch_bounds__(kEigThreads) void k_eig_tri(EigJobs jobs) {
     __syncthreads();
     for (int round = 0; round < m - 1; ++round) {
       // ---- phase 1: pairs of this round and their rotations ----
+      int rot = 0;
       if (tid < half) {
         int p, q;
         jacobi_pair(tid, round, m, p, q);
-        int rot = 0;
         double c = 1.;
         double2 s = make_double2(0., 0.);
         if (q < n)                                     // a_pq = conj(T[q, p]) since p < q
@@ -499,7 +499,7 @@ __global__ __launch_bounds__(kEigThreads) void k_eig_tri(EigJobs jobs) {
         srot[tid] = rot;
         if (rot) atomicAdd(&nrot, 1);
       }
-      __syncthreads();
+      if (!__syncthreads_or(rot)) continue;            // nothing rotates in this round (late sweeps)
       // ---- phase 2a: V[:, p] <- c V[:, p] - conj(s) V[:, q],  V[:, q] <- s V[:, p] + c V[:, q]
       //      (memory; loads of a batch issued together) ----
       for (int e0 = tid; e0 < n * half; e0 += kEigThreads * kEigBatch) {
