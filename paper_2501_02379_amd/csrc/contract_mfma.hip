@@ -824,6 +824,9 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate_fused(const float2* __res
   uint32_t nj0 = sp.tile_start[nxt + vzero], nj1 = sp.tile_start[nxt + 1 + vzero];
   issue_sparse(cj0, cj1);
   claim_sparse();
+  float2 y1[JT2];                                              // stage-A operand rows of the current slab
+#pragma unroll
+  for (int jj = 0; jj < JT2; ++jj) y1[jj] = make_float2(0.f, 0.f);
   while (true) {
     int lane_now = lane;                                       // opaque per-tile copy (see k_lproj)
     asm volatile("" : "+v"(lane_now));
@@ -839,15 +842,21 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate_fused(const float2* __res
     // ---- stage-A operands of this tile (small, cache-resident: the slab's Y1 and 32 columns of the
     //      factor copy), issued BEFORE the W pieces so that waiting for them leaves those in flight.
     //      Unconditional loads with clamped indices: clamped rows / columns meet zero coefficients. ----
-    float2 y1[JT2], u2[JT2];
+    // The slab's Y1 rows stay in registers for all S tiles of the slab: they are fetched on its first
+    // tile only.  On the other tiles the same instructions read one fixed, cache-resident element and
+    // the old value is kept by a select - a branch around the loads would end in a wait and a copy.
+    float2 u2[JT2];
     {
+      const bool first = ts == 0;
       const int m3 = (col >> 1) < K ? (col >> 1) : K - 1;
-      const float2* yp = fz.y1 + (size_t)slab * fz.K2 * K + m3;
+      const float2* yp = fz.y1 + (first ? (size_t)slab * fz.K2 * K + m3 : (size_t)0);
       const float2* up = fz.ut + (size_t)half * I2 + 32 * ts + col;
 #pragma unroll
       for (int jj = 0; jj < JT2; ++jj) {
         const int m2 = 2 * jj + half;
-        y1[jj] = yp[(size_t)(m2 < fz.K2 ? m2 : fz.K2 - 1) * K];
+        const float2 v = yp[first ? (size_t)(m2 < fz.K2 ? m2 : fz.K2 - 1) * K : (size_t)0];
+        y1[jj].x = first ? v.x : y1[jj].x;
+        y1[jj].y = first ? v.y : y1[jj].y;
         u2[jj] = up[(size_t)(2 * jj) * I2];
       }
     }
