@@ -50,6 +50,9 @@ the design notes of this repository):
   G = -grad and W <- W + eta * G~ is the same update because every operation
   applied to G is odd.
 * AdamW decay is decoupled: W <- W (1 - lr wd) - lr * D.
+* Uniform random selection (rand-k) draws its subset from a counter-based integer
+  hash of (index, seed, step count at the refresh); see `random_keys`.  The
+  paper does not say how the subset is drawn.
 
 Parity pins for every function below live in tests/test_oracle_*.py.  The HOOI
 refinement sweeps (`hooi_sweeps > 0`) are "parity unpinned" beyond monotone core
@@ -141,6 +144,57 @@ def sparse_indices(G: np.ndarray, k: int) -> np.ndarray:
         raise ValueError("k out of range")
     # stable sort of the negated key: equal keys keep ascending index order
     order = np.argsort(-key, kind="stable")
+    return np.sort(order[:k]).astype(np.int64)
+
+
+# --------------------------------------------------------------------------
+# uniform random support (rand-k)
+# --------------------------------------------------------------------------
+# The paper names uniform random selection of the k entries as an alternative to top-k
+# (section "Unstructured sparse gradient tensor"; the ablation on selection strategies) and says
+# nothing about the sampler.  Reading used here: every linear index i gets a pseudo-random 32-bit
+# key that depends only on (i, seed, t) -- t the step count at the refresh -- and the support is
+# the k indices with the largest keys.  The key map is a bijection of the 32-bit integers, so the
+# keys of distinct indices differ and the subset is what a random permutation of the indices
+# would give.  The mixing function is the 32-bit finalizer of MurmurHash3 (a public-domain,
+# published integer hash), applied twice around the two seed words.
+_M32 = 0xFFFFFFFF
+
+
+def _fmix32(x: np.ndarray) -> np.ndarray:
+    x = x.astype(np.uint64)                     # products below stay under 2^64
+    x ^= x >> np.uint64(16)
+    x = (x * np.uint64(0x85EBCA6B)) & np.uint64(_M32)
+    x ^= x >> np.uint64(13)
+    x = (x * np.uint64(0xC2B2AE35)) & np.uint64(_M32)
+    x ^= x >> np.uint64(16)
+    return x
+
+
+def random_key_words(seed: int, t: int):
+    """The two 32-bit words (s0, s1) the keys of one refresh are built from."""
+    seed = int(seed) & 0xFFFFFFFFFFFFFFFF
+    t32 = int(t) & _M32
+    s0 = (seed & _M32) ^ ((t32 * 0x9E3779B9) & _M32)
+    s1 = ((seed >> 32) + t32 + 0x7F4A7C15) & _M32
+    return s0, s1
+
+
+def random_keys(numel: int, seed: int, t: int) -> np.ndarray:
+    """key(i) = fmix32(fmix32(i xor s0) + s1) for i = 0 .. numel-1 (uint32)."""
+    s0, s1 = random_key_words(seed, t)
+    i = np.arange(numel, dtype=np.uint64)
+    a = _fmix32(i ^ np.uint64(s0))
+    return _fmix32((a + np.uint64(s1)) & np.uint64(_M32)).astype(np.uint32)
+
+
+def sparse_indices_random(numel: int, k: int, seed: int, t: int) -> np.ndarray:
+    """SparseIndices(., rho, rand-k): the k indices first in the order (key descending, linear
+    index ascending) of the pseudo-random keys, returned ascending (int64)."""
+    if k < 0 or k > numel:
+        raise ValueError("k out of range")
+    key = random_keys(numel, seed, t)
+    order = np.argsort(-key.astype(np.int64), kind="stable")
     return np.sort(order[:k]).astype(np.int64)
 
 
@@ -272,6 +326,8 @@ class Hyper:
     weight_decay: float = 0.0
     T: int = 1                 # refresh when t % T == 0; 0 = only on request
     hooi_sweeps: int = 0
+    select_rule: str = "topk"  # "topk" (magnitude) or "randk" (uniform random subset)
+    select_seed: int = 0       # rand-k only
 
 
 @dataclass
@@ -302,7 +358,12 @@ class State:
 def refresh(st: State, G: np.ndarray) -> None:
     """Algorithm 1, the `t mod T = 0` branch.  Touches neither moments nor t."""
     Gc = to_complex128(G)
-    st.omega = sparse_indices(G, st.hyper.k)
+    if st.hyper.select_rule == "randk":
+        st.omega = sparse_indices_random(int(np.prod(st.shape)), st.hyper.k, st.hyper.select_seed, st.t)
+    elif st.hyper.select_rule == "topk":
+        st.omega = sparse_indices(G, st.hyper.k)
+    else:
+        raise ValueError("unknown selection rule")
     R_L = remove_sparse(Gc, st.omega)
     st.U = tucker_factors(R_L, st.hyper.ranks, st.hyper.hooi_sweeps)
 

@@ -487,6 +487,92 @@ def test_bf16_gradient_path_is_exact_widening():
     assert np.array_equal(Wa, Wb)
 
 
+# ----------------------------------------------------------------- rand-k support
+def _fmix32_int(x):
+    x ^= x >> 16
+    x = (x * 0x85EBCA6B) % (1 << 32)
+    x ^= x >> 13
+    x = (x * 0xC2B2AE35) % (1 << 32)
+    x ^= x >> 16
+    return x
+
+
+def test_random_support_structure():
+    """k distinct in-range ascending indices; k = 0 and k = I; nested in k; a function of
+    (seed, t) only; the key map is a bijection (no ties can arise)."""
+    I = 1000
+    a = O.sparse_indices_random(I, 137, seed=5, t=0)
+    assert a.dtype == np.int64 and a.size == 137 and np.all(np.diff(a) > 0) and a[0] >= 0 and a[-1] < I
+    assert O.sparse_indices_random(I, 0, 5, 0).size == 0
+    assert np.array_equal(O.sparse_indices_random(I, I, 5, 0), np.arange(I))
+    b = O.sparse_indices_random(I, 300, seed=5, t=0)
+    assert np.all(np.isin(a, b))                                   # the k-subsets of one draw are nested
+    assert np.array_equal(a, O.sparse_indices_random(I, 137, 5, 0))
+    for other in (O.sparse_indices_random(I, 137, 6, 0), O.sparse_indices_random(I, 137, 5, 1),
+                  O.sparse_indices_random(I, 137, 5 + (1 << 32), 0)):
+        assert 0 < np.intersect1d(a, other).size < 60              # expected overlap 137^2 / 1000 = 19
+    with pytest.raises(ValueError):
+        O.sparse_indices_random(10, 11, 0, 0)
+    for seed, t in ((0, 0), (12345678901234567, 77), ((1 << 64) - 1, (1 << 32) - 1)):
+        keys = O.random_keys(1 << 20, seed, t)
+        assert keys.dtype == np.uint32 and np.unique(keys).size == keys.size
+
+
+def test_random_support_matches_integer_brute_force():
+    """The vectorised keys against exact Python-integer arithmetic and a full sort of (key, index)
+    tuples on small inputs (catches wrap-around and ordering mistakes in the array code)."""
+    for I, k, seed, t in ((1, 1, 0, 0), (37, 9, 3, 0), (257, 100, (7 << 32) | 9, 400), (64, 63, (1 << 64) - 1, 5)):
+        s0 = (seed & 0xFFFFFFFF) ^ ((t % (1 << 32)) * 0x9E3779B9 % (1 << 32))
+        s1 = ((seed >> 32) + t + 0x7F4A7C15) % (1 << 32)
+        assert O.random_key_words(seed, t) == (s0, s1)
+        keys = [_fmix32_int((_fmix32_int(i ^ s0) + s1) % (1 << 32)) for i in range(I)]
+        assert [int(x) for x in O.random_keys(I, seed, t)] == keys
+        order = sorted(range(I), key=lambda i: (-keys[i], i))
+        assert np.array_equal(O.sparse_indices_random(I, k, seed, t), np.array(sorted(order[:k])))
+
+
+def test_random_support_is_uniform():
+    """Over many seeds every index is chosen with frequency k / I and neighbouring indices are
+    chosen together as often as independent draws without replacement would be (5 sigma)."""
+    I, k, trials = 64, 16, 4000
+    hits = np.zeros(I)
+    pair = np.zeros(I - 1)
+    for seed in range(trials):
+        sel = np.zeros(I, dtype=bool)
+        sel[O.sparse_indices_random(I, k, seed * 2654435761 + 17, t=seed % 7)] = True
+        hits += sel
+        pair += sel[1:] & sel[:-1]
+    p1 = k / I
+    assert np.max(np.abs(hits - trials * p1)) < 5 * np.sqrt(trials * p1 * (1 - p1))
+    p2 = p1 * (k - 1) / (I - 1)
+    assert np.max(np.abs(pair - trials * p2)) < 5 * np.sqrt(trials * p2 * (1 - p2))
+    # consecutive refreshes of one job (same seed, t = 0, T, 2T, ...) are spread the same way
+    hits[:] = 0
+    for r in range(trials):
+        hits[O.sparse_indices_random(I, k, 99, t=25 * r)] += 1
+    assert np.max(np.abs(hits - trials * p1)) < 5 * np.sqrt(trials * p1 * (1 - p1))
+
+
+def test_random_rule_in_the_step():
+    """With the rand-k rule the refresh ignores the gradient's magnitudes, uses the step count of
+    the refresh, and everything downstream (gather, residual, moments by position) is unchanged."""
+    shape = (4, 3, 5)
+    rng = np.random.default_rng(8)
+    W = np.zeros(shape, dtype=np.complex128)
+    st = O.State(shape, O.Hyper(ranks=(2, 2, 2), k=7, T=2, select_rule="randk", select_seed=11))
+    supports = []
+    for t in range(4):
+        g = (rng.standard_normal(shape) + 1j * rng.standard_normal(shape)).astype(np.complex64)
+        W = O.step(st, W, g)
+        supports.append(st.omega.copy())
+    assert np.array_equal(supports[0], O.sparse_indices_random(60, 7, 11, 0))
+    assert np.array_equal(supports[1], supports[0])
+    assert np.array_equal(supports[2], O.sparse_indices_random(60, 7, 11, 2))
+    assert not np.array_equal(supports[2], supports[0])
+    with pytest.raises(ValueError):
+        O.refresh(O.State(shape, O.Hyper(ranks=(2, 2, 2), k=7, select_rule="probk")), g)
+
+
 # ----------------------------------------------------------------- generators
 def test_synthetic_inputs_are_seeded_and_shaped():
     w = synth.WORKLOADS["cfg1"]
