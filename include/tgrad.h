@@ -42,7 +42,7 @@ extern "C" {
 typedef struct tgrad_ctx tgrad_ctx;   /* opaque; host memory owned by the library */
 
 enum { TGRAD_C64 = 0, TGRAD_CBF16 = 1 };
-enum { TGRAD_SELECT_TOPK_MAG = 0 };
+enum { TGRAD_SELECT_TOPK_MAG = 0, TGRAD_SELECT_RANDOM = 1 };
 
 enum {
   TGRAD_OK = 0,
@@ -88,7 +88,15 @@ typedef struct {
   int32_t refresh_every;              /* T >= 1: tgrad_step refreshes first when t % T == 0.
                                          0: only tgrad_refresh_factors refreshes */
   int32_t hooi_sweeps;                /* 0 = HOSVD factors.  > 0 (HOOI refinement): UNSUPPORTED */
-  int32_t select_rule;                /* TGRAD_SELECT_TOPK_MAG */
+  int32_t select_rule;                /* how SparseIndices picks Omega (section "Unstructured sparse
+                                         gradient tensor"): TGRAD_SELECT_TOPK_MAG = the k entries of
+                                         largest |g|^2 (float32), ties to the lower linear index;
+                                         TGRAD_SELECT_RANDOM = a uniform random k-subset that depends
+                                         only on (select_seed, t at the refresh): the k largest of the
+                                         keys fmix32(fmix32(i ^ s0) + s1), fmix32 = MurmurHash3's
+                                         32-bit finalizer, s0 = lo32(seed) ^ (t32 * 0x9E3779B9),
+                                         s1 = hi32(seed) + t32 + 0x7F4A7C15, t32 = t mod 2^32 */
+  uint64_t select_seed;               /* TGRAD_SELECT_RANDOM only */
 } tgrad_config;
 
 /*

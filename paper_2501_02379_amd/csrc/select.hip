@@ -12,6 +12,11 @@
 //     #(key > T before i) + min(#(key == T before i), need_eq),
 // so two independent exclusive prefix counts are enough and no atomics decide an output slot.
 // Everything is integer work: the result is bit-exact and run-to-run deterministic.
+//
+// Uniform random selection (rand-k, the alternative rule the same section names) runs through the
+// same passes with a different key: key(i) = fmix32(fmix32(i xor s0) + s1), fmix32 the 32-bit
+// finalizer of MurmurHash3 and (s0, s1) two words made from the seed and the step count of the
+// refresh.  The key map is a bijection, so no two entries tie, and the gradient is never read.
 #include "device_common.h"
 
 namespace tgrad {
@@ -30,8 +35,46 @@ __device__ __forceinline__ bool in_prefix(uint32_t key, int pass, uint32_t prefi
   return pass == 0 ? true : pass == 1 ? ((key >> 20) == prefix) : ((key >> 8) == prefix);
 }
 
+// Where the keys come from: the gradient (KS = its dtype) or the index hash (KS = kKeyRandom).
+constexpr int kKeyRandom = 2;
+struct KeySource {
+  const void* g;
+  uint32_t s0, s1;
+};
+
+__device__ __forceinline__ uint32_t fmix32(uint32_t x) {
+  x ^= x >> 16;
+  x *= 0x85EBCA6Bu;
+  x ^= x >> 13;
+  x *= 0xC2B2AE35u;
+  x ^= x >> 16;
+  return x;
+}
+
+// Keys of elements 2p and 2p+1 (the caller guarantees 2p + 1 < I).
+template <int KS>
+__device__ __forceinline__ void pair_keys(const KeySource& src, int64_t p, uint32_t& k0, uint32_t& k1) {
+  if constexpr (KS == kKeyRandom) {
+    const uint32_t i0 = (uint32_t)(2 * p);
+    k0 = fmix32(fmix32(i0 ^ src.s0) + src.s1);
+    k1 = fmix32(fmix32((i0 + 1u) ^ src.s0) + src.s1);
+  } else {
+    float2 e0, e1;
+    load_pair<KS>(src.g, p, e0, e1);
+    k0 = select_key(e0);
+    k1 = select_key(e1);
+  }
+}
+template <int KS>
+__device__ __forceinline__ uint32_t elem_key(const KeySource& src, int64_t i) {
+  if constexpr (KS == kKeyRandom)
+    return fmix32(fmix32((uint32_t)i ^ src.s0) + src.s1);
+  else
+    return select_key(load_elem<KS>(src.g, i));
+}
+
 template <int DT>
-__global__ __launch_bounds__(kSelThreads) void k_select_hist(const void* __restrict__ g, int64_t I,
+__global__ __launch_bounds__(kSelThreads) void k_select_hist(const KeySource g, int64_t I,
                                                              int pass,
                                                              const SelectScalars* __restrict__ sc,
                                                              uint32_t* __restrict__ hist) {
@@ -42,14 +85,13 @@ __global__ __launch_bounds__(kSelThreads) void k_select_hist(const void* __restr
   const int64_t npairs = I >> 1;
   const int64_t stride = (int64_t)gridDim.x * kSelThreads;
   for (int64_t p = (int64_t)blockIdx.x * kSelThreads + threadIdx.x; p < npairs; p += stride) {
-    float2 e0, e1;
-    load_pair<DT>(g, p, e0, e1);
-    uint32_t k0 = select_key(e0), k1 = select_key(e1);
+    uint32_t k0, k1;
+    pair_keys<DT>(g, p, k0, k1);
     if (in_prefix(k0, pass, prefix)) atomicAdd(&h[digit_of(k0, pass)], 1u);
     if (in_prefix(k1, pass, prefix)) atomicAdd(&h[digit_of(k1, pass)], 1u);
   }
   if ((I & 1) && blockIdx.x == 0 && threadIdx.x == 0) {
-    uint32_t k0 = select_key(load_elem<DT>(g, I - 1));
+    uint32_t k0 = elem_key<DT>(g, I - 1);
     if (in_prefix(k0, pass, prefix)) atomicAdd(&h[digit_of(k0, pass)], 1u);
   }
   __syncthreads();
@@ -99,7 +141,7 @@ __global__ __launch_bounds__(1024) void k_select_pick(int pass, uint32_t k, Sele
 
 // Flags of the (up to) two elements a lane holds in iteration `it` of segment `seg`.
 template <int DT>
-__device__ __forceinline__ void seg_keys(const void* g, int64_t I, int64_t seg, int it, int lane,
+__device__ __forceinline__ void seg_keys(const KeySource& g, int64_t I, int64_t seg, int it, int lane,
                                          int64_t& i0, bool& v0, bool& v1, uint32_t& k0, uint32_t& k1) {
   i0 = seg * kSegElems + (int64_t)it * (2 * kPairsPerIter) + 2 * lane;
   v0 = i0 < I;
@@ -107,17 +149,14 @@ __device__ __forceinline__ void seg_keys(const void* g, int64_t I, int64_t seg, 
   k0 = 0;
   k1 = 0;
   if (v1) {
-    float2 e0, e1;
-    load_pair<DT>(g, i0 >> 1, e0, e1);
-    k0 = select_key(e0);
-    k1 = select_key(e1);
+    pair_keys<DT>(g, i0 >> 1, k0, k1);
   } else if (v0) {
-    k0 = select_key(load_elem<DT>(g, i0));
+    k0 = elem_key<DT>(g, i0);
   }
 }
 
 template <int DT>
-__global__ __launch_bounds__(kSelThreads) void k_select_count(const void* __restrict__ g, int64_t I,
+__global__ __launch_bounds__(kSelThreads) void k_select_count(const KeySource g, int64_t I,
                                                               const SelectScalars* __restrict__ sc,
                                                               uint32_t* __restrict__ seg_gt,
                                                               uint32_t* __restrict__ seg_eq,
@@ -186,7 +225,7 @@ __device__ __forceinline__ uint32_t spread16(uint32_t x) {
 }
 
 template <int DT>
-__global__ __launch_bounds__(kSelThreads) void k_select_emit(const void* __restrict__ g, int64_t I,
+__global__ __launch_bounds__(kSelThreads) void k_select_emit(const KeySource g, int64_t I,
                                                              const SelectScalars* __restrict__ sc,
                                                              const uint32_t* __restrict__ seg_gt,
                                                              const uint32_t* __restrict__ seg_eq,
@@ -271,43 +310,53 @@ void zero_u32(hipStream_t s, uint32_t* p, int64_t n) {
   k_zero_u32<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(p, n);
 }
 
-void launch_select_hist(hipStream_t s, const void* g, int dtype, int64_t I, int pass,
-                        const SelectScalars* sc, uint32_t* hist) {
+void launch_select_hist(hipStream_t s, const void* g, int dtype, const SelectKeys& keys, int64_t I,
+                        int pass, const SelectScalars* sc, uint32_t* hist) {
   int64_t npairs = I >> 1;
   int64_t want = (npairs + kSelThreads - 1) / kSelThreads;
   unsigned grid = (unsigned)(want < 1 ? 1 : want > 4096 ? 4096 : want);
-  if (dtype == TGRAD_C64)
-    k_select_hist<TGRAD_C64><<<dim3(grid), dim3(kSelThreads), 0, s>>>(g, I, pass, sc, hist);
+  const KeySource src{g, keys.s0, keys.s1};
+  if (keys.random)
+    k_select_hist<kKeyRandom><<<dim3(grid), dim3(kSelThreads), 0, s>>>(src, I, pass, sc, hist);
+  else if (dtype == TGRAD_C64)
+    k_select_hist<TGRAD_C64><<<dim3(grid), dim3(kSelThreads), 0, s>>>(src, I, pass, sc, hist);
   else
-    k_select_hist<TGRAD_CBF16><<<dim3(grid), dim3(kSelThreads), 0, s>>>(g, I, pass, sc, hist);
+    k_select_hist<TGRAD_CBF16><<<dim3(grid), dim3(kSelThreads), 0, s>>>(src, I, pass, sc, hist);
 }
 
 void launch_select_pick(hipStream_t s, int pass, uint32_t k, SelectScalars* sc, const uint32_t* hist) {
   k_select_pick<<<dim3(1), dim3(1024), 0, s>>>(pass, k, sc, hist);
 }
 
-void launch_select_count(hipStream_t s, const void* g, int dtype, int64_t I, const SelectScalars* sc,
-                         uint32_t* seg_gt, uint32_t* seg_eq, int64_t nseg) {
+void launch_select_count(hipStream_t s, const void* g, int dtype, const SelectKeys& keys, int64_t I,
+                         const SelectScalars* sc, uint32_t* seg_gt, uint32_t* seg_eq, int64_t nseg) {
   unsigned grid = (unsigned)((nseg + kWavesPerBlock - 1) / kWavesPerBlock);
-  if (dtype == TGRAD_C64)
-    k_select_count<TGRAD_C64><<<dim3(grid), dim3(kSelThreads), 0, s>>>(g, I, sc, seg_gt, seg_eq, nseg);
+  const KeySource src{g, keys.s0, keys.s1};
+  if (keys.random)
+    k_select_count<kKeyRandom><<<dim3(grid), dim3(kSelThreads), 0, s>>>(src, I, sc, seg_gt, seg_eq, nseg);
+  else if (dtype == TGRAD_C64)
+    k_select_count<TGRAD_C64><<<dim3(grid), dim3(kSelThreads), 0, s>>>(src, I, sc, seg_gt, seg_eq, nseg);
   else
-    k_select_count<TGRAD_CBF16><<<dim3(grid), dim3(kSelThreads), 0, s>>>(g, I, sc, seg_gt, seg_eq, nseg);
+    k_select_count<TGRAD_CBF16><<<dim3(grid), dim3(kSelThreads), 0, s>>>(src, I, sc, seg_gt, seg_eq, nseg);
 }
 
 void launch_select_scan(hipStream_t s, uint32_t* seg_gt, uint32_t* seg_eq, int64_t nseg) {
   k_select_scan<<<dim3(1), dim3(1024), 0, s>>>(seg_gt, seg_eq, nseg);
 }
 
-void launch_select_emit(hipStream_t s, const void* g, int dtype, int64_t I, const SelectScalars* sc,
-                        const uint32_t* seg_gt, const uint32_t* seg_eq, int64_t nseg, int32_t* omega,
-                        uint32_t* mask) {
+void launch_select_emit(hipStream_t s, const void* g, int dtype, const SelectKeys& keys, int64_t I,
+                        const SelectScalars* sc, const uint32_t* seg_gt, const uint32_t* seg_eq,
+                        int64_t nseg, int32_t* omega, uint32_t* mask) {
   unsigned grid = (unsigned)((nseg + kWavesPerBlock - 1) / kWavesPerBlock);
-  if (dtype == TGRAD_C64)
-    k_select_emit<TGRAD_C64><<<dim3(grid), dim3(kSelThreads), 0, s>>>(g, I, sc, seg_gt, seg_eq, nseg,
+  const KeySource src{g, keys.s0, keys.s1};
+  if (keys.random)
+    k_select_emit<kKeyRandom><<<dim3(grid), dim3(kSelThreads), 0, s>>>(src, I, sc, seg_gt, seg_eq, nseg,
+                                                                       omega, mask);
+  else if (dtype == TGRAD_C64)
+    k_select_emit<TGRAD_C64><<<dim3(grid), dim3(kSelThreads), 0, s>>>(src, I, sc, seg_gt, seg_eq, nseg,
                                                                       omega, mask);
   else
-    k_select_emit<TGRAD_CBF16><<<dim3(grid), dim3(kSelThreads), 0, s>>>(g, I, sc, seg_gt, seg_eq, nseg,
+    k_select_emit<TGRAD_CBF16><<<dim3(grid), dim3(kSelThreads), 0, s>>>(src, I, sc, seg_gt, seg_eq, nseg,
                                                                         omega, mask);
 }
 

@@ -76,7 +76,8 @@ int validate(const tgrad_config* c) {
   if (c->refresh_every < 0) return TGRAD_ERR_INVALID_ARG;
   if (c->hooi_sweeps < 0) return TGRAD_ERR_INVALID_ARG;
   if (c->hooi_sweeps > 0) return TGRAD_ERR_UNSUPPORTED;
-  if (c->select_rule != TGRAD_SELECT_TOPK_MAG) return TGRAD_ERR_UNSUPPORTED;
+  if (c->select_rule != TGRAD_SELECT_TOPK_MAG && c->select_rule != TGRAD_SELECT_RANDOM)
+    return TGRAD_ERR_INVALID_ARG;
   return TGRAD_OK;
 }
 
@@ -278,16 +279,24 @@ int do_refresh(tgrad_ctx* c, const void* g) {
   uint32_t* mask = c->w<uint32_t>(p.ws_mask);
   int32_t* omega = c->st<int32_t>(p.st_omega);
 
-  // --- Omega <- SparseIndices(G, rho, top-k) ---
+  // --- Omega <- SparseIndices(G, rho, top-k | rand-k) ---
+  SelectKeys keys{false, 0u, 0u};
+  if (c->cfg.select_rule == TGRAD_SELECT_RANDOM) {
+    const uint64_t seed = c->cfg.select_seed;
+    const uint32_t t32 = (uint32_t)((uint64_t)c->t & 0xFFFFFFFFull);
+    keys.random = true;
+    keys.s0 = (uint32_t)(seed & 0xFFFFFFFFull) ^ (t32 * 0x9E3779B9u);
+    keys.s1 = (uint32_t)(seed >> 32) + t32 + 0x7F4A7C15u;
+  }
   if (p.k > 0) {
     zero_u32(s, hist, 3 * kHistBins);
     for (int pass = 0; pass < 3; ++pass) {
-      { Scope sc_(c, KID_SEL_HIST); launch_select_hist(s, g, dt, p.I, pass, sc, hist + pass * kHistBins); }
+      { Scope sc_(c, KID_SEL_HIST); launch_select_hist(s, g, dt, keys, p.I, pass, sc, hist + pass * kHistBins); }
       { Scope sc_(c, KID_SEL_PICK); launch_select_pick(s, pass, (uint32_t)p.k, sc, hist + pass * kHistBins); }
     }
-    { Scope sc_(c, KID_SEL_COUNT); launch_select_count(s, g, dt, p.I, sc, seg_gt, seg_eq, p.nseg); }
+    { Scope sc_(c, KID_SEL_COUNT); launch_select_count(s, g, dt, keys, p.I, sc, seg_gt, seg_eq, p.nseg); }
     { Scope sc_(c, KID_SEL_SCAN); launch_select_scan(s, seg_gt, seg_eq, p.nseg); }
-    { Scope sc_(c, KID_SEL_EMIT); launch_select_emit(s, g, dt, p.I, sc, seg_gt, seg_eq, p.nseg, omega, mask); }
+    { Scope sc_(c, KID_SEL_EMIT); launch_select_emit(s, g, dt, keys, p.I, sc, seg_gt, seg_eq, p.nseg, omega, mask); }
   }
   {
     Scope sc_(c, KID_TILE_OFFSETS);

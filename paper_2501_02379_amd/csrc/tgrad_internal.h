@@ -44,16 +44,21 @@ struct Launch {                            // what every launcher needs
   hipStream_t stream;
 };
 
-// selection
-void launch_select_hist(hipStream_t s, const void* g, int dtype, int64_t I, int pass,
-                        const SelectScalars* sc, uint32_t* hist);
+// selection.  SelectKeys: random == false -> keys are |g|^2 of the gradient; true -> keys are the
+// index hash built from the two words (the gradient pointer is then unused).
+struct SelectKeys {
+  bool random;
+  uint32_t s0, s1;
+};
+void launch_select_hist(hipStream_t s, const void* g, int dtype, const SelectKeys& keys, int64_t I,
+                        int pass, const SelectScalars* sc, uint32_t* hist);
 void launch_select_pick(hipStream_t s, int pass, uint32_t k, SelectScalars* sc, const uint32_t* hist);
-void launch_select_count(hipStream_t s, const void* g, int dtype, int64_t I, const SelectScalars* sc,
-                         uint32_t* seg_gt, uint32_t* seg_eq, int64_t nseg);
+void launch_select_count(hipStream_t s, const void* g, int dtype, const SelectKeys& keys, int64_t I,
+                         const SelectScalars* sc, uint32_t* seg_gt, uint32_t* seg_eq, int64_t nseg);
 void launch_select_scan(hipStream_t s, uint32_t* seg_gt, uint32_t* seg_eq, int64_t nseg);
-void launch_select_emit(hipStream_t s, const void* g, int dtype, int64_t I, const SelectScalars* sc,
-                        const uint32_t* seg_gt, const uint32_t* seg_eq, int64_t nseg,
-                        int32_t* omega, uint32_t* mask);
+void launch_select_emit(hipStream_t s, const void* g, int dtype, const SelectKeys& keys, int64_t I,
+                        const SelectScalars* sc, const uint32_t* seg_gt, const uint32_t* seg_eq,
+                        int64_t nseg, int32_t* omega, uint32_t* mask);
 void launch_mask_from_indices(hipStream_t s, const int32_t* omega, int64_t k, uint32_t* mask,
                               int64_t mask_words);
 

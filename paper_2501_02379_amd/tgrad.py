@@ -17,6 +17,7 @@ import numpy as np
 MAX_NDIM = 6
 TGRAD_C64, TGRAD_CBF16 = 0, 1
 TGRAD_SELECT_TOPK_MAG = 0
+TGRAD_SELECT_RANDOM = 1
 
 TGRAD_OK = 0
 TGRAD_ERR_INVALID_ARG = -1
@@ -56,6 +57,7 @@ class tgrad_config(C.Structure):
         ("refresh_every", C.c_int32),
         ("hooi_sweeps", C.c_int32),
         ("select_rule", C.c_int32),
+        ("select_seed", C.c_uint64),
     ]
 
 
@@ -119,7 +121,7 @@ def rank_from_ratio(ratio: Fraction, extent: int) -> int:
 def make_config(shape: Sequence[int], rank: Sequence[int], k_sparse: int, *, grad_dtype=TGRAD_C64,
                 weight_dtype=TGRAD_C64, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, alpha=1.0,
                 lam=1.0, weight_decay=0.0, refresh_every=1, hooi_sweeps=0,
-                select_rule=TGRAD_SELECT_TOPK_MAG) -> tgrad_config:
+                select_rule=TGRAD_SELECT_TOPK_MAG, select_seed=0) -> tgrad_config:
     cfg = tgrad_config()
     cfg.ndim = len(shape)
     if len(shape) <= MAX_NDIM and len(rank) == len(shape):
@@ -132,6 +134,7 @@ def make_config(shape: Sequence[int], rank: Sequence[int], k_sparse: int, *, gra
     cfg.lr, cfg.beta1, cfg.beta2, cfg.eps = lr, beta1, beta2, eps
     cfg.alpha, cfg.lambda_, cfg.weight_decay = alpha, lam, weight_decay
     cfg.refresh_every, cfg.hooi_sweeps, cfg.select_rule = refresh_every, hooi_sweeps, select_rule
+    cfg.select_seed = int(select_seed) & 0xFFFFFFFFFFFFFFFF
     return cfg
 
 

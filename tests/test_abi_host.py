@@ -64,7 +64,8 @@ def test_query_sizes_counts_the_compressed_state():
     (lambda c: setattr(c, "lr", float("nan")), T.TGRAD_ERR_INVALID_ARG),
     (lambda c: setattr(c, "refresh_every", -1), T.TGRAD_ERR_INVALID_ARG),
     (lambda c: setattr(c, "hooi_sweeps", 2), T.TGRAD_ERR_UNSUPPORTED),
-    (lambda c: setattr(c, "select_rule", 1), T.TGRAD_ERR_UNSUPPORTED),
+    (lambda c: setattr(c, "select_rule", 2), T.TGRAD_ERR_INVALID_ARG),
+    (lambda c: setattr(c, "select_rule", -1), T.TGRAD_ERR_INVALID_ARG),
     (lambda c: c.shape.__setitem__(0, 1 << 31), T.TGRAD_ERR_UNSUPPORTED),
 ])
 def test_bad_configs_are_rejected(mutate, expected):

@@ -170,3 +170,19 @@ def test_cfg4_headline_shape_sampled_parity():
     assert np.count_nonzero(Wg.reshape(-1)[idx] == W0.reshape(-1)[idx]) == 0
     _progress("cfg4: done, sampled dW rel err %.2e" % (np.linalg.norm(dWg - dWo) / np.linalg.norm(dWo)))
     ctx.tgrad_destroy()
+
+
+def test_cfg4_random_support_bit_exact():
+    """rand-k at the bench workload's size: 136 M keys, k = 681575, against the oracle's full sort."""
+    w = synth.WORKLOADS["cfg4"]
+    _progress("cfg4 rand-k: GPU refresh")
+    ctx = T.Context(T.make_config(w.shape, w.ranks, w.k, **_kw(w, refresh_every=0),
+                                  select_rule=T.TGRAD_SELECT_RANDOM, select_seed=0xC0FFEE1234))
+    ctx.tgrad_set_state(T.STATE_STEP, np.array([400], dtype=np.int64))
+    ctx.tgrad_refresh_factors(T.to_device_grad(synth.gradient(w, 0)))
+    got = ctx.tgrad_get_state(T.STATE_INDICES)
+    _progress("cfg4 rand-k: oracle sort of %d keys" % w.numel)
+    want = O.sparse_indices_random(w.numel, w.k, 0xC0FFEE1234, 400)
+    assert np.array_equal(got, want)
+    ctx.tgrad_destroy()
+    _progress("cfg4 rand-k: done")

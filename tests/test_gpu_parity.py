@@ -54,6 +54,39 @@ def test_sparse_indices_all_equal_and_zero_tensors():
         assert np.array_equal(ctx.tgrad_get_state(T.STATE_INDICES), np.arange(100))
 
 
+@pytest.mark.parametrize("shape,seed,dt", SEL_CASES)
+def test_random_support_bit_exact(shape, seed, dt):
+    """The rand-k rule: same counter-based keys on both sides, so the support is bit-exact; it
+    depends on (seed, step count) and not on the gradient."""
+    g = synth.small_case(shape, seed, dtype=dt)
+    I = int(np.prod(shape))
+    gd = T.to_device_grad(g)
+    seeds = (0, seed, (seed << 40) | 12345, (1 << 64) - 1)
+    for j, k in enumerate(sorted(set([0, 1, I // 100 + 1, I // 7, I // 2, I - 1, I]))):
+        sd = seeds[j % len(seeds)]
+        _announce("rand-k", shape, dt, "k=", k, "seed=", sd)
+        ctx = make_gpu_ctx(T, shape, [1] * len(shape), k, grad_dtype=T.TGRAD_CBF16 if dt == "cbf16" else 0,
+                           refresh_every=0, select_rule=T.TGRAD_SELECT_RANDOM, select_seed=sd)
+        for t in (0, 7, (1 << 32) + 3):
+            ctx.tgrad_set_state(T.STATE_STEP, np.array([t], dtype=np.int64))
+            ctx.tgrad_refresh_factors(gd)
+            got = ctx.tgrad_get_state(T.STATE_INDICES)
+            assert np.array_equal(got, O.sparse_indices_random(I, k, sd, t))
+        ctx.tgrad_destroy()
+
+
+def test_random_rule_end_to_end():
+    w = synth.WORKLOADS["cfg1"]
+    _announce("cfg1 end to end, rand-k support")
+    info, W0 = _end_to_end(w, 10, select_rule=T.TGRAD_SELECT_RANDOM, select_seed=2025)
+    assert all(info["omega_equal"]) and len(info["omega_equal"]) == 2
+    st = info["state"]
+    assert np.array_equal(st.omega, O.sparse_indices_random(w.numel, w.k, 2025, (9 // w.T) * w.T))
+    assert max(max(d) for d in info["proj_dist"]) < PROJ_TOL
+    assert rel_err(info["W_gpu"], info["W_oracle"]) < W_TOL
+    assert rel_err(info["W_gpu"] - W0, info["W_oracle"] - W0) < DW_TOL
+
+
 # ------------------------------------------------------------------ factors
 @pytest.mark.parametrize("shape,ranks,k,seed", [
     ((16, 16, 8, 5), (8, 8, 4, 3), 103, 21),
