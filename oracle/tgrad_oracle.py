@@ -54,9 +54,17 @@ the design notes of this repository):
   hash of (index, seed, step count at the refresh); see `random_keys`.  The
   paper does not say how the subset is drawn.
 
+* HOOI refinement (appendix "Implementation": the factors are refined iteratively
+  and a warm restart reuses the previous ones): a sweep re-solves mode 1, 2, ..., N
+  in turn, each on the tensor compressed in every OTHER mode with the factors as
+  they stand at that moment (an updated factor is used at once by the modes after
+  it); the sweep count is a parameter.  Warm restart: from the second refresh on,
+  the sweeps start from the factors in use instead of from HOSVD.
+
 Parity pins for every function below live in tests/test_oracle_*.py.  The HOOI
 refinement sweeps (`hooi_sweeps > 0`) are "parity unpinned" beyond monotone core
-energy and the exact-low-rank fixed point: the paper gives no sweep count.
+energy, the exact-low-rank fixed point and the one-sweep closed form on an
+order-2 tensor: the paper gives no sweep count.
 """
 from __future__ import annotations
 
@@ -326,6 +334,7 @@ class Hyper:
     weight_decay: float = 0.0
     T: int = 1                 # refresh when t % T == 0; 0 = only on request
     hooi_sweeps: int = 0
+    warm_restart: bool = False  # with hooi_sweeps >= 1: later refreshes start from the current factors
     select_rule: str = "topk"  # "topk" (magnitude) or "randk" (uniform random subset)
     select_seed: int = 0       # rand-k only
 
@@ -365,7 +374,10 @@ def refresh(st: State, G: np.ndarray) -> None:
     else:
         raise ValueError("unknown selection rule")
     R_L = remove_sparse(Gc, st.omega)
-    st.U = tucker_factors(R_L, st.hyper.ranks, st.hyper.hooi_sweeps)
+    if st.hyper.warm_restart and st.hyper.hooi_sweeps < 1:
+        raise ValueError("warm restart needs at least one HOOI sweep")
+    init = st.U if (st.hyper.warm_restart and st.U is not None) else None
+    st.U = tucker_factors(R_L, st.hyper.ranks, st.hyper.hooi_sweeps, init)
 
 
 def step(st: State, W: np.ndarray, G: np.ndarray) -> np.ndarray:

@@ -325,6 +325,60 @@ def test_hooi_core_energy_is_monotone():
     assert np.linalg.norm(O.compress(X, Uw)) >= np.linalg.norm(O.compress(X, U1)) * (1 - 1e-12)
 
 
+def test_hooi_sweep_against_svd_of_compressed_unfoldings():
+    """One sweep written out with library SVDs: mode n is re-solved as the leading left singular
+    vectors of the mode-n unfolding of X compressed (with conjugate-transposed factors) in every
+    other mode, and an updated factor is used at once by the modes after it."""
+    rng = np.random.default_rng(31)
+    X = _crandn(rng, 6, 5, 4)
+    ranks = (3, 2, 2)
+    U = [np.linalg.qr(_crandn(rng, i, r))[0] for i, r in zip(X.shape, ranks)]     # arbitrary start
+    got = O.tucker_factors(X, ranks, hooi_sweeps=1, init=U)
+    W = [u.copy() for u in U]
+    Y0 = np.einsum("abc,bq,cr->aqr", X, W[1].conj(), W[2].conj())
+    W[0] = np.linalg.svd(Y0.reshape(6, -1))[0][:, :3]
+    Y1 = np.einsum("abc,ap,cr->pbr", X, W[0].conj(), W[2].conj())
+    W[1] = np.linalg.svd(np.moveaxis(Y1, 1, 0).reshape(5, -1))[0][:, :2]
+    Y2 = np.einsum("abc,ap,bq->pqc", X, W[0].conj(), W[1].conj())
+    W[2] = np.linalg.svd(np.moveaxis(Y2, 2, 0).reshape(4, -1))[0][:, :2]
+    for a, b in zip(got, W):
+        assert np.allclose(_projector(a), _projector(b), atol=1e-10)
+    # had the sweep used the OLD factors throughout, the last mode would differ
+    Y2old = np.einsum("abc,ap,bq->pqc", X, U[0].conj(), U[1].conj())
+    W2old = np.linalg.svd(np.moveaxis(Y2old, 2, 0).reshape(4, -1))[0][:, :2]
+    assert np.linalg.norm(_projector(got[2]) - _projector(W2old)) > 1e-3
+
+
+def test_hooi_on_a_matrix_keeps_the_truncated_svd():
+    """Order 2, equal ranks: the truncated SVD is the best approximation, so the sweeps stay there."""
+    rng = np.random.default_rng(32)
+    X = _crandn(rng, 7, 5)
+    u, s, vh = np.linalg.svd(X)
+    U = O.tucker_factors(X, (2, 2), hooi_sweeps=3)
+    assert np.allclose(_projector(U[0]), _projector(u[:, :2]), atol=1e-9)
+    assert np.allclose(_projector(U[1]), _projector(vh[:2].T), atol=1e-9)          # X = u s vh: the mode-2 Gram X^T conj(X) has eigenvectors vh^T
+    assert np.isclose(np.linalg.norm(O.compress(X, U)) ** 2, np.sum(s[:2] ** 2), rtol=1e-10)
+
+
+def test_warm_restart_in_the_refresh():
+    shape, ranks = (6, 5, 4), (2, 2, 2)
+    rng = np.random.default_rng(33)
+    ga, gb = (_crandn(rng, *shape).astype(np.complex64) for _ in range(2))
+    st = O.State(shape, O.Hyper(ranks=ranks, k=3, T=0, hooi_sweeps=1, warm_restart=True))
+    O.refresh(st, ga)                                         # nothing to restart from: HOSVD + 1 sweep
+    Xa = O.remove_sparse(O.to_complex128(ga), st.omega)
+    Ua = O.tucker_factors(Xa, ranks, hooi_sweeps=1)
+    assert all(np.allclose(_projector(a), _projector(b), atol=1e-10) for a, b in zip(st.U, Ua))
+    O.refresh(st, gb)                                         # second refresh: one sweep from Ua
+    Xb = O.remove_sparse(O.to_complex128(gb), st.omega)
+    Ub = O.tucker_factors(Xb, ranks, hooi_sweeps=1, init=Ua)
+    assert all(np.allclose(_projector(a), _projector(b), atol=1e-10) for a, b in zip(st.U, Ub))
+    cold = O.tucker_factors(Xb, ranks, hooi_sweeps=1)
+    assert max(np.linalg.norm(_projector(a) - _projector(b)) for a, b in zip(st.U, cold)) > 1e-3
+    with pytest.raises(ValueError):
+        O.refresh(O.State(shape, O.Hyper(ranks=ranks, k=3, T=0, warm_restart=True)), ga)
+
+
 # ----------------------------------------------------------------- Adam
 def test_adam_real_gradient_matches_torch_adam():
     """With purely real gradients the complex rule is textbook Adam: pin it to
