@@ -37,6 +37,7 @@ extern "C" {
 #endif
 
 #define TGRAD_MAX_NDIM 6
+#define TGRAD_MAX_HOOI_SWEEPS 64
 #define TGRAD_MAX_EXTENT 256          /* largest I_n the factor refresh accepts */
 
 typedef struct tgrad_ctx tgrad_ctx;   /* opaque; host memory owned by the library */
@@ -87,7 +88,11 @@ typedef struct {
   float weight_decay;                 /* decoupled (AdamW) decay; 0 disables */
   int32_t refresh_every;              /* T >= 1: tgrad_step refreshes first when t % T == 0.
                                          0: only tgrad_refresh_factors refreshes */
-  int32_t hooi_sweeps;                /* 0 = HOSVD factors.  > 0 (HOOI refinement): UNSUPPORTED */
+  int32_t hooi_sweeps;                /* 0 = HOSVD factors (appendix "Implementation": truncated SVD of
+                                         each unfolding).  1..TGRAD_MAX_HOOI_SWEEPS: that many HOOI
+                                         sweeps after it; a sweep re-solves mode 1, 2, .., N in turn,
+                                         each on the residual compressed in every other mode with the
+                                         factors as they stand (an updated factor is used at once) */
   int32_t select_rule;                /* how SparseIndices picks Omega (section "Unstructured sparse
                                          gradient tensor"): TGRAD_SELECT_TOPK_MAG = the k entries of
                                          largest |g|^2 (float32), ties to the lower linear index;
@@ -97,6 +102,10 @@ typedef struct {
                                          32-bit finalizer, s0 = lo32(seed) ^ (t32 * 0x9E3779B9),
                                          s1 = hi32(seed) + t32 + 0x7F4A7C15, t32 = t mod 2^32 */
   uint64_t select_seed;               /* TGRAD_SELECT_RANDOM only */
+  int32_t warm_restart;               /* 0 or 1; 1 needs hooi_sweeps >= 1 (else INVALID_ARG): a refresh
+                                         that finds every factor present (from an earlier refresh or
+                                         tgrad_set_state) starts its sweeps from those factors instead
+                                         of from HOSVD (the warm restart of the same appendix) */
 } tgrad_config;
 
 /*

@@ -27,7 +27,8 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 const char* const kKernelNames[KID_COUNT] = {
     "select_hist", "select_pick", "select_count", "select_scan", "select_emit", "mask_from_indices",
     "tile_offsets", "gram", "gram_reduce", "eig_jacobi", "factor_pack",
-    "gather", "project_first", "project", "adam_core", "backproject", "update", "sparse_update"};
+    "gather", "project_first", "project", "adam_core", "backproject", "update", "sparse_update",
+    "hooi_project"};
 
 struct Plan {
   int N = 0;
@@ -50,7 +51,42 @@ struct Plan {
   size_t ws_sel, ws_hist, ws_seg_gt, ws_seg_eq, ws_mask, ws_tile_start, ws_fpad, ws_ut, ws_partials, ws_gram[kMaxNdim],
       ws_eig_a[kMaxNdim], ws_eig_v[kMaxNdim], ws_gs, ws_core_g, ws_core_n, ws_buf[2], workspace_bytes;
   int gram_chunks[kMaxNdim];
+  int hooi_sweeps = 0;
+  int hooi_gram_chunks[kMaxNdim];  // Gram of the chain result of mode n
 };
+
+// The stages of one HOOI projection chain: the residual compressed in every mode but `keep`
+// (last mode first, like the step's own chain), then the extents of the result.
+struct HooiChain {
+  int nstages;
+  Stage stage[kMaxNdim];
+  int64_t out_elems[kMaxNdim];             // elements of each stage's output
+  int64_t gram_A, gram_B;                  // the result viewed as (gram_A, I_keep, gram_B)
+};
+
+void hooi_chain(const Plan& p, int keep, HooiChain* ch) {
+  int64_t cur[kMaxNdim];
+  for (int m = 0; m < p.N; ++m) cur[m] = p.shape[m];
+  ch->nstages = 0;
+  for (int m = p.N - 1; m >= 0; --m) {
+    if (m == keep) continue;
+    Stage& st = ch->stage[ch->nstages];
+    st.mode = m;
+    st.A = 1;
+    for (int j = 0; j < m; ++j) st.A *= cur[j];
+    st.B = 1;
+    for (int j = m + 1; j < p.N; ++j) st.B *= cur[j];
+    st.K = (int)p.shape[m];
+    st.M = p.rank[m];
+    cur[m] = p.rank[m];
+    ch->out_elems[ch->nstages] = st.A * st.M * st.B;
+    ++ch->nstages;
+  }
+  ch->gram_A = 1;
+  for (int j = 0; j < keep; ++j) ch->gram_A *= cur[j];
+  ch->gram_B = 1;
+  for (int j = keep + 1; j < p.N; ++j) ch->gram_B *= cur[j];
+}
 
 int validate(const tgrad_config* c) {
   if (!c) return TGRAD_ERR_INVALID_ARG;
@@ -74,8 +110,9 @@ int validate(const tgrad_config* c) {
   if (c->beta1 < 0.f || c->beta1 >= 1.f || c->beta2 < 0.f || c->beta2 >= 1.f) return TGRAD_ERR_INVALID_ARG;
   if (c->eps < 0.f) return TGRAD_ERR_INVALID_ARG;
   if (c->refresh_every < 0) return TGRAD_ERR_INVALID_ARG;
-  if (c->hooi_sweeps < 0) return TGRAD_ERR_INVALID_ARG;
-  if (c->hooi_sweeps > 0) return TGRAD_ERR_UNSUPPORTED;
+  if (c->hooi_sweeps < 0 || c->hooi_sweeps > TGRAD_MAX_HOOI_SWEEPS) return TGRAD_ERR_INVALID_ARG;
+  if (c->warm_restart != 0 && c->warm_restart != 1) return TGRAD_ERR_INVALID_ARG;
+  if (c->warm_restart == 1 && c->hooi_sweeps < 1) return TGRAD_ERR_INVALID_ARG;
   if (c->select_rule != TGRAD_SELECT_TOPK_MAG && c->select_rule != TGRAD_SELECT_RANDOM)
     return TGRAD_ERR_INVALID_ARG;
   return TGRAD_OK;
@@ -172,6 +209,21 @@ void make_plan(const tgrad_config* c, Plan* p) {
     size_t bytes = (size_t)p->gram_chunks[n] * p->shape[n] * p->shape[n] * 16;
     if (bytes > partial_max) partial_max = bytes;
   }
+  p->hooi_sweeps = c->hooi_sweeps;
+  size_t hooi_buf[2] = {0, 0};
+  for (int n = 0; n < N; ++n) {
+    p->hooi_gram_chunks[n] = 0;
+    if (p->hooi_sweeps == 0 || p->rank[n] == p->shape[n]) continue;
+    HooiChain ch;
+    hooi_chain(*p, n, &ch);
+    for (int s = 0; s < ch.nstages; ++s) {
+      const size_t b = (size_t)ch.out_elems[s] * 8;
+      if (b > hooi_buf[s & 1]) hooi_buf[s & 1] = b;
+    }
+    p->hooi_gram_chunks[n] = gram_num_chunks(ch.gram_A, (int)p->shape[n], ch.gram_B);
+    const size_t bytes = (size_t)p->hooi_gram_chunks[n] * p->shape[n] * p->shape[n] * 16;
+    if (bytes > partial_max) partial_max = bytes;
+  }
   p->ws_partials = take(partial_max);
   for (int n = 0; n < N; ++n) {
     const size_t mat = p->rank[n] < p->shape[n] ? (size_t)p->shape[n] * p->shape[n] * 16 : 0;
@@ -182,7 +234,7 @@ void make_plan(const tgrad_config* c, Plan* p) {
   p->ws_gs = take((size_t)p->k * 8);
   p->ws_core_g = take((size_t)p->C * 8);
   p->ws_core_n = take((size_t)p->C * 8);
-  size_t buf[2] = {0, 0};
+  size_t buf[2] = {hooi_buf[0], hooi_buf[1]};
   for (int s = 0; s + 1 < N; ++s) {
     size_t bp = (size_t)(p->proj[s].A * p->proj[s].M * p->proj[s].B) * 8;
     size_t bb = (size_t)(p->back[s].A * p->back[s].M * p->back[s].B) * 8;
@@ -306,6 +358,9 @@ int do_refresh(tgrad_ctx* c, const void* g) {
   const uint32_t* use_mask = p.k > 0 ? mask : nullptr;
 
   // --- {U^(n)} <- TuckerFactors(G - Sparse(G, Omega), r) ---
+  // Warm restart: the sweeps below start from the factors in place instead of from HOSVD.
+  bool warm = c->cfg.warm_restart == 1 && p.hooi_sweeps > 0;
+  for (int n = 0; n < p.N; ++n) warm = warm && c->have_factor[n];
   const double* grams[kMaxNdim];
   double* wa[kMaxNdim];
   double* wv[kMaxNdim];
@@ -317,7 +372,7 @@ int do_refresh(tgrad_ctx* c, const void* g) {
     if (p.rank[n] == p.shape[n]) {
       Scope sc_(c, KID_FACTOR_PACK);
       launch_identity_factor(s, U, (int)p.shape[n]);
-    } else {
+    } else if (!warm) {
       int64_t A = 1, B = 1;
       for (int m = 0; m < n; ++m) A *= p.shape[m];
       for (int m = n + 1; m < p.N; ++m) B *= p.shape[m];
@@ -338,6 +393,45 @@ int do_refresh(tgrad_ctx* c, const void* g) {
   if (njobs > 0) {
     Scope sc_(c, KID_EIG);
     launch_eig_batch(s, njobs, grams, wa, wv, In, rr, Us);
+  }
+
+  // --- HOOI sweeps: mode n re-solved on the residual compressed in every other mode ---
+  float2* buf[2] = {c->w<float2>(p.ws_buf[0]), c->w<float2>(p.ws_buf[1])};
+  for (int sweep = 0; sweep < p.hooi_sweeps; ++sweep) {
+    for (int n = 0; n < p.N; ++n) {
+      if (p.rank[n] == p.shape[n]) continue;
+      HooiChain ch;
+      hooi_chain(p, n, &ch);
+      const float2* src = nullptr;
+      for (int st = 0; st < ch.nstages; ++st) {
+        const Stage& sg = ch.stage[st];
+        float2* dst = buf[st & 1];
+        const float2* Um = c->st<float2>(p.st_U[sg.mode]);
+        Scope sc_(c, KID_HOOI_PROJECT);
+        if (st == 0) {
+          // the stage that reads G: the support is removed on the way in
+          if (sg.mode == p.N - 1 && p.tile_waves > 0)
+            launch_lproj(s, g, dt, omega, c->w<uint32_t>(p.ws_tile_start), c->w<float2>(p.ws_gs), Um, sg.M, sg,
+                         p.tile_waves, dst, 0, 0, nullptr);
+          else
+            launch_contract(s, g, dt, use_mask, Um, sg.K, sg.M, true, sg, dst);
+        } else {
+          launch_mid(s, src, Um, sg.M, true, sg, dst);
+        }
+        src = dst;
+      }
+      double* partials = c->w<double>(p.ws_partials);
+      double* gram = c->w<double>(p.ws_gram[n]);
+      { Scope sc_(c, KID_GRAM); launch_gram(s, src, TGRAD_C64, nullptr, ch.gram_A, (int)p.shape[n], ch.gram_B, p.hooi_gram_chunks[n], partials); }
+      { Scope sc_(c, KID_GRAM_REDUCE); launch_gram_reduce(s, partials, p.hooi_gram_chunks[n], (int)p.shape[n], gram); }
+      const double* g1[1] = {gram};
+      double* a1[1] = {c->w<double>(p.ws_eig_a[n])};
+      double* v1[1] = {c->w<double>(p.ws_eig_v[n])};
+      int i1[1] = {(int)p.shape[n]}, r1[1] = {p.rank[n]};
+      float* u1[1] = {c->st<float>(p.st_U[n])};
+      Scope sc_(c, KID_EIG);
+      launch_eig_batch(s, 1, g1, a1, v1, i1, r1, u1);
+    }
   }
   return check_launch();
 }

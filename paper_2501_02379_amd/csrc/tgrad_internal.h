@@ -37,7 +37,7 @@ enum KernelId {
   KID_SEL_HIST = 0, KID_SEL_PICK, KID_SEL_COUNT, KID_SEL_SCAN, KID_SEL_EMIT, KID_MASK_FROM_IDX,
   KID_TILE_OFFSETS, KID_GRAM, KID_GRAM_REDUCE, KID_EIG, KID_FACTOR_PACK,
   KID_GATHER, KID_PROJECT_FIRST, KID_PROJECT, KID_ADAM_CORE, KID_BACKPROJECT, KID_UPDATE,
-  KID_SPARSE_UPDATE, KID_COUNT
+  KID_SPARSE_UPDATE, KID_HOOI_PROJECT, KID_COUNT
 };
 
 struct Launch {                            // what every launcher needs

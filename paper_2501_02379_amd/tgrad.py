@@ -58,6 +58,7 @@ class tgrad_config(C.Structure):
         ("hooi_sweeps", C.c_int32),
         ("select_rule", C.c_int32),
         ("select_seed", C.c_uint64),
+        ("warm_restart", C.c_int32),
     ]
 
 
@@ -121,7 +122,7 @@ def rank_from_ratio(ratio: Fraction, extent: int) -> int:
 def make_config(shape: Sequence[int], rank: Sequence[int], k_sparse: int, *, grad_dtype=TGRAD_C64,
                 weight_dtype=TGRAD_C64, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, alpha=1.0,
                 lam=1.0, weight_decay=0.0, refresh_every=1, hooi_sweeps=0,
-                select_rule=TGRAD_SELECT_TOPK_MAG, select_seed=0) -> tgrad_config:
+                select_rule=TGRAD_SELECT_TOPK_MAG, select_seed=0, warm_restart=False) -> tgrad_config:
     cfg = tgrad_config()
     cfg.ndim = len(shape)
     if len(shape) <= MAX_NDIM and len(rank) == len(shape):
@@ -135,6 +136,7 @@ def make_config(shape: Sequence[int], rank: Sequence[int], k_sparse: int, *, gra
     cfg.alpha, cfg.lambda_, cfg.weight_decay = alpha, lam, weight_decay
     cfg.refresh_every, cfg.hooi_sweeps, cfg.select_rule = refresh_every, hooi_sweeps, select_rule
     cfg.select_seed = int(select_seed) & 0xFFFFFFFFFFFFFFFF
+    cfg.warm_restart = int(warm_restart)
     return cfg
 
 

@@ -24,7 +24,8 @@ def oracle_hyper(shape, ranks, k, **kw) -> O.Hyper:
     return O.Hyper(ranks=tuple(ranks), k=int(k), lr=kw.get("lr", 1e-3), beta1=kw.get("beta1", 0.9),
                    beta2=kw.get("beta2", 0.999), eps=kw.get("eps", 1e-8), alpha=kw.get("alpha", 1.0),
                    lam=kw.get("lam", 1.0), weight_decay=kw.get("weight_decay", 0.0),
-                   T=kw.get("refresh_every", 1),
+                   T=kw.get("refresh_every", 1), hooi_sweeps=kw.get("hooi_sweeps", 0),
+                   warm_restart=bool(kw.get("warm_restart", False)),
                    select_rule="randk" if kw.get("select_rule", 0) == 1 else "topk",
                    select_seed=kw.get("select_seed", 0))
 

@@ -129,6 +129,88 @@ def test_exact_low_rank_gradient_gives_planted_subspace():
         assert projector_distance(ctx.tgrad_get_state(T.STATE_FACTOR0 + n), Q[n]) < 1e-4
 
 
+# ------------------------------------------------------------------ HOOI sweeps, warm restart
+def test_hooi_refresh_matches_oracle_cfg1():
+    """Two refinement sweeps after HOSVD.  On this noise-like tensor the refined factors are far
+    from the HOSVD ones (projector distance 0.2 ... 0.7), so agreement is not inherited from the
+    HOSVD test."""
+    w = synth.WORKLOADS["cfg1"]
+    _announce("cfg1, 2 HOOI sweeps")
+    info, W0 = _end_to_end(w, 10, hooi_sweeps=2)
+    assert all(info["omega_equal"]) and len(info["omega_equal"]) == 2
+    assert max(max(d) for d in info["proj_dist"]) < PROJ_TOL
+    assert rel_err(info["W_gpu"], info["W_oracle"]) < W_TOL
+    assert rel_err(info["W_gpu"] - W0, info["W_oracle"] - W0) < DW_TOL
+    g = synth.gradient(w, 5)                                       # the gradient of the last refresh
+    X = O.remove_sparse(O.to_complex128(g), info["state"].omega)
+    hosvd = O.tucker_factors(X, w.ranks)
+    ctx = info["ctx"]
+    far = [projector_distance(ctx.tgrad_get_state(T.STATE_FACTOR0 + n), hosvd[n]) for n in range(4)]
+    assert min(far) > 0.05
+
+
+def test_hooi_warm_restart_matches_oracle():
+    w = synth.WORKLOADS["cfg1"]
+    _announce("cfg1, 1 HOOI sweep, warm restart")
+    info, W0 = _end_to_end(w, 12, hooi_sweeps=1, warm_restart=True)
+    assert all(info["omega_equal"]) and len(info["omega_equal"]) == 3
+    assert max(max(d) for d in info["proj_dist"]) < PROJ_TOL
+    assert rel_err(info["W_gpu"], info["W_oracle"]) < W_TOL
+    assert rel_err(info["W_gpu"] - W0, info["W_oracle"] - W0) < DW_TOL
+    # the restart matters: a cold start on the last refresh's gradient gives other factors
+    g = synth.gradient(w, 10)
+    X = O.remove_sparse(O.to_complex128(g), info["state"].omega)
+    cold = O.tucker_factors(X, w.ranks, hooi_sweeps=1)
+    ctx = info["ctx"]
+    assert max(projector_distance(ctx.tgrad_get_state(T.STATE_FACTOR0 + n), cold[n]) for n in range(4)) > 10 * PROJ_TOL
+
+
+def test_hooi_planted_low_rank_cfg2():
+    w = synth.WORKLOADS["cfg2"]
+    _announce("cfg2, 1 HOOI sweep")
+    info, W0 = _end_to_end(w, 6, refresh_every=5, hooi_sweeps=1)
+    assert all(info["omega_equal"]) and len(info["omega_equal"]) == 2
+    assert max(max(d) for d in info["proj_dist"]) < PROJ_TOL
+    assert rel_err(info["W_gpu"], info["W_oracle"]) < W_TOL
+    assert rel_err(info["W_gpu"] - W0, info["W_oracle"] - W0) < DW_TOL
+
+
+@pytest.mark.parametrize("shape,ranks,k,dt,sweeps", [
+    ((7, 5, 3, 2), (3, 2, 2, 1), 3, "c64", 2),
+    ((6, 5, 4, 3, 5), (2, 2, 2, 2, 2), 18, "cbf16", 1),
+    ((3, 4, 2, 3, 2, 5), (2, 2, 1, 2, 1, 3), 7, "c64", 1),
+    ((33, 20, 9), (5, 20, 2), 60, "c64", 2),                        # one mode at full rank (identity factor)
+    ((40, 9, 66), (6, 3, 9), 0, "c64", 1),                          # no sparse part, last-mode rank 9
+])
+def test_hooi_odd_shapes(shape, ranks, k, dt, sweeps):
+    """Ranks obey r_n <= prod of the other ranks: beyond that the compressed unfolding is rank
+    deficient and the trailing factor columns are arbitrary on both sides."""
+    _announce("HOOI odd shape", shape, ranks, k, dt, sweeps)
+    grads = [synth.small_case(shape, 300 + t, dtype=dt) for t in range(6)]
+    rng = np.random.default_rng(5)
+    W0 = ((rng.standard_normal(shape) + 1j * rng.standard_normal(shape)) * 0.02).astype(np.complex64)
+    info = run_both(T, shape, ranks, k, grads, W0, grad_dtype=T.TGRAD_CBF16 if dt == "cbf16" else 0,
+                    refresh_every=4, hooi_sweeps=sweeps, warm_restart=(sweeps == 1), lr=2e-3)
+    assert all(info["omega_equal"])
+    assert max(max(d) for d in info["proj_dist"]) < PROJ_TOL
+    assert rel_err(info["W_gpu"], info["W_oracle"]) < W_TOL
+    assert rel_err(info["W_gpu"] - W0, info["W_oracle"] - W0) < DW_TOL
+
+
+def test_hooi_order2_factors():
+    """N = 2: compares the factors only (a step on the refresh gradient makes the core exactly
+    diagonal and Adam amplifies the rounding noise of its vanishing entries)."""
+    shape, ranks, k = (9, 6), (3, 3), 5
+    g = synth.small_case(shape, 77)
+    ctx = make_gpu_ctx(T, shape, ranks, k, refresh_every=0, hooi_sweeps=3)
+    st = O.State(shape, O.Hyper(ranks=ranks, k=k, T=0, hooi_sweeps=3))
+    ctx.tgrad_refresh_factors(T.to_device_grad(g))
+    O.refresh(st, g)
+    assert np.array_equal(ctx.tgrad_get_state(T.STATE_INDICES), st.omega)
+    for n in range(2):
+        assert projector_distance(ctx.tgrad_get_state(T.STATE_FACTOR0 + n), st.U[n]) < PROJ_TOL
+
+
 # ------------------------------------------------------------------ step with injected state
 def test_step_with_injected_support_and_factors():
     """Kernel arithmetic only: Omega and U come from the oracle, so eigen-sensitivity is out."""
