@@ -182,6 +182,11 @@ def main():
     ap.add_argument("--calibrate-copy", type=int, default=0,
                     help="also launch the library's plain copy kernel this many times on a gradient-sized "
                          "buffer (a known number of HBM bytes, for scaling rocprofv3 --pmc counters)")
+    ap.add_argument("--hooi-sweeps", type=int, default=0,
+                    help="HOOI refinement sweeps per refresh (default 0 = HOSVD factors, the headline configuration)")
+    ap.add_argument("--warm-restart", action="store_true", help="with --hooi-sweeps: refreshes restart from the factors in place")
+    ap.add_argument("--select", choices=("topk", "random"), default="topk",
+                    help="support selection rule (default top-k magnitude, the headline configuration)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU (one process, one MI355X); --gpus %d is not supported."
@@ -206,7 +211,10 @@ def main():
     for layer in range(w.layers):
         cfg = T.make_config(w.shape, w.ranks, w.k, grad_dtype=T.TGRAD_CBF16 if w.grad_dtype == "cbf16" else 0,
                             lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps, alpha=w.alpha, lam=w.lam,
-                            weight_decay=w.weight_decay, refresh_every=w.T)
+                            weight_decay=w.weight_decay, refresh_every=w.T, hooi_sweeps=args.hooi_sweeps,
+                            warm_restart=args.warm_restart,
+                            select_rule=T.TGRAD_SELECT_RANDOM if args.select == "random" else T.TGRAD_SELECT_TOPK_MAG,
+                            select_seed=2501 + layer)
         ctxs.append(T.Context(cfg, device=dev))
         Ws.append(T.to_device_weight(synth.initial_weight(w, layer), dev))
         Gs.append([T.to_device_grad(synth.gradient(w, t, layer), dev) for t in range(2)])
@@ -286,7 +294,7 @@ def main():
             ent["GBps"] = round(mm["bytes"] / lp / (avg * 1e-3) / 1e9, 1)
             ent["TFLOPs"] = round(mm["flops"] / lp / (avg * 1e-3) / 1e12, 2)
         kernels[name] = ent
-    step_kernels = [n for n in kernels if not n.startswith(("select", "gram", "eig", "mask", "factor"))]
+    step_kernels = [n for n in kernels if not n.startswith(("select", "gram", "eig", "mask", "factor", "hooi", "tile"))]
     dom = max(step_kernels, key=lambda n: kernels[n]["total_ms"]) if step_kernels else None
     roofline = None
     if dom and dom in model:
@@ -311,7 +319,8 @@ def main():
         "config": {"workload": "%s: %d x %s %s gradient, Tucker ranks %s, k=%d sparse, refresh every %d"
                                % (w.name, w.layers, "x".join(map(str, w.shape)), w.grad_dtype,
                                   ",".join(map(str, w.ranks)), w.k, w.T),
-                   "refreshes_in_timed_region": refreshes, "fused_mode_stages": bool(fused)},
+                   "refreshes_in_timed_region": refreshes, "fused_mode_stages": bool(fused),
+                   "select": args.select, "hooi_sweeps": args.hooi_sweeps, "warm_restart": bool(args.warm_restart)},
         "roofline": roofline,
         "ms_per_step_with_kernel_events": round(ms_per_step_profiled, 4),
         "refresh_ms": refresh_ms,

@@ -186,3 +186,61 @@ def test_cfg4_random_support_bit_exact():
     assert np.array_equal(got, want)
     ctx.tgrad_destroy()
     _progress("cfg4 rand-k: done")
+
+
+def test_cfg5_bf16_hooi_sweep():
+    w = synth.WORKLOADS["cfg5"]
+    _progress("cfg5 HOOI: generating 2 gradients")
+    grads = [synth.gradient(w, t) for t in range(2)]
+    W0 = synth.initial_weight(w)
+    _progress("cfg5 HOOI: running both sides (1 sweep)")
+    info = run_both(T, w.shape, w.ranks, w.k, grads, W0, grad_dtype=T.TGRAD_CBF16, **_kw(w, hooi_sweeps=1))
+    assert all(info["omega_equal"]) and len(info["omega_equal"]) == 1
+    assert max(info["proj_dist"][0]) < PROJ_TOL
+    assert rel_err(info["W_gpu"], info["W_oracle"]) < W_TOL
+    assert rel_err(info["W_gpu"] - W0, info["W_oracle"] - W0) < DW_TOL
+    _progress("cfg5 HOOI: done, proj dist %s" % (["%.1e" % d for d in info["proj_dist"][0]],))
+
+
+def test_cfg4_hooi_sweep_stage_by_stage():
+    """One HOOI sweep at the bench workload's size, checked mode by mode: the sweep's Gram matrix
+    of mode n must be that of the residual compressed with the NEW factors of the modes before n
+    and the HOSVD factors of the modes after n (taken from a second context without sweeps: the
+    refresh is run-to-run deterministic), and the new factor must hold its leading eigenvectors."""
+    w = synth.WORKLOADS["cfg4"]
+    shape, ranks, N = w.shape, w.ranks, len(w.shape)
+    g0 = synth.gradient(w, 0)
+    gd = T.to_device_grad(g0)
+    _progress("cfg4 HOOI: GPU refresh without and with one sweep")
+    ctx_a = T.Context(T.make_config(shape, ranks, w.k, **_kw(w, refresh_every=0)))
+    ctx_a.tgrad_refresh_factors(gd)
+    Ua = [ctx_a.tgrad_get_state(T.STATE_FACTOR0 + n).astype(np.complex128) for n in range(N)]
+    omega = ctx_a.tgrad_get_state(T.STATE_INDICES)
+    ctx_a.tgrad_destroy()
+    ctx_b = T.Context(T.make_config(shape, ranks, w.k, **_kw(w, refresh_every=0, hooi_sweeps=1)))
+    ctx_b.tgrad_refresh_factors(gd)
+    Ub = [ctx_b.tgrad_get_state(T.STATE_FACTOR0 + n).astype(np.complex128) for n in range(N)]
+    Gb = [ctx_b.tgrad_get_state(T.STATE_GRAM0 + n) for n in range(N)]
+    assert np.array_equal(ctx_b.tgrad_get_state(T.STATE_INDICES), omega)
+    ctx_b.tgrad_destroy()
+    del gd
+    _progress("cfg4 HOOI: oracle residual")
+    assert np.array_equal(omega, O.sparse_indices(g0, w.k))
+    X = O.remove_sparse(O.to_complex128(g0), omega)
+    for n in range(N):
+        _progress("cfg4 HOOI: oracle chain of mode %d" % n)
+        Y = X
+        for m in reversed(range(N)):                                   # cheapest order; the result does not depend on it
+            if m != n:
+                Y = O.mode_product(Y, (Ub[m] if m < n else Ua[m]).conj().T, m)
+        Ao = O.mode_gram(Y, n)
+        del Y
+        assert np.linalg.norm(Gb[n] - Ao) <= 2e-5 * np.linalg.norm(Ao)
+        assert projector_distance(Ub[n], O.top_eigvecs(Gb[n], ranks[n])) < PROJ_TOL
+        assert np.max(np.abs(Ub[n].conj().T @ Ub[n] - np.eye(ranks[n]))) < 1e-5
+        assert projector_distance(Ub[n], Ua[n]) > 10 * PROJ_TOL        # the sweep did move the factor
+    # the sweep never loses core energy (the property the iteration is built on)
+    ea = np.linalg.norm(O.compress(X, Ua)) ** 2
+    eb = np.linalg.norm(O.compress(X, Ub)) ** 2
+    assert eb >= ea * (1 - 1e-6)
+    _progress("cfg4 HOOI: done, core energy %.6e -> %.6e" % (ea, eb))
