@@ -50,6 +50,9 @@ the design notes of this repository):
   G = -grad and W <- W + eta * G~ is the same update because every operation
   applied to G is odd.
 * AdamW decay is decoupled: W <- W (1 - lr wd) - lr * D.
+* Half-precision weights are bf16 (re, im) pairs without a full-precision copy:
+  each step widens them, applies the update and rounds the result once, to
+  nearest even.  The paper says only that weights are kept in half precision.
 * Uniform random selection (rand-k) draws its subset from a counter-based integer
   hash of (index, seed, step count at the refresh); see `random_keys`.  The
   paper does not say how the subset is drawn.
@@ -123,6 +126,30 @@ def _as_c64_pairs(G: np.ndarray) -> np.ndarray:
     if G.dtype != np.complex64:
         raise TypeError("gradient must be complex64 or uint16 bf16 pairs")
     return np.ascontiguousarray(G).view(np.float32).reshape(G.shape + (2,))
+
+
+def round_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """Real float64 values -> bf16 bit patterns (uint16), round to nearest, ties to even.
+
+    bf16 = 1 sign, 8 exponent, 7 stored fraction bits: a normal number x = m 2^e with
+    0.5 <= |m| < 1 lies on a grid of spacing 2^(e-8); below the smallest normal (2^-126) the
+    spacing stays 2^-133.  numpy's rint rounds halves to even, which on that grid is the
+    required tie rule.  Values beyond the largest finite bf16 become infinities."""
+    x = np.asarray(x, dtype=np.float64)
+    _, e = np.frexp(x)
+    e = np.maximum(e, -125)
+    q = np.ldexp(1.0, e - 8)
+    y = np.rint(x / q) * q
+    y = np.where(np.abs(y) > 3.3895313892515355e38, np.copysign(np.inf, y), y)   # (2 - 2^-7) 2^127
+    f = y.astype(np.float32)                                 # exact: every bf16 is a float32
+    bits = (f.view(np.uint32) >> np.uint32(16)).astype(np.uint16)
+    return np.where(np.isnan(x), np.uint16(0x7FC0), bits).astype(np.uint16)
+
+
+def complex_to_bf16_pairs(Z: np.ndarray) -> np.ndarray:
+    """complex128 -> (..., 2) uint16 bf16 bit patterns (re, im), each part rounded to nearest even."""
+    Z = np.asarray(Z, dtype=np.complex128)
+    return np.stack([round_to_bf16_bits(Z.real), round_to_bf16_bits(Z.imag)], axis=-1)
 
 
 def to_complex128(G: np.ndarray) -> np.ndarray:
@@ -381,7 +408,14 @@ def refresh(st: State, G: np.ndarray) -> None:
 
 
 def step(st: State, W: np.ndarray, G: np.ndarray) -> np.ndarray:
-    """One pass of Algorithm 1's loop body; returns W_{t+1} (complex128)."""
+    """One pass of Algorithm 1's loop body; returns W_{t+1} (complex128).
+
+    Weights stored in half precision (section "Mixed precision training": weights, activations and
+    gradients in half precision, optimizer states in full precision): W given as bf16 pairs
+    (uint16, trailing axis 2) is widened exactly, updated as below, and returned rounded ONCE to
+    bf16 pairs (nearest even) - there is no full-precision copy of the weights."""
+    if np.asarray(W).dtype == np.uint16:
+        return complex_to_bf16_pairs(step(st, bf16_pairs_to_complex(W), G))
     h = st.hyper
     if h.T > 0 and st.t % h.T == 0:
         refresh(st, G)

@@ -627,6 +627,50 @@ def test_random_rule_in_the_step():
         O.refresh(O.State(shape, O.Hyper(ranks=(2, 2, 2), k=7, select_rule="probk")), g)
 
 
+# ----------------------------------------------------------------- bf16-stored weights
+def test_bf16_rounding_matches_torch_and_the_tie_rule():
+    import torch
+    rng = np.random.default_rng(41)
+    x = np.concatenate([rng.standard_normal(20000) * 10.0 ** rng.integers(-6, 6, 20000),
+                        [0.0, -0.0, 1.0, -1.0, 3.3e38, -3.3e38, 1e-40, -1e-40, 2.0 ** -126, 2.0 ** -133, 2.0 ** -134]])
+    x32 = x.astype(np.float32)                              # torch rounds float32 -> bf16; feed both the same values
+    want = torch.from_numpy(x32).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    got = O.round_to_bf16_bits(x32.astype(np.float64))
+    assert np.array_equal(got, want)
+    assert np.array_equal(got, synth.float32_to_bf16_bits(x32))
+    # ties go to the even neighbour; just off a tie goes to the nearer one (float64 inputs)
+    one = 0x3F80
+    cases = [(1.0 + 2.0 ** -8, one), (1.0 + 3 * 2.0 ** -8, one + 2), (1.0 + 2.0 ** -8 + 2.0 ** -40, one + 1),
+             (1.0 + 2.0 ** -8 - 2.0 ** -40, one), (-(1.0 + 2.0 ** -8), 0x8000 | one), (2.0 - 2.0 ** -9, one + 128)]
+    for v, bits in cases:
+        assert int(O.round_to_bf16_bits(np.array([v]))[0]) == bits
+    # widening inverts rounding exactly on every finite pattern
+    allbits = np.arange(1 << 16, dtype=np.uint16)
+    vals32 = (allbits.astype(np.uint32) << np.uint32(16)).view(np.float32)
+    fin = np.isfinite(vals32)
+    assert np.array_equal(O.round_to_bf16_bits(vals32[fin].astype(np.float64)), allbits[fin])
+    assert np.isinf((O.round_to_bf16_bits(np.array([3.4e38])).astype(np.uint32) << 16).view(np.float32))[0]
+
+
+def test_step_with_bf16_weights_rounds_once():
+    shape = (4, 3, 5)
+    rng = np.random.default_rng(42)
+    g = _crandn(rng, *shape).astype(np.complex64)
+    Wb = O.complex_to_bf16_pairs(0.02 * _crandn(rng, *shape))
+    assert Wb.dtype == np.uint16 and Wb.shape == shape + (2,)
+    h = O.Hyper(ranks=(2, 2, 2), k=7, lr=1e-3, weight_decay=0.1)
+    sa, sb = O.State(shape, h), O.State(shape, h)
+    out_bits = O.step(sa, Wb, g)
+    out_full = O.step(sb, O.bf16_pairs_to_complex(Wb), g)                 # same step on the widened weights
+    assert out_bits.dtype == np.uint16
+    assert np.array_equal(out_bits, O.complex_to_bf16_pairs(out_full))
+    back = O.bf16_pairs_to_complex(out_bits)
+    for a, b in ((back.real, out_full.real), (back.imag, out_full.imag)):           # half a grid step per part
+        assert np.all(np.abs(a - b) <= 2.0 ** -8 * np.abs(b))
+    assert np.array_equal(sa.M_S, sb.M_S) and np.array_equal(sa.M_L, sb.M_L)        # states untouched by storage
+    assert not np.array_equal(out_bits, Wb)
+
+
 # ----------------------------------------------------------------- generators
 def test_synthetic_inputs_are_seeded_and_shaped():
     w = synth.WORKLOADS["cfg1"]
