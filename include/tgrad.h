@@ -80,7 +80,10 @@ typedef struct {
                                          compressed (identity factor) */
   int64_t k_sparse;                   /* k = ceil(rho * I), 0..I, computed by the caller exactly */
   int32_t grad_dtype;                 /* TGRAD_C64 or TGRAD_CBF16 */
-  int32_t weight_dtype;               /* TGRAD_C64 (bf16-stored weights: TGRAD_ERR_UNSUPPORTED) */
+  int32_t weight_dtype;               /* TGRAD_C64, or TGRAD_CBF16: weights kept in half precision
+                                         (section "Mixed precision training"; optimizer states stay
+                                         float32): bf16 (re, im) pairs, 4 bytes per element, widened
+                                         exactly, updated in float32, rounded once to nearest even */
   float lr;                           /* eta */
   float beta1, beta2, eps;            /* Adam decay rates and epsilon */
   float alpha;                        /* scale of the reconstructed update */
@@ -150,7 +153,7 @@ int tgrad_refresh_factors(tgrad_ctx* ctx, const void* grad_dev);
  * correction, N = (M / (1 - beta1^tau)) / (sqrt(V / (1 - beta2^tau)) + eps), V from |x|^2;
  * D <- alpha * (N_L x_1 U1 ... x_N UN); D[Omega] += lambda * N_S;
  * W <- W (1 - lr wd) - lr D; t <- t + 1.
- *  weight_dev  device pointer to W (TGRAD_C64), updated in place.
+ *  weight_dev  device pointer to W (layout per cfg.weight_dtype), updated in place.
  *  grad_dev    device pointer to G (cfg.grad_dtype), read only, must not alias W.
  * Errors: INVALID_ARG, NOT_READY (refresh_every == 0 and no refresh yet), HIP.
  */

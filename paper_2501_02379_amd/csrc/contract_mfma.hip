@@ -571,11 +571,67 @@ __device__ __forceinline__ void sparse_adam_entry(const SparseAdam& sp, uint32_t
 
 constexpr int kUpdPrefetch = 17;          // 16-byte pieces of W per lane kept in flight during the MFMA phase
 
-template <int W, int NTB, int JT>
+// float32 -> bf16 bit pattern, round to nearest, ties to even (NaN stays a quiet NaN).
+__device__ __forceinline__ uint32_t bf16_rne(float f) {
+  const uint32_t u = __float_as_uint(f);
+  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return 0x7FC0u;
+  return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+__device__ __forceinline__ uint32_t bf16_pack(float re, float im) { return bf16_rne(re) | (bf16_rne(im) << 16); }
+
+// How the weight tensor is stored (section "Mixed precision training": weights may be kept in half
+// precision while the optimizer states stay in full precision).  A "piece" is 16 bytes of the W tile:
+// 2 complex64 elements, or 4 elements stored as bf16 (re, im) pairs.  apply() returns
+// decay * w + d for the piece, d read from the float32 image `sD` of the tile's update; bf16 weights
+// are widened exactly, updated in float32 and rounded once (nearest even).
+template <int WDT> struct WStore;
+template <> struct WStore<TGRAD_C64> {
+  typedef float4 raw;
+  static constexpr int kElems = 2;
+  static constexpr int kPrefetch = kUpdPrefetch;
+  static __device__ __forceinline__ raw* tile(void* w, int64_t w_base) {
+    return reinterpret_cast<raw*>(reinterpret_cast<float*>(w) + 2 * w_base);
+  }
+  static __device__ __forceinline__ raw apply(const raw o, const float* sD, int q, float decay) {
+    const float4 d = reinterpret_cast<const float4*>(sD)[q];
+    return make_float4(decay * o.x + d.x, decay * o.y + d.y, decay * o.z + d.z, decay * o.w + d.w);
+  }
+  static __device__ __forceinline__ void apply_one(void* w, int64_t e, const float* d, float decay) {
+    float2* p = reinterpret_cast<float2*>(w) + e;
+    const float2 o = *p;
+    *p = make_float2(decay * o.x + d[0], decay * o.y + d[1]);
+  }
+};
+template <> struct WStore<TGRAD_CBF16> {
+  typedef uint4 raw;
+  static constexpr int kElems = 4;
+  static constexpr int kPrefetch = (kUpdPrefetch + 1) / 2;
+  static __device__ __forceinline__ raw* tile(void* w, int64_t w_base) {
+    return reinterpret_cast<raw*>(reinterpret_cast<uint32_t*>(w) + w_base);
+  }
+  static __device__ __forceinline__ uint32_t one(uint32_t o, float dre, float dim, float decay) {
+    return bf16_pack(decay * __uint_as_float(o << 16) + dre, decay * __uint_as_float(o & 0xFFFF0000u) + dim);
+  }
+  static __device__ __forceinline__ raw apply(const raw o, const float* sD, int q, float decay) {
+    const float4 d0 = reinterpret_cast<const float4*>(sD)[2 * q];
+    const float4 d1 = reinterpret_cast<const float4*>(sD)[2 * q + 1];
+    return make_uint4(one(o.x, d0.x, d0.y, decay), one(o.y, d0.z, d0.w, decay), one(o.z, d1.x, d1.y, decay),
+                      one(o.w, d1.z, d1.w, decay));
+  }
+  static __device__ __forceinline__ void apply_one(void* w, int64_t e, const float* d, float decay) {
+    uint32_t* p = reinterpret_cast<uint32_t*>(w) + e;
+    *p = one(*p, d[0], d[1], decay);
+  }
+};
+__device__ __forceinline__ void claim_raw(uint4& r) { asm volatile("" : "+v"(r.x), "+v"(r.y), "+v"(r.z), "+v"(r.w)); }
+
+template <int WDT, int W, int NTB, int JT>
 __global__ __launch_bounds__(64 * W, 2) void k_lupdate(const float* __restrict__ z,
                                                        const float2* __restrict__ U, int64_t A, int K,
-                                                       int M, int64_t ntiles, float* __restrict__ w,
+                                                       int M, int64_t ntiles, void* __restrict__ w,
                                                        float decay, float c_alpha, SparseAdam sp) {
+  typedef WStore<WDT> WS;
+  typedef typename WS::raw wraw;
   constexpr int T = 64 * W;
   extern __shared__ float smem[];
   const int N2 = 2 * M;
@@ -645,8 +701,8 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate(const float* __restrict__
     const int part = col & 1;
     const int64_t w_base = tile * tile_w;                      // complex index of the tile in W
     const int n_w = (int)((Iw - w_base) < tile_w ? (Iw - w_base) : tile_w);
-    float4* w4 = reinterpret_cast<float4*>(w + 2 * w_base);    // 16-byte aligned: 32 M is even
-    const int n4 = n_w >> 1;                                   // whole 16-byte pieces (2 complex each)
+    wraw* w4 = WS::tile(w, w_base);                            // 16-byte aligned: a tile holds 32 M elements
+    const int n4 = n_w / WS::kElems;                           // whole 16-byte pieces
     // ---- what was fetched one tile ago moves out of the prefetch registers; the next tile's small
     //      loads and this tile's W pieces go in flight ----
     float2 zcur[JT];
@@ -664,9 +720,9 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate(const float* __restrict__
         nnj1 = sp.tile_start[nn + 1 + vzero];
       }
     }
-    float4 wpre[kUpdPrefetch];                                 // unconditional loads, clamped onto the last
-#pragma unroll                                                 // piece (n4 >= 1: the host keeps M >= 2 here)
-    for (int i = 0; i < kUpdPrefetch; ++i) {
+    wraw wpre[WS::kPrefetch];                                  // unconditional loads, clamped onto the last
+#pragma unroll                                                 // piece (the host keeps n4 >= 1 for every tile)
+    for (int i = 0; i < WS::kPrefetch; ++i) {
       const int q = lane_now + i * 64;
       wpre[i] = w4[q < n4 ? q : n4 - 1];
     }
@@ -714,27 +770,17 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate(const float* __restrict__
     // ---- stream the tile into W ----
     claim_small();
 #pragma unroll
-    for (int i = 0; i < kUpdPrefetch; ++i) claim_raw(wpre[i]);
-    const float4* d4 = reinterpret_cast<const float4*>(sD);
+    for (int i = 0; i < WS::kPrefetch; ++i) claim_raw(wpre[i]);
     const int nfull = n4 >> 6;                                 // pieces every lane owns: no per-lane branch
 #pragma unroll
-    for (int i = 0; i < kUpdPrefetch; ++i) {
+    for (int i = 0; i < WS::kPrefetch; ++i) {
       const int q = lane_now + i * 64;
-      if (i < nfull || q < n4) {
-        const float4 d = d4[q];
-        const float4 o = wpre[i];
-        w4[q] = make_float4(decay * o.x + d.x, decay * o.y + d.y, decay * o.z + d.z, decay * o.w + d.w);
-      }
+      if (i < nfull || q < n4) w4[q] = WS::apply(wpre[i], sD, q, decay);
     }
-    for (int q = lane + kUpdPrefetch * 64; q < n4; q += 64) {
-      const float4 d = d4[q];
-      const float4 o = w4[q];
-      w4[q] = make_float4(decay * o.x + d.x, decay * o.y + d.y, decay * o.z + d.z, decay * o.w + d.w);
-    }
-    if ((n_w & 1) && lane == 0) {                              // odd element count: last complex alone
-      float2* w2 = reinterpret_cast<float2*>(w) + w_base + (n_w - 1);
-      const float2 o = *w2;
-      *w2 = make_float2(decay * o.x + sD[2 * (n_w - 1)], decay * o.y + sD[2 * (n_w - 1) + 1]);
+    for (int q = lane + WS::kPrefetch * 64; q < n4; q += 64) w4[q] = WS::apply(w4[q], sD, q, decay);
+    {                                                          // elements past the last whole piece
+      const int e = n4 * WS::kElems + lane;
+      if (e < n_w) WS::apply_one(w, w_base + e, sD + 2 * e, decay);
     }
     if (nxt >= ntiles) break;
     tile = nxt;
@@ -764,11 +810,13 @@ struct FusedPrev {
   int K2;               // rank of mode N-1
 };
 
-template <int W, int NTB, int JT2>
+template <int WDT, int W, int NTB, int JT2>
 __global__ __launch_bounds__(64 * W, 2) void k_lupdate_fused(const float2* __restrict__ U, int64_t A, int K,
-                                                             int M, int64_t ntiles, float* __restrict__ w,
+                                                             int M, int64_t ntiles, void* __restrict__ w,
                                                              float decay, float c_alpha, SparseAdam sp,
                                                              FusedPrev fz) {
+  typedef WStore<WDT> WS;
+  typedef typename WS::raw wraw;
   constexpr int T = 64 * W;
   extern __shared__ float smem[];
   const int N2 = 2 * M;
@@ -834,8 +882,8 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate_fused(const float2* __res
     const int part = col & 1;
     const int64_t w_base = tile * tile_w;
     const int n_w = (int)((Iw - w_base) < tile_w ? (Iw - w_base) : tile_w);
-    float4* w4 = reinterpret_cast<float4*>(w + 2 * w_base);
-    const int n4 = n_w >> 1;
+    wraw* w4 = WS::tile(w, w_base);
+    const int n4 = n_w / WS::kElems;                           // tiles are whole here: 32 M elements, a multiple of 4
     const int32_t c_om = my_om;
     const float2 c_g = my_g, c_m = my_m;
     const float c_v = my_v;
@@ -861,9 +909,9 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate_fused(const float2* __res
       }
     }
     // ---- this tile's W pieces go in flight ----
-    float4 wpre[kUpdPrefetch];
+    wraw wpre[WS::kPrefetch];
 #pragma unroll
-    for (int i = 0; i < kUpdPrefetch; ++i) {
+    for (int i = 0; i < WS::kPrefetch; ++i) {
       const int q = lane_now + i * 64;
       wpre[i] = w4[q < n4 ? q : n4 - 1];
     }
@@ -936,23 +984,14 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate_fused(const float2* __res
     // ---- the wait point for everything still in flight, then stream the tile into W ----
     claim_sparse();
 #pragma unroll
-    for (int i = 0; i < kUpdPrefetch; ++i) claim_raw(wpre[i]);
-    const float4* d4 = reinterpret_cast<const float4*>(sD);
+    for (int i = 0; i < WS::kPrefetch; ++i) claim_raw(wpre[i]);
     const int nfull = n4 >> 6;
 #pragma unroll
-    for (int i = 0; i < kUpdPrefetch; ++i) {
+    for (int i = 0; i < WS::kPrefetch; ++i) {
       const int q = lane_now + i * 64;
-      if (i < nfull || q < n4) {
-        const float4 d = d4[q];
-        const float4 o = wpre[i];
-        w4[q] = make_float4(decay * o.x + d.x, decay * o.y + d.y, decay * o.z + d.z, decay * o.w + d.w);
-      }
+      if (i < nfull || q < n4) w4[q] = WS::apply(wpre[i], sD, q, decay);
     }
-    for (int q = lane + kUpdPrefetch * 64; q < n4; q += 64) {
-      const float4 d = d4[q];
-      const float4 o = w4[q];
-      w4[q] = make_float4(decay * o.x + d.x, decay * o.y + d.y, decay * o.z + d.z, decay * o.w + d.w);
-    }
+    for (int q = lane + WS::kPrefetch * 64; q < n4; q += 64) w4[q] = WS::apply(w4[q], sD, q, decay);
     if (!have_next) break;
     tile = nxt;
     slab = nslab;
@@ -1164,8 +1203,8 @@ void launch_lproj(hipStream_t s, const void* g, int dtype, const int32_t* omega,
 #undef TGRAD_LP
 }
 
-void launch_lupdate(hipStream_t s, const float2* z, const float2* U, const Stage& st, int W, float2* w,
-                    float decay, float c_alpha, const int32_t* omega, const uint32_t* tile_start,
+void launch_lupdate(hipStream_t s, const float2* z, const float2* U, const Stage& st, int W, void* w,
+                    int wdtype, float decay, float c_alpha, const int32_t* omega, const uint32_t* tile_start,
                     const float2* gs, float2* ms, float* vs, float beta1, float beta2, float inv_c1,
                     float inv_c2, float eps, float c_lambda) {
   const int64_t A = st.A;
@@ -1177,12 +1216,16 @@ void launch_lupdate(hipStream_t s, const float2* z, const float2* U, const Stage
   dim3 grid((unsigned)grid_for_tiles((ntiles + W - 1) / W, per_cu < 1 ? 1 : per_cu > 2 ? 2 : per_cu)), block(64 * W);
   SparseAdam sp{omega, tile_start, gs, ms, vs, beta1, beta2, inv_c1, inv_c2, eps, c_lambda, 0};
   const float* zf = reinterpret_cast<const float*>(z);
-  float* wf = reinterpret_cast<float*>(w);
   const int jt = lupdate_jt(K);
 #define TGRAD_LU(W_, JT_)                                                                                \
   do {                                                                                                   \
-    allow_lds(k_lupdate<W_, 2, JT_>, lds);                                                               \
-    k_lupdate<W_, 2, JT_><<<grid, block, lds, s>>>(zf, U, A, K, M, ntiles, wf, decay, c_alpha, sp);      \
+    if (wdtype == TGRAD_C64) {                                                                           \
+      allow_lds(k_lupdate<TGRAD_C64, W_, 2, JT_>, lds);                                                  \
+      k_lupdate<TGRAD_C64, W_, 2, JT_><<<grid, block, lds, s>>>(zf, U, A, K, M, ntiles, w, decay, c_alpha, sp); \
+    } else {                                                                                             \
+      allow_lds(k_lupdate<TGRAD_CBF16, W_, 2, JT_>, lds);                                                \
+      k_lupdate<TGRAD_CBF16, W_, 2, JT_><<<grid, block, lds, s>>>(zf, U, A, K, M, ntiles, w, decay, c_alpha, sp); \
+    }                                                                                                    \
   } while (0)
 #define TGRAD_LU_J(W_)                                                                                   \
   do {                                                                                                   \
@@ -1197,7 +1240,7 @@ void launch_lupdate(hipStream_t s, const float2* z, const float2* U, const Stage
 // k_lupdate with the reconstruction stage of mode N-1 in front (see k_lupdate_fused): `y1` is the
 // tensor before that stage, (slabs, K2, K) complex; `ut` the transposed factor copy; I2 = 32 S.
 void launch_lupdate_fused(hipStream_t s, const float2* y1, const float2* ut, int I2, int K2, const float2* U,
-                          const Stage& st, float2* w, float decay, float c_alpha, const int32_t* omega,
+                          const Stage& st, void* w, int wdtype, float decay, float c_alpha, const int32_t* omega,
                           const uint32_t* tile_start, int64_t k, const float2* gs, float2* ms, float* vs,
                           float beta1, float beta2, float inv_c1, float inv_c2, float eps, float c_lambda) {
   const int64_t A = st.A;
@@ -1214,11 +1257,15 @@ void launch_lupdate_fused(hipStream_t s, const float2* y1, const float2* ut, int
   SparseAdam sp{omega, tile_start, gs, ms, vs, beta1, beta2, inv_c1, inv_c2, eps, c_lambda,
                 (int)(k > 0 ? k - 1 : 0)};
   FusedPrev fz{y1, ut, S, K2};
-  float* wf = reinterpret_cast<float*>(w);
 #define TGRAD_LUF(JT2_)                                                                                  \
   do {                                                                                                   \
-    allow_lds(k_lupdate_fused<W, 1, JT2_>, lds);                                                         \
-    k_lupdate_fused<W, 1, JT2_><<<grid, block, lds, s>>>(U, A, K, M, ntiles, wf, decay, c_alpha, sp, fz); \
+    if (wdtype == TGRAD_C64) {                                                                           \
+      allow_lds(k_lupdate_fused<TGRAD_C64, W, 1, JT2_>, lds);                                            \
+      k_lupdate_fused<TGRAD_C64, W, 1, JT2_><<<grid, block, lds, s>>>(U, A, K, M, ntiles, w, decay, c_alpha, sp, fz); \
+    } else {                                                                                             \
+      allow_lds(k_lupdate_fused<TGRAD_CBF16, W, 1, JT2_>, lds);                                          \
+      k_lupdate_fused<TGRAD_CBF16, W, 1, JT2_><<<grid, block, lds, s>>>(U, A, K, M, ntiles, w, decay, c_alpha, sp, fz); \
+    }                                                                                                    \
   } while (0)
   if (K2 <= 8) TGRAD_LUF(4); else if (K2 <= 16) TGRAD_LUF(8); else TGRAD_LUF(16);
 #undef TGRAD_LUF

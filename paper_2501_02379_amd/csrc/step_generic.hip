@@ -77,32 +77,12 @@ __global__ void k_adam_core(const float2* __restrict__ r, float2* __restrict__ m
   n_out[i] = make_float2(mm.x * inv_c1 * d, mm.y * inv_c1 * d);
 }
 
-// Last reconstruction stage fused with the weight update (Algorithm 1, "Reconstruct low-rank
-// part" and W <- W + eta G~): W[a, m] <- decay * W[a, m] + neg_lr_alpha * sum_k U[m, k] z[a, k].
-__global__ __launch_bounds__(kThreads) void k_update(const float2* __restrict__ z,
-                                                     const float2* __restrict__ U, int rn, int64_t A,
-                                                     int M, float2* __restrict__ w, float decay,
-                                                     float neg_lr_alpha) {
-  const int64_t o = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-  if (o >= A * M) return;
-  const int m = (int)(o % M);
-  const int64_t a = o / M;
-  float2 acc = make_float2(0.f, 0.f);
-  for (int k = 0; k < rn; ++k) {
-    float2 p = cmul(U[(int64_t)m * rn + k], z[a * rn + k]);
-    acc.x += p.x;
-    acc.y += p.y;
-  }
-  float2 ww = w[o];
-  w[o] = make_float2(decay * ww.x + neg_lr_alpha * acc.x, decay * ww.y + neg_lr_alpha * acc.y);
-}
-
-// AdamUpdate on the sparse values, then "Add scaled sparse tensor": W[Omega_j] += -lr lambda N_S[j]
-// (a scatter-ADD onto the already updated entry; Omega has no duplicates, so no atomics).
-__global__ void k_sparse_update(const float2* __restrict__ gs, const int32_t* __restrict__ omega,
-                                int64_t k, float2* __restrict__ m, float* __restrict__ v,
-                                float2* __restrict__ w, float beta1, float beta2, float inv_c1,
-                                float inv_c2, float eps, float neg_lr_lambda) {
+// AdamUpdate on the sparse values (appendix algorithm "Adam with low-rank tensor decomposition",
+// applied to g_S): moments in place; gs[j] <- neg_lr_lambda * N_S[j], the scaled sparse update
+// that k_update adds at Omega_j.
+__global__ void k_sparse_adam(float2* __restrict__ gs, int64_t k, float2* __restrict__ m,
+                              float* __restrict__ v, float beta1, float beta2, float inv_c1,
+                              float inv_c2, float eps, float neg_lr_lambda) {
   int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (j >= k) return;
   float2 x = gs[j];
@@ -113,9 +93,60 @@ __global__ void k_sparse_update(const float2* __restrict__ gs, const int32_t* __
   m[j] = mm;
   v[j] = vv;
   float d = 1.f / (sqrtf(vv * inv_c2) + eps);
-  const int64_t i = omega[j];
-  float2 ww = w[i];
-  w[i] = make_float2(ww.x + neg_lr_lambda * (mm.x * inv_c1 * d), ww.y + neg_lr_lambda * (mm.y * inv_c1 * d));
+  gs[j] = make_float2(neg_lr_lambda * (mm.x * inv_c1 * d), neg_lr_lambda * (mm.y * inv_c1 * d));
+}
+
+__device__ __forceinline__ uint32_t bf16_bits_rne(float f) {
+  const uint32_t u = __float_as_uint(f);
+  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return 0x7FC0u;
+  return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+
+// Last reconstruction stage fused with the weight update (Algorithm 1, "Reconstruct low-rank
+// part", "Add scaled sparse tensor" and W <- W + eta G~):
+//   W[a, m] <- decay * W[a, m] + neg_lr_alpha * sum_k U[m, k] z[a, k]  (+ ns[j] where (a, m) = Omega_j).
+// The support is found through the bitmask and a binary search of the ascending index list.
+// WDT: weights stored as complex64, or as bf16 pairs that are widened, updated in float32 and
+// rounded once to nearest even.
+template <int WDT>
+__global__ __launch_bounds__(kThreads) void k_update(const float2* __restrict__ z,
+                                                     const float2* __restrict__ U, int rn, int64_t A,
+                                                     int M, void* __restrict__ w, float decay,
+                                                     float neg_lr_alpha, const uint32_t* __restrict__ mask,
+                                                     const int32_t* __restrict__ omega, int64_t k,
+                                                     const float2* __restrict__ ns) {
+  const int64_t o = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (o >= A * M) return;
+  const int m = (int)(o % M);
+  const int64_t a = o / M;
+  float2 acc = make_float2(0.f, 0.f);
+  for (int kk = 0; kk < rn; ++kk) {
+    float2 p = cmul(U[(int64_t)m * rn + kk], z[a * rn + kk]);
+    acc.x += p.x;
+    acc.y += p.y;
+  }
+  float2 upd = make_float2(neg_lr_alpha * acc.x, neg_lr_alpha * acc.y);
+  if (mask && ((mask[o >> 5] >> (o & 31)) & 1u)) {
+    int64_t lo = 0, hi = k - 1;                    // the bit is set, so o is in omega[0 .. k-1]
+    while (lo < hi) {
+      const int64_t mid = (lo + hi) >> 1;
+      if ((int64_t)omega[mid] < o) lo = mid + 1; else hi = mid;
+    }
+    const float2 sv = ns[lo];
+    upd.x += sv.x;
+    upd.y += sv.y;
+  }
+  if constexpr (WDT == TGRAD_C64) {
+    float2* wp = reinterpret_cast<float2*>(w) + o;
+    const float2 ww = *wp;
+    *wp = make_float2(decay * ww.x + upd.x, decay * ww.y + upd.y);
+  } else {
+    uint32_t* wp = reinterpret_cast<uint32_t*>(w) + o;
+    const uint32_t raw = *wp;
+    const float re = decay * __uint_as_float(raw << 16) + upd.x;
+    const float im = decay * __uint_as_float(raw & 0xFFFF0000u) + upd.y;
+    *wp = bf16_bits_rne(re) | (bf16_bits_rne(im) << 16);
+  }
 }
 
 inline unsigned blocks_for(int64_t n, int threads) { return (unsigned)((n + threads - 1) / threads); }
@@ -154,20 +185,24 @@ void launch_adam_core(hipStream_t s, const float2* r, float2* m, float* v, float
                                                             inv_c2, eps);
 }
 
-void launch_update(hipStream_t s, const float2* z, const float2* U, int In, int rn, const Stage& st,
-                   float2* w, float decay, float neg_lr_alpha) {
-  (void)In;
-  const int64_t total = st.A * st.M;
-  k_update<<<dim3(blocks_for(total, kThreads)), dim3(kThreads), 0, s>>>(z, U, rn, st.A, st.M, w, decay,
-                                                                       neg_lr_alpha);
+void launch_sparse_adam(hipStream_t s, float2* gs, int64_t k, float2* m, float* v, float beta1, float beta2,
+                        float inv_c1, float inv_c2, float eps, float neg_lr_lambda) {
+  if (k <= 0) return;
+  k_sparse_adam<<<dim3(blocks_for(k, 256)), dim3(256), 0, s>>>(gs, k, m, v, beta1, beta2, inv_c1, inv_c2, eps,
+                                                              neg_lr_lambda);
 }
 
-void launch_sparse_update(hipStream_t s, const float2* gs, const int32_t* omega, int64_t k, float2* m,
-                          float* v, float2* w, float beta1, float beta2, float inv_c1, float inv_c2,
-                          float eps, float neg_lr_lambda) {
-  if (k <= 0) return;
-  k_sparse_update<<<dim3(blocks_for(k, 256)), dim3(256), 0, s>>>(gs, omega, k, m, v, w, beta1, beta2,
-                                                                inv_c1, inv_c2, eps, neg_lr_lambda);
+void launch_update(hipStream_t s, const float2* z, const float2* U, int In, int rn, const Stage& st, void* w,
+                   int wdtype, float decay, float neg_lr_alpha, const uint32_t* mask, const int32_t* omega,
+                   int64_t k, const float2* ns) {
+  (void)In;
+  const int64_t total = st.A * st.M;
+  if (total <= 0) return;
+  dim3 grid(blocks_for(total, kThreads)), block(kThreads);
+  if (wdtype == TGRAD_C64)
+    k_update<TGRAD_C64><<<grid, block, 0, s>>>(z, U, rn, st.A, st.M, w, decay, neg_lr_alpha, mask, omega, k, ns);
+  else
+    k_update<TGRAD_CBF16><<<grid, block, 0, s>>>(z, U, rn, st.A, st.M, w, decay, neg_lr_alpha, mask, omega, k, ns);
 }
 
 }  // namespace tgrad

@@ -102,8 +102,7 @@ int validate(const tgrad_config* c) {
     if (c->shape[n] > TGRAD_MAX_EXTENT && c->rank[n] != c->shape[n]) return TGRAD_ERR_UNSUPPORTED;
   if (c->k_sparse < 0 || (long double)c->k_sparse > numel) return TGRAD_ERR_INVALID_ARG;
   if (c->grad_dtype != TGRAD_C64 && c->grad_dtype != TGRAD_CBF16) return TGRAD_ERR_INVALID_ARG;
-  if (c->weight_dtype == TGRAD_CBF16) return TGRAD_ERR_UNSUPPORTED;
-  if (c->weight_dtype != TGRAD_C64) return TGRAD_ERR_INVALID_ARG;
+  if (c->weight_dtype != TGRAD_C64 && c->weight_dtype != TGRAD_CBF16) return TGRAD_ERR_INVALID_ARG;
   const float fl[] = {c->lr, c->beta1, c->beta2, c->eps, c->alpha, c->lambda, c->weight_decay};
   for (float f : fl)
     if (!std::isfinite(f)) return TGRAD_ERR_INVALID_ARG;
@@ -161,6 +160,7 @@ void make_plan(const tgrad_config* c, Plan* p) {
     if (const char* e = std::getenv("TGRAD_TILE_WAVES")) prefer = std::atoi(e);   // tuning knob: 0, 1, 2, 4
     const int last = N - 1;
     p->tile_waves = prefer > 0 ? choose_tile_waves((int)p->shape[last], p->rank[last], prefer) : 0;
+    if (c->weight_dtype == TGRAD_CBF16 && p->I < 4) p->tile_waves = 0;   // a bf16 tile needs one whole 16-byte piece
     const int64_t rows = p->I / p->shape[last];
     p->ntiles = (rows + 31) / 32;                 // last-mode kernels: flat tiles of 32 rows
     p->tile_elems = (int64_t)32 * p->shape[last];
@@ -514,24 +514,23 @@ int do_step(tgrad_ctx* c, void* weight, const void* g) {
     if (mfma_last && p.fuse_next) {
       Scope sc_(c, KID_UPDATE);
       launch_lupdate_fused(s, zsrc, c->w<float2>(p.ws_ut), (int)p.shape[N - 2], p.rank[N - 2], U, sg,
-                           reinterpret_cast<float2*>(weight), decay, -cf.lr * cf.alpha, omega, tile_start, p.k, gs,
+                           weight, cf.weight_dtype, decay, -cf.lr * cf.alpha, omega, tile_start, p.k, gs,
                            c->st<float2>(p.st_ms), c->st<float>(p.st_vs), cf.beta1, cf.beta2, inv_c1, inv_c2,
                            cf.eps, -cf.lr * cf.lambda);
     } else if (mfma_last) {
       Scope sc_(c, KID_UPDATE);
-      launch_lupdate(s, zsrc, U, sg, p.tile_waves, reinterpret_cast<float2*>(weight), decay, -cf.lr * cf.alpha,
+      launch_lupdate(s, zsrc, U, sg, p.tile_waves, weight, cf.weight_dtype, decay, -cf.lr * cf.alpha,
                      omega, tile_start, gs, c->st<float2>(p.st_ms), c->st<float>(p.st_vs), cf.beta1, cf.beta2,
                      inv_c1, inv_c2, cf.eps, -cf.lr * cf.lambda);
     } else {
       {
-        Scope sc_(c, KID_UPDATE);
-        launch_update(s, zsrc, U, (int)p.shape[sg.mode], p.rank[sg.mode], sg, reinterpret_cast<float2*>(weight),
-                      decay, -cf.lr * cf.alpha);
+        Scope sc_(c, KID_SPARSE_UPDATE);
+        launch_sparse_adam(s, gs, p.k, c->st<float2>(p.st_ms), c->st<float>(p.st_vs), cf.beta1, cf.beta2, inv_c1,
+                           inv_c2, cf.eps, -cf.lr * cf.lambda);
       }
-      Scope sc_(c, KID_SPARSE_UPDATE);
-      launch_sparse_update(s, gs, omega, p.k, c->st<float2>(p.st_ms), c->st<float>(p.st_vs),
-                           reinterpret_cast<float2*>(weight), cf.beta1, cf.beta2, inv_c1, inv_c2, cf.eps,
-                           -cf.lr * cf.lambda);
+      Scope sc_(c, KID_UPDATE);
+      launch_update(s, zsrc, U, (int)p.shape[sg.mode], p.rank[sg.mode], sg, weight, cf.weight_dtype, decay,
+                    -cf.lr * cf.alpha, mask, omega, p.k, gs);
     }
   }
   c->t += 1;

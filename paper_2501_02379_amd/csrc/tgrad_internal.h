@@ -77,11 +77,11 @@ void launch_contract(hipStream_t s, const void* x, int x_dtype, const uint32_t* 
                      const float2* U, int In, int rn, bool project, const Stage& st, float2* out);
 void launch_adam_core(hipStream_t s, const float2* r, float2* m, float* v, float2* n_out, int64_t C,
                       float beta1, float beta2, float inv_c1, float inv_c2, float eps);
-void launch_update(hipStream_t s, const float2* z, const float2* U, int In, int rn, const Stage& st,
-                   float2* w, float decay, float neg_lr_alpha);
-void launch_sparse_update(hipStream_t s, const float2* gs, const int32_t* omega, int64_t k,
-                          float2* m, float* v, float2* w, float beta1, float beta2, float inv_c1,
-                          float inv_c2, float eps, float neg_lr_lambda);
+void launch_sparse_adam(hipStream_t s, float2* gs, int64_t k, float2* m, float* v, float beta1, float beta2,
+                        float inv_c1, float inv_c2, float eps, float neg_lr_lambda);
+void launch_update(hipStream_t s, const float2* z, const float2* U, int In, int rn, const Stage& st, void* w,
+                   int wdtype, float decay, float neg_lr_alpha, const uint32_t* mask, const int32_t* omega,
+                   int64_t k, const float2* ns);
 
 // matrix-core kernels of the step (contract_mfma.hip)
 int choose_tile_waves(int Klast, int rlast, int prefer);
@@ -93,13 +93,13 @@ void launch_pack_fused_factor(hipStream_t s, const float2* U, int I2, int r, flo
 void launch_lproj(hipStream_t s, const void* g, int dtype, const int32_t* omega, const uint32_t* tile_start,
                   float2* gs, const float2* U, int rn, const Stage& st, int W, float2* out, int fused_I2,
                   int fused_M2, const float2* fpad);
-void launch_lupdate(hipStream_t s, const float2* z, const float2* U, const Stage& st, int W, float2* w,
-                    float decay, float c_alpha, const int32_t* omega, const uint32_t* tile_start,
+void launch_lupdate(hipStream_t s, const float2* z, const float2* U, const Stage& st, int W, void* w,
+                    int wdtype, float decay, float c_alpha, const int32_t* omega, const uint32_t* tile_start,
                     const float2* gs, float2* ms, float* vs, float beta1, float beta2, float inv_c1,
                     float inv_c2, float eps, float c_lambda);
 
 void launch_lupdate_fused(hipStream_t s, const float2* y1, const float2* ut, int I2, int K2, const float2* U,
-                          const Stage& st, float2* w, float decay, float c_alpha, const int32_t* omega,
+                          const Stage& st, void* w, int wdtype, float decay, float c_alpha, const int32_t* omega,
                           const uint32_t* tile_start, int64_t k, const float2* gs, float2* ms, float* vs,
                           float beta1, float beta2, float inv_c1, float inv_c2, float eps, float c_lambda);
 

@@ -280,11 +280,18 @@ def to_device_grad(g: np.ndarray, device="cuda:0"):
 
 
 def to_device_weight(w: np.ndarray, device="cuda:0"):
+    """Upload weights: complex64, or uint16 bf16 (re, im) pairs with a trailing axis of 2 (for a
+    context made with weight_dtype=TGRAD_CBF16)."""
     import torch
+    if np.asarray(w).dtype == np.uint16:
+        return torch.from_numpy(np.ascontiguousarray(w).view(np.int16)).to(device)
     w = np.ascontiguousarray(w, dtype=np.complex64)
     return torch.from_numpy(w.view(np.float32).reshape(w.shape + (2,))).to(device)
 
 
 def weight_to_host(w_dev) -> np.ndarray:
-    a = w_dev.detach().cpu().numpy()
-    return np.ascontiguousarray(a).view(np.complex64).reshape(a.shape[:-1])
+    """complex64 array, or uint16 bf16 pairs (trailing axis 2) for half-precision weights."""
+    a = np.ascontiguousarray(w_dev.detach().cpu().numpy())
+    if a.dtype == np.int16:
+        return a.view(np.uint16)
+    return a.view(np.complex64).reshape(a.shape[:-1])

@@ -60,3 +60,31 @@ def run_both(T, shape, ranks, k, grads, W0, grad_dtype=0, check_every_refresh=Tr
     info["ctx"] = ctx
     info["state"] = st
     return info
+
+
+def bf16_ordinal(bits: np.ndarray) -> np.ndarray:
+    """bf16 bit patterns -> integers that increase with the value (consecutive bf16 numbers differ by 1)."""
+    b = np.asarray(bits, dtype=np.uint16).astype(np.int32)
+    mag = b & 0x7FFF
+    return np.where(b & 0x8000, -mag, mag)
+
+
+def run_both_bf16_weights(T, shape, ranks, k, grads, W0_bits, grad_dtype=0, resync=False, **kw):
+    """Like run_both, with weights stored as bf16 pairs on both sides.  `resync`: before every step
+    the GPU receives the oracle's current weights, so each step starts from identical bits and the
+    comparison isolates one step's rounding.  Returns per-step ulp statistics and the final bits."""
+    import torch
+    ctx = make_gpu_ctx(T, shape, ranks, k, grad_dtype=grad_dtype, weight_dtype=T.TGRAD_CBF16, **kw)
+    st = O.State(tuple(shape), oracle_hyper(shape, ranks, k, **kw))
+    Wo = np.array(W0_bits, dtype=np.uint16, copy=True)
+    Wd = T.to_device_weight(Wo)
+    stats = []
+    for g in grads:
+        if resync:
+            Wd = T.to_device_weight(Wo)
+        ctx.tgrad_step(Wd, T.to_device_grad(g))
+        Wo = O.step(st, Wo, g)
+        torch.cuda.synchronize()
+        d = np.abs(bf16_ordinal(T.weight_to_host(Wd)) - bf16_ordinal(Wo))
+        stats.append((int(d.max()), float(np.count_nonzero(d)) / d.size))
+    return {"stats": stats, "W_gpu": T.weight_to_host(Wd), "W_oracle": Wo, "ctx": ctx, "state": st}

@@ -59,7 +59,7 @@ def test_query_sizes_counts_the_compressed_state():
     (lambda c: setattr(c, "k_sparse", -1), T.TGRAD_ERR_INVALID_ARG),
     (lambda c: setattr(c, "k_sparse", 16 * 16 * 8 * 5 + 1), T.TGRAD_ERR_INVALID_ARG),
     (lambda c: setattr(c, "grad_dtype", 7), T.TGRAD_ERR_INVALID_ARG),
-    (lambda c: setattr(c, "weight_dtype", T.TGRAD_CBF16), T.TGRAD_ERR_UNSUPPORTED),
+    (lambda c: setattr(c, "weight_dtype", 5), T.TGRAD_ERR_INVALID_ARG),
     (lambda c: setattr(c, "beta1", 1.0), T.TGRAD_ERR_INVALID_ARG),
     (lambda c: setattr(c, "lr", float("nan")), T.TGRAD_ERR_INVALID_ARG),
     (lambda c: setattr(c, "refresh_every", -1), T.TGRAD_ERR_INVALID_ARG),

@@ -10,7 +10,7 @@ import pytest
 from oracle import tgrad_oracle as O
 from paper_2501_02379_amd import synth
 from paper_2501_02379_amd import tgrad as T
-from helpers import projector_distance, rel_err, run_both, make_gpu_ctx
+from helpers import projector_distance, rel_err, run_both, make_gpu_ctx, run_both_bf16_weights, bf16_ordinal
 
 pytestmark = pytest.mark.gpu
 
@@ -127,6 +127,83 @@ def test_exact_low_rank_gradient_gives_planted_subspace():
     ctx.tgrad_refresh_factors(T.to_device_grad(g))
     for n in range(3):
         assert projector_distance(ctx.tgrad_get_state(T.STATE_FACTOR0 + n), Q[n]) < 1e-4
+
+
+# ------------------------------------------------------------------ the three kernel tiers, small
+FUSED_SHAPES = [
+    ((16, 32, 32, 9), (4, 8, 8, 4), 300),          # one tile per slab
+    ((16, 32, 64, 5), (4, 8, 16, 2), 200),         # two tiles per slab
+]
+
+
+@pytest.mark.parametrize("shape,ranks,k", FUSED_SHAPES)
+def test_fused_tier_small_shapes(shape, ranks, k):
+    """Shapes that take the fused kernels (modes N-1 and N in one pass) at a size the oracle runs
+    whole; the launch counts prove which tier ran."""
+    _announce("fused tier", shape, ranks, k)
+    grads = [synth.small_case(shape, 500 + t, outlier_frac=(1, 200)) for t in range(6)]
+    rng = np.random.default_rng(6)
+    W0 = ((rng.standard_normal(shape) + 1j * rng.standard_normal(shape)) * 0.02).astype(np.complex64)
+    info = run_both(T, shape, ranks, k, grads, W0, refresh_every=4, lr=2e-3, weight_decay=0.01)
+    assert all(info["omega_equal"])
+    assert max(max(d) for d in info["proj_dist"]) < PROJ_TOL
+    assert rel_err(info["W_gpu"], info["W_oracle"]) < W_TOL
+    assert rel_err(info["W_gpu"] - W0, info["W_oracle"] - W0) < DW_TOL
+    ctx = info["ctx"]
+    ctx.tgrad_set_profiling(True)
+    ctx.tgrad_step(T.to_device_weight(W0), T.to_device_grad(grads[0]))
+    times = ctx.tgrad_get_kernel_times()
+    assert times["project"]["launches"] == len(shape) - 2 and times["backproject"]["launches"] == len(shape) - 2
+
+
+# ------------------------------------------------------------------ weights stored as bf16 pairs
+def _bf16_weights(shape, seed):
+    rng = np.random.default_rng(seed)
+    return O.complex_to_bf16_pairs((rng.standard_normal(shape) + 1j * rng.standard_normal(shape)) * 0.02)
+
+
+BF16W_CASES = [
+    # shape, ranks, k, gradient dtype            kernel tier
+    ((16, 16, 8, 5), (8, 8, 4, 3), 103, "c64"),      # matrix-core, unfused
+    ((16, 32, 32, 9), (4, 8, 8, 4), 300, "c64"),     # fused
+    ((16, 32, 64, 5), (4, 8, 16, 2), 200, "cbf16"),  # fused, half-precision gradients too
+    ((7, 5, 3), (3, 2, 2), 9, "c64"),                # last tile ragged: 3 rows x 3 elements
+    ((9, 7, 6), (3, 3, 2), 11, "c64"),               # tail of 2 elements after the whole pieces
+    ((8, 7, 40), (2, 2, 36), 30, "c64"),             # generic kernels (last-mode rank above 32)
+    ((5, 4, 3, 1), (2, 2, 2, 1), 3, "c64"),          # generic kernels (last extent 1)
+]
+
+
+@pytest.mark.parametrize("shape,ranks,k,dt", BF16W_CASES)
+def test_bf16_weights_single_steps(shape, ranks, k, dt):
+    """Each step starts from the oracle's bits: the GPU (float32 arithmetic) and the oracle
+    (float64) may round differently only where the exact result sits within a few float32 ulps of
+    a bf16 rounding boundary: at most one bf16 ulp apart, on a small share of the entries."""
+    _announce("bf16 weights, single steps", shape, ranks, k, dt)
+    grads = [synth.small_case(shape, 600 + t, dtype=dt) for t in range(6)]
+    info = run_both_bf16_weights(T, shape, ranks, k, grads, _bf16_weights(shape, 7), resync=True,
+                                 grad_dtype=T.TGRAD_CBF16 if dt == "cbf16" else 0,
+                                 refresh_every=4, lr=2e-3, weight_decay=0.01)
+    I = int(np.prod(shape))
+    for worst, frac in info["stats"]:
+        assert worst <= 1
+        assert frac <= max(2e-3, 2.0 / (2 * I))
+    assert np.array_equal(info["ctx"].tgrad_get_state(T.STATE_INDICES), info["state"].omega)
+    assert rel_err(info["ctx"].tgrad_get_state(T.STATE_SPARSE_M), info["state"].M_S) < 1e-5
+
+
+def test_bf16_weights_ten_free_running_steps():
+    w = synth.WORKLOADS["cfg1"]
+    grads = [synth.gradient(w, t) for t in range(10)]
+    W0 = _bf16_weights(w.shape, 8)
+    info = run_both_bf16_weights(T, w.shape, w.ranks, w.k, grads, W0, refresh_every=w.T, lr=w.lr)
+    worst, frac = info["stats"][-1]
+    assert worst <= 2 and frac < 1e-2                      # single flips persist; they do not grow
+    moved = np.count_nonzero(bf16_ordinal(info["W_gpu"]) != bf16_ordinal(W0))
+    assert moved > 0.5 * 2 * w.numel                        # the update is visible at bf16 resolution
+    a = O.bf16_pairs_to_complex(info["W_gpu"]) - O.bf16_pairs_to_complex(W0)
+    b = O.bf16_pairs_to_complex(info["W_oracle"]) - O.bf16_pairs_to_complex(W0)
+    assert np.linalg.norm(a - b) <= 1e-2 * np.linalg.norm(b)
 
 
 # ------------------------------------------------------------------ HOOI sweeps, warm restart
