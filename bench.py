@@ -30,12 +30,12 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def kernel_model(w, fused):
+def kernel_model(w, fused, weight_bytes=8):
     """Algorithmic bytes and flops per launch of every kernel, from the tensor shapes alone
     (8 real flops per complex multiply-add; a complex64 element is 8 bytes).  `fused`: the library
     ran the mode-(N-1) compression / reconstruction stages inside the first-stage and the
     weight-update kernels (it does whenever the shape allows), so the tensors between them are
-    neither written nor read."""
+    neither written nor read.  `weight_bytes`: 8 for complex64 weights, 4 for bf16 pairs."""
     shape, ranks, k = w.shape, w.ranks, w.k
     N = len(shape)
     I = int(np.prod(shape))
@@ -84,7 +84,7 @@ def kernel_model(w, fused):
     # update: reads its input tensor and W, writes W; per sparse entry its index, gathered value
     # and both moments are read and the moments written back
     A, K, M, B = stage_dims(False, N - 1)
-    by, fl = A * K * 8 + 16 * I + k * (4 + 8 + 12 + 12), 8 * A * K * M + 4 * I + 14 * k
+    by, fl = A * K * 8 + 2 * weight_bytes * I + k * (4 + 8 + 12 + 12), 8 * A * K * M + 4 * I + 14 * k
     if fused:
         A1, K1, M1, B1 = stage_dims(False, N - 2)
         by += A1 * K1 * B1 * 8 - A * K * 8                  # reads the stage-(N-2) input instead
@@ -187,6 +187,8 @@ def main():
     ap.add_argument("--warm-restart", action="store_true", help="with --hooi-sweeps: refreshes restart from the factors in place")
     ap.add_argument("--select", choices=("topk", "random"), default="topk",
                     help="support selection rule (default top-k magnitude, the headline configuration)")
+    ap.add_argument("--weights", choices=("c64", "bf16"), default="c64",
+                    help="weight storage (default complex64, the headline configuration; bf16 = half-precision pairs)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU (one process, one MI355X); --gpus %d is not supported."
@@ -214,9 +216,11 @@ def main():
                             weight_decay=w.weight_decay, refresh_every=w.T, hooi_sweeps=args.hooi_sweeps,
                             warm_restart=args.warm_restart,
                             select_rule=T.TGRAD_SELECT_RANDOM if args.select == "random" else T.TGRAD_SELECT_TOPK_MAG,
-                            select_seed=2501 + layer)
+                            select_seed=2501 + layer,
+                            weight_dtype=T.TGRAD_CBF16 if args.weights == "bf16" else T.TGRAD_C64)
         ctxs.append(T.Context(cfg, device=dev))
-        Ws.append(T.to_device_weight(synth.initial_weight(w, layer), dev))
+        w0 = synth.initial_weight(w, layer)
+        Ws.append(T.to_device_weight(synth.complex64_to_bf16_pairs(w0) if args.weights == "bf16" else w0, dev))
         Gs.append([T.to_device_grad(synth.gradient(w, t, layer), dev) for t in range(2)])
     torch.cuda.synchronize()
 
@@ -283,7 +287,7 @@ def main():
     # the library fuses the mode-(N-1) stages when the shape allows: then k_mid runs N - 2 times each way
     nstep = max(1, times.get("project_first", {}).get("launches", 1))
     fused = len(w.shape) >= 3 and times.get("project", {}).get("launches", 0) == (len(w.shape) - 2) * nstep
-    model = kernel_model(w, fused)
+    model = kernel_model(w, fused, 4 if args.weights == "bf16" else 8)
     kernels = {}
     for name, v in sorted(times.items(), key=lambda kv: -kv[1]["total_ms"]):
         avg = v["total_ms"] / max(1, v["launches"])
@@ -307,7 +311,7 @@ def main():
             ach, peak, unit = mm["flops"] / lp / avg_s / 1e12, MFMA_FP32_PEAK_TF, "TFLOP/s"
         roofline = {"kernel": dom, "bound": "hbm" if mm["bound"] == "hbm" else "mfma",
                     "achieved": round(ach, 2), "peak": peak, "unit": unit, "frac": round(ach / peak, 4),
-                    "traffic": measured_traffic(w.name, dom),
+                    "traffic": measured_traffic(w.name, dom) if args.weights == "c64" else None,
                     "algorithmic_bytes_per_launch": mm["bytes"] // lp,
                     "avg_launch_ms": kernels[dom]["avg_ms"]}
 
@@ -320,7 +324,7 @@ def main():
                                % (w.name, w.layers, "x".join(map(str, w.shape)), w.grad_dtype,
                                   ",".join(map(str, w.ranks)), w.k, w.T),
                    "refreshes_in_timed_region": refreshes, "fused_mode_stages": bool(fused),
-                   "select": args.select, "hooi_sweeps": args.hooi_sweeps, "warm_restart": bool(args.warm_restart)},
+                   "weights": args.weights, "select": args.select, "hooi_sweeps": args.hooi_sweeps, "warm_restart": bool(args.warm_restart)},
         "roofline": roofline,
         "ms_per_step_with_kernel_events": round(ms_per_step_profiled, 4),
         "refresh_ms": refresh_ms,

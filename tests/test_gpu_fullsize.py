@@ -22,7 +22,7 @@ import pytest
 from oracle import tgrad_oracle as O
 from paper_2501_02379_amd import synth
 from paper_2501_02379_amd import tgrad as T
-from helpers import projector_distance, rel_err, run_both
+from helpers import projector_distance, rel_err, run_both, run_both_bf16_weights
 
 pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
 
@@ -244,3 +244,19 @@ def test_cfg4_hooi_sweep_stage_by_stage():
     eb = np.linalg.norm(O.compress(X, Ub)) ** 2
     assert eb >= ea * (1 - 1e-6)
     _progress("cfg4 HOOI: done, core energy %.6e -> %.6e" % (ea, eb))
+
+
+def test_cfg3_one_layer_bf16_weights():
+    """Half-precision weights at full size through the fused kernels: two free-running steps."""
+    w = synth.WORKLOADS["cfg3"]
+    _progress("cfg3 bf16 weights: generating inputs")
+    grads = [synth.gradient(w, t, layer=2) for t in range(2)]
+    W0 = O.complex_to_bf16_pairs(synth.initial_weight(w, layer=2))
+    _progress("cfg3 bf16 weights: running both sides")
+    info = run_both_bf16_weights(T, w.shape, w.ranks, w.k, grads, W0, **_kw(w))
+    (w1, f1), (w2, f2) = info["stats"]
+    _progress("cfg3 bf16 weights: worst %d / %d ulps, mismatching share %.1e / %.1e" % (w1, w2, f1, f2))
+    assert w1 <= 1 and f1 < 1e-2                      # first step: identical starting bits
+    assert w2 <= 2 and f2 < 2e-2
+    assert np.array_equal(info["ctx"].tgrad_get_state(T.STATE_INDICES), info["state"].omega)
+    _progress("cfg3 bf16 weights: done, mismatching share %.1e then %.1e" % (f1, f2))

