@@ -205,6 +205,18 @@ struct EigJobs {
   EigJob job[kMaxNdim];
 };
 
+// Rotation log of the LDS solver (extents <= 128), kept in the job's work buffer `A`: a header,
+// then one entry per (logged round, slot).  p < 0: the slot's pivot was already negligible.
+struct RotLog {
+  double c, sx, sy;     // cos, sin e^{i phi}
+  int p, q;
+};
+struct EigLogHeader {
+  double lam[128];      // eigenvalues (diagonal of the converged work matrix)
+  int rounds;           // logged rounds (rounds in which nothing rotates are not logged)
+  int pad[3];
+};
+
 constexpr int kEigThreads = 1024;
 constexpr int kEigMaxN = TGRAD_MAX_EXTENT;
 constexpr int kEigMaxSweeps = 30;
@@ -444,8 +456,10 @@ __global__ __launch_bounds__(kEigThreads) void k_eig_tri(EigJobs jobs) {
   const EigJob jb = jobs.job[blockIdx.x];
   const int n = jb.n, r = jb.r;
   const int tid = threadIdx.x;
-  double2* V = reinterpret_cast<double2*>(jb.V);
   const double2* G = reinterpret_cast<const double2*>(jb.gram);
+  EigLogHeader* hdr = reinterpret_cast<EigLogHeader*>(jb.A);
+  RotLog* rlog = reinterpret_cast<RotLog*>(reinterpret_cast<char*>(jb.A) + sizeof(EigLogHeader));
+  int nlogged = 0;                               // rounds written to the log (uniform over the block)
 
   __shared__ int sp[kEigTriMaxN / 2 + 1], sq[kEigTriMaxN / 2 + 1];
   __shared__ double sc[kEigTriMaxN / 2 + 1];
@@ -453,16 +467,12 @@ __global__ __launch_bounds__(kEigThreads) void k_eig_tri(EigJobs jobs) {
   __shared__ int srot[kEigTriMaxN / 2 + 1];
   __shared__ int nrot;
   __shared__ double red[kEigThreads];
-  __shared__ double lam[kEigTriMaxN];
-  __shared__ int col_of[kEigTriMaxN];
-  __shared__ double2 phase[kEigTriMaxN];
 
   double tr = 0.;
   for (int e = tid; e < n * n; e += kEigThreads) {
     const int i = e / n, j = e - i * n;
     const double2 g = G[e];
     if (i >= j) T[tri_idx(i, j)] = g;
-    V[e] = make_double2(i == j ? 1. : 0., 0.);
     if (i == j) tr += g.x;
   }
   red[tid] = tr;
@@ -500,37 +510,18 @@ __global__ __launch_bounds__(kEigThreads) void k_eig_tri(EigJobs jobs) {
         if (rot) atomicAdd(&nrot, 1);
       }
       if (!__syncthreads_or(rot)) continue;            // nothing rotates in this round (late sweeps)
-      // ---- phase 2a: V[:, p] <- c V[:, p] - conj(s) V[:, q],  V[:, q] <- s V[:, p] + c V[:, q]
-      //      (memory; loads of a batch issued together) ----
-      for (int e0 = tid; e0 < n * half; e0 += kEigThreads * kEigBatch) {
-        double2 xp[kEigBatch], xq[kEigBatch];
-        int off_p[kEigBatch], off_q[kEigBatch], prs[kEigBatch];
-#pragma unroll
-        for (int u = 0; u < kEigBatch; ++u) {
-          const int e = e0 + u * kEigThreads;
-          prs[u] = -1;
-          if (e < n * half) {
-            const int i = e / half, pr = e - i * half;
-            if (srot[pr]) {
-              prs[u] = pr;
-              off_p[u] = i * n + sp[pr];
-              off_q[u] = i * n + sq[pr];
-              xp[u] = V[off_p[u]];
-              xq[u] = V[off_q[u]];
-            }
-          }
-        }
-#pragma unroll
-        for (int u = 0; u < kEigBatch; ++u) {
-          if (prs[u] >= 0) {
-            const double c = sc[prs[u]];
-            const double2 s = ss[prs[u]];
-            const double2 t1 = cmuld(conjd(s), xq[u]), t2 = cmuld(s, xp[u]);
-            V[off_p[u]] = make_double2(c * xp[u].x - t1.x, c * xp[u].y - t1.y);
-            V[off_q[u]] = make_double2(t2.x + c * xq[u].x, t2.y + c * xq[u].y);
-          }
-        }
+      // ---- phase 2a: the round's rotations go to the log; the eigenvector accumulator is built from
+      //      it afterwards by k_eig_apply, all rows in parallel ----
+      if (tid < half) {
+        RotLog e;
+        e.c = sc[tid];
+        e.sx = ss[tid].x;
+        e.sy = ss[tid].y;
+        e.p = srot[tid] ? sp[tid] : -1;
+        e.q = sq[tid];
+        rlog[(size_t)nlogged * half + tid] = e;
       }
+      ++nlogged;
       // ---- phase 2b: every block (pair a, pair b), a >= b:  B <- L_a B R_b  with
       //      L = [[c, -s], [conj(s), c]] on the rows (p_a, q_a), R = [[c, s], [-conj(s), c]] on the
       //      columns (p_b, q_b) ----
@@ -588,9 +579,67 @@ __global__ __launch_bounds__(kEigThreads) void k_eig_tri(EigJobs jobs) {
     __syncthreads();
     if (done) break;
   }
-  for (int i = tid; i < n; i += kEigThreads) lam[i] = T[tri_idx(i, i)].x;
+  for (int i = tid; i < n; i += kEigThreads) hdr->lam[i] = T[tri_idx(i, i)].x;
+  if (tid == 0) hdr->rounds = nlogged;
+}
+
+// Eigenvector accumulator from the rotation log: V = R_1 R_2 ... (every round's rotations act on
+// column pairs), so each ROW of V evolves on its own: one wavefront per row, the row in LDS, lane =
+// slot of the round; the arithmetic per element is that of the in-kernel update of k_eig.
+constexpr int kLogAhead = 4;                     // rounds whose log entries are in flight
+
+__global__ __launch_bounds__(64) void k_eig_apply(EigJobs jobs) {
+  const EigJob jb = jobs.job[blockIdx.y];
+  const int n = jb.n;
+  const int row = blockIdx.x;
+  if (row >= n) return;
+  __shared__ double2 x[kEigTriMaxN];
+  const int lane = threadIdx.x;
+  for (int j = lane; j < n; j += 64) x[j] = make_double2(j == row ? 1. : 0., 0.);
+  const EigLogHeader* hdr = reinterpret_cast<const EigLogHeader*>(jb.A);
+  const RotLog* rlog = reinterpret_cast<const RotLog*>(reinterpret_cast<const char*>(jb.A) + sizeof(EigLogHeader));
+  const int half = (n + (n & 1)) / 2;
+  const int rounds = hdr->rounds;
+  const int slot = lane < half ? lane : half - 1;          // idle lanes shadow the last slot, write nothing
+  RotLog ahead[kLogAhead];
+#pragma unroll
+  for (int d = 0; d < kLogAhead; ++d) ahead[d] = rlog[(size_t)(d < rounds ? d : 0) * half + slot];
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  for (int r0 = 0; r0 < rounds; r0 += kLogAhead) {
+#pragma unroll
+    for (int d = 0; d < kLogAhead; ++d) {
+      const int rr = r0 + d;
+      const RotLog e = ahead[d];
+      const int nxt = rr + kLogAhead;
+      ahead[d] = rlog[(size_t)(nxt < rounds ? nxt : 0) * half + slot];
+      if (rr < rounds && lane < half && e.p >= 0) {
+        const double2 xp = x[e.p], xq = x[e.q];
+        const double2 sc_ = make_double2(e.sx, e.sy);
+        const double2 t1 = cmuld(conjd(sc_), xq), t2 = cmuld(sc_, xp);
+        x[e.p] = make_double2(e.c * xp.x - t1.x, e.c * xp.y - t1.y);
+        x[e.q] = make_double2(t2.x + e.c * xq.x, t2.y + e.c * xq.y);
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // the next round reads what this one wrote
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+  }
+  double2* V = reinterpret_cast<double2*>(jb.V);
+  for (int j = lane; j < n; j += 64) V[(size_t)row * n + j] = x[j];
+}
+
+// Ordering, phase convention and the float32 factor, from the eigenvalues in the log header and V.
+__global__ __launch_bounds__(kEigThreads) void k_eig_finish(EigJobs jobs) {
+  const EigJob jb = jobs.job[blockIdx.x];
+  __shared__ double lam[kEigTriMaxN];
+  __shared__ int col_of[kEigTriMaxN];
+  __shared__ double2 phase[kEigTriMaxN];
+  const EigLogHeader* hdr = reinterpret_cast<const EigLogHeader*>(jb.A);
+  for (int i = threadIdx.x; i < jb.n; i += kEigThreads) lam[i] = hdr->lam[i];
   __syncthreads();
-  eig_finish(n, r, tid, lam, col_of, phase, V, reinterpret_cast<float2*>(jb.U));
+  eig_finish(jb.n, jb.r, threadIdx.x, lam, col_of, phase, reinterpret_cast<const double2*>(jb.V),
+             reinterpret_cast<float2*>(jb.U));
 }
 
 __global__ void k_identity_factor(float2* U, int n) {
@@ -599,6 +648,14 @@ __global__ void k_identity_factor(float2* U, int n) {
 }
 
 }  // namespace
+
+// Bytes of the per-mode work buffer `work_a` of launch_eig_batch: the work matrix for the
+// memory-resident solver, header + rotation log (every round of every sweep) for the LDS solver.
+size_t eig_work_bytes(int n) {
+  if (n > kEigTriMaxN) return (size_t)n * n * sizeof(double2);
+  const int m = n + (n & 1);
+  return sizeof(EigLogHeader) + (size_t)kEigMaxSweeps * (m - 1) * (m / 2) * sizeof(RotLog);
+}
 
 int gram_num_chunks(int64_t A, int In, int64_t B) {
   (void)In;
@@ -655,6 +712,8 @@ void launch_eig_batch(hipStream_t s, int njobs, const double* const* gram, doubl
       attr_set = true;
     }
     k_eig_tri<<<dim3((unsigned)nsmall), dim3(kEigThreads), lds, s>>>(small);
+    k_eig_apply<<<dim3((unsigned)nmax, (unsigned)nsmall), dim3(64), 0, s>>>(small);
+    k_eig_finish<<<dim3((unsigned)nsmall), dim3(kEigThreads), 0, s>>>(small);
   }
   if (nlarge > 0) k_eig<<<dim3((unsigned)nlarge), dim3(kEigThreads), 0, s>>>(large);
 }

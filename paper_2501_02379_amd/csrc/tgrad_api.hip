@@ -228,7 +228,7 @@ void make_plan(const tgrad_config* c, Plan* p) {
   for (int n = 0; n < N; ++n) {
     const size_t mat = p->rank[n] < p->shape[n] ? (size_t)p->shape[n] * p->shape[n] * 16 : 0;
     p->ws_gram[n] = take(mat);
-    p->ws_eig_a[n] = take(mat);
+    p->ws_eig_a[n] = take(mat ? eig_work_bytes((int)p->shape[n]) : 0);
     p->ws_eig_v[n] = take(mat);
   }
   p->ws_gs = take((size_t)p->k * 8);

@@ -64,6 +64,7 @@ void launch_mask_from_indices(hipStream_t s, const int32_t* omega, int64_t k, ui
 
 // factor refresh
 int gram_num_chunks(int64_t A, int In, int64_t B);
+size_t eig_work_bytes(int n);                      // size of launch_eig_batch's per-mode buffer work_a
 void launch_gram(hipStream_t s, const void* g, int dtype, const uint32_t* mask, int64_t A, int In,
                  int64_t B, int nchunks, double* partials);
 void launch_gram_reduce(hipStream_t s, const double* partials, int nchunks, int In, double* gram);
