@@ -487,6 +487,21 @@ __global__ __launch_bounds__(kEigThreads) void k_eig_tri(EigJobs jobs) {
   const int m = n + (n & 1);
   const int half = m / 2;
   const int nblocks = half * (half + 1) / 2;
+  // The blocks (pair a, pair b), a >= b, a thread updates in every round: e = tid, tid + 1024, ...
+  // (at most 3 for 64 pairs); decoded once, packed as a << 8 | b, -1 = none.
+  constexpr int kBlocksPerThread = (kEigTriMaxN / 2) * (kEigTriMaxN / 2 + 1) / 2 / kEigThreads + 1;
+  int my_ab[kBlocksPerThread];
+#pragma unroll
+  for (int u = 0; u < kBlocksPerThread; ++u) {
+    const int e = tid + u * kEigThreads;
+    my_ab[u] = -1;
+    if (e < nblocks) {
+      int a = (int)((sqrtf(8.f * (float)e + 1.f) - 1.f) * 0.5f);
+      while (a * (a + 1) / 2 > e) --a;
+      while ((a + 1) * (a + 2) / 2 <= e) ++a;
+      my_ab[u] = (a << 8) | (e - a * (a + 1) / 2);
+    }
+  }
 
   for (int sweep = 0; sweep < kEigMaxSweeps; ++sweep) {
     if (tid == 0) nrot = 0;
@@ -525,11 +540,10 @@ __global__ __launch_bounds__(kEigThreads) void k_eig_tri(EigJobs jobs) {
       // ---- phase 2b: every block (pair a, pair b), a >= b:  B <- L_a B R_b  with
       //      L = [[c, -s], [conj(s), c]] on the rows (p_a, q_a), R = [[c, s], [-conj(s), c]] on the
       //      columns (p_b, q_b) ----
-      for (int e = tid; e < nblocks; e += kEigThreads) {
-        int a = (int)((sqrtf(8.f * (float)e + 1.f) - 1.f) * 0.5f);
-        while (a * (a + 1) / 2 > e) --a;
-        while ((a + 1) * (a + 2) / 2 <= e) ++a;
-        const int b = e - a * (a + 1) / 2;
+#pragma unroll
+      for (int u = 0; u < kBlocksPerThread; ++u) {
+        if (my_ab[u] < 0) continue;
+        const int a = my_ab[u] >> 8, b = my_ab[u] & 255;
         if (!srot[a] && !srot[b]) continue;
         const int pa = sp[a], qa = sq[a], pb = sp[b], qb = sq[b];
         const bool qa_ok = qa < n, qb_ok = qb < n;     // padding player of an odd n: no such row / column

@@ -180,37 +180,53 @@ __global__ __launch_bounds__(kSelThreads) void k_select_count(const KeySource g,
   }
 }
 
-// In-place exclusive prefix sums of both per-segment count arrays; one block.
+// In-place exclusive prefix sums of both per-segment count arrays; one block of 16 wavefronts.
+// Wavefront w owns the contiguous range [w * per, (w + 1) * per): it first adds the range up
+// (coalesced 64-entry reads), the 16 totals are scanned through LDS, then the range is walked again
+// and every 64-entry group is scanned with lane shuffles on top of the running offset.
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v, int lane) {
+#pragma unroll
+  for (int off = 1; off < kWave; off <<= 1) {
+    const uint32_t up = __shfl_up(v, off, kWave);
+    if (lane >= off) v += up;
+  }
+  return v;
+}
+
 __global__ __launch_bounds__(1024) void k_select_scan(uint32_t* seg_gt, uint32_t* seg_eq, int64_t nseg) {
-  __shared__ uint32_t sg[1024];
-  __shared__ uint32_t se[1024];
-  const int t = threadIdx.x;
-  const int64_t per = (nseg + 1023) / 1024;
-  const int64_t lo = t * per;
+  __shared__ uint32_t tot_g[16], tot_e[16];
+  const int lane = lane_id();
+  const int wave = threadIdx.x / kWave;
+  const int64_t per = ((nseg + 15) / 16 + kWave - 1) / kWave * kWave;       // a multiple of the group size
+  const int64_t lo = wave * per;
   const int64_t hi = lo + per < nseg ? lo + per : nseg;
   uint32_t a = 0, b = 0;
-  for (int64_t i = lo; i < hi; ++i) {
+  for (int64_t i = lo + lane; i < hi; i += kWave) {
     a += seg_gt[i];
     b += seg_eq[i];
   }
-  sg[t] = a;
-  se[t] = b;
-  __syncthreads();
-  for (int off = 1; off < 1024; off <<= 1) {
-    uint32_t va = sg[t], vb = se[t];
-    uint32_t aa = t >= off ? sg[t - off] : 0u, ab = t >= off ? se[t - off] : 0u;
-    __syncthreads();
-    sg[t] = va + aa;
-    se[t] = vb + ab;
-    __syncthreads();
+  a = wave_inclusive_scan(a, lane);
+  b = wave_inclusive_scan(b, lane);
+  if (lane == kWave - 1) {
+    tot_g[wave] = a;
+    tot_e[wave] = b;
   }
-  uint32_t ra = sg[t] - a, rb = se[t] - b;            // exclusive prefix of this thread's chunk
-  for (int64_t i = lo; i < hi; ++i) {
-    uint32_t ca = seg_gt[i], cb = seg_eq[i];
-    seg_gt[i] = ra;
-    seg_eq[i] = rb;
-    ra += ca;
-    rb += cb;
+  __syncthreads();
+  uint32_t run_g = 0, run_e = 0;                      // entries in the ranges of lower wavefronts
+  for (int w = 0; w < wave; ++w) {
+    run_g += tot_g[w];
+    run_e += tot_e[w];
+  }
+  for (int64_t i0 = lo; i0 < hi; i0 += kWave) {
+    const int64_t i = i0 + lane;
+    const uint32_t cg = i < hi ? seg_gt[i] : 0u, ce = i < hi ? seg_eq[i] : 0u;
+    const uint32_t sg = wave_inclusive_scan(cg, lane), se = wave_inclusive_scan(ce, lane);
+    if (i < hi) {
+      seg_gt[i] = run_g + sg - cg;
+      seg_eq[i] = run_e + se - ce;
+    }
+    run_g += __shfl(sg, kWave - 1, kWave);
+    run_e += __shfl(se, kWave - 1, kWave);
   }
 }
 
