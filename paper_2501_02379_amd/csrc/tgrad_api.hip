@@ -320,6 +320,16 @@ int drain_events(tgrad_ctx* c) {
 
 int check_launch() { return hipGetLastError() == hipSuccess ? TGRAD_OK : TGRAD_ERR_HIP; }
 
+// Kernel-ready copies of U^(N-1) for the fused kernels; rebuilt whenever that factor changes
+// (refresh, HOOI sweep, tgrad_set_state), never on the step path.
+void pack_fused_factor(tgrad_ctx* c) {
+  Plan& p = c->plan;
+  if (!p.fuse_next) return;
+  Scope sc_(c, KID_FACTOR_PACK);
+  launch_pack_fused_factor(c->stream, c->st<float2>(p.st_U[p.N - 2]), (int)p.shape[p.N - 2], p.rank[p.N - 2],
+                           c->w<float2>(p.ws_fpad), c->w<float2>(p.ws_ut));
+}
+
 int do_refresh(tgrad_ctx* c, const void* g) {
   Plan& p = c->plan;
   hipStream_t s = c->stream;
@@ -433,6 +443,7 @@ int do_refresh(tgrad_ctx* c, const void* g) {
       launch_eig_batch(s, 1, g1, a1, v1, i1, r1, u1);
     }
   }
+  pack_fused_factor(c);
   return check_launch();
 }
 
@@ -453,11 +464,6 @@ int do_step(tgrad_ctx* c, void* weight, const void* g) {
 
   // g_S <- Sparse(G, Omega);  g_L <- (G - g_S) x_N UN^H ... x_1 U1^H
   if (!mfma_last) { Scope sc_(c, KID_GATHER); launch_gather(s, g, cf.grad_dtype, omega, p.k, gs); }
-  if (p.fuse_next) {
-    Scope sc_(c, KID_FACTOR_PACK);
-    launch_pack_fused_factor(s, c->st<float2>(p.st_U[N - 2]), (int)p.shape[N - 2], p.rank[N - 2],
-                             c->w<float2>(p.ws_fpad), c->w<float2>(p.ws_ut));
-  }
   const float2* src = nullptr;
   for (int st = 0; st < N; ++st) {
     const Stage& sg = p.proj[st];
@@ -718,7 +724,14 @@ int tgrad_set_state(tgrad_ctx* ctx, int what, const void* host_in, size_t bytes)
   if (bytes != it.bytes) return TGRAD_ERR_INVALID_ARG;
   if (hipStreamSynchronize(ctx->stream) != hipSuccess) return TGRAD_ERR_HIP;
   if (it.bytes && hipMemcpy(it.dev, host_in, it.bytes, hipMemcpyHostToDevice) != hipSuccess) return TGRAD_ERR_HIP;
-  if (it.needs_factor) ctx->have_factor[it.mode] = true;
+  if (it.needs_factor) {
+    ctx->have_factor[it.mode] = true;
+    if (it.mode == ctx->plan.N - 2) {
+      pack_fused_factor(ctx);
+      if (hipStreamSynchronize(ctx->stream) != hipSuccess) return TGRAD_ERR_HIP;
+      return check_launch();
+    }
+  }
   return TGRAD_OK;
 }
 

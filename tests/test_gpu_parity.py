@@ -462,6 +462,31 @@ def test_checkpoint_restore_is_bit_identical():
     assert np.array_equal(T.weight_to_host(Wd2), W_a)
 
 
+def test_checkpoint_restore_fused_tier():
+    """The same on a shape that takes the fused kernels: their factor copies must follow
+    tgrad_set_state (they are rebuilt when a factor is written, not on every step)."""
+    shape, ranks, k = FUSED_SHAPES[1]
+    grads = [synth.small_case(shape, 700 + t) for t in range(6)]
+    rng = np.random.default_rng(9)
+    W0 = ((rng.standard_normal(shape) + 1j * rng.standard_normal(shape)) * 0.02).astype(np.complex64)
+    ctx = make_gpu_ctx(T, shape, ranks, k, refresh_every=4)
+    Wd = T.to_device_weight(W0)
+    for t in range(3):
+        ctx.tgrad_step(Wd, T.to_device_grad(grads[t]))
+    items = [T.STATE_STEP, T.STATE_INDICES, T.STATE_CORE_M, T.STATE_CORE_V, T.STATE_SPARSE_M, T.STATE_SPARSE_V] + \
+            [T.STATE_FACTOR0 + n for n in range(4)]
+    saved = {it: ctx.tgrad_get_state(it) for it in items}
+    W_saved = T.weight_to_host(Wd).copy()
+    ctx.tgrad_step(Wd, T.to_device_grad(grads[3]))          # t = 3: no refresh, uses the restored factors
+    W_a = T.weight_to_host(Wd)
+    ctx2 = make_gpu_ctx(T, shape, ranks, k, refresh_every=4)
+    for it in items:
+        ctx2.tgrad_set_state(it, saved[it])
+    Wd2 = T.to_device_weight(W_saved)
+    ctx2.tgrad_step(Wd2, T.to_device_grad(grads[3]))
+    assert np.array_equal(T.weight_to_host(Wd2), W_a)
+
+
 def test_set_state_rejects_bad_indices():
     ctx = make_gpu_ctx(T, (6, 5, 4), (2, 2, 2), 3, refresh_every=0)
     for bad in ([0, 0, 1], [2, 1, 3], [0, 1, 120], [-1, 0, 1]):
