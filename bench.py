@@ -30,7 +30,7 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def kernel_model(w, fused, weight_bytes=8):
+def kernel_model(w, fused, weight_bytes=8, core_fused=False):
     """Algorithmic bytes and flops per launch of every kernel, from the tensor shapes alone
     (8 real flops per complex multiply-add; a complex64 element is 8 bytes).  `fused`: the library
     ran the mode-(N-1) compression / reconstruction stages inside the first-stage and the
@@ -67,19 +67,29 @@ def kernel_model(w, fused, weight_bytes=8):
         fl += 8 * A1 * K1 * M1 * B1
         first_mid = 2
     m["project_first"] = {"bytes": by, "flops": fl, "bound": "hbm"}
+    # `core_fused`: the last compression stage, AdamUpdate on the core and the first reconstruction
+    # stage (all three on mode 1) run as one kernel: reads its input tensor, writes a tensor of the
+    # same size, reads and writes the moments and writes the core gradient
+    proj_end = N - 1 if core_fused else N
     by = fl = 0
-    for s in range(first_mid, N):
+    for s in range(first_mid, proj_end):
         b_, f_ = vol(*stage_dims(True, s))
         by += b_
         fl += f_
-    m["project"] = {"bytes": by, "flops": fl, "bound": "mfma", "launches_per_step": N - first_mid}
+    if proj_end > first_mid:
+        m["project"] = {"bytes": by, "flops": fl, "bound": "mfma", "launches_per_step": proj_end - first_mid}
     last_mid = N - 2 if fused else N - 1                  # reconstruction stages 0 .. last_mid - 1 run alone
+    back_start = 1 if core_fused else 0
     by = fl = 0
-    for s in range(0, last_mid):
+    for s in range(back_start, last_mid):
         b_, f_ = vol(*stage_dims(False, s))
         by += b_
         fl += f_
-    m["backproject"] = {"bytes": by, "flops": fl, "bound": "mfma", "launches_per_step": last_mid}
+    if last_mid > back_start:
+        m["backproject"] = {"bytes": by, "flops": fl, "bound": "mfma", "launches_per_step": last_mid - back_start}
+    if core_fused:
+        A0, K0, M0, B0 = stage_dims(True, N - 1)
+        m["core"] = {"bytes": 2 * K0 * B0 * 8 + C * (8 + 12 + 12), "flops": 16 * K0 * M0 * B0 + 12 * C, "bound": "mfma"}
     # last reconstruction stage fused with the sparse AdamUpdate, the scatter-add and the weight
     # update: reads its input tensor and W, writes W; per sparse entry its index, gathered value
     # and both moments are read and the moments written back
@@ -286,8 +296,10 @@ def main():
 
     # the library fuses the mode-(N-1) stages when the shape allows: then k_mid runs N - 2 times each way
     nstep = max(1, times.get("project_first", {}).get("launches", 1))
-    fused = len(w.shape) >= 3 and times.get("project", {}).get("launches", 0) == (len(w.shape) - 2) * nstep
-    model = kernel_model(w, fused, 4 if args.weights == "bf16" else 8)
+    core_fused = "core" in times
+    nproj = times.get("project", {}).get("launches", 0) + (nstep if core_fused else 0)
+    fused = len(w.shape) >= 3 and nproj == (len(w.shape) - 2) * nstep
+    model = kernel_model(w, fused, 4 if args.weights == "bf16" else 8, core_fused)
     kernels = {}
     for name, v in sorted(times.items(), key=lambda kv: -kv[1]["total_ms"]):
         avg = v["total_ms"] / max(1, v["launches"])
@@ -323,7 +335,7 @@ def main():
         "config": {"workload": "%s: %d x %s %s gradient, Tucker ranks %s, k=%d sparse, refresh every %d"
                                % (w.name, w.layers, "x".join(map(str, w.shape)), w.grad_dtype,
                                   ",".join(map(str, w.ranks)), w.k, w.T),
-                   "refreshes_in_timed_region": refreshes, "fused_mode_stages": bool(fused),
+                   "refreshes_in_timed_region": refreshes, "fused_mode_stages": bool(fused), "fused_core_stage": bool(core_fused),
                    "weights": args.weights, "select": args.select, "hooi_sweeps": args.hooi_sweeps, "warm_restart": bool(args.warm_restart)},
         "roofline": roofline,
         "ms_per_step_with_kernel_events": round(ms_per_step_profiled, 4),

@@ -25,6 +25,7 @@
 // Operand layout of v_mfma_f32_32x32x2f32 (D = A B + C, A 32 x 2, B 2 x 32, 64 lanes):
 //   lane l supplies A[l % 32][l / 32] and B[l / 32][l % 32];
 //   register r of lane l receives D[(r % 4) + 8 (r / 4) + 4 (l / 32)][l % 32].
+#include <cstdlib>
 #include <type_traits>
 
 #include "device_common.h"
@@ -55,6 +56,26 @@ __device__ __forceinline__ uint32_t div_magic(uint32_t n, uint32_t magic) {
 constexpr int kMidThreads = 256;
 constexpr int kMidJChunk = 64;            // row pairs of the factor staged in LDS at a time
 constexpr int kMidUnroll = 8;
+
+// Fills dst[0 .. total) with gen(e), `kStageBatch` global loads per thread in flight at a time (a
+// plain loop would pay one memory round trip per element and thread).
+constexpr int kStageBatch = 8;
+template <typename Gen>
+__device__ __forceinline__ void stage_batched(float2* dst, int total, int tid, int nthreads, Gen gen) {
+  for (int e0 = tid; e0 < total; e0 += nthreads * kStageBatch) {
+    float2 f[kStageBatch];
+#pragma unroll
+    for (int u = 0; u < kStageBatch; ++u) {
+      const int e = e0 + u * nthreads;
+      f[u] = gen(e < total ? e : total - 1);
+    }
+#pragma unroll
+    for (int u = 0; u < kStageBatch; ++u) {
+      const int e = e0 + u * nthreads;
+      if (e < total) dst[e] = f[u];
+    }
+  }
+}
 
 template <int VEC> struct VecT;
 template <> struct VecT<1> { typedef float2 type; };
@@ -132,23 +153,17 @@ __global__ __launch_bounds__(kMidThreads) void k_mid(const float* __restrict__ x
   for (int jc0 = 0; jc0 < J; jc0 += kMidJChunk) {
     const int jn = (J - jc0) < kMidJChunk ? (J - jc0) : kMidJChunk;
     __syncthreads();                                           // previous chunk fully consumed
-    for (int e = tid; e < jn * TL * 64; e += kMidThreads) {
+    stage_batched(sF, jn * TL * 64, tid, kMidThreads, [&](int e) -> float2 {
       const int l = e & 63;
       const int mt = (e >> 6) % TL;
       const int jj = e / (64 * TL);
       const int m = mbase + 32 * mt + (l & 31);
       const int k = 2 * (jc0 + jj) + (l >> 5);
-      float2 f = make_float2(0.f, 0.f);
-      if (m < M && k < K) {
-        if (PROJECT) {
-          const float2 u = U[(int64_t)k * rn + m];
-          f = make_float2(u.x, -u.y);
-        } else {
-          f = U[(int64_t)m * rn + k];
-        }
-      }
-      sF[e] = f;
-    }
+      const bool in = m < M && k < K;                          // outside: a clamped, valid element times zero
+      const int mc = in ? m : 0, kc = in ? k : 0;
+      const float2 u = PROJECT ? U[(int64_t)kc * rn + mc] : U[(int64_t)mc * rn + kc];
+      return in ? make_float2(u.x, PROJECT ? -u.y : u.y) : make_float2(0.f, 0.f);
+    });
     __syncthreads();
     int jj = jfirst;
     for (; jj + (kMidUnroll - 1) * JSTEP < jn; jj += kMidUnroll * JSTEP) {
@@ -195,6 +210,197 @@ __global__ __launch_bounds__(kMidThreads) void k_mid(const float* __restrict__ x
         }
       }
     }
+}
+
+// -------------------------------------------------------------------------------------------
+// k_core: the three steps around the Tucker core in one kernel, for mode 1 (the slowest index):
+//   g_L[m, b] = sum_k conj(U[k, m]) x[k, b]            last compression stage (K = I_1, M = r_1 <= 32)
+//   N_L = AdamUpdate(g_L)                               appendix algorithm "Adam with low-rank tensor
+//                                                       decomposition" (moments updated in place)
+//   z[i, b]   = sum_m U[i, m] N_L[m, b]                 first reconstruction stage
+// so the core gradient and the core update never travel through memory between kernels (g_L is
+// still written out: it is part of the readable state).
+// A workgroup of 4 wavefronts owns 32 column vectors (VEC complex each).  Compression is split over
+// the wavefronts by row pairs (wavefront w takes pairs w, w + 4, ...) and summed through LDS in a
+// fixed order; every wavefront runs AdamUpdate on a quarter of the 32 x 32 VEC tile and hands its
+// part of N_L back through LDS; then wavefront w expands the output row tiles w, w + 4, ...  The accumulator registers of the
+// compression ARE the B operands of the expansion: register r of lane (col, half) holds row
+// m = d_row(r, half), so expansion step r pairs rows d_row(r, 0) and d_row(r, 1) and its factor
+// operand is U[i, d_row(r, half)].
+// `z` may be `x` (in place): a workgroup writes only the columns it alone has read, and its reads
+// are complete (workgroup barriers in between) before its first write.
+struct CoreAdam {
+  float2* m;            // first moments, (M, B) complex
+  float* v;             // second moments
+  float2* g_out;        // compressed gradient, written for the state accessors
+  float beta1, beta2, inv_c1, inv_c2, eps;
+};
+
+template <int VEC>
+__global__ __launch_bounds__(kMidThreads) void k_core(const float* x, const float2* __restrict__ U,
+                                                      int rn, int K, int M, int64_t B, CoreAdam ad,
+                                                      float* z) {
+  typedef typename VecT<VEC>::type V;
+  constexpr int NT = 2 * VEC;                   // accumulator tiles: (column of the vector, re / im)
+  extern __shared__ float2 sF[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int col = lane & 31, half = lane >> 5;
+  const int64_t BV = B / VEC;
+  const int64_t cv_raw = (int64_t)blockIdx.x * 32 + col;
+  const bool valid = cv_raw < BV;
+  const int64_t cv = valid ? cv_raw : BV - 1;
+  const int64_t row_stride = B * 2;
+  const float* xp = x + cv * VEC * 2;
+  const int J = (K + 1) >> 1;                   // row pairs of the compression
+  const int NTI = (K + 31) >> 5;                // output row tiles of the expansion
+  // LDS: [0, J*64) compression operands, reused afterwards for the reduction / hand-over buffer;
+  //      then 16 * NTI * 64 expansion operands
+  float2* sFp = sF;
+  const int red_f2 = 4 * NT * 16 * 64 / 2;                       // float2 slots of the reduction buffer
+  float2* sFe = sF + (J * 64 > red_f2 ? J * 64 : red_f2);
+  stage_batched(sFp, J * 64, tid, kMidThreads, [&](int e) -> float2 {
+    const int l = e & 63, jj = e >> 6;
+    const int m = l & 31, k = 2 * jj + (l >> 5);
+    const bool in = m < M && k < K;
+    const float2 u = U[in ? (int64_t)k * rn + m : 0];
+    return in ? make_float2(u.x, -u.y) : make_float2(0.f, 0.f);
+  });
+  stage_batched(sFe, 16 * NTI * 64, tid, kMidThreads, [&](int e) -> float2 {
+    const int l = e & 63, mt = (e >> 6) % NTI, r = e / (64 * NTI);
+    const int i = 32 * mt + (l & 31), m = d_row(r, l >> 5);
+    const bool in = i < K && m < M;
+    const float2 u = U[in ? (int64_t)i * rn + m : 0];
+    return in ? u : make_float2(0.f, 0.f);
+  });
+  __syncthreads();
+
+  v16f acc[NT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+  auto load_pair_row = [&](int j) -> V {
+    const int k = 2 * j + half;
+    return *reinterpret_cast<const V*>(xp + (int64_t)(k < K ? k : K - 1) * row_stride);
+  };
+  auto mfma_pair_row = [&](const V& v, int jj) {
+    float xs[NT], xj[NT];
+    if constexpr (VEC == 1) {
+      xs[0] = v.x; xs[1] = v.y;
+    } else {
+      xs[0] = v.x; xs[1] = v.y; xs[2] = v.z; xs[3] = v.w;
+    }
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) {
+      xj[2 * c] = -xs[2 * c + 1];
+      xj[2 * c + 1] = xs[2 * c];
+    }
+    const float2 f = sFp[jj * 64 + lane];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      acc[t] = mfma32(f.x, xs[t], acc[t]);
+      acc[t] = mfma32(f.y, xj[t], acc[t]);
+    }
+  };
+  {
+    constexpr int kAhead = 16;                                 // row pairs in flight: all of them for K <= 128
+    int jj = wave;
+    for (; jj + (kAhead - 1) * 4 < J; jj += kAhead * 4) {
+      V v[kAhead];
+#pragma unroll
+      for (int u = 0; u < kAhead; ++u) v[u] = load_pair_row(jj + u * 4);
+#pragma unroll
+      for (int u = 0; u < kAhead; ++u) mfma_pair_row(v[u], jj + u * 4);
+    }
+    for (; jj < J; jj += 4) mfma_pair_row(load_pair_row(jj), jj);
+  }
+  // ---- all partial tiles -> LDS; wavefront w then owns registers r = 4 w .. 4 w + 3 of the tile: it
+  //      sums the four partials in a fixed order (wavefront 0's first), runs AdamUpdate on those
+  //      core rows and hands N_L back through LDS ----
+  __syncthreads();                                             // compression operands no longer needed
+  float* red = reinterpret_cast<float*>(sF);                   // [wave][t][r][lane]
+#pragma unroll
+  for (int t = 0; t < NT; ++t)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) red[((wave * NT + t) * 16 + r) * 64 + lane] = acc[t][r];
+  __syncthreads();
+  float2 nn[4][VEC];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int r = 4 * wave + q;
+    const int m = d_row(r, half);
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) {
+      float gre = 0.f, gim = 0.f;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        gre += red[((w * NT + 2 * c) * 16 + r) * 64 + lane];
+        gim += red[((w * NT + 2 * c + 1) * 16 + r) * 64 + lane];
+      }
+      nn[q][c] = make_float2(0.f, 0.f);
+      if (valid && m < M) {
+        const int64_t idx = (int64_t)m * B + cv * VEC + c;
+        float2 mm = ad.m[idx];
+        mm.x = ad.beta1 * mm.x + (1.f - ad.beta1) * gre;
+        mm.y = ad.beta1 * mm.y + (1.f - ad.beta1) * gim;
+        const float vv = ad.beta2 * ad.v[idx] + (1.f - ad.beta2) * (gre * gre + gim * gim);
+        ad.m[idx] = mm;
+        ad.v[idx] = vv;
+        ad.g_out[idx] = make_float2(gre, gim);
+        const float d = 1.f / (sqrtf(vv * ad.inv_c2) + ad.eps);
+        nn[q][c] = make_float2(mm.x * ad.inv_c1 * d, mm.y * ad.inv_c1 * d);
+      }
+    }
+  }
+  __syncthreads();                                             // every partial has been read
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) {
+      red[((2 * c) * 16 + 4 * wave + q) * 64 + lane] = nn[q][c].x;
+      red[((2 * c + 1) * 16 + 4 * wave + q) * 64 + lane] = nn[q][c].y;
+    }
+  __syncthreads();
+#pragma unroll
+  for (int t = 0; t < NT; ++t)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[t][r] = red[(t * 16 + r) * 64 + lane];
+  // ---- expansion: wavefront w writes output row tiles w, w + 4, ... ----
+  float* op = z + cv * VEC * 2;
+  for (int mt = wave; mt < NTI; mt += 4) {
+    v16f out[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) out[t][r] = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const float2 f = sFe[(r * NTI + mt) * 64 + lane];
+#pragma unroll
+      for (int c = 0; c < VEC; ++c) {
+        const float nr = acc[2 * c][r], ni = acc[2 * c + 1][r];
+        out[2 * c] = mfma32(f.x, nr, out[2 * c]);
+        out[2 * c] = mfma32(f.y, -ni, out[2 * c]);
+        out[2 * c + 1] = mfma32(f.x, ni, out[2 * c + 1]);
+        out[2 * c + 1] = mfma32(f.y, nr, out[2 * c + 1]);
+      }
+    }
+    if (valid) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int i = 32 * mt + d_row(r, half);
+        if (i < K) {
+          float* o = op + (int64_t)i * row_stride;
+          if constexpr (VEC == 1) {
+            *reinterpret_cast<float2*>(o) = make_float2(out[0][r], out[1][r]);
+          } else {
+            *reinterpret_cast<float4*>(o) = make_float4(out[0][r], out[1][r], out[2][r], out[3][r]);
+          }
+        }
+      }
+    }
+  }
 }
 
 // -------------------------------------------------------------------------------------------
@@ -1147,6 +1353,33 @@ void launch_mid(hipStream_t s, const float2* x, const float2* U, int rn, bool pr
   }
 #undef TGRAD_MID_P
 #undef TGRAD_MID
+}
+
+// Limits of k_core: one 32-row tile of core rows, and LDS for both operand tables.
+bool core_kernel_fits(int K, int M) { return M >= 1 && M <= 32 && K >= 1 && K <= TGRAD_MAX_EXTENT; }
+
+// Last compression stage + AdamUpdate on the core + first reconstruction stage (mode 1: the tensor
+// before is (K, B), the tensor after is (K, B) again, the core in between (M, B)).
+void launch_core(hipStream_t s, const float2* x, const float2* U, int rn, int K, int M, int64_t B, float2* m,
+                 float* v, float2* g_out, float beta1, float beta2, float inv_c1, float inv_c2, float eps,
+                 float2* z) {
+  if (B <= 0) return;
+  const int vec = (B % 2 == 0) ? 2 : 1;
+  const int64_t BV = B / vec;
+  const int J = (K + 1) / 2, NTI = (K + 31) / 32;
+  const size_t red = (size_t)4 * 2 * vec * 16 * 64 / 2;
+  const size_t lds = (((size_t)J * 64 > red ? (size_t)J * 64 : red) + (size_t)16 * NTI * 64) * 8;
+  dim3 grid((unsigned)((BV + 31) / 32)), block(kMidThreads);
+  CoreAdam ad{m, v, g_out, beta1, beta2, inv_c1, inv_c2, eps};
+  const float* xf = reinterpret_cast<const float*>(x);
+  float* zf = reinterpret_cast<float*>(z);
+  if (vec == 2) {
+    allow_lds(k_core<2>, lds);
+    k_core<2><<<grid, block, lds, s>>>(xf, U, rn, K, M, B, ad, zf);
+  } else {
+    allow_lds(k_core<1>, lds);
+    k_core<1><<<grid, block, lds, s>>>(xf, U, rn, K, M, B, ad, zf);
+  }
 }
 
 void launch_pack_fused_factor(hipStream_t s, const float2* U, int I2, int r, float2* fpad, float2* ut) {

@@ -28,7 +28,7 @@ const char* const kKernelNames[KID_COUNT] = {
     "select_hist", "select_pick", "select_count", "select_scan", "select_emit", "mask_from_indices",
     "tile_offsets", "gram", "gram_reduce", "eig_jacobi", "factor_pack",
     "gather", "project_first", "project", "adam_core", "backproject", "update", "sparse_update",
-    "hooi_project"};
+    "hooi_project", "core"};
 
 struct Plan {
   int N = 0;
@@ -45,6 +45,7 @@ struct Plan {
   int64_t ntiles = 0;            // tiles of the tensor seen as (I / I_N rows, I_N)
   int64_t tile_elems = 0;
   bool fuse_next = false;        // the last-mode kernels also handle mode N-1 (see make_plan)
+  bool fuse_core = false;        // last compression stage + AdamUpdate + first reconstruction stage in one kernel
   // byte offsets into state
   size_t st_omega, st_ms, st_vs, st_ml, st_vl, st_U[kMaxNdim], state_bytes;
   // byte offsets into workspace
@@ -174,6 +175,9 @@ void make_plan(const tgrad_config* c, Plan* p) {
              rows / I2 >= 512;
     }
     p->fuse_next = fuse;
+    bool fc = core_kernel_fits((int)p->shape[0], p->rank[0]);
+    if (const char* e = std::getenv("TGRAD_FUSE_CORE")) fc = fc && std::atoi(e) != 0;     // tuning knob
+    p->fuse_core = fc;
   }
 
   size_t o = 0;
@@ -478,6 +482,7 @@ int do_step(tgrad_ctx* c, void* weight, const void* g) {
       st = 1;
       continue;
     }
+    if (st == N - 1 && p.fuse_core) break;                     // mode 1 is contracted inside k_core below
     Scope sc_(c, st == 0 ? KID_PROJECT_FIRST : KID_PROJECT);
     if (st == 0) {
       if (mfma_last)
@@ -495,7 +500,17 @@ int do_step(tgrad_ctx* c, void* weight, const void* g) {
   const double tau = (double)(c->t + 1);
   const float inv_c1 = (float)(1.0 / (1.0 - std::pow((double)cf.beta1, tau)));
   const float inv_c2 = (float)(1.0 / (1.0 - std::pow((double)cf.beta2, tau)));
-  {
+  const float2* zsrc = core_n;
+  int first_back = 0;
+  if (p.fuse_core) {
+    // last compression stage, AdamUpdate on the core and first reconstruction stage (all mode 1)
+    const Stage& sg = p.proj[N - 1];
+    Scope sc_(c, KID_CORE);
+    launch_core(s, src, c->st<float2>(p.st_U[0]), p.rank[0], sg.K, sg.M, sg.B, c->st<float2>(p.st_ml),
+                c->st<float>(p.st_vl), core_g, cf.beta1, cf.beta2, inv_c1, inv_c2, cf.eps, buf[0]);
+    zsrc = buf[0];
+    first_back = 1;
+  } else {
     Scope sc_(c, KID_ADAM_CORE);
     launch_adam_core(s, core_g, c->st<float2>(p.st_ml), c->st<float>(p.st_vl), core_n, p.C, cf.beta1,
                      cf.beta2, inv_c1, inv_c2, cf.eps);
@@ -503,9 +518,8 @@ int do_step(tgrad_ctx* c, void* weight, const void* g) {
 
   // D <- alpha (N_L x_1 U1 ... x_N UN); the last stage is fused with AdamUpdate on the sparse values,
   // D[Omega] += lambda N_S and W <- W (1 - lr wd) - lr D
-  const float2* zsrc = core_n;
   const int nmid = (mfma_last && p.fuse_next) ? N - 2 : N - 1;   // reconstruction stages run by k_mid
-  for (int st = 0; st < nmid; ++st) {
+  for (int st = first_back; st < nmid; ++st) {
     const Stage& sg = p.back[st];
     float2* dst = buf[st & 1];
     const float2* U = c->st<float2>(p.st_U[sg.mode]);

@@ -37,7 +37,7 @@ enum KernelId {
   KID_SEL_HIST = 0, KID_SEL_PICK, KID_SEL_COUNT, KID_SEL_SCAN, KID_SEL_EMIT, KID_MASK_FROM_IDX,
   KID_TILE_OFFSETS, KID_GRAM, KID_GRAM_REDUCE, KID_EIG, KID_FACTOR_PACK,
   KID_GATHER, KID_PROJECT_FIRST, KID_PROJECT, KID_ADAM_CORE, KID_BACKPROJECT, KID_UPDATE,
-  KID_SPARSE_UPDATE, KID_HOOI_PROJECT, KID_COUNT
+  KID_SPARSE_UPDATE, KID_HOOI_PROJECT, KID_CORE, KID_COUNT
 };
 
 struct Launch {                            // what every launcher needs
@@ -90,6 +90,10 @@ void launch_tile_offsets(hipStream_t s, const int32_t* omega, int64_t k, int64_t
                          int64_t ntiles, uint32_t* tile_start);
 void launch_mid(hipStream_t s, const float2* x, const float2* U, int rn, bool project, const Stage& st,
                 float2* out);
+bool core_kernel_fits(int K, int M);
+void launch_core(hipStream_t s, const float2* x, const float2* U, int rn, int K, int M, int64_t B, float2* m,
+                 float* v, float2* g_out, float beta1, float beta2, float inv_c1, float inv_c2, float eps,
+                 float2* z);
 void launch_pack_fused_factor(hipStream_t s, const float2* U, int I2, int r, float2* fpad, float2* ut);
 void launch_lproj(hipStream_t s, const void* g, int dtype, const int32_t* omega, const uint32_t* tile_start,
                   float2* gs, const float2* U, int rn, const Stage& st, int W, float2* out, int fused_I2,
