@@ -477,6 +477,7 @@ __device__ __forceinline__ void claim_raw(uint2& r) { asm volatile("" : "+v"(r.x
 
 constexpr int kTileBatch = 17;            // 2-element pieces per lane in flight while a tile is staged
 constexpr int kJUnroll = 4;               // row pairs whose LDS operands are fetched ahead of their MFMAs
+constexpr int kCoefPairs = 34;            // fused first stage: row pairs whose coefficients stay in registers
 
 // k_lproj: out[a, m] = sum_k conj(U[k, m]) (G - Sparse(G, Omega))[a, k];  gs[j] = G[Omega_j].
 // Wavefront w of workgroup b walks tiles b W + w, + gridDim.x W, ...; the global loads of its next
@@ -525,6 +526,17 @@ __global__ __launch_bounds__(64 * W, 2) void k_lproj(const void* __restrict__ g,
   for (int e = lane; e < slice; e += 64) sX[e] = 0.f;          // pads and never-staged rows stay finite
   stage_factor_table<true>(sF, U, rn, K, M, 2 * J, ld, tid, T);
   __syncthreads();                                             // the only workgroup barrier
+  // FUSE (one column tile, J <= kCoefPairs): the lane's first-stage coefficients - one (re, im)
+  // pair per row pair - do not depend on the tile, so they live in registers for the whole kernel
+  // and the matrix-core loop reads only its A operand from LDS.  Row pairs past J carry zeros.
+  float2 creg[FUSE ? kCoefPairs : 1];
+  if constexpr (FUSE) {
+    const int c0 = lane & 31, h0 = lane >> 5;
+    const float2* fl0 = sF + h0 * ld + (c0 >> 1);
+#pragma unroll
+    for (int j = 0; j < kCoefPairs; ++j)
+      creg[j] = j < J ? column_coef(fl0[2 * j * ld], c0 & 1) : make_float2(0.f, 0.f);
+  }
 
   const int64_t I = A * K;
   const int tile_elems = kTileRows * K;
@@ -663,6 +675,25 @@ __global__ __launch_bounds__(64 * W, 2) void k_lproj(const void* __restrict__ g,
         for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
       const float2* fb = fl + 16 * nt0;
       int j = 0;
+      if constexpr (FUSE) {
+        // straight-line: kCoefPairs row pairs, A operands fetched kJUnroll pairs ahead; pairs past J
+        // re-read the last one and meet zero coefficients
+        const int jlast = J - 1;
+        float2 a2[kJUnroll];
+#pragma unroll
+        for (int u = 0; u < kJUnroll; ++u) a2[u] = *reinterpret_cast<const float2*>(xa + 4 * (u < jlast ? u : jlast));
+#pragma unroll
+        for (int jj = 0; jj < kCoefPairs; ++jj) {
+          const float2 a = a2[jj % kJUnroll];
+          if (jj + kJUnroll < kCoefPairs) {
+            const int jn = jj + kJUnroll;
+            a2[jj % kJUnroll] = *reinterpret_cast<const float2*>(xa + 4 * (jn < jlast ? jn : jlast));
+          }
+          acc[0] = mfma32(a.x, creg[jj].x, acc[0]);
+          acc[0] = mfma32(a.y, creg[jj].y, acc[0]);
+        }
+        j = J;
+      }
       for (; j + kJUnroll <= J; j += kJUnroll) {
         float2 a2[kJUnroll], f2[kJUnroll][N];
 #pragma unroll
@@ -1283,6 +1314,8 @@ constexpr int kUpdMaxJT = 16;                   // k_lupdate keeps a row of z in
 // Wavefronts per workgroup for the two last-mode kernels (each wavefront stages its own 32-row
 // tile in LDS), or 0 if the shape is outside what they cover.  `Klast` / `rlast` are the extent
 // and the rank of the last mode.  Two workgroups per compute unit are preferred.
+int fused_max_last_extent() { return 2 * kCoefPairs; }
+
 int choose_tile_waves(int Klast, int rlast, int prefer) {
   if (lupdate_jt(rlast) > kUpdMaxJT) return 0;
   if (Klast < 2) return 0;                      // the tile loaders assume at least one 2-element piece per tile

@@ -172,7 +172,7 @@ void make_plan(const tgrad_config* c, Plan* p) {
     if (fuse) {
       const int64_t I2 = p->shape[last - 1];
       fuse = (I2 % 32 == 0) && I2 <= TGRAD_MAX_EXTENT && p->rank[last - 1] <= 32 && 2 * p->rank[last] <= 32 &&
-             rows / I2 >= 512;
+             rows / I2 >= 512 && p->shape[last] <= fused_max_last_extent();
     }
     p->fuse_next = fuse;
     bool fc = core_kernel_fits((int)p->shape[0], p->rank[0]);

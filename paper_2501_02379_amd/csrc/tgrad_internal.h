@@ -86,6 +86,7 @@ void launch_update(hipStream_t s, const float2* z, const float2* U, int In, int 
 
 // matrix-core kernels of the step (contract_mfma.hip)
 int choose_tile_waves(int Klast, int rlast, int prefer);
+int fused_max_last_extent();                       // largest I_N the fused first-stage kernel takes
 void launch_tile_offsets(hipStream_t s, const int32_t* omega, int64_t k, int64_t tile_elems,
                          int64_t ntiles, uint32_t* tile_start);
 void launch_mid(hipStream_t s, const float2* x, const float2* U, int rn, bool project, const Stage& st,
