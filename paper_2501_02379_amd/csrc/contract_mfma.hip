@@ -477,7 +477,8 @@ __device__ __forceinline__ void claim_raw(uint2& r) { asm volatile("" : "+v"(r.x
 
 constexpr int kTileBatch = 17;            // 2-element pieces per lane in flight while a tile is staged
 constexpr int kJUnroll = 4;               // row pairs whose LDS operands are fetched ahead of their MFMAs
-constexpr int kCoefPairs = 34;            // fused first stage: row pairs whose coefficients stay in registers
+constexpr int kCoefPairs = 34;            // fused first stage: most row pairs whose coefficients stay in registers
+constexpr int kCoefPairsShort = 17;       // ... and the variant for short last modes (I_N <= 34)
 
 // k_lproj: out[a, m] = sum_k conj(U[k, m]) (G - Sparse(G, Omega))[a, k];  gs[j] = G[Omega_j].
 // Wavefront w of workgroup b walks tiles b W + w, + gridDim.x W, ...; the global loads of its next
@@ -501,7 +502,7 @@ struct FusedNext {
   int M2;
 };
 
-template <int DT, int W, int NTB, bool FLAT, bool FUSE>
+template <int DT, int W, int NTB, bool FLAT, bool FUSE, int CP>
 __global__ __launch_bounds__(64 * W, 2) void k_lproj(const void* __restrict__ g,
                                                      const int32_t* __restrict__ omega,
                                                      const uint32_t* __restrict__ tile_start,
@@ -526,15 +527,15 @@ __global__ __launch_bounds__(64 * W, 2) void k_lproj(const void* __restrict__ g,
   for (int e = lane; e < slice; e += 64) sX[e] = 0.f;          // pads and never-staged rows stay finite
   stage_factor_table<true>(sF, U, rn, K, M, 2 * J, ld, tid, T);
   __syncthreads();                                             // the only workgroup barrier
-  // FUSE (one column tile, J <= kCoefPairs): the lane's first-stage coefficients - one (re, im)
-  // pair per row pair - do not depend on the tile, so they live in registers for the whole kernel
-  // and the matrix-core loop reads only its A operand from LDS.  Row pairs past J carry zeros.
-  float2 creg[FUSE ? kCoefPairs : 1];
+  // FUSE (one column tile, J <= CP): the lane's first-stage coefficients - one (re, im) pair per
+  // row pair - do not depend on the tile, so they live in registers for the whole kernel and the
+  // matrix-core loop reads only its A operand from LDS.  Row pairs past J carry zeros.
+  float2 creg[FUSE ? CP : 1];
   if constexpr (FUSE) {
     const int c0 = lane & 31, h0 = lane >> 5;
     const float2* fl0 = sF + h0 * ld + (c0 >> 1);
 #pragma unroll
-    for (int j = 0; j < kCoefPairs; ++j)
+    for (int j = 0; j < CP; ++j)
       creg[j] = j < J ? column_coef(fl0[2 * j * ld], c0 & 1) : make_float2(0.f, 0.f);
   }
 
@@ -676,16 +677,16 @@ __global__ __launch_bounds__(64 * W, 2) void k_lproj(const void* __restrict__ g,
       const float2* fb = fl + 16 * nt0;
       int j = 0;
       if constexpr (FUSE) {
-        // straight-line: kCoefPairs row pairs, A operands fetched kJUnroll pairs ahead; pairs past J
-        // re-read the last one and meet zero coefficients
+        // straight-line: CP row pairs, A operands fetched kJUnroll pairs ahead; pairs past J re-read
+        // the last one and meet zero coefficients
         const int jlast = J - 1;
         float2 a2[kJUnroll];
 #pragma unroll
         for (int u = 0; u < kJUnroll; ++u) a2[u] = *reinterpret_cast<const float2*>(xa + 4 * (u < jlast ? u : jlast));
 #pragma unroll
-        for (int jj = 0; jj < kCoefPairs; ++jj) {
+        for (int jj = 0; jj < CP; ++jj) {
           const float2 a = a2[jj % kJUnroll];
-          if (jj + kJUnroll < kCoefPairs) {
+          if (jj + kJUnroll < CP) {
             const int jn = jj + kJUnroll;
             a2[jj % kJUnroll] = *reinterpret_cast<const float2*>(xa + 4 * (jn < jlast ? jn : jlast));
           }
@@ -1439,11 +1440,17 @@ void launch_lproj(hipStream_t s, const void* g, int dtype, const int32_t* omega,
   float* of = reinterpret_cast<float*>(out);
   const uint32_t magic = magic_for(K);
   FusedNext fz{fpad, of, S, fused_M2};
-#define TGRAD_LP(DT_, W_, NTB_, F_, Z_)                                                                  \
+#define TGRAD_LP_C(DT_, W_, NTB_, F_, Z_, CP_)                                                           \
   do {                                                                                                   \
-    allow_lds(k_lproj<DT_, W_, NTB_, F_, Z_>, lds);                                                      \
-    k_lproj<DT_, W_, NTB_, F_, Z_><<<grid, block, lds, s>>>(g, omega, tile_start, gs, U, rn, A, K, M,    \
-                                                            magic, ntiles, of, fz);                      \
+    allow_lds(k_lproj<DT_, W_, NTB_, F_, Z_, CP_>, lds);                                                 \
+    k_lproj<DT_, W_, NTB_, F_, Z_, CP_><<<grid, block, lds, s>>>(g, omega, tile_start, gs, U, rn, A, K,  \
+                                                                 M, magic, ntiles, of, fz);              \
+  } while (0)
+#define TGRAD_LP(DT_, W_, NTB_, F_, Z_) TGRAD_LP_C(DT_, W_, NTB_, F_, false, 1)
+#define TGRAD_LP_FUSED(DT_, F_)                                                                          \
+  do {                                                                                                   \
+    if ((K + 1) / 2 <= kCoefPairsShort) TGRAD_LP_C(DT_, 4, 1, F_, true, kCoefPairsShort);                \
+    else TGRAD_LP_C(DT_, 4, 1, F_, true, kCoefPairs);                                                    \
   } while (0)
 #define TGRAD_LP_F(DT_, W_, NTB_)                                                                        \
   do {                                                                                                   \
@@ -1455,9 +1462,9 @@ void launch_lproj(hipStream_t s, const void* g, int dtype, const int32_t* omega,
   } while (0)
   if (fuse) {                                   // the host only fuses with W == 4 and one column tile
     if (dtype == TGRAD_C64) {
-      if (K & 1) TGRAD_LP(TGRAD_C64, 4, 1, true, true); else TGRAD_LP(TGRAD_C64, 4, 1, false, true);
+      if (K & 1) TGRAD_LP_FUSED(TGRAD_C64, true); else TGRAD_LP_FUSED(TGRAD_C64, false);
     } else {
-      if (K & 1) TGRAD_LP(TGRAD_CBF16, 4, 1, true, true); else TGRAD_LP(TGRAD_CBF16, 4, 1, false, true);
+      if (K & 1) TGRAD_LP_FUSED(TGRAD_CBF16, true); else TGRAD_LP_FUSED(TGRAD_CBF16, false);
     }
   } else if (dtype == TGRAD_C64) {
     if (ntb == 2) TGRAD_LP_W(TGRAD_C64, 2); else TGRAD_LP_W(TGRAD_C64, 1);
@@ -1466,7 +1473,9 @@ void launch_lproj(hipStream_t s, const void* g, int dtype, const int32_t* omega,
   }
 #undef TGRAD_LP_W
 #undef TGRAD_LP_F
+#undef TGRAD_LP_FUSED
 #undef TGRAD_LP
+#undef TGRAD_LP_C
 }
 
 void launch_lupdate(hipStream_t s, const float2* z, const float2* U, const Stage& st, int W, void* w,
