@@ -50,6 +50,13 @@ the design notes of this repository):
   G = -grad and W <- W + eta * G~ is the same update because every operation
   applied to G is odd.
 * AdamW decay is decoupled: W <- W (1 - lr wd) - lr * D.
+* Composition orders other than Algorithm 1's (paragraph "Residual and
+  composition", ablation on combinations): "lr_us" compresses the full gradient
+  to low rank first and gives the sparse part the residual of that low-rank
+  approximation (support = top-k of the residual at refresh, values = the
+  residual of the CURRENT gradient at the support every step); "sum" applies
+  both to the full gradient.  For the top-k key the residual is rounded to
+  complex64 first (the key is defined on float32 parts).
 * Half-precision weights are bf16 (re, im) pairs without a full-precision copy:
   each step widens them, applies the update and rounds the result once, to
   nearest even.  The paper says only that weights are kept in half precision.
@@ -362,6 +369,7 @@ class Hyper:
     T: int = 1                 # refresh when t % T == 0; 0 = only on request
     hooi_sweeps: int = 0
     warm_restart: bool = False  # with hooi_sweeps >= 1: later refreshes start from the current factors
+    order: str = "us_lr"       # composition: "us_lr" (Algorithm 1), "lr_us", or "sum"
     select_rule: str = "topk"  # "topk" (magnitude) or "randk" (uniform random subset)
     select_seed: int = 0       # rand-k only
 
@@ -391,20 +399,40 @@ class State:
         self.V_S = np.zeros(self.hyper.k, dtype=np.float64)
 
 
-def refresh(st: State, G: np.ndarray) -> None:
-    """Algorithm 1, the `t mod T = 0` branch.  Touches neither moments nor t."""
-    Gc = to_complex128(G)
+def _select(st: State, X: np.ndarray) -> np.ndarray:
+    """SparseIndices on X (complex64 or bf16 pairs) by the configured rule."""
     if st.hyper.select_rule == "randk":
-        st.omega = sparse_indices_random(int(np.prod(st.shape)), st.hyper.k, st.hyper.select_seed, st.t)
-    elif st.hyper.select_rule == "topk":
-        st.omega = sparse_indices(G, st.hyper.k)
-    else:
-        raise ValueError("unknown selection rule")
-    R_L = remove_sparse(Gc, st.omega)
-    if st.hyper.warm_restart and st.hyper.hooi_sweeps < 1:
+        return sparse_indices_random(int(np.prod(st.shape)), st.hyper.k, st.hyper.select_seed, st.t)
+    if st.hyper.select_rule == "topk":
+        return sparse_indices(X, st.hyper.k)
+    raise ValueError("unknown selection rule")
+
+
+def refresh(st: State, G: np.ndarray) -> None:
+    """The `t mod T = 0` branch.  Touches neither moments nor t.
+
+    order "us_lr" is Algorithm 1: the support comes from G, the factors from G with the support
+    removed.  The paragraph "Residual and composition" and the ablation on sparse / low-rank
+    combinations define the two other orders: "lr_us" - the first component (low rank) sees the
+    full gradient and the second (sparse) the residual R = G - G~_L of the first; "sum" - both see
+    the full gradient and their outputs are added."""
+    h = st.hyper
+    if h.order not in ("us_lr", "lr_us", "sum"):
+        raise ValueError("unknown composition order")
+    if h.warm_restart and h.hooi_sweeps < 1:
         raise ValueError("warm restart needs at least one HOOI sweep")
-    init = st.U if (st.hyper.warm_restart and st.U is not None) else None
-    st.U = tucker_factors(R_L, st.hyper.ranks, st.hyper.hooi_sweeps, init)
+    Gc = to_complex128(G)
+    init = st.U if (h.warm_restart and st.U is not None) else None
+    if h.order == "us_lr":
+        st.omega = _select(st, G)
+        st.U = tucker_factors(remove_sparse(Gc, st.omega), h.ranks, h.hooi_sweeps, init)
+    elif h.order == "sum":
+        st.omega = _select(st, G)
+        st.U = tucker_factors(Gc, h.ranks, h.hooi_sweeps, init)
+    else:
+        st.U = tucker_factors(Gc, h.ranks, h.hooi_sweeps, init)
+        R = Gc - reconstruct(compress(Gc, st.U), st.U)
+        st.omega = _select(st, R.astype(np.complex64))       # the key is formed from float32 parts
 
 
 def step(st: State, W: np.ndarray, G: np.ndarray) -> np.ndarray:
@@ -424,8 +452,15 @@ def step(st: State, W: np.ndarray, G: np.ndarray) -> np.ndarray:
     Gc = to_complex128(G)
     W = np.asarray(W, dtype=np.complex128)
 
-    g_S = sparse_gather(Gc, st.omega)                       # sparse tensor, current step
-    g_L = compress(remove_sparse(Gc, st.omega), st.U)       # low-rank compression
+    if h.order == "us_lr":
+        g_S = sparse_gather(Gc, st.omega)                   # sparse tensor, current step
+        g_L = compress(remove_sparse(Gc, st.omega), st.U)   # low-rank compression of the rest
+    elif h.order == "sum":
+        g_S = sparse_gather(Gc, st.omega)                   # both components see the full gradient
+        g_L = compress(Gc, st.U)
+    else:                                                   # lr_us: the sparse part sees the residual
+        g_L = compress(Gc, st.U)
+        g_S = sparse_gather(Gc - reconstruct(g_L, st.U), st.omega)
 
     tau = st.t + 1
     n_S, st.M_S, st.V_S = adam_update(g_S, st.M_S, st.V_S, h.beta1, h.beta2, tau, h.eps)

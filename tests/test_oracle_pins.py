@@ -627,6 +627,95 @@ def test_random_rule_in_the_step():
         O.refresh(O.State(shape, O.Hyper(ranks=(2, 2, 2), k=7, select_rule="probk")), g)
 
 
+# ----------------------------------------------------------------- composition orders
+def test_orders_written_out_on_a_small_tensor():
+    """lr_us and sum against the definitions written with einsum: the second component of lr_us
+    works on R = G - G~_L (support from the refresh gradient's residual, values from the current
+    gradient's residual); sum gives both components the full gradient."""
+    shape, ranks, k = (5, 4, 3), (2, 2, 2), 6
+    rng = np.random.default_rng(51)
+    g0, g1 = (_crandn(rng, *shape).astype(np.complex64) for _ in range(2))
+    W0 = 0.02 * _crandn(rng, *shape)
+
+    def project(X, U):                                       # U U^H applied in every mode
+        C = np.einsum("abc,ap,bq,cr->pqr", X, U[0].conj(), U[1].conj(), U[2].conj())
+        return C, np.einsum("pqr,ap,bq,cr->abc", C, U[0], U[1], U[2])
+
+    for order in ("lr_us", "sum"):
+        h = O.Hyper(ranks=ranks, k=k, T=0, lr=1e-2, order=order)
+        st = O.State(shape, h)
+        O.refresh(st, g0)
+        X0 = g0.astype(np.complex128)
+        U = O.tucker_factors(X0, ranks)                      # factors of the FULL gradient
+        assert all(np.allclose(_projector(a), _projector(b), atol=1e-10) for a, b in zip(st.U, U))
+        _, L0 = project(X0, st.U)
+        key = np.abs((X0 - L0).reshape(-1)) if order == "lr_us" else np.abs(X0.reshape(-1))
+        assert np.array_equal(st.omega, np.sort(np.argsort(-key, kind="stable")[:k]))
+        W1 = O.step(st, W0, g1)
+        X1 = g1.astype(np.complex128)
+        C1, L1 = project(X1, st.U)
+        sv = ((X1 - L1) if order == "lr_us" else X1).reshape(-1)[st.omega]
+        nL, _, _ = O.adam_update(C1, np.zeros_like(C1), np.zeros(C1.shape), 0.9, 0.999, 1, 1e-8)
+        nS, _, _ = O.adam_update(sv, np.zeros_like(sv), np.zeros(sv.shape), 0.9, 0.999, 1, 1e-8)
+        D = np.einsum("pqr,ap,bq,cr->abc", nL, *st.U).reshape(-1).copy()
+        D[st.omega] += nS
+        assert np.allclose(W1.reshape(-1), W0.reshape(-1) - 1e-2 * D, atol=1e-12)
+
+
+def test_orders_coincide_without_a_sparse_part_and_on_exact_low_rank():
+    shape, ranks = (6, 5, 4), (2, 3, 2)
+    rng = np.random.default_rng(52)
+    g = _crandn(rng, *shape).astype(np.complex64)
+    W0 = np.zeros(shape, dtype=np.complex128)
+    outs = [O.step(O.State(shape, O.Hyper(ranks=ranks, k=0, order=o)), W0, g) for o in ("us_lr", "lr_us", "sum")]
+    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
+    # exact low rank: the residual of the low-rank part vanishes, so lr_us gives its sparse part (numerically) nothing
+    Q = [np.linalg.qr(_crandn(rng, i, r))[0] for i, r in zip(shape, ranks)]
+    gl = O.reconstruct(_crandn(rng, *ranks), Q).astype(np.complex64)
+    st = O.State(shape, O.Hyper(ranks=ranks, k=7, order="lr_us", eps=1e-3))
+    O.step(st, W0, gl)
+    assert np.max(np.abs(st.M_S)) < 1e-6 * np.max(np.abs(gl))
+    with pytest.raises(ValueError):
+        O.refresh(O.State(shape, O.Hyper(ranks=ranks, k=1, order="us+lr")), g)
+
+
+def test_reconstruction_error_of_the_three_strategies():
+    """The comparison of the section on robust decomposition, on a small synthetic gradient with
+    outliers: sparse-then-low-rank, low-rank-then-sparse and pure low rank at equal budget.
+    One-shot approximations G~ (no Adam): both combined strategies remove the high-magnitude
+    errors that pure low rank leaves at the outliers (which of the two has the smaller average is
+    data dependent and not asserted); on the sparse-first support only the leakage of the low-rank
+    part remains, the sparse-second error vanishes exactly on its support, and its energy is that
+    of the residual minus what the sparse part took."""
+    shape = (16, 16, 16, 8)
+    g = synth.small_case(shape, 53, outlier_frac=(1, 100))
+    X = g.astype(np.complex128)
+    I = X.size
+    k5 = int(np.ceil(0.05 * I))
+
+    def lowrank(Y, frac):
+        ranks = tuple(max(1, int(round(frac * i))) for i in shape)
+        U = O.tucker_factors(Y, ranks)
+        return O.reconstruct(O.compress(Y, U), U)
+
+    om = O.sparse_indices(g, k5)                              # (1) sparse 5 % first, low rank 20 % on the rest
+    S = np.zeros_like(X)
+    S.reshape(-1)[om] = X.reshape(-1)[om]
+    e1 = np.abs(X - (S + lowrank(X - S, 0.20)))
+    L = lowrank(X, 0.20)                                      # (2) low rank 20 % first, sparse 5 % of the residual
+    R = X - L
+    om2 = O.sparse_indices(R.astype(np.complex64), k5)
+    S2 = np.zeros_like(X)
+    S2.reshape(-1)[om2] = R.reshape(-1)[om2]
+    e2 = np.abs(X - (L + S2))
+    e3 = np.abs(X - lowrank(X, 0.25))                         # (3) pure low rank 25 %
+    assert e1.max() < 0.5 * e3.max() and e2.max() < 0.5 * e3.max()
+    assert np.max(e2.reshape(-1)[om2]) < 1e-12
+    assert np.isclose(np.sum(e2 ** 2), np.sum(np.abs(R) ** 2) - np.sum(np.abs(R.reshape(-1)[om2]) ** 2), rtol=1e-10)
+    assert np.max(e1.reshape(-1)[om]) < e3.max() * 0.5          # only low-rank leakage remains there
+    assert len(np.intersect1d(om, om2)) > 0.5 * k5               # both supports are mostly the outliers
+
+
 # ----------------------------------------------------------------- bf16-stored weights
 def test_bf16_rounding_matches_torch_and_the_tie_rule():
     import torch
