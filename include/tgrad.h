@@ -44,6 +44,7 @@ typedef struct tgrad_ctx tgrad_ctx;   /* opaque; host memory owned by the librar
 
 enum { TGRAD_C64 = 0, TGRAD_CBF16 = 1 };
 enum { TGRAD_SELECT_TOPK_MAG = 0, TGRAD_SELECT_RANDOM = 1 };
+enum { TGRAD_ORDER_US_LR = 0, TGRAD_ORDER_LR_US = 1, TGRAD_ORDER_SUM = 2 };
 
 enum {
   TGRAD_OK = 0,
@@ -105,6 +106,15 @@ typedef struct {
                                          32-bit finalizer, s0 = lo32(seed) ^ (t32 * 0x9E3779B9),
                                          s1 = hi32(seed) + t32 + 0x7F4A7C15, t32 = t mod 2^32 */
   uint64_t select_seed;               /* TGRAD_SELECT_RANDOM only */
+  int32_t order;                      /* how the two components are composed (paragraph "Residual and
+                                         composition"; ablation on sparse / low-rank combinations):
+                                         TGRAD_ORDER_US_LR = Algorithm 1: support from G, low rank on G
+                                         with the support removed; TGRAD_ORDER_LR_US = low rank on the
+                                         full G, the sparse part works on R = G - G~_L (support = top-k
+                                         of R at refresh, values = R of the current gradient at the
+                                         support every step; the refresh needs one more G-sized
+                                         float32 buffer in the workspace); TGRAD_ORDER_SUM = both on
+                                         the full G */
   int32_t warm_restart;               /* 0 or 1; 1 needs hooi_sweeps >= 1 (else INVALID_ARG): a refresh
                                          that finds every factor present (from an earlier refresh or
                                          tgrad_set_state) starts its sweeps from those factors instead

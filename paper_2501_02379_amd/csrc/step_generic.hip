@@ -149,6 +149,45 @@ __global__ __launch_bounds__(kThreads) void k_update(const float2* __restrict__ 
   }
 }
 
+// Residual of the low-rank approximation, R = G - G~_L (paragraph "Residual and composition"), from the
+// tensor z = (G~_L before its last expansion), seen as (A, rn):  R[a, m] = G[a, m] - sum_k U[m, k] z[a, k].
+//   k_residual        the whole tensor (refresh of the low-rank-first order: top-k runs on it);
+//   k_residual_gather only at the support, in place on the gathered values: gs[j] <- gs[j] - G~_L[Omega_j].
+template <int DT>
+__global__ __launch_bounds__(kThreads) void k_residual(const void* __restrict__ g, const float2* __restrict__ z,
+                                                       const float2* __restrict__ U, int rn, int64_t A, int M,
+                                                       float2* __restrict__ r) {
+  const int64_t o = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (o >= A * M) return;
+  const int m = (int)(o % M);
+  const int64_t a = o / M;
+  float2 acc = make_float2(0.f, 0.f);
+  for (int kk = 0; kk < rn; ++kk) {
+    float2 p = cmul(U[(int64_t)m * rn + kk], z[a * rn + kk]);
+    acc.x += p.x;
+    acc.y += p.y;
+  }
+  const float2 gv = load_elem<DT>(g, o);
+  r[o] = make_float2(gv.x - acc.x, gv.y - acc.y);
+}
+
+__global__ void k_residual_gather(float2* __restrict__ gs, const int32_t* __restrict__ omega, int64_t k,
+                                  const float2* __restrict__ z, const float2* __restrict__ U, int rn, int M) {
+  int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= k) return;
+  const int64_t o = omega[j];
+  const int m = (int)(o % M);
+  const int64_t a = o / M;
+  float2 acc = make_float2(0.f, 0.f);
+  for (int kk = 0; kk < rn; ++kk) {
+    float2 p = cmul(U[(int64_t)m * rn + kk], z[a * rn + kk]);
+    acc.x += p.x;
+    acc.y += p.y;
+  }
+  const float2 gv = gs[j];
+  gs[j] = make_float2(gv.x - acc.x, gv.y - acc.y);
+}
+
 inline unsigned blocks_for(int64_t n, int threads) { return (unsigned)((n + threads - 1) / threads); }
 
 }  // namespace
@@ -203,6 +242,23 @@ void launch_update(hipStream_t s, const float2* z, const float2* U, int In, int 
     k_update<TGRAD_C64><<<grid, block, 0, s>>>(z, U, rn, st.A, st.M, w, decay, neg_lr_alpha, mask, omega, k, ns);
   else
     k_update<TGRAD_CBF16><<<grid, block, 0, s>>>(z, U, rn, st.A, st.M, w, decay, neg_lr_alpha, mask, omega, k, ns);
+}
+
+void launch_residual(hipStream_t s, const void* g, int dtype, const float2* z, const float2* U, int rn, int64_t A,
+                     int M, float2* r) {
+  const int64_t total = A * M;
+  if (total <= 0) return;
+  dim3 grid(blocks_for(total, kThreads)), block(kThreads);
+  if (dtype == TGRAD_C64)
+    k_residual<TGRAD_C64><<<grid, block, 0, s>>>(g, z, U, rn, A, M, r);
+  else
+    k_residual<TGRAD_CBF16><<<grid, block, 0, s>>>(g, z, U, rn, A, M, r);
+}
+
+void launch_residual_gather(hipStream_t s, float2* gs, const int32_t* omega, int64_t k, const float2* z,
+                            const float2* U, int rn, int M) {
+  if (k <= 0) return;
+  k_residual_gather<<<dim3(blocks_for(k, 256)), dim3(256), 0, s>>>(gs, omega, k, z, U, rn, M);
 }
 
 }  // namespace tgrad

@@ -28,7 +28,7 @@ const char* const kKernelNames[KID_COUNT] = {
     "select_hist", "select_pick", "select_count", "select_scan", "select_emit", "mask_from_indices",
     "tile_offsets", "gram", "gram_reduce", "eig_jacobi", "factor_pack",
     "gather", "project_first", "project", "adam_core", "backproject", "update", "sparse_update",
-    "hooi_project", "core"};
+    "hooi_project", "core", "residual"};
 
 struct Plan {
   int N = 0;
@@ -52,6 +52,10 @@ struct Plan {
   size_t ws_sel, ws_hist, ws_seg_gt, ws_seg_eq, ws_mask, ws_tile_start, ws_fpad, ws_ut, ws_partials, ws_gram[kMaxNdim],
       ws_eig_a[kMaxNdim], ws_eig_v[kMaxNdim], ws_gs, ws_core_g, ws_core_n, ws_buf[2], workspace_bytes;
   int gram_chunks[kMaxNdim];
+  int order = 0;                   // TGRAD_ORDER_*
+  size_t ws_tile_zero = 0;         // all-zero tile offsets: "no support" for the first-stage kernel
+  size_t ws_resid = 0;             // low-rank-first order: the residual G - G~_L at refresh
+  size_t ws_rbuf[2] = {0, 0};      // low-rank-first order: intermediates of the raw reconstruction chain
   int hooi_sweeps = 0;
   int hooi_gram_chunks[kMaxNdim];  // Gram of the chain result of mode n
 };
@@ -111,6 +115,8 @@ int validate(const tgrad_config* c) {
   if (c->eps < 0.f) return TGRAD_ERR_INVALID_ARG;
   if (c->refresh_every < 0) return TGRAD_ERR_INVALID_ARG;
   if (c->hooi_sweeps < 0 || c->hooi_sweeps > TGRAD_MAX_HOOI_SWEEPS) return TGRAD_ERR_INVALID_ARG;
+  if (c->order != TGRAD_ORDER_US_LR && c->order != TGRAD_ORDER_LR_US && c->order != TGRAD_ORDER_SUM)
+    return TGRAD_ERR_INVALID_ARG;
   if (c->warm_restart != 0 && c->warm_restart != 1) return TGRAD_ERR_INVALID_ARG;
   if (c->warm_restart == 1 && c->hooi_sweeps < 1) return TGRAD_ERR_INVALID_ARG;
   if (c->select_rule != TGRAD_SELECT_TOPK_MAG && c->select_rule != TGRAD_SELECT_RANDOM)
@@ -247,6 +253,23 @@ void make_plan(const tgrad_config* c, Plan* p) {
   }
   p->ws_buf[0] = take(buf[0]);
   p->ws_buf[1] = take(buf[1]);
+  p->order = c->order;
+  p->ws_tile_zero = take(p->order != TGRAD_ORDER_US_LR ? (size_t)(p->ntiles + 1) * 4 : 0);
+  {
+    // unfused chains (every stage through memory) for the residual of the low-rank part
+    size_t rb[2] = {0, 0};
+    if (p->order == TGRAD_ORDER_LR_US) {
+      for (int s = 0; s + 1 < N; ++s) {
+        size_t bp = (size_t)(p->proj[s].A * p->proj[s].M * p->proj[s].B) * 8;
+        size_t bb = (size_t)(p->back[s].A * p->back[s].M * p->back[s].B) * 8;
+        if (bp > rb[s & 1]) rb[s & 1] = bp;
+        if (bb > rb[s & 1]) rb[s & 1] = bb;
+      }
+    }
+    p->ws_rbuf[0] = take(rb[0]);
+    p->ws_rbuf[1] = take(rb[1]);
+    p->ws_resid = take(p->order == TGRAD_ORDER_LR_US ? (size_t)p->I * 8 : 0);
+  }
   p->workspace_bytes = o;
 }
 
@@ -334,18 +357,16 @@ void pack_fused_factor(tgrad_ctx* c) {
                            c->w<float2>(p.ws_fpad), c->w<float2>(p.ws_ut));
 }
 
-int do_refresh(tgrad_ctx* c, const void* g) {
+// Omega <- SparseIndices(x, rho, top-k | rand-k), plus the support bitmask and the tile offsets.
+void select_support(tgrad_ctx* c, const void* x, int dt) {
   Plan& p = c->plan;
   hipStream_t s = c->stream;
-  const int dt = c->cfg.grad_dtype;
   SelectScalars* sc = c->w<SelectScalars>(p.ws_sel);
   uint32_t* hist = c->w<uint32_t>(p.ws_hist);
   uint32_t* seg_gt = c->w<uint32_t>(p.ws_seg_gt);
   uint32_t* seg_eq = c->w<uint32_t>(p.ws_seg_eq);
   uint32_t* mask = c->w<uint32_t>(p.ws_mask);
   int32_t* omega = c->st<int32_t>(p.st_omega);
-
-  // --- Omega <- SparseIndices(G, rho, top-k | rand-k) ---
   SelectKeys keys{false, 0u, 0u};
   if (c->cfg.select_rule == TGRAD_SELECT_RANDOM) {
     const uint64_t seed = c->cfg.select_seed;
@@ -357,21 +378,39 @@ int do_refresh(tgrad_ctx* c, const void* g) {
   if (p.k > 0) {
     zero_u32(s, hist, 3 * kHistBins);
     for (int pass = 0; pass < 3; ++pass) {
-      { Scope sc_(c, KID_SEL_HIST); launch_select_hist(s, g, dt, keys, p.I, pass, sc, hist + pass * kHistBins); }
+      { Scope sc_(c, KID_SEL_HIST); launch_select_hist(s, x, dt, keys, p.I, pass, sc, hist + pass * kHistBins); }
       { Scope sc_(c, KID_SEL_PICK); launch_select_pick(s, pass, (uint32_t)p.k, sc, hist + pass * kHistBins); }
     }
-    { Scope sc_(c, KID_SEL_COUNT); launch_select_count(s, g, dt, keys, p.I, sc, seg_gt, seg_eq, p.nseg); }
+    { Scope sc_(c, KID_SEL_COUNT); launch_select_count(s, x, dt, keys, p.I, sc, seg_gt, seg_eq, p.nseg); }
     { Scope sc_(c, KID_SEL_SCAN); launch_select_scan(s, seg_gt, seg_eq, p.nseg); }
-    { Scope sc_(c, KID_SEL_EMIT); launch_select_emit(s, g, dt, keys, p.I, sc, seg_gt, seg_eq, p.nseg, omega, mask); }
+    { Scope sc_(c, KID_SEL_EMIT); launch_select_emit(s, x, dt, keys, p.I, sc, seg_gt, seg_eq, p.nseg, omega, mask); }
   }
   {
     Scope sc_(c, KID_TILE_OFFSETS);
     launch_tile_offsets(s, omega, p.k, p.tile_elems, p.ntiles, c->w<uint32_t>(p.ws_tile_start));
   }
   c->have_indices = true;
-  const uint32_t* use_mask = p.k > 0 ? mask : nullptr;
+}
 
-  // --- {U^(n)} <- TuckerFactors(G - Sparse(G, Omega), r) ---
+// First stage of a compression chain that reads G itself.  `tile_start` / `use_mask` say which
+// support is removed on the way in: the real one, or none (all-zero offsets, null mask).
+void first_stage(tgrad_ctx* c, const void* g, const Stage& sg, const uint32_t* tile_start, const uint32_t* use_mask,
+                 float2* dst) {
+  Plan& p = c->plan;
+  const float2* Um = c->st<float2>(p.st_U[sg.mode]);
+  if (sg.mode == p.N - 1 && p.tile_waves > 0)
+    launch_lproj(c->stream, g, c->cfg.grad_dtype, c->st<int32_t>(p.st_omega), tile_start, c->w<float2>(p.ws_gs), Um,
+                 sg.M, sg, p.tile_waves, dst, 0, 0, nullptr);
+  else
+    launch_contract(c->stream, g, c->cfg.grad_dtype, use_mask, Um, sg.K, sg.M, true, sg, dst);
+}
+
+// {U^(n)} <- TuckerFactors(G with the given support removed, r): HOSVD (or the factors in place,
+// warm restart), then the HOOI sweeps.
+void compute_factors(tgrad_ctx* c, const void* g, const uint32_t* tile_start, const uint32_t* use_mask) {
+  Plan& p = c->plan;
+  hipStream_t s = c->stream;
+  const int dt = c->cfg.grad_dtype;
   // Warm restart: the sweeps below start from the factors in place instead of from HOSVD.
   bool warm = c->cfg.warm_restart == 1 && p.hooi_sweeps > 0;
   for (int n = 0; n < p.N; ++n) warm = warm && c->have_factor[n];
@@ -409,7 +448,7 @@ int do_refresh(tgrad_ctx* c, const void* g) {
     launch_eig_batch(s, njobs, grams, wa, wv, In, rr, Us);
   }
 
-  // --- HOOI sweeps: mode n re-solved on the residual compressed in every other mode ---
+  // --- HOOI sweeps: mode n re-solved on the tensor compressed in every other mode ---
   float2* buf[2] = {c->w<float2>(p.ws_buf[0]), c->w<float2>(p.ws_buf[1])};
   for (int sweep = 0; sweep < p.hooi_sweeps; ++sweep) {
     for (int n = 0; n < p.N; ++n) {
@@ -420,18 +459,11 @@ int do_refresh(tgrad_ctx* c, const void* g) {
       for (int st = 0; st < ch.nstages; ++st) {
         const Stage& sg = ch.stage[st];
         float2* dst = buf[st & 1];
-        const float2* Um = c->st<float2>(p.st_U[sg.mode]);
         Scope sc_(c, KID_HOOI_PROJECT);
-        if (st == 0) {
-          // the stage that reads G: the support is removed on the way in
-          if (sg.mode == p.N - 1 && p.tile_waves > 0)
-            launch_lproj(s, g, dt, omega, c->w<uint32_t>(p.ws_tile_start), c->w<float2>(p.ws_gs), Um, sg.M, sg,
-                         p.tile_waves, dst, 0, 0, nullptr);
-          else
-            launch_contract(s, g, dt, use_mask, Um, sg.K, sg.M, true, sg, dst);
-        } else {
-          launch_mid(s, src, Um, sg.M, true, sg, dst);
-        }
+        if (st == 0)
+          first_stage(c, g, sg, tile_start, use_mask, dst);
+        else
+          launch_mid(s, src, c->st<float2>(p.st_U[sg.mode]), sg.M, true, sg, dst);
         src = dst;
       }
       double* partials = c->w<double>(p.ws_partials);
@@ -448,6 +480,64 @@ int do_refresh(tgrad_ctx* c, const void* g) {
     }
   }
   pack_fused_factor(c);
+}
+
+// z = (G~_L before its last expansion), (A, r_N): the core `core` expanded in modes 1 .. N-1 through the
+// buffers of the raw chain.  Returns where it lies.
+const float2* raw_expand(tgrad_ctx* c, const float2* core) {
+  Plan& p = c->plan;
+  float2* rb[2] = {c->w<float2>(p.ws_rbuf[0]), c->w<float2>(p.ws_rbuf[1])};
+  const float2* src = core;
+  for (int st = 0; st + 1 < p.N; ++st) {
+    const Stage& sg = p.back[st];
+    float2* dst = rb[st & 1];
+    Scope sc_(c, KID_RESIDUAL);
+    launch_mid(c->stream, src, c->st<float2>(p.st_U[sg.mode]), p.rank[sg.mode], false, sg, dst);
+    src = dst;
+  }
+  return src;
+}
+
+int do_refresh(tgrad_ctx* c, const void* g) {
+  Plan& p = c->plan;
+  hipStream_t s = c->stream;
+  const int dt = c->cfg.grad_dtype;
+  const uint32_t* real_ts = c->w<uint32_t>(p.ws_tile_start);
+  if (p.order == TGRAD_ORDER_US_LR) {
+    // Algorithm 1: support from G, factors from G with the support removed
+    select_support(c, g, dt);
+    compute_factors(c, g, real_ts, p.k > 0 ? c->w<uint32_t>(p.ws_mask) : nullptr);
+    return check_launch();
+  }
+  const uint32_t* zero_ts = c->w<uint32_t>(p.ws_tile_zero);
+  if (p.order == TGRAD_ORDER_SUM) {
+    // both components see the full gradient
+    select_support(c, g, dt);
+    compute_factors(c, g, zero_ts, nullptr);
+    return check_launch();
+  }
+  // low rank first: factors of the full gradient, then the support from R = G - G~_L
+  compute_factors(c, g, zero_ts, nullptr);
+  float2* rb[2] = {c->w<float2>(p.ws_rbuf[0]), c->w<float2>(p.ws_rbuf[1])};
+  float2* core = c->w<float2>(p.ws_core_g);
+  const float2* src = nullptr;
+  for (int st = 0; st < p.N; ++st) {                           // unfused compression chain, nothing removed
+    const Stage& sg = p.proj[st];
+    float2* dst = (st == p.N - 1) ? core : rb[st & 1];
+    Scope sc_(c, KID_RESIDUAL);
+    if (st == 0)
+      first_stage(c, g, sg, zero_ts, nullptr, dst);
+    else
+      launch_mid(s, src, c->st<float2>(p.st_U[sg.mode]), p.rank[sg.mode], true, sg, dst);
+    src = dst;
+  }
+  const float2* z = raw_expand(c, core);
+  {
+    const Stage& sg = p.back[p.N - 1];
+    Scope sc_(c, KID_RESIDUAL);
+    launch_residual(s, g, dt, z, c->st<float2>(p.st_U[p.N - 1]), p.rank[p.N - 1], sg.A, sg.M, c->w<float2>(p.ws_resid));
+  }
+  select_support(c, c->w<float2>(p.ws_resid), TGRAD_C64);
   return check_launch();
 }
 
@@ -465,9 +555,15 @@ int do_step(tgrad_ctx* c, void* weight, const void* g) {
 
   const uint32_t* tile_start = c->w<uint32_t>(p.ws_tile_start);
   const bool mfma_last = p.tile_waves > 0;
+  // What the compression chain removes on the way in: the support (Algorithm 1), or nothing (the
+  // low-rank part sees the full gradient in the two other composition orders).
+  const bool remove_support = p.order == TGRAD_ORDER_US_LR;
+  const uint32_t* in_ts = remove_support ? tile_start : c->w<uint32_t>(p.ws_tile_zero);
+  const uint32_t* in_mask = remove_support ? mask : nullptr;
 
   // g_S <- Sparse(G, Omega);  g_L <- (G - g_S) x_N UN^H ... x_1 U1^H
-  if (!mfma_last) { Scope sc_(c, KID_GATHER); launch_gather(s, g, cf.grad_dtype, omega, p.k, gs); }
+  // (the matrix-core first stage gathers the values it removes; otherwise a gather kernel does)
+  if (!mfma_last || !remove_support) { Scope sc_(c, KID_GATHER); launch_gather(s, g, cf.grad_dtype, omega, p.k, gs); }
   const float2* src = nullptr;
   for (int st = 0; st < N; ++st) {
     const Stage& sg = p.proj[st];
@@ -476,7 +572,7 @@ int do_step(tgrad_ctx* c, void* weight, const void* g) {
     if (st == 0 && mfma_last && p.fuse_next) {                 // stages 0 and 1 in one kernel
       float2* dst1 = (N == 2) ? core_g : buf[1];
       Scope sc_(c, KID_PROJECT_FIRST);
-      launch_lproj(s, g, cf.grad_dtype, omega, tile_start, gs, U, p.rank[sg.mode], sg, p.tile_waves, dst1,
+      launch_lproj(s, g, cf.grad_dtype, omega, in_ts, gs, U, p.rank[sg.mode], sg, p.tile_waves, dst1,
                    (int)p.shape[N - 2], p.rank[N - 2], c->w<float2>(p.ws_fpad));
       src = dst1;
       st = 1;
@@ -486,10 +582,10 @@ int do_step(tgrad_ctx* c, void* weight, const void* g) {
     Scope sc_(c, st == 0 ? KID_PROJECT_FIRST : KID_PROJECT);
     if (st == 0) {
       if (mfma_last)
-        launch_lproj(s, g, cf.grad_dtype, omega, tile_start, gs, U, p.rank[sg.mode], sg, p.tile_waves, dst, 0, 0,
+        launch_lproj(s, g, cf.grad_dtype, omega, in_ts, gs, U, p.rank[sg.mode], sg, p.tile_waves, dst, 0, 0,
                      nullptr);
       else
-        launch_contract(s, g, cf.grad_dtype, mask, U, (int)p.shape[sg.mode], p.rank[sg.mode], true, sg, dst);
+        launch_contract(s, g, cf.grad_dtype, in_mask, U, (int)p.shape[sg.mode], p.rank[sg.mode], true, sg, dst);
     } else {
       launch_mid(s, src, U, p.rank[sg.mode], true, sg, dst);
     }
@@ -514,6 +610,14 @@ int do_step(tgrad_ctx* c, void* weight, const void* g) {
     Scope sc_(c, KID_ADAM_CORE);
     launch_adam_core(s, core_g, c->st<float2>(p.st_ml), c->st<float>(p.st_vl), core_n, p.C, cf.beta1,
                      cf.beta2, inv_c1, inv_c2, cf.eps);
+  }
+
+  // low rank first: the sparse part works on the residual of the low-rank approximation of THIS
+  // gradient: g_S <- g_S - (g_L x_1 U1 ... x_N UN)[Omega]
+  if (p.order == TGRAD_ORDER_LR_US && p.k > 0) {
+    const float2* z = raw_expand(c, core_g);
+    Scope sc_(c, KID_RESIDUAL);
+    launch_residual_gather(s, gs, omega, p.k, z, c->st<float2>(p.st_U[N - 1]), p.rank[N - 1], (int)p.shape[N - 1]);
   }
 
   // D <- alpha (N_L x_1 U1 ... x_N UN); the last stage is fused with AdamUpdate on the sparse values,
@@ -640,6 +744,8 @@ int tgrad_init(tgrad_ctx** out, const tgrad_config* cfg, void* state_dev, void* 
   }
   // moments <- 0 (and everything else in the state block), with a fill kernel
   zero_u32(c->stream, reinterpret_cast<uint32_t*>(c->state), (int64_t)(c->plan.state_bytes / 4));
+  if (c->plan.order != TGRAD_ORDER_US_LR)
+    zero_u32(c->stream, c->w<uint32_t>(c->plan.ws_tile_zero), c->plan.ntiles + 1);
   if (check_launch() != TGRAD_OK) {
     delete c;
     return TGRAD_ERR_HIP;

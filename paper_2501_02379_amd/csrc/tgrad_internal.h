@@ -37,7 +37,7 @@ enum KernelId {
   KID_SEL_HIST = 0, KID_SEL_PICK, KID_SEL_COUNT, KID_SEL_SCAN, KID_SEL_EMIT, KID_MASK_FROM_IDX,
   KID_TILE_OFFSETS, KID_GRAM, KID_GRAM_REDUCE, KID_EIG, KID_FACTOR_PACK,
   KID_GATHER, KID_PROJECT_FIRST, KID_PROJECT, KID_ADAM_CORE, KID_BACKPROJECT, KID_UPDATE,
-  KID_SPARSE_UPDATE, KID_HOOI_PROJECT, KID_CORE, KID_COUNT
+  KID_SPARSE_UPDATE, KID_HOOI_PROJECT, KID_CORE, KID_RESIDUAL, KID_COUNT
 };
 
 struct Launch {                            // what every launcher needs
@@ -83,6 +83,11 @@ void launch_sparse_adam(hipStream_t s, float2* gs, int64_t k, float2* m, float* 
 void launch_update(hipStream_t s, const float2* z, const float2* U, int In, int rn, const Stage& st, void* w,
                    int wdtype, float decay, float neg_lr_alpha, const uint32_t* mask, const int32_t* omega,
                    int64_t k, const float2* ns);
+
+void launch_residual(hipStream_t s, const void* g, int dtype, const float2* z, const float2* U, int rn, int64_t A,
+                     int M, float2* r);
+void launch_residual_gather(hipStream_t s, float2* gs, const int32_t* omega, int64_t k, const float2* z,
+                            const float2* U, int rn, int M);
 
 // matrix-core kernels of the step (contract_mfma.hip)
 int choose_tile_waves(int Klast, int rlast, int prefer);

@@ -18,6 +18,7 @@ MAX_NDIM = 6
 TGRAD_C64, TGRAD_CBF16 = 0, 1
 TGRAD_SELECT_TOPK_MAG = 0
 TGRAD_SELECT_RANDOM = 1
+TGRAD_ORDER_US_LR, TGRAD_ORDER_LR_US, TGRAD_ORDER_SUM = 0, 1, 2
 
 TGRAD_OK = 0
 TGRAD_ERR_INVALID_ARG = -1
@@ -58,6 +59,7 @@ class tgrad_config(C.Structure):
         ("hooi_sweeps", C.c_int32),
         ("select_rule", C.c_int32),
         ("select_seed", C.c_uint64),
+        ("order", C.c_int32),
         ("warm_restart", C.c_int32),
     ]
 
@@ -122,7 +124,8 @@ def rank_from_ratio(ratio: Fraction, extent: int) -> int:
 def make_config(shape: Sequence[int], rank: Sequence[int], k_sparse: int, *, grad_dtype=TGRAD_C64,
                 weight_dtype=TGRAD_C64, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, alpha=1.0,
                 lam=1.0, weight_decay=0.0, refresh_every=1, hooi_sweeps=0,
-                select_rule=TGRAD_SELECT_TOPK_MAG, select_seed=0, warm_restart=False) -> tgrad_config:
+                select_rule=TGRAD_SELECT_TOPK_MAG, select_seed=0, warm_restart=False,
+                order=TGRAD_ORDER_US_LR) -> tgrad_config:
     cfg = tgrad_config()
     cfg.ndim = len(shape)
     if len(shape) <= MAX_NDIM and len(rank) == len(shape):
@@ -137,6 +140,7 @@ def make_config(shape: Sequence[int], rank: Sequence[int], k_sparse: int, *, gra
     cfg.refresh_every, cfg.hooi_sweeps, cfg.select_rule = refresh_every, hooi_sweeps, select_rule
     cfg.select_seed = int(select_seed) & 0xFFFFFFFFFFFFFFFF
     cfg.warm_restart = int(warm_restart)
+    cfg.order = int(order)
     return cfg
 
 

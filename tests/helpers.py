@@ -26,6 +26,7 @@ def oracle_hyper(shape, ranks, k, **kw) -> O.Hyper:
                    lam=kw.get("lam", 1.0), weight_decay=kw.get("weight_decay", 0.0),
                    T=kw.get("refresh_every", 1), hooi_sweeps=kw.get("hooi_sweeps", 0),
                    warm_restart=bool(kw.get("warm_restart", False)),
+                   order={0: "us_lr", 1: "lr_us", 2: "sum"}[kw.get("order", 0)],
                    select_rule="randk" if kw.get("select_rule", 0) == 1 else "topk",
                    select_seed=kw.get("select_seed", 0))
 

@@ -68,6 +68,7 @@ def test_query_sizes_counts_the_compressed_state():
     (lambda c: setattr(c, "warm_restart", 1), T.TGRAD_ERR_INVALID_ARG),      # needs hooi_sweeps >= 1
     (lambda c: (setattr(c, "hooi_sweeps", 1), setattr(c, "warm_restart", 2)), T.TGRAD_ERR_INVALID_ARG),
     (lambda c: setattr(c, "select_rule", 2), T.TGRAD_ERR_INVALID_ARG),
+    (lambda c: setattr(c, "order", 3), T.TGRAD_ERR_INVALID_ARG),
     (lambda c: setattr(c, "select_rule", -1), T.TGRAD_ERR_INVALID_ARG),
     (lambda c: c.shape.__setitem__(0, 1 << 31), T.TGRAD_ERR_UNSUPPORTED),
 ])

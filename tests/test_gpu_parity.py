@@ -209,6 +209,52 @@ def test_bf16_weights_ten_free_running_steps():
     assert np.linalg.norm(a - b) <= 1e-2 * np.linalg.norm(b)
 
 
+# ------------------------------------------------------------------ composition orders
+ORDER_CASES = [
+    # shape, ranks, k, gradient dtype                 kernel tier
+    ((16, 16, 8, 5), (8, 8, 4, 3), 103, "c64"),       # matrix-core, unfused
+    ((16, 32, 32, 9), (4, 8, 8, 4), 300, "c64"),      # fused
+    ((6, 5, 4, 3, 5), (2, 2, 2, 2, 2), 18, "cbf16"),  # five modes, half-precision gradients
+    ((8, 7, 40), (2, 2, 36), 30, "c64"),              # generic last-mode kernels
+    ((33, 20, 9), (5, 20, 2), 60, "c64"),             # one mode at full rank
+]   # (no matrix here: stepping a matrix on its own refresh gradient makes the core exactly diagonal,
+    #  see test_order2_tensor_with_explicit_refresh)
+
+
+@pytest.mark.parametrize("order", ["lr_us", "sum"])
+@pytest.mark.parametrize("shape,ranks,k,dt", ORDER_CASES)
+def test_composition_orders_end_to_end(shape, ranks, k, dt, order):
+    """Low rank first (the sparse part on the residual of the low-rank approximation) and the
+    additive composition, against the oracle: support at every refresh, factors, weights."""
+    _announce("order", order, shape, ranks, k, dt)
+    oid = T.TGRAD_ORDER_LR_US if order == "lr_us" else T.TGRAD_ORDER_SUM
+    grads = [synth.small_case(shape, 800 + t, dtype=dt) for t in range(7)]
+    rng = np.random.default_rng(10)
+    W0 = ((rng.standard_normal(shape) + 1j * rng.standard_normal(shape)) * 0.02).astype(np.complex64)
+    info = run_both(T, shape, ranks, k, grads, W0, grad_dtype=T.TGRAD_CBF16 if dt == "cbf16" else 0,
+                    refresh_every=3, lr=2e-3, lam=0.7, alpha=1.2, order=oid)
+    assert all(info["omega_equal"]) and len(info["omega_equal"]) == 3
+    assert max(max(d) for d in info["proj_dist"]) < PROJ_TOL
+    assert rel_err(info["W_gpu"], info["W_oracle"]) < W_TOL
+    assert rel_err(info["W_gpu"] - W0, info["W_oracle"] - W0) < DW_TOL
+    st, ctx = info["state"], info["ctx"]
+    assert rel_err(ctx.tgrad_get_state(T.STATE_SPARSE_M), st.M_S) < 1e-4
+    assert rel_err(ctx.tgrad_get_state(T.STATE_CORE_M), st.M_L) < 1e-4
+    if order == "lr_us" and len(shape) > 2:
+        # the support is that of the residual, not of the gradient itself
+        assert not np.array_equal(st.omega, O.sparse_indices(grads[6], k))
+
+
+def test_low_rank_first_with_hooi_and_random_support():
+    w = synth.WORKLOADS["cfg1"]
+    info, W0 = _end_to_end(w, 10, order=T.TGRAD_ORDER_LR_US, hooi_sweeps=1, select_rule=T.TGRAD_SELECT_RANDOM,
+                           select_seed=77)
+    assert all(info["omega_equal"]) and len(info["omega_equal"]) == 2
+    assert max(max(d) for d in info["proj_dist"]) < PROJ_TOL
+    assert rel_err(info["W_gpu"], info["W_oracle"]) < W_TOL
+    assert rel_err(info["W_gpu"] - W0, info["W_oracle"] - W0) < DW_TOL
+
+
 # ------------------------------------------------------------------ HOOI sweeps, warm restart
 def test_hooi_refresh_matches_oracle_cfg1():
     """Two refinement sweeps after HOSVD.  On this noise-like tensor the refined factors are far
