@@ -197,6 +197,8 @@ def main():
     ap.add_argument("--warm-restart", action="store_true", help="with --hooi-sweeps: refreshes restart from the factors in place")
     ap.add_argument("--select", choices=("topk", "random"), default="topk",
                     help="support selection rule (default top-k magnitude, the headline configuration)")
+    ap.add_argument("--order", choices=("us_lr", "lr_us", "sum"), default="us_lr",
+                    help="composition of the two components (default us_lr = Algorithm 1, the headline configuration)")
     ap.add_argument("--weights", choices=("c64", "bf16"), default="c64",
                     help="weight storage (default complex64, the headline configuration; bf16 = half-precision pairs)")
     args = ap.parse_args()
@@ -227,6 +229,7 @@ def main():
                             warm_restart=args.warm_restart,
                             select_rule=T.TGRAD_SELECT_RANDOM if args.select == "random" else T.TGRAD_SELECT_TOPK_MAG,
                             select_seed=2501 + layer,
+                            order={"us_lr": T.TGRAD_ORDER_US_LR, "lr_us": T.TGRAD_ORDER_LR_US, "sum": T.TGRAD_ORDER_SUM}[args.order],
                             weight_dtype=T.TGRAD_CBF16 if args.weights == "bf16" else T.TGRAD_C64)
         ctxs.append(T.Context(cfg, device=dev))
         w0 = synth.initial_weight(w, layer)
@@ -310,7 +313,7 @@ def main():
             ent["GBps"] = round(mm["bytes"] / lp / (avg * 1e-3) / 1e9, 1)
             ent["TFLOPs"] = round(mm["flops"] / lp / (avg * 1e-3) / 1e12, 2)
         kernels[name] = ent
-    step_kernels = [n for n in kernels if not n.startswith(("select", "gram", "eig", "mask", "factor", "hooi", "tile"))]
+    step_kernels = [n for n in kernels if not n.startswith(("select", "gram", "eig", "mask", "factor", "hooi", "tile", "residual", "gather"))]
     dom = max(step_kernels, key=lambda n: kernels[n]["total_ms"]) if step_kernels else None
     roofline = None
     if dom and dom in model:
@@ -336,7 +339,7 @@ def main():
                                % (w.name, w.layers, "x".join(map(str, w.shape)), w.grad_dtype,
                                   ",".join(map(str, w.ranks)), w.k, w.T),
                    "refreshes_in_timed_region": refreshes, "fused_mode_stages": bool(fused), "fused_core_stage": bool(core_fused),
-                   "weights": args.weights, "select": args.select, "hooi_sweeps": args.hooi_sweeps, "warm_restart": bool(args.warm_restart)},
+                   "order": args.order, "weights": args.weights, "select": args.select, "hooi_sweeps": args.hooi_sweeps, "warm_restart": bool(args.warm_restart)},
         "roofline": roofline,
         "ms_per_step_with_kernel_events": round(ms_per_step_profiled, 4),
         "refresh_ms": refresh_ms,
