@@ -425,11 +425,12 @@ __device__ __forceinline__ void wave_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// Factor table in LDS: sF[k * ld + m] = F[m, k] as (fr, fi), ld = 16 NT, zero for k >= K or
-// m >= M.  PROJECT: F[m, k] = conj(U[k, m]); otherwise F[m, k] = U[m, k].
+// Factor table in LDS: sF[k * ld + m] = scale * F[m, k] as (fr, fi), ld = 16 NT, zero for k >= K
+// or m >= M.  PROJECT: F[m, k] = conj(U[k, m]); otherwise F[m, k] = U[m, k].
 template <bool PROJECT>
 __device__ __forceinline__ void stage_factor_table(float2* sF, const float2* __restrict__ U, int rn, int K,
-                                                   int M, int krows, int ld, int tid, int nthreads) {
+                                                   int M, int krows, int ld, int tid, int nthreads,
+                                                   float scale = 1.f) {
   for (int e = tid; e < krows * ld; e += nthreads) {
     const int k = e / ld, m = e - k * ld;
     float2 f = make_float2(0.f, 0.f);
@@ -441,7 +442,7 @@ __device__ __forceinline__ void stage_factor_table(float2* sF, const float2* __r
         f = U[(int64_t)m * rn + k];
       }
     }
-    sF[e] = f;
+    sF[e] = make_float2(scale * f.x, scale * f.y);
   }
 }
 // Coefficients of the (re, im) parts of input element k for real output column (m, p):
@@ -880,7 +881,7 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate(const float* __restrict__
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // in a scalar register: tile bookkeeping stays scalar
   float* sD = smem + wave * slice;
   float2* sF = reinterpret_cast<float2*>(smem + W * slice);
-  stage_factor_table<false>(sF, U, K, K, M, 2 * JT, ld, tid, T);
+  stage_factor_table<false>(sF, U, K, K, M, 2 * JT, ld, tid, T, c_alpha);   // the update's scale rides in the table
   __syncthreads();                                             // the only workgroup barrier
 
   const int64_t Iw = A * M;                                    // complex elements of W
@@ -965,7 +966,7 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate(const float* __restrict__
       wpre[i] = w4[q < n4 ? q : n4 - 1];
     }
     wave_sync();                                               // previous tile's LDS reads are done
-    // ---- expand the 32 rows: sD[row, c] = c_alpha * sum_k ..., NTB column tiles at a time ----
+    // ---- expand the 32 rows: sD[row, c] = sum_k (c_alpha U)[c, k] z[row, k], NTB column tiles at a time ----
     auto block = [&](int nt0, auto ntile_count) {
       constexpr int N = decltype(ntile_count)::value;
       v16f acc[N];
@@ -988,7 +989,7 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate(const float* __restrict__
         const int c = 32 * (nt0 + i) + col;
         if (c < N2) {
 #pragma unroll
-          for (int r = 0; r < 16; ++r) sD[d_row(r, half) * N2 + c] = c_alpha * acc[i][r];
+          for (int r = 0; r < 16; ++r) sD[d_row(r, half) * N2 + c] = acc[i][r];
         }
       }
     };
@@ -1065,7 +1066,7 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate_fused(const float2* __res
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   float* sD = smem + wave * slice;
   float2* sF = reinterpret_cast<float2*>(smem + W * slice);
-  stage_factor_table<false>(sF, U, K, K, M, 16, ld, tid, T);   // 16 rows: K <= 16 here
+  stage_factor_table<false>(sF, U, K, K, M, 16, ld, tid, T, c_alpha);   // 16 rows: K <= 16 here; scaled by c_alpha
   __syncthreads();                                             // the only workgroup barrier
 
   const int64_t Iw = A * M;
@@ -1178,7 +1179,7 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate_fused(const float2* __res
     issue_sparse(nj0, nj1);
     const uint32_t nnj0 = sp.tile_start[nn + vzero], nnj1 = sp.tile_start[nn + 1 + vzero];
     wave_sync();                                               // previous tile's LDS reads are done
-    // ---- stage B: expand the last mode: sD[row, c] = c_alpha * sum_k ..., NTB column tiles at a time ----
+    // ---- stage B: expand the last mode: sD[row, c] = sum_k (c_alpha U)[c, k] ..., NTB column tiles at a time ----
     const float2* fl = sF + (2 * half) * ld + (col >> 1);      // row k(u, half) = (u & 1) + 4 (u >> 1) + 2 half
     auto block = [&](int nt0, auto ntile_count) {
       constexpr int N = decltype(ntile_count)::value;
@@ -1202,15 +1203,42 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate_fused(const float2* __res
         const int c = 32 * (nt0 + i) + col;
         if (c < N2) {
 #pragma unroll
-          for (int r = 0; r < 16; ++r) sD[d_row(r, half) * N2 + c] = c_alpha * acc[i][r];
+          for (int r = 0; r < 16; ++r) sD[d_row(r, half) * N2 + c] = acc[i][r];
         }
       }
     };
-    {
+    if constexpr (NTB == 1) {
+      // one column tile at a time, its 8 coefficient pairs fetched while the previous tile is in the
+      // matrix cores (the last tile re-reads itself)
+      float2 cf[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) cf[u] = fl[((u & 1) + 4 * (u >> 1)) * ld];
+      for (int nt0 = 0; nt0 < NT; ++nt0) {
+        float2 cn[8];
+        const float2* fn = fl + 16 * (nt0 + 1 < NT ? nt0 + 1 : nt0);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) cn[u] = fn[((u & 1) + 4 * (u >> 1)) * ld];
+        v16f acc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const float2 b2 = column_coef(cf[u], part);
+          acc = mfma32(dz[2 * u], b2.x, acc);
+          acc = mfma32(dz[2 * u + 1], b2.y, acc);
+        }
+        const int c = 32 * nt0 + col;
+        if (c < N2) {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) sD[d_row(r, half) * N2 + c] = acc[r];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) cf[u] = cn[u];
+      }
+    } else {
       int nt0 = 0;
       for (; nt0 + NTB <= NT; nt0 += NTB) block(nt0, std::integral_constant<int, NTB>());
-      if (NTB > 1)
-        for (; nt0 < NT; ++nt0) block(nt0, std::integral_constant<int, 1>());
+      for (; nt0 < NT; ++nt0) block(nt0, std::integral_constant<int, 1>());
     }
     wave_sync();
     // ---- AdamUpdate on the sparse values that live in this tile; add lambda N_S into the tile ----
