@@ -110,9 +110,10 @@ __global__ __launch_bounds__(kGramThreads) void k_gram(const void* __restrict__ 
     if (i < In && c < c_end) {
       const int64_t a = c / B, b = c - a * B;
       const int64_t idx = (a * In + i) * B + b;
-      bool drop = false;
-      if (mask) drop = (mask[idx >> 5] >> (idx & 31)) & 1u;
-      if (!drop) v = load_elem<DT>(x, idx);
+      // both loads are issued together (a load that waits for the mask bit would double the latency)
+      const uint32_t mw = mask ? mask[idx >> 5] : 0u;
+      const float2 xv = load_elem<DT>(x, idx);
+      if (!((mw >> (idx & 31)) & 1u)) v = xv;
     }
     return v;
   };
