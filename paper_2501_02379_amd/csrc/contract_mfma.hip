@@ -478,7 +478,7 @@ __device__ __forceinline__ void claim_raw(uint2& r) { asm volatile("" : "+v"(r.x
 
 constexpr int kTileBatch = 17;            // 2-element pieces per lane in flight while a tile is staged
 constexpr int kJUnroll = 4;               // row pairs whose LDS operands are fetched ahead of their MFMAs
-constexpr int kCoefPairs = 34;            // fused first stage: most row pairs whose coefficients stay in registers
+constexpr int kCoefPairs = 33;            // fused first stage: most row pairs whose coefficients stay in registers
 constexpr int kCoefPairsShort = 17;       // ... and the variant for short last modes (I_N <= 34)
 
 // k_lproj: out[a, m] = sum_k conj(U[k, m]) (G - Sparse(G, Omega))[a, k];  gs[j] = G[Omega_j].
