@@ -1068,6 +1068,19 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate_fused(const float2* __res
   float2* sF = reinterpret_cast<float2*>(smem + W * slice);
   stage_factor_table<false>(sF, U, K, K, M, 16, ld, tid, T, c_alpha);   // 16 rows: K <= 16 here; scaled by c_alpha
   __syncthreads();                                             // the only workgroup barrier
+  // A half-spectrum last mode has 2^m + 1 entries: its last complex column would occupy a whole
+  // 32-column matrix-core tile on its own.  That column is expanded with ordinary arithmetic
+  // instead: each lane holds 8 of the 16 elements of its row (see stage B), multiplies them with
+  // the column's coefficients - which do not depend on the tile and stay in registers - and the
+  // two halves of the wavefront are added with one lane exchange.
+  const bool vtail = (N2 & 31) == 2;
+  const int NTm = vtail ? NT - 1 : NT;                         // column tiles that go through the matrix cores
+  float2 ctail[8];
+#pragma unroll
+  for (int u = 0; u < 8; ++u) {
+    const int k = (u & 1) + 4 * (u >> 1) + 2 * (lane >> 5);
+    ctail[u] = vtail ? sF[k * ld + (M - 1)] : make_float2(0.f, 0.f);
+  }
 
   const int64_t Iw = A * M;
   const int tile_w = kTileRows * M;
@@ -1213,9 +1226,9 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate_fused(const float2* __res
       float2 cf[8];
 #pragma unroll
       for (int u = 0; u < 8; ++u) cf[u] = fl[((u & 1) + 4 * (u >> 1)) * ld];
-      for (int nt0 = 0; nt0 < NT; ++nt0) {
+      for (int nt0 = 0; nt0 < NTm; ++nt0) {
         float2 cn[8];
-        const float2* fn = fl + 16 * (nt0 + 1 < NT ? nt0 + 1 : nt0);
+        const float2* fn = fl + 16 * (nt0 + 1 < NTm ? nt0 + 1 : nt0);
 #pragma unroll
         for (int u = 0; u < 8; ++u) cn[u] = fn[((u & 1) + 4 * (u >> 1)) * ld];
         v16f acc;
@@ -1237,8 +1250,20 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate_fused(const float2* __res
       }
     } else {
       int nt0 = 0;
-      for (; nt0 + NTB <= NT; nt0 += NTB) block(nt0, std::integral_constant<int, NTB>());
-      for (; nt0 < NT; ++nt0) block(nt0, std::integral_constant<int, 1>());
+      for (; nt0 + NTB <= NTm; nt0 += NTB) block(nt0, std::integral_constant<int, NTB>());
+      for (; nt0 < NTm; ++nt0) block(nt0, std::integral_constant<int, 1>());
+    }
+    if (vtail) {                                               // the last complex column, without the matrix cores
+      float pre = 0.f, pim = 0.f;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const float zr = dz[2 * u], zi = dz[2 * u + 1];
+        pre += zr * ctail[u].x - zi * ctail[u].y;
+        pim += zr * ctail[u].y + zi * ctail[u].x;
+      }
+      pre += __shfl_xor(pre, 32, 64);
+      pim += __shfl_xor(pim, 32, 64);
+      if (half == 0) *reinterpret_cast<float2*>(&sD[col * N2 + N2 - 2]) = make_float2(pre, pim);
     }
     wave_sync();
     // ---- AdamUpdate on the sparse values that live in this tile; add lambda N_S into the tile ----
