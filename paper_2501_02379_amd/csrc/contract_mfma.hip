@@ -883,6 +883,10 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate(const float* __restrict__
   float2* sF = reinterpret_cast<float2*>(smem + W * slice);
   stage_factor_table<false>(sF, U, K, K, M, 2 * JT, ld, tid, T, c_alpha);   // the update's scale rides in the table
   __syncthreads();                                             // the only workgroup barrier
+  // a lone last complex column (half-spectrum modes have 2^m + 1 entries) does not get a 32-column
+  // matrix-core tile of its own: it is expanded with vector arithmetic (see k_lupdate_fused)
+  const bool vtail = (N2 & 31) == 2;
+  const int NTm = vtail ? NT - 1 : NT;
 
   const int64_t Iw = A * M;                                    // complex elements of W
   const int tile_w = kTileRows * M;
@@ -995,9 +999,22 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate(const float* __restrict__
     };
     {
       int nt0 = 0;
-      for (; nt0 + NTB <= NT; nt0 += NTB) block(nt0, std::integral_constant<int, NTB>());
+      for (; nt0 + NTB <= NTm; nt0 += NTB) block(nt0, std::integral_constant<int, NTB>());
       if (NTB > 1)
-        for (; nt0 < NT; ++nt0) block(nt0, std::integral_constant<int, 1>());
+        for (; nt0 < NTm; ++nt0) block(nt0, std::integral_constant<int, 1>());
+    }
+    if (vtail) {                                               // the last complex column, without the matrix cores
+      const float2* ft = sF + half * JT * ld + (M - 1);
+      float pre = 0.f, pim = 0.f;
+#pragma unroll
+      for (int jj = 0; jj < JT; ++jj) {
+        const float2 cf = ft[jj * ld];
+        pre += zcur[jj].x * cf.x - zcur[jj].y * cf.y;
+        pim += zcur[jj].x * cf.y + zcur[jj].y * cf.x;
+      }
+      pre += __shfl_xor(pre, 32, 64);
+      pim += __shfl_xor(pim, 32, 64);
+      if (half == 0) *reinterpret_cast<float2*>(&sD[col * N2 + N2 - 2]) = make_float2(pre, pim);
     }
     wave_sync();
     // ---- AdamUpdate on the sparse values that live in this tile; add lambda N_S into the tile ----
