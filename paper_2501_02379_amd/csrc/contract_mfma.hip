@@ -476,7 +476,8 @@ __device__ __forceinline__ void claim_raw(float4& r) {
 }
 __device__ __forceinline__ void claim_raw(uint2& r) { asm volatile("" : "+v"(r.x), "+v"(r.y)); }
 
-constexpr int kTileBatch = 17;            // 2-element pieces per lane in flight while a tile is staged
+constexpr int kTileBatch = 17;            // 2-element pieces per lane in flight while a tile is staged (the most;
+                                          // narrower last modes use 9 or 5: a tile of K-wide rows has K / 4 per lane)
 constexpr int kJUnroll = 4;               // row pairs whose LDS operands are fetched ahead of their MFMAs
 constexpr int kCoefPairs = 33;            // fused first stage: most row pairs whose coefficients stay in registers
 constexpr int kCoefPairsShort = 17;       // ... and the variant for short last modes (I_N <= 34)
@@ -503,7 +504,7 @@ struct FusedNext {
   int M2;
 };
 
-template <int DT, int W, int NTB, bool FLAT, bool FUSE, int CP>
+template <int DT, int W, int NTB, bool FLAT, bool FUSE, int CP, int TB>
 __global__ __launch_bounds__(64 * W, 2) void k_lproj(const void* __restrict__ g,
                                                      const int32_t* __restrict__ omega,
                                                      const uint32_t* __restrict__ tile_start,
@@ -554,7 +555,7 @@ __global__ __launch_bounds__(64 * W, 2) void k_lproj(const void* __restrict__ g,
     if (t + 1 < S) { t += 1; } else { t = 0; sl += nw; }
   };
 
-  Raw raw[kTileBatch];
+  Raw raw[TB];
   int32_t my_om = -1;
   // issue the first batch of tile `t` (its support range is [j0, j1)) into raw / my_om.  The loads
   // are unconditional (indices past the tile are clamped onto its last pair): a conditional load
@@ -564,7 +565,7 @@ __global__ __launch_bounds__(64 * W, 2) void k_lproj(const void* __restrict__ g,
     const int n_e = (int)((I - e_base) < tile_elems ? (I - e_base) : tile_elems);
     const int npairs = n_e >> 1;                               // >= 1: the host keeps K >= 2 here
 #pragma unroll
-    for (int i = 0; i < kTileBatch; ++i) {
+    for (int i = 0; i < TB; ++i) {
       const int pi = lane + i * 64;
       raw[i] = load_raw_pair<DT>(g, (e_base >> 1) + (pi < npairs ? pi : npairs - 1));
     }
@@ -618,14 +619,14 @@ __global__ __launch_bounds__(64 * W, 2) void k_lproj(const void* __restrict__ g,
     // one wait for the whole batch (the only memory operations issued after it were loads)
     asm volatile("" : "+v"(my_om));
 #pragma unroll
-    for (int i = 0; i < kTileBatch; ++i) claim_raw(raw[i]);
+    for (int i = 0; i < TB; ++i) claim_raw(raw[i]);
     const int npairs = n_e >> 1;
 #pragma unroll
-    for (int i = 0; i < kTileBatch; ++i) {
+    for (int i = 0; i < TB; ++i) {
       const int pi = lane_now + i * 64;
       if (pi < npairs) commit_pair(raw[i], 2 * pi);
     }
-    for (int pi = lane + kTileBatch * 64; pi < npairs; pi += 64)          // long rows: the rest, unpipelined
+    for (int pi = lane + TB * 64; pi < npairs; pi += 64)          // long rows: the rest, unpipelined
       commit_pair(load_raw_pair<DT>(g, (e_base >> 1) + pi), 2 * pi);
     if ((n_e & 1) && lane == 0) {                              // odd element count: the last one alone
       const int e = n_e - 1;
@@ -1505,30 +1506,42 @@ void launch_lproj(hipStream_t s, const void* g, int dtype, const int32_t* omega,
   const bool fuse = fused_I2 > 0;
   const int S = fuse ? fused_I2 / kTileRows : 1;
   const int64_t nslabs = (ntiles + S - 1) / S;
-  const int per_cu = (int)(kLdsLimit / (lds ? lds : 1));
-  dim3 grid((unsigned)grid_for_tiles((nslabs + W - 1) / W, per_cu < 1 ? 1 : per_cu > 2 ? 2 : per_cu)), block(64 * W);
+  const int tb = (K + 3) / 4 <= 5 ? 5 : (K + 3) / 4 <= 9 ? 9 : kTileBatch;   // pieces per lane a tile needs (capped)
+  // workgroups per compute unit: LDS allows lds-many; the wide-tile variants fill the register file
+  // with 2 wavefronts per SIMD, the narrow ones leave room for up to 4
+  const int per_cu_lds = (int)(kLdsLimit / (lds ? lds : 1));
+  const int per_cu_cap = (W == 4 && tb < kTileBatch) ? 4 : 2;
+  const int per_cu = per_cu_lds < 1 ? 1 : per_cu_lds > per_cu_cap ? per_cu_cap : per_cu_lds;
+  dim3 grid((unsigned)grid_for_tiles((nslabs + W - 1) / W, per_cu)), block(64 * W);
   float* of = reinterpret_cast<float*>(out);
   const uint32_t magic = magic_for(K);
   FusedNext fz{fpad, of, S, fused_M2};
-#define TGRAD_LP_C(DT_, W_, NTB_, F_, Z_, CP_)                                                           \
+#define TGRAD_LP_C(DT_, W_, NTB_, F_, Z_, CP_, TB_)                                                      \
   do {                                                                                                   \
-    allow_lds(k_lproj<DT_, W_, NTB_, F_, Z_, CP_>, lds);                                                 \
-    k_lproj<DT_, W_, NTB_, F_, Z_, CP_><<<grid, block, lds, s>>>(g, omega, tile_start, gs, U, rn, A, K,  \
-                                                                 M, magic, ntiles, of, fz);              \
+    allow_lds(k_lproj<DT_, W_, NTB_, F_, Z_, CP_, TB_>, lds);                                            \
+    k_lproj<DT_, W_, NTB_, F_, Z_, CP_, TB_><<<grid, block, lds, s>>>(g, omega, tile_start, gs, U, rn,   \
+                                                                      A, K, M, magic, ntiles, of, fz);   \
   } while (0)
-#define TGRAD_LP(DT_, W_, NTB_, F_, Z_) TGRAD_LP_C(DT_, W_, NTB_, F_, false, 1)
+#define TGRAD_LP(DT_, W_, NTB_, F_) TGRAD_LP_C(DT_, W_, NTB_, F_, false, 1, kTileBatch)
 #define TGRAD_LP_FUSED(DT_, F_)                                                                          \
   do {                                                                                                   \
-    if ((K + 1) / 2 <= kCoefPairsShort) TGRAD_LP_C(DT_, 4, 1, F_, true, kCoefPairsShort);                \
-    else TGRAD_LP_C(DT_, 4, 1, F_, true, kCoefPairs);                                                    \
+    if ((K + 1) / 2 > kCoefPairsShort) TGRAD_LP_C(DT_, 4, 1, F_, true, kCoefPairs, kTileBatch);          \
+    else if (tb == 5) TGRAD_LP_C(DT_, 4, 1, F_, true, kCoefPairsShort, 5);                               \
+    else TGRAD_LP_C(DT_, 4, 1, F_, true, kCoefPairsShort, 9);                                            \
   } while (0)
 #define TGRAD_LP_F(DT_, W_, NTB_)                                                                        \
   do {                                                                                                   \
-    if (K & 1) TGRAD_LP(DT_, W_, NTB_, true, false); else TGRAD_LP(DT_, W_, NTB_, false, false);         \
+    if (K & 1) TGRAD_LP(DT_, W_, NTB_, true); else TGRAD_LP(DT_, W_, NTB_, false);                       \
+  } while (0)
+#define TGRAD_LP_F4(DT_, NTB_)   /* 4 wavefronts: also the variants for narrow last modes */              \
+  do {                                                                                                   \
+    if (tb == kTileBatch) TGRAD_LP_F(DT_, 4, NTB_);                                                      \
+    else if (tb == 9) { if (K & 1) TGRAD_LP_C(DT_, 4, NTB_, true, false, 1, 9); else TGRAD_LP_C(DT_, 4, NTB_, false, false, 1, 9); } \
+    else { if (K & 1) TGRAD_LP_C(DT_, 4, NTB_, true, false, 1, 5); else TGRAD_LP_C(DT_, 4, NTB_, false, false, 1, 5); } \
   } while (0)
 #define TGRAD_LP_W(DT_, NTB_)                                                                            \
   do {                                                                                                   \
-    if (W == 4) TGRAD_LP_F(DT_, 4, NTB_); else if (W == 2) TGRAD_LP_F(DT_, 2, NTB_); else TGRAD_LP_F(DT_, 1, NTB_); \
+    if (W == 4) TGRAD_LP_F4(DT_, NTB_); else if (W == 2) TGRAD_LP_F(DT_, 2, NTB_); else TGRAD_LP_F(DT_, 1, NTB_); \
   } while (0)
   if (fuse) {                                   // the host only fuses with W == 4 and one column tile
     if (dtype == TGRAD_C64) {
@@ -1541,6 +1554,7 @@ void launch_lproj(hipStream_t s, const void* g, int dtype, const int32_t* omega,
   } else {
     if (ntb == 2) TGRAD_LP_W(TGRAD_CBF16, 2); else TGRAD_LP_W(TGRAD_CBF16, 1);
   }
+#undef TGRAD_LP_F4
 #undef TGRAD_LP_W
 #undef TGRAD_LP_F
 #undef TGRAD_LP_FUSED
