@@ -26,7 +26,10 @@
 //   lane l supplies A[l % 32][l / 32] and B[l / 32][l % 32];
 //   register r of lane l receives D[(r % 4) + 8 (r / 4) + 4 (l / 32)][l % 32].
 #include <cstdlib>
+#include <map>
+#include <mutex>
 #include <type_traits>
+#include <utility>
 
 #include "device_common.h"
 
@@ -809,7 +812,8 @@ __device__ __forceinline__ void sparse_adam_entry(const SparseAdam& sp, uint32_t
   sD[2 * e + 1] += d * mm.y;
 }
 
-constexpr int kUpdPrefetch = 17;          // 16-byte pieces of W per lane kept in flight during the MFMA phase
+constexpr int kUpdPrefetch = 17;          // complex64 pairs of W per lane kept in flight during the MFMA phase (the
+                                          // most; narrower last modes use 9 or 5: a tile of M-wide rows has M / 4)
 
 // float32 -> bf16 bit pattern, round to nearest, ties to even (NaN stays a quiet NaN).
 __device__ __forceinline__ uint32_t bf16_rne(float f) {
@@ -828,7 +832,6 @@ template <int WDT> struct WStore;
 template <> struct WStore<TGRAD_C64> {
   typedef float4 raw;
   static constexpr int kElems = 2;
-  static constexpr int kPrefetch = kUpdPrefetch;
   static __device__ __forceinline__ raw* tile(void* w, int64_t w_base) {
     return reinterpret_cast<raw*>(reinterpret_cast<float*>(w) + 2 * w_base);
   }
@@ -845,7 +848,6 @@ template <> struct WStore<TGRAD_C64> {
 template <> struct WStore<TGRAD_CBF16> {
   typedef uint4 raw;
   static constexpr int kElems = 4;
-  static constexpr int kPrefetch = (kUpdPrefetch + 1) / 2;
   static __device__ __forceinline__ raw* tile(void* w, int64_t w_base) {
     return reinterpret_cast<raw*>(reinterpret_cast<uint32_t*>(w) + w_base);
   }
@@ -865,13 +867,14 @@ template <> struct WStore<TGRAD_CBF16> {
 };
 __device__ __forceinline__ void claim_raw(uint4& r) { asm volatile("" : "+v"(r.x), "+v"(r.y), "+v"(r.z), "+v"(r.w)); }
 
-template <int WDT, int W, int NTB, int JT>
+template <int WDT, int W, int NTB, int JT, int UP>
 __global__ __launch_bounds__(64 * W, 2) void k_lupdate(const float* __restrict__ z,
                                                        const float2* __restrict__ U, int64_t A, int K,
                                                        int M, int64_t ntiles, void* __restrict__ w,
                                                        float decay, float c_alpha, SparseAdam sp) {
   typedef WStore<WDT> WS;
   typedef typename WS::raw wraw;
+  constexpr int kPre = WS::kElems == 2 ? UP : (UP + 1) / 2;   // 16-byte pieces of the W tile per lane in flight
   constexpr int T = 64 * W;
   extern __shared__ float smem[];
   const int N2 = 2 * M;
@@ -964,9 +967,9 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate(const float* __restrict__
         nnj1 = sp.tile_start[nn + 1 + vzero];
       }
     }
-    wraw wpre[WS::kPrefetch];                                  // unconditional loads, clamped onto the last
+    wraw wpre[kPre];                                  // unconditional loads, clamped onto the last
 #pragma unroll                                                 // piece (the host keeps n4 >= 1 for every tile)
-    for (int i = 0; i < WS::kPrefetch; ++i) {
+    for (int i = 0; i < kPre; ++i) {
       const int q = lane_now + i * 64;
       wpre[i] = w4[q < n4 ? q : n4 - 1];
     }
@@ -1027,14 +1030,14 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate(const float* __restrict__
     // ---- stream the tile into W ----
     claim_small();
 #pragma unroll
-    for (int i = 0; i < WS::kPrefetch; ++i) claim_raw(wpre[i]);
+    for (int i = 0; i < kPre; ++i) claim_raw(wpre[i]);
     const int nfull = n4 >> 6;                                 // pieces every lane owns: no per-lane branch
 #pragma unroll
-    for (int i = 0; i < WS::kPrefetch; ++i) {
+    for (int i = 0; i < kPre; ++i) {
       const int q = lane_now + i * 64;
       if (i < nfull || q < n4) w4[q] = WS::apply(wpre[i], sD, q, decay);
     }
-    for (int q = lane + WS::kPrefetch * 64; q < n4; q += 64) w4[q] = WS::apply(w4[q], sD, q, decay);
+    for (int q = lane + kPre * 64; q < n4; q += 64) w4[q] = WS::apply(w4[q], sD, q, decay);
     {                                                          // elements past the last whole piece
       const int e = n4 * WS::kElems + lane;
       if (e < n_w) WS::apply_one(w, w_base + e, sD + 2 * e, decay);
@@ -1067,13 +1070,14 @@ struct FusedPrev {
   int K2;               // rank of mode N-1
 };
 
-template <int WDT, int W, int NTB, int JT2>
+template <int WDT, int W, int NTB, int JT2, int UP>
 __global__ __launch_bounds__(64 * W, 2) void k_lupdate_fused(const float2* __restrict__ U, int64_t A, int K,
                                                              int M, int64_t ntiles, void* __restrict__ w,
                                                              float decay, float c_alpha, SparseAdam sp,
                                                              FusedPrev fz) {
   typedef WStore<WDT> WS;
   typedef typename WS::raw wraw;
+  constexpr int kPre = WS::kElems == 2 ? UP : (UP + 1) / 2;   // 16-byte pieces of the W tile per lane in flight
   constexpr int T = 64 * W;
   extern __shared__ float smem[];
   const int N2 = 2 * M;
@@ -1179,9 +1183,9 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate_fused(const float2* __res
       }
     }
     // ---- this tile's W pieces go in flight ----
-    wraw wpre[WS::kPrefetch];
+    wraw wpre[kPre];
 #pragma unroll
-    for (int i = 0; i < WS::kPrefetch; ++i) {
+    for (int i = 0; i < kPre; ++i) {
       const int q = lane_now + i * 64;
       wpre[i] = w4[q < n4 ? q : n4 - 1];
     }
@@ -1293,14 +1297,14 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate_fused(const float2* __res
     // ---- the wait point for everything still in flight, then stream the tile into W ----
     claim_sparse();
 #pragma unroll
-    for (int i = 0; i < WS::kPrefetch; ++i) claim_raw(wpre[i]);
+    for (int i = 0; i < kPre; ++i) claim_raw(wpre[i]);
     const int nfull = n4 >> 6;
 #pragma unroll
-    for (int i = 0; i < WS::kPrefetch; ++i) {
+    for (int i = 0; i < kPre; ++i) {
       const int q = lane_now + i * 64;
       if (i < nfull || q < n4) w4[q] = WS::apply(wpre[i], sD, q, decay);
     }
-    for (int q = lane + WS::kPrefetch * 64; q < n4; q += 64) w4[q] = WS::apply(w4[q], sD, q, decay);
+    for (int q = lane + kPre * 64; q < n4; q += 64) w4[q] = WS::apply(w4[q], sD, q, decay);
     if (!have_next) break;
     tile = nxt;
     slab = nslab;
@@ -1354,6 +1358,24 @@ bool allow_lds(Kern kern, size_t bytes) {
   if (bytes <= 48 * 1024) return true;
   return hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                              (int)bytes) == hipSuccess;
+}
+
+// Workgroups of `kern` that are resident on one compute unit at a time (registers, LDS), asked of
+// the runtime once per kernel and LDS size.  The tile loops are persistent (stride = grid size), so
+// the grid is exactly one resident set: more workgroups would run as a ragged second round.
+template <typename Kern>
+int resident_blocks(Kern kern, int threads, size_t lds) {
+  static std::mutex mu;
+  static std::map<std::pair<const void*, size_t>, int> cache;
+  const std::pair<const void*, size_t> key(reinterpret_cast<const void*>(kern), lds);
+  std::lock_guard<std::mutex> lock(mu);
+  auto it = cache.find(key);
+  if (it != cache.end()) return it->second;
+  int nb = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kern, threads, lds) != hipSuccess || nb < 1) nb = 1;
+  if (nb > 4) nb = 4;
+  cache[key] = nb;
+  return nb;
 }
 
 int grid_for_tiles(int64_t ntiles, int blocks_per_cu) {
@@ -1507,18 +1529,15 @@ void launch_lproj(hipStream_t s, const void* g, int dtype, const int32_t* omega,
   const int S = fuse ? fused_I2 / kTileRows : 1;
   const int64_t nslabs = (ntiles + S - 1) / S;
   const int tb = (K + 3) / 4 <= 5 ? 5 : (K + 3) / 4 <= 9 ? 9 : kTileBatch;   // pieces per lane a tile needs (capped)
-  // workgroups per compute unit: LDS allows lds-many; the wide-tile variants fill the register file
-  // with 2 wavefronts per SIMD, the narrow ones leave room for up to 4
-  const int per_cu_lds = (int)(kLdsLimit / (lds ? lds : 1));
-  const int per_cu_cap = (W == 4 && tb < kTileBatch) ? 4 : 2;
-  const int per_cu = per_cu_lds < 1 ? 1 : per_cu_lds > per_cu_cap ? per_cu_cap : per_cu_lds;
-  dim3 grid((unsigned)grid_for_tiles((nslabs + W - 1) / W, per_cu)), block(64 * W);
+  const int64_t ngroups = (nslabs + W - 1) / W;                // workgroups' worth of tile sequences
+  dim3 grid(1), block(64 * W);
   float* of = reinterpret_cast<float*>(out);
   const uint32_t magic = magic_for(K);
   FusedNext fz{fpad, of, S, fused_M2};
 #define TGRAD_LP_C(DT_, W_, NTB_, F_, Z_, CP_, TB_)                                                      \
   do {                                                                                                   \
     allow_lds(k_lproj<DT_, W_, NTB_, F_, Z_, CP_, TB_>, lds);                                            \
+    grid.x = (unsigned)grid_for_tiles(ngroups, resident_blocks(k_lproj<DT_, W_, NTB_, F_, Z_, CP_, TB_>, 64 * W_, lds)); \
     k_lproj<DT_, W_, NTB_, F_, Z_, CP_, TB_><<<grid, block, lds, s>>>(g, omega, tile_start, gs, U, rn,   \
                                                                       A, K, M, magic, ntiles, of, fz);   \
   } while (0)
@@ -1571,20 +1590,29 @@ void launch_lupdate(hipStream_t s, const float2* z, const float2* U, const Stage
   if (A * M <= 0) return;
   const int64_t ntiles = (A + kTileRows - 1) / kTileRows;
   const size_t lds = lupdate_lds_bytes(W, K, M);
-  const int per_cu = (int)(kLdsLimit / (lds ? lds : 1));
-  dim3 grid((unsigned)grid_for_tiles((ntiles + W - 1) / W, per_cu < 1 ? 1 : per_cu > 2 ? 2 : per_cu)), block(64 * W);
+  const int64_t ngroups = (ntiles + W - 1) / W;
+  dim3 grid(1), block(64 * W);
   SparseAdam sp{omega, tile_start, gs, ms, vs, beta1, beta2, inv_c1, inv_c2, eps, c_lambda, 0};
   const float* zf = reinterpret_cast<const float*>(z);
   const int jt = lupdate_jt(K);
-#define TGRAD_LU(W_, JT_)                                                                                \
+  const int up = (M + 3) / 4 <= 5 ? 5 : (M + 3) / 4 <= 9 ? 9 : kUpdPrefetch;
+#define TGRAD_LU_U(W_, JT_, UP_)                                                                         \
   do {                                                                                                   \
     if (wdtype == TGRAD_C64) {                                                                           \
-      allow_lds(k_lupdate<TGRAD_C64, W_, 2, JT_>, lds);                                                  \
-      k_lupdate<TGRAD_C64, W_, 2, JT_><<<grid, block, lds, s>>>(zf, U, A, K, M, ntiles, w, decay, c_alpha, sp); \
+      allow_lds(k_lupdate<TGRAD_C64, W_, 2, JT_, UP_>, lds);   \
+      grid.x = (unsigned)grid_for_tiles(ngroups, resident_blocks(k_lupdate<TGRAD_C64, W_, 2, JT_, UP_>, 64 * W_, lds));                                             \
+      k_lupdate<TGRAD_C64, W_, 2, JT_, UP_><<<grid, block, lds, s>>>(zf, U, A, K, M, ntiles, w, decay, c_alpha, sp); \
     } else {                                                                                             \
-      allow_lds(k_lupdate<TGRAD_CBF16, W_, 2, JT_>, lds);                                                \
-      k_lupdate<TGRAD_CBF16, W_, 2, JT_><<<grid, block, lds, s>>>(zf, U, A, K, M, ntiles, w, decay, c_alpha, sp); \
+      allow_lds(k_lupdate<TGRAD_CBF16, W_, 2, JT_, UP_>, lds);   \
+      grid.x = (unsigned)grid_for_tiles(ngroups, resident_blocks(k_lupdate<TGRAD_CBF16, W_, 2, JT_, UP_>, 64 * W_, lds));                                           \
+      k_lupdate<TGRAD_CBF16, W_, 2, JT_, UP_><<<grid, block, lds, s>>>(zf, U, A, K, M, ntiles, w, decay, c_alpha, sp); \
     }                                                                                                    \
+  } while (0)
+#define TGRAD_LU(W_, JT_)        /* 4 wavefronts: also the variants for narrow last modes */              \
+  do {                                                                                                   \
+    if (W_ == 4 && up == 5) TGRAD_LU_U(4, JT_, 5);                                                       \
+    else if (W_ == 4 && up == 9) TGRAD_LU_U(4, JT_, 9);                                                  \
+    else TGRAD_LU_U(W_, JT_, kUpdPrefetch);                                                              \
   } while (0)
 #define TGRAD_LU_J(W_)                                                                                   \
   do {                                                                                                   \
@@ -1592,6 +1620,7 @@ void launch_lupdate(hipStream_t s, const float2* z, const float2* U, const Stage
     else if (jt == 8) TGRAD_LU(W_, 8); else TGRAD_LU(W_, 16);                                            \
   } while (0)
   if (W == 4) TGRAD_LU_J(4); else if (W == 2) TGRAD_LU_J(2); else TGRAD_LU_J(1);
+#undef TGRAD_LU_U
 #undef TGRAD_LU_J
 #undef TGRAD_LU
 }
@@ -1611,22 +1640,30 @@ void launch_lupdate_fused(hipStream_t s, const float2* y1, const float2* ut, int
   const int64_t nslabs = ntiles / S;
   const int NT = (2 * M + 31) / 32;
   const size_t lds = (size_t)W * ((kTileRows * 2 * M + 3) & ~3) * 4 + (size_t)16 * 16 * NT * 8;
-  const int per_cu = (int)(kLdsLimit / (lds ? lds : 1));
-  dim3 grid((unsigned)grid_for_tiles((nslabs + W - 1) / W, per_cu < 1 ? 1 : per_cu > 2 ? 2 : per_cu)), block(64 * W);
+  const int64_t ngroups = (nslabs + W - 1) / W;
+  dim3 grid(1), block(64 * W);
   SparseAdam sp{omega, tile_start, gs, ms, vs, beta1, beta2, inv_c1, inv_c2, eps, c_lambda,
                 (int)(k > 0 ? k - 1 : 0)};
   FusedPrev fz{y1, ut, S, K2};
-#define TGRAD_LUF(JT2_)                                                                                  \
+  const int up = (M + 3) / 4 <= 5 ? 5 : (M + 3) / 4 <= 9 ? 9 : kUpdPrefetch;
+#define TGRAD_LUF_U(JT2_, UP_)                                                                           \
   do {                                                                                                   \
     if (wdtype == TGRAD_C64) {                                                                           \
-      allow_lds(k_lupdate_fused<TGRAD_C64, W, 1, JT2_>, lds);                                            \
-      k_lupdate_fused<TGRAD_C64, W, 1, JT2_><<<grid, block, lds, s>>>(U, A, K, M, ntiles, w, decay, c_alpha, sp, fz); \
+      allow_lds(k_lupdate_fused<TGRAD_C64, W, 1, JT2_, UP_>, lds);   \
+      grid.x = (unsigned)grid_for_tiles(ngroups, resident_blocks(k_lupdate_fused<TGRAD_C64, W, 1, JT2_, UP_>, 64 * W, lds));                                       \
+      k_lupdate_fused<TGRAD_C64, W, 1, JT2_, UP_><<<grid, block, lds, s>>>(U, A, K, M, ntiles, w, decay, c_alpha, sp, fz); \
     } else {                                                                                             \
-      allow_lds(k_lupdate_fused<TGRAD_CBF16, W, 1, JT2_>, lds);                                          \
-      k_lupdate_fused<TGRAD_CBF16, W, 1, JT2_><<<grid, block, lds, s>>>(U, A, K, M, ntiles, w, decay, c_alpha, sp, fz); \
+      allow_lds(k_lupdate_fused<TGRAD_CBF16, W, 1, JT2_, UP_>, lds);   \
+      grid.x = (unsigned)grid_for_tiles(ngroups, resident_blocks(k_lupdate_fused<TGRAD_CBF16, W, 1, JT2_, UP_>, 64 * W, lds));                                     \
+      k_lupdate_fused<TGRAD_CBF16, W, 1, JT2_, UP_><<<grid, block, lds, s>>>(U, A, K, M, ntiles, w, decay, c_alpha, sp, fz); \
     }                                                                                                    \
   } while (0)
+#define TGRAD_LUF(JT2_)                                                                                  \
+  do {                                                                                                   \
+    if (up == 5) TGRAD_LUF_U(JT2_, 5); else if (up == 9) TGRAD_LUF_U(JT2_, 9); else TGRAD_LUF_U(JT2_, kUpdPrefetch); \
+  } while (0)
   if (K2 <= 8) TGRAD_LUF(4); else if (K2 <= 16) TGRAD_LUF(8); else TGRAD_LUF(16);
+#undef TGRAD_LUF_U
 #undef TGRAD_LUF
 }
 
