@@ -758,6 +758,7 @@ __global__ __launch_bounds__(64 * W, 2) void k_lproj(const void* __restrict__ g,
       }
     };
     if constexpr (FUSE) {
+      __builtin_amdgcn_s_setprio(1);                           // matrix-core phase: ahead of the other wavefront's loads and stores
       block(0, std::integral_constant<int, 1>());              // exactly one column tile (and no loop around the
     } else {                                                   // claim of f2s: a loop preheader would drain all loads)
       int nt0 = 0;
@@ -765,6 +766,7 @@ __global__ __launch_bounds__(64 * W, 2) void k_lproj(const void* __restrict__ g,
       if (NTB > 1)
         for (; nt0 < NT; ++nt0) block(nt0, std::integral_constant<int, 1>());
     }
+    if constexpr (FUSE) __builtin_amdgcn_s_setprio(0);
     if (!have_next) break;
     tile = nxt;
     slab = nslab;
