@@ -168,15 +168,24 @@ __global__ __launch_bounds__(kMidThreads) void k_mid(const float* __restrict__ x
       return in ? make_float2(u.x, PROJECT ? -u.y : u.y) : make_float2(0.f, 0.f);
     });
     __syncthreads();
+    // Row pairs in batches of kMidUnroll, the next batch's loads issued before the current batch
+    // goes to the matrix cores (rows past the end are clamped onto the last one and not used).
     int jj = jfirst;
+    V cur[kMidUnroll];
+#pragma unroll
+    for (int u = 0; u < kMidUnroll; ++u) cur[u] = load_pair_row(jc0 + jj + u * JSTEP);
     for (; jj + (kMidUnroll - 1) * JSTEP < jn; jj += kMidUnroll * JSTEP) {
-      V v[kMidUnroll];
+      V nxt[kMidUnroll];
 #pragma unroll
-      for (int u = 0; u < kMidUnroll; ++u) v[u] = load_pair_row(jc0 + jj + u * JSTEP);
+      for (int u = 0; u < kMidUnroll; ++u) nxt[u] = load_pair_row(jc0 + jj + (kMidUnroll + u) * JSTEP);
 #pragma unroll
-      for (int u = 0; u < kMidUnroll; ++u) mfma_pair_row(v[u], jj + u * JSTEP);
+      for (int u = 0; u < kMidUnroll; ++u) mfma_pair_row(cur[u], jj + u * JSTEP);
+#pragma unroll
+      for (int u = 0; u < kMidUnroll; ++u) cur[u] = nxt[u];
     }
-    for (; jj < jn; jj += JSTEP) mfma_pair_row(load_pair_row(jc0 + jj), jj);
+#pragma unroll
+    for (int u = 0; u < kMidUnroll; ++u)
+      if (jj + u * JSTEP < jn) mfma_pair_row(cur[u], jj + u * JSTEP);
   }
   if constexpr (MODE == 1) {
     // partial tiles of wavefronts 1..3 -> LDS, summed by wavefront 0 in a fixed order
