@@ -155,6 +155,10 @@ __global__ __launch_bounds__(kMidThreads) void k_mid(const float* __restrict__ x
   const int J = (K + 1) >> 1;
   for (int jc0 = 0; jc0 < J; jc0 += kMidJChunk) {
     const int jn = (J - jc0) < kMidJChunk ? (J - jc0) : kMidJChunk;
+    // the chunk's first batch of rows goes in flight before the factor operands are staged
+    V cur[kMidUnroll];
+#pragma unroll
+    for (int u = 0; u < kMidUnroll; ++u) cur[u] = load_pair_row(jc0 + jfirst + u * JSTEP);
     __syncthreads();                                           // previous chunk fully consumed
     stage_batched(sF, jn * TL * 64, tid, kMidThreads, [&](int e) -> float2 {
       const int l = e & 63;
@@ -171,9 +175,6 @@ __global__ __launch_bounds__(kMidThreads) void k_mid(const float* __restrict__ x
     // Row pairs in batches of kMidUnroll, the next batch's loads issued before the current batch
     // goes to the matrix cores (rows past the end are clamped onto the last one and not used).
     int jj = jfirst;
-    V cur[kMidUnroll];
-#pragma unroll
-    for (int u = 0; u < kMidUnroll; ++u) cur[u] = load_pair_row(jc0 + jj + u * JSTEP);
     for (; jj + (kMidUnroll - 1) * JSTEP < jn; jj += kMidUnroll * JSTEP) {
       V nxt[kMidUnroll];
 #pragma unroll
