@@ -511,7 +511,7 @@ constexpr int kCoefPairsShort = 17;       // ... and the variant for short last 
 // re/im swap of Y for the imaginary part of F2 is a swap of neighbouring lanes (DPP).  D2 is
 // stored once per slab; the intermediate tensor between the two stages never exists.
 struct FusedNext {
-  const float2* fpad;   // [32 S][32]: conj(U^(N-1)[i2, m2]) as (re, im), zero for m2 >= M2
+  const float2* fpad;   // conj(U^(N-1)[i2, m2]) as (re, im), zero for m2 >= M2, in operand order (k_pack_fused_factor)
   float* out;           // (slabs, M2, M) complex, row-major
   int S;                // tiles per slab; 1 when nothing is fused
   int M2;
@@ -651,9 +651,13 @@ __global__ __launch_bounds__(64 * W, 2) void k_lproj(const void* __restrict__ g,
     //      the next tile's loads so that waiting for them leaves those in flight ----
     float2 f2s[FUSE ? 16 : 1];
     if constexpr (FUSE) {
-      const float2* fp = fz.fpad + (size_t)(32 * ts + 4 * half) * 32 + col;
+      const float4* fp = reinterpret_cast<const float4*>(fz.fpad) + (size_t)ts * 8 * 64 + lane_now;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) f2s[r] = fp[((r & 3) + 8 * (r >> 2)) * 32];
+      for (int rp = 0; rp < 8; ++rp) {
+        const float4 f = fp[rp * 64];
+        f2s[2 * rp] = make_float2(f.x, f.y);
+        f2s[2 * rp + 1] = make_float2(f.z, f.w);
+      }
     }
     // ---- the staging registers are free: the next tile's loads go in flight right away (its
     //      support range was fetched one tile earlier).  All unconditional: see `issue`. ----
@@ -1333,7 +1337,8 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate_fused(const float2* __res
 }
 
 // Kernel-ready copies of the mode-(N-1) factor for the fused stages:
-//   fpad[i2][m2] = conj(U[i2, m2]) (m2 < r, else 0), 32 columns  -> second compression stage in k_lproj
+//   fpad = conj(U[i2, m2]) (m2 < r, else 0; 32 columns), tile by tile in matrix-core operand order
+//                                                               -> second compression stage in k_lproj
 //   ut[m2][i2]   = U[i2, m2]       (m2 < r, else 0), 32 rows     -> first reconstruction stage in k_lupdate
 __global__ void k_pack_fused_factor(const float2* __restrict__ U, int I2, int r, float2* __restrict__ fpad,
                                     float2* __restrict__ ut) {
@@ -1341,7 +1346,12 @@ __global__ void k_pack_fused_factor(const float2* __restrict__ U, int I2, int r,
   if (e >= I2 * 32) return;
   const int i2 = e >> 5, m2 = e & 31;
   const float2 u = m2 < r ? U[(int64_t)i2 * r + m2] : make_float2(0.f, 0.f);
-  fpad[e] = make_float2(u.x, -u.y);
+  // fpad in the order the second compression stage consumes it: tile ts = i2 / 32, row i2 % 32 =
+  // d_row(rr, half), lane = 32 half + m2; slot [ts][rr / 2][lane][rr % 2], so that a lane fetches the
+  // operands of two accumulator rows with one 16-byte load and a wavefront reads 1 KB contiguous
+  const int ts = i2 >> 5, il = i2 & 31;
+  const int half = (il >> 2) & 1, rr = (il & 3) + 4 * (il >> 3);
+  fpad[(((size_t)ts * 8 + (rr >> 1)) * 64 + 32 * half + m2) * 2 + (rr & 1)] = make_float2(u.x, -u.y);
   ut[(int64_t)m2 * I2 + i2] = u;
 }
 
