@@ -1074,14 +1074,14 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate(const float* __restrict__
 //   stage A   D'[(m3, p), i2] = sum_m2 Y1[m2, m3] U2[i2, m2]            (rows = interleaved (m3, p))
 //             A operand: lane (rho = 2 m3 + p, half) holds Y1[2 jj + half][m3] (parts chosen per p and
 //             per factor part: re(u y) = ur yr - ui yi, im(u y) = ur yi + ui yr),
-//             B operand: U2[i2, 2 jj + half] from the transposed copy `ut` (coalesced over i2);
+//             B operand: U2[i2, 2 jj + half] from the packed copy `ut` (two steps per 16-byte load);
 //   stage B   the accumulator registers of D' ARE the operand rows of the last-mode expansion: in lane
 //             (i2, half) registers (2 u, 2 u + 1) hold (re, im) of element k = (u & 1) + 4 (u >> 1) + 2 half
 //             of row i2, so step (u, part) pairs elements k(u, 0) and k(u, 1) and the coefficient
 //             table is read at those rows.  Everything after that is k_lupdate.
 struct FusedPrev {
   const float2* y1;     // (slabs, K2, K) complex: input of the fused stage
-  const float2* ut;     // [32][32 S]: ut[m2][i2] = U^(N-1)[i2, m2], zero for m2 >= K2
+  const float2* ut;     // U^(N-1)[i2, m2], zero for m2 >= K2, in operand order (k_pack_fused_factor)
   int S;                // tiles per slab
   int K2;               // rank of mode N-1
 };
@@ -1188,14 +1188,19 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate_fused(const float2* __res
       const bool first = ts == 0;
       const int m3 = (col >> 1) < K ? (col >> 1) : K - 1;
       const float2* yp = fz.y1 + (first ? (size_t)slab * fz.K2 * K + m3 : (size_t)0);
-      const float2* up = fz.ut + (size_t)half * I2 + 32 * ts + col;
 #pragma unroll
       for (int jj = 0; jj < JT2; ++jj) {
         const int m2 = 2 * jj + half;
         const float2 v = yp[first ? (size_t)(m2 < fz.K2 ? m2 : fz.K2 - 1) * K : (size_t)0];
         y1[jj].x = first ? v.x : y1[jj].x;
         y1[jj].y = first ? v.y : y1[jj].y;
-        u2[jj] = up[(size_t)(2 * jj) * I2];
+      }
+      const float4* up = reinterpret_cast<const float4*>(fz.ut) + (size_t)ts * 8 * 64 + lane_now;
+#pragma unroll
+      for (int jp = 0; jp < JT2 / 2; ++jp) {                   // two operand rows per 16-byte load
+        const float4 f = up[jp * 64];
+        u2[2 * jp] = make_float2(f.x, f.y);
+        u2[2 * jp + 1] = make_float2(f.z, f.w);
       }
     }
     // ---- this tile's W pieces go in flight ----
@@ -1339,7 +1344,8 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate_fused(const float2* __res
 // Kernel-ready copies of the mode-(N-1) factor for the fused stages:
 //   fpad = conj(U[i2, m2]) (m2 < r, else 0; 32 columns), tile by tile in matrix-core operand order
 //                                                               -> second compression stage in k_lproj
-//   ut[m2][i2]   = U[i2, m2]       (m2 < r, else 0), 32 rows     -> first reconstruction stage in k_lupdate
+//   ut   = U[i2, m2] (m2 < r, else 0; 32 columns), tile by tile in matrix-core operand order
+//                                                               -> first reconstruction stage in k_lupdate_fused
 __global__ void k_pack_fused_factor(const float2* __restrict__ U, int I2, int r, float2* __restrict__ fpad,
                                     float2* __restrict__ ut) {
   const int e = blockIdx.x * blockDim.x + threadIdx.x;
@@ -1352,7 +1358,10 @@ __global__ void k_pack_fused_factor(const float2* __restrict__ U, int I2, int r,
   const int ts = i2 >> 5, il = i2 & 31;
   const int half = (il >> 2) & 1, rr = (il & 3) + 4 * (il >> 3);
   fpad[(((size_t)ts * 8 + (rr >> 1)) * 64 + 32 * half + m2) * 2 + (rr & 1)] = make_float2(u.x, -u.y);
-  ut[(int64_t)m2 * I2 + i2] = u;
+  // ut in the order the first reconstruction stage consumes it: step jj = m2 / 2 of the lane
+  // (i2 % 32, m2 % 2); slot [ts][jj / 2][lane][jj % 2]
+  const int jj = m2 >> 1;
+  ut[(((size_t)ts * 8 + (jj >> 1)) * 64 + 32 * (m2 & 1) + il) * 2 + (jj & 1)] = u;
 }
 
 // tile_start[t] = #{ j : Omega_j < t * tile_elems }, t = 0 .. ntiles (Omega ascending).
