@@ -487,22 +487,68 @@ __global__ __launch_bounds__(kEigThreads) void k_eig_tri(EigJobs jobs) {
   const double eps2 = 4.93e-32;
   const int m = n + (n & 1);
   const int half = m / 2;
-  const int nblocks = half * (half + 1) / 2;
-  // The blocks (pair a, pair b), a >= b, a thread updates in every round: e = tid, tid + 1024, ...
-  // (at most 3 for 64 pairs); decoded once, packed as a << 8 | b, -1 = none.
-  constexpr int kBlocksPerThread = (kEigTriMaxN / 2) * (kEigTriMaxN / 2 + 1) / 2 / kEigThreads + 1;
+  const int nblocks = half * (half - 1) / 2;
+  // The off-pivot blocks (pair a, pair b), a > b, a thread updates in every round: e = tid, tid + 1024
+  // (2016 blocks for 64 pairs: two per thread); decoded once, packed as a << 8 | b, -1 = none.  The
+  // pivot block (a, a) is updated by the thread that computes its rotation.
+  constexpr int kBlocksPerThread = (kEigTriMaxN / 2) * (kEigTriMaxN / 2 - 1) / 2 / kEigThreads + 1;
   int my_ab[kBlocksPerThread];
 #pragma unroll
   for (int u = 0; u < kBlocksPerThread; ++u) {
     const int e = tid + u * kEigThreads;
     my_ab[u] = -1;
     if (e < nblocks) {
-      int a = (int)((sqrtf(8.f * (float)e + 1.f) - 1.f) * 0.5f);
-      while (a * (a + 1) / 2 > e) --a;
-      while ((a + 1) * (a + 2) / 2 <= e) ++a;
-      my_ab[u] = (a << 8) | (e - a * (a + 1) / 2);
+      int a = (int)((sqrtf(8.f * (float)e + 1.f) + 1.f) * 0.5f);
+      while (a * (a - 1) / 2 > e) --a;
+      while ((a + 1) * a / 2 <= e) ++a;
+      my_ab[u] = (a << 8) | (e - a * (a - 1) / 2);
     }
   }
+  // B <- L_a B R_b for the 2 x 2 block (rows p_a, q_a; columns p_b, q_b), L = [[c, -s], [conj(s), c]],
+  // R = [[c, s], [-conj(s), c]]; a == b: the pivot block, of which the lower triangle is kept
+  auto update_block = [&](int a, int b) {
+    const int pa = sp[a], qa = sq[a], pb = sp[b], qb = sq[b];
+    const bool qa_ok = qa < n, qb_ok = qb < n;         // padding player of an odd n: no such row / column
+    const double ca = sc[a], cb = sc[b];
+    const double2 sa = ss[a], sb = ss[b];
+    const double2 zero = make_double2(0., 0.);
+    double2 b00 = tri_get(T, pa, pb);
+    double2 b01 = qb_ok ? tri_get(T, pa, qb) : zero;
+    double2 b10 = qa_ok ? tri_get(T, qa, pb) : zero;
+    double2 b11 = (qa_ok && qb_ok) ? tri_get(T, qa, qb) : zero;
+    // rows: [r_p; r_q] <- [c r_p - s r_q; conj(s) r_p + c r_q]
+    {
+      const double2 t00 = cmuld(sa, b10), t01 = cmuld(sa, b11);
+      const double2 u00 = cmuld(conjd(sa), b00), u01 = cmuld(conjd(sa), b01);
+      const double2 n00 = make_double2(ca * b00.x - t00.x, ca * b00.y - t00.y);
+      const double2 n01 = make_double2(ca * b01.x - t01.x, ca * b01.y - t01.y);
+      const double2 n10 = make_double2(u00.x + ca * b10.x, u00.y + ca * b10.y);
+      const double2 n11 = make_double2(u01.x + ca * b11.x, u01.y + ca * b11.y);
+      b00 = n00; b01 = n01; b10 = n10; b11 = n11;
+    }
+    // columns: [x_p, x_q] <- [c x_p - conj(s) x_q, s x_p + c x_q]
+    {
+      const double2 t00 = cmuld(conjd(sb), b01), t10 = cmuld(conjd(sb), b11);
+      const double2 u00 = cmuld(sb, b00), u10 = cmuld(sb, b10);
+      const double2 n00 = make_double2(cb * b00.x - t00.x, cb * b00.y - t00.y);
+      const double2 n10 = make_double2(cb * b10.x - t10.x, cb * b10.y - t10.y);
+      const double2 n01 = make_double2(u00.x + cb * b01.x, u00.y + cb * b01.y);
+      const double2 n11 = make_double2(u10.x + cb * b11.x, u10.y + cb * b11.y);
+      b00 = n00; b01 = n01; b10 = n10; b11 = n11;
+    }
+    if (a == b) {
+      T[tri_idx(pa, pa)] = b00;
+      if (qa_ok) {
+        T[tri_idx(qa, qa)] = b11;
+        T[tri_idx(qa, pa)] = b10;
+      }
+    } else {
+      tri_put(T, pa, pb, b00);
+      if (qb_ok) tri_put(T, pa, qb, b01);
+      if (qa_ok) tri_put(T, qa, pb, b10);
+      if (qa_ok && qb_ok) tri_put(T, qa, qb, b11);
+    }
+  };
 
   for (int sweep = 0; sweep < kEigMaxSweeps; ++sweep) {
     if (tid == 0) nrot = 0;
@@ -538,55 +584,14 @@ __global__ __launch_bounds__(kEigThreads) void k_eig_tri(EigJobs jobs) {
         rlog[(size_t)nlogged * half + tid] = e;
       }
       ++nlogged;
-      // ---- phase 2b: every block (pair a, pair b), a >= b:  B <- L_a B R_b  with
-      //      L = [[c, -s], [conj(s), c]] on the rows (p_a, q_a), R = [[c, s], [-conj(s), c]] on the
-      //      columns (p_b, q_b) ----
+      // ---- phase 2b: every block (pair a, pair b), a >= b:  B <- L_a B R_b ----
+      if (tid < half && srot[tid]) update_block(tid, tid);   // own pivot block (nobody else touches it)
 #pragma unroll
       for (int u = 0; u < kBlocksPerThread; ++u) {
         if (my_ab[u] < 0) continue;
         const int a = my_ab[u] >> 8, b = my_ab[u] & 255;
         if (!srot[a] && !srot[b]) continue;
-        const int pa = sp[a], qa = sq[a], pb = sp[b], qb = sq[b];
-        const bool qa_ok = qa < n, qb_ok = qb < n;     // padding player of an odd n: no such row / column
-        const double ca = sc[a], cb = sc[b];
-        const double2 sa = ss[a], sb = ss[b];
-        const double2 zero = make_double2(0., 0.);
-        double2 b00 = tri_get(T, pa, pb);
-        double2 b01 = qb_ok ? tri_get(T, pa, qb) : zero;
-        double2 b10 = qa_ok ? tri_get(T, qa, pb) : zero;
-        double2 b11 = (qa_ok && qb_ok) ? tri_get(T, qa, qb) : zero;
-        // rows: [r_p; r_q] <- [c r_p - s r_q; conj(s) r_p + c r_q]
-        {
-          const double2 t00 = cmuld(sa, b10), t01 = cmuld(sa, b11);
-          const double2 u00 = cmuld(conjd(sa), b00), u01 = cmuld(conjd(sa), b01);
-          const double2 n00 = make_double2(ca * b00.x - t00.x, ca * b00.y - t00.y);
-          const double2 n01 = make_double2(ca * b01.x - t01.x, ca * b01.y - t01.y);
-          const double2 n10 = make_double2(u00.x + ca * b10.x, u00.y + ca * b10.y);
-          const double2 n11 = make_double2(u01.x + ca * b11.x, u01.y + ca * b11.y);
-          b00 = n00; b01 = n01; b10 = n10; b11 = n11;
-        }
-        // columns: [x_p, x_q] <- [c x_p - conj(s) x_q, s x_p + c x_q]
-        {
-          const double2 t00 = cmuld(conjd(sb), b01), t10 = cmuld(conjd(sb), b11);
-          const double2 u00 = cmuld(sb, b00), u10 = cmuld(sb, b10);
-          const double2 n00 = make_double2(cb * b00.x - t00.x, cb * b00.y - t00.y);
-          const double2 n10 = make_double2(cb * b10.x - t10.x, cb * b10.y - t10.y);
-          const double2 n01 = make_double2(u00.x + cb * b01.x, u00.y + cb * b01.y);
-          const double2 n11 = make_double2(u10.x + cb * b11.x, u10.y + cb * b11.y);
-          b00 = n00; b01 = n01; b10 = n10; b11 = n11;
-        }
-        if (a == b) {                                  // pivot block: keep its lower triangle
-          T[tri_idx(pa, pa)] = b00;
-          if (qa_ok) {
-            T[tri_idx(qa, qa)] = b11;
-            T[tri_idx(qa, pa)] = b10;
-          }
-        } else {
-          tri_put(T, pa, pb, b00);
-          if (qb_ok) tri_put(T, pa, qb, b01);
-          if (qa_ok) tri_put(T, qa, pb, b10);
-          if (qa_ok && qb_ok) tri_put(T, qa, qb, b11);
-        }
+        update_block(a, b);
       }
       __syncthreads();
     }
