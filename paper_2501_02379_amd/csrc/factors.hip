@@ -287,12 +287,14 @@ __device__ __forceinline__ bool jacobi_rotation(double app, double aqq, double2 
   s = make_double2(0., 0.);
   const double mag2 = apq.x * apq.x + apq.y * apq.y;
   if (!(mag2 > eps2 * fabs(app * aqq) && mag2 > floor2)) return false;
-  const double mag = sqrt(mag2);
-  const double tau = (aqq - app) / (2. * mag);
+  // two reciprocal square roots, one square root and one division (the threads that compute the
+  // rotations are the critical path of a round: every other wavefront waits for them)
+  const double inv_mag = rsqrt(mag2);
+  const double tau = 0.5 * (aqq - app) * inv_mag;
   const double t = (tau >= 0. ? 1. : -1.) / (fabs(tau) + sqrt(1. + tau * tau));
-  c = 1. / sqrt(1. + t * t);
-  const double sn = t * c;
-  s = make_double2(sn * apq.x / mag, sn * apq.y / mag);
+  c = rsqrt(1. + t * t);
+  const double sn = t * c * inv_mag;
+  s = make_double2(sn * apq.x, sn * apq.y);
   return true;
 }
 
