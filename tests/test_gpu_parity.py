@@ -391,6 +391,22 @@ def test_cfg1_ten_steps_end_to_end():
     assert rel_err(info["W_gpu"] - W0, info["W_oracle"] - W0) < DW_TOL
 
 
+def test_cfg1_sixty_steps_no_drift():
+    """Six times the protocol's length, twelve refreshes: the difference to the oracle stays at the
+    float32 rounding level instead of growing with the step count."""
+    w = synth.WORKLOADS["cfg1"]
+    _announce("cfg1, 60 steps")
+    info, W0 = _end_to_end(w, 60)
+    assert all(info["omega_equal"]) and len(info["omega_equal"]) == 12
+    assert max(max(d) for d in info["proj_dist"]) < PROJ_TOL
+    assert rel_err(info["W_gpu"], info["W_oracle"]) < W_TOL
+    assert rel_err(info["W_gpu"] - W0, info["W_oracle"] - W0) < DW_TOL
+    st, ctx = info["state"], info["ctx"]
+    assert rel_err(ctx.tgrad_get_state(T.STATE_CORE_V), st.V_L) < 1e-4
+    assert rel_err(ctx.tgrad_get_state(T.STATE_SPARSE_V), st.V_S) < 1e-4
+    assert ctx.t == 60
+
+
 def test_cfg1_rescaled_gradients():
     """Gradients of order 1e-4 (the paper notes moments of order 1e-5)."""
     w = synth.WORKLOADS["cfg1"]
