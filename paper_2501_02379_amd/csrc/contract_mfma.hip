@@ -438,6 +438,14 @@ __device__ __forceinline__ void wave_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// Zero in a vector register that the compiler can neither fold nor prove uniform: an index built
+// with it is loaded per lane (vector memory), not through the scalar cache.
+__device__ __forceinline__ int opaque_zero() {
+  int z = 0;
+  asm volatile("" : "+v"(z));
+  return z;
+}
+
 // Factor table in LDS: sF[k * ld + m] = scale * F[m, k] as (fr, fi), ld = 16 NT, zero for k >= K
 // or m >= M.  PROJECT: F[m, k] = conj(U[k, m]); otherwise F[m, k] = U[m, k].
 template <bool PROJECT>
@@ -603,7 +611,7 @@ __global__ __launch_bounds__(64 * W, 2) void k_lproj(const void* __restrict__ g,
 
   // The support ranges are fetched with per-lane (vector) loads on purpose: a scalar load shares
   // its wait counter with the LDS reads of the matrix-core phase and would stall its first step.
-  const int vzero = tid >> 30;                                 // 0, but not known to be uniform
+  const int vzero = opaque_zero();
   int64_t tile = slab * S;
   int64_t nslab = slab;
   int nts = ts;
@@ -796,6 +804,278 @@ __global__ __launch_bounds__(64 * W, 2) void k_lproj(const void* __restrict__ g,
   }
 }
 
+// -------------------------------------------------------------------------------------------
+// k_lproj_flat: k_lproj<.., FUSE> for odd last extents (the LDS image of a tile is its memory image),
+// written so that everything a wavefront does OUTSIDE its matrix-core phase is scalar, LDS or
+// vector-memory work with loop-invariant vector registers.  fp32 MFMA instructions run on the SIMD's
+// vector ALU: while one wavefront of a SIMD is in its matrix-core phase, a vector-ALU instruction of
+// the other one does not issue, so address arithmetic, clamps and lane masks in the staging phase
+// serialise the two wavefronts instead of overlapping them.  Here
+//  - the tile is fetched with buffer loads: the descriptor (scalar registers) carries the tile's
+//    base and size, lanes past the tile's end read zero without touching memory, and the lane's
+//    offset is one invariant register;
+//  - every lane commits what it loaded (the slice has room for TB x 64 pieces; the host picks TB so
+//    that they cover the tile: TB x 64 >= 16 K), so no lane masks;
+//  - support ranges, factor operands and results go through scalar bases + invariant lane offsets.
+// Same tile sequence and the same arithmetic, in the same order, as k_lproj<.., FUSE>.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t raw_buffer(const void* base, uint32_t bytes) {
+  // untyped buffer, stride 0: an access at offset >= bytes returns zero (loads) or is dropped (stores)
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), (short)0, (int)bytes, 0x00020000);
+}
+// Two consecutive gradient elements as a buffer load returns them (one register tuple), and their
+// float32 image in LDS.
+template <int DT> struct BufPair;
+template <> struct BufPair<TGRAD_C64> {
+  typedef u32x4 type;
+  static __device__ __forceinline__ type load(__amdgpu_buffer_rsrc_t r, int voff) {
+    return __builtin_amdgcn_raw_buffer_load_b128(r, voff, 0, 0);
+  }
+  static __device__ __forceinline__ void commit(float* dst, const type& v) { *reinterpret_cast<type*>(dst) = v; }
+};
+template <> struct BufPair<TGRAD_CBF16> {
+  typedef u32x2 type;
+  static __device__ __forceinline__ type load(__amdgpu_buffer_rsrc_t r, int voff) {
+    return __builtin_amdgcn_raw_buffer_load_b64(r, voff, 0, 0);
+  }
+  static __device__ __forceinline__ void commit(float* dst, const type& v) {   // a bf16 is the upper half of a float32
+    u32x4 w;
+    w.x = v.x << 16;
+    w.y = v.x & 0xFFFF0000u;
+    w.z = v.y << 16;
+    w.w = v.y & 0xFFFF0000u;
+    *reinterpret_cast<u32x4*>(dst) = w;
+  }
+};
+
+// floats of LDS per wavefront: the tile (32 rows of K complex + one pad pair for the row pair past
+// an odd K) or, if larger, what TB x 64 committed pieces cover; a multiple of 4 (16-byte writes)
+__host__ __device__ inline int lproj_flat_slice(int K, int TB) {
+  const int tile = kTileRows * 2 * K + 2, staged = TB * 64 * 4;
+  return ((tile > staged ? tile : staged) + 3) & ~3;
+}
+
+template <int DT, int CP, int TB>
+__global__ __launch_bounds__(256, 2) void k_lproj_flat(const void* __restrict__ g,
+                                                       const int32_t* __restrict__ omega,
+                                                       const uint32_t* __restrict__ tile_start,
+                                                       float2* __restrict__ gs, const float2* __restrict__ U,
+                                                       int rn, int64_t A, int K, int M, int64_t ntiles,
+                                                       FusedNext fz) {
+  typedef typename BufPair<DT>::type Raw;
+  constexpr int W = 4, T = 64 * W;
+  constexpr int kPiece = (int)sizeof(Raw);                     // bytes of G per lane and load (2 elements)
+  extern __shared__ float smem[];
+  const int stride = 2 * K;                                    // floats per LDS row; K is odd
+  const int slice = lproj_flat_slice(K, TB);
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  float* sX = smem + wave * slice;
+  float2* sF = reinterpret_cast<float2*>(smem + W * slice);
+  const int J = (K + 1) >> 1;
+  const int N2 = 2 * M;                                        // <= 32: one column tile
+  const int ld = 16;
+  for (int e = lane; e < slice; e += 64) sX[e] = 0.f;          // pads stay finite
+  stage_factor_table<true>(sF, U, rn, K, M, 2 * J, ld, tid, T);
+  __syncthreads();                                             // the only workgroup barrier
+  const int col = lane & 31, half = lane >> 5, part = col & 1;
+  float2 creg[CP];                                             // first-stage coefficients, one pair per row pair
+  {
+    const float2* fl0 = sF + half * ld + (col >> 1);
+#pragma unroll
+    for (int j = 0; j < CP; ++j)
+      creg[j] = j < J ? column_coef(fl0[2 * j * ld], part) : make_float2(0.f, 0.f);
+  }
+  float sgn = part ? 1.f : -1.f;                               // (Y J): re column <- -im, im column <- re
+  asm volatile("" : "+v"(sgn));                                // (kept a multiplication: it takes the lane swap as its operand modifier)
+
+  const uint32_t tile_elems = (uint32_t)(kTileRows * K);
+  const uint32_t tile_bytes = tile_elems * (uint32_t)(kPiece / 2);
+  const int S = fz.S;
+  const int nslabs = (int)(ntiles / S);                        // whole slabs (host); tile counts fit 32 bits
+  const int nw = (int)gridDim.x * W;
+  int slab = (int)blockIdx.x * W + wave;
+  int ts = 0;
+  if (slab >= nslabs) return;
+  auto advance = [&](int& sl, int& t) {
+    if (t + 1 < S) { t += 1; } else { t = 0; sl += nw; }
+  };
+  // loop-invariant lane addresses
+  const int voff_g = lane * kPiece;                            // into the tile, bytes
+  float* sW = sX + lane * 4;                                   // commit: piece i goes to sW + i * 256
+  const float* xa = sX + col * stride + 2 * half;              // matrix-core A operand: own row, own half of a pair
+  const bool full_out = fz.M2 == 32 && N2 == 32;
+  const uint32_t voff_out = (uint32_t)(4 * half * N2 + col);
+
+  Raw raw[TB];
+  int32_t my_om = 0;
+  // bytes of the tile from the first piece of every group of 4 loads on (scalar registers: a
+  // saturating subtraction inside the loop would be done by the vector ALU)
+  constexpr int kGroups = (TB + 3) / 4;
+  uint32_t rest[kGroups];
+#pragma unroll
+  for (int k = 0; k < kGroups; ++k) {
+    const uint32_t done = (uint32_t)(k * 4 * 64 * kPiece);
+    rest[k] = __builtin_amdgcn_readfirstlane(tile_bytes > done ? tile_bytes - done : 0u);
+  }
+  // tile t (support range [j0, j1)) -> raw / my_om; nothing here uses the vector ALU
+  auto issue = [&](int t, uint32_t j0, uint32_t j1) {
+    const char* tb = reinterpret_cast<const char*>(g) + (int64_t)t * (int64_t)tile_bytes;
+#pragma unroll
+    for (int i0 = 0; i0 < TB; i0 += 4) {                       // a descriptor per 4 loads: immediates reach 4 KB
+      const uint32_t done = (uint32_t)(i0 * 64 * kPiece);
+      const __amdgpu_buffer_rsrc_t r = raw_buffer(tb + done, rest[i0 / 4]);
+#pragma unroll
+      for (int i = i0; i < i0 + 4 && i < TB; ++i) raw[i] = BufPair<DT>::load(r, voff_g + (i - i0) * 64 * kPiece);
+    }
+    const uint32_t cnt = j1 - j0;                              // (s_min_u32: scalar)
+    const __amdgpu_buffer_rsrc_t ro = raw_buffer(omega + j0, (cnt < 64u ? cnt : 64u) * 4u);
+    my_om = (int32_t)__builtin_amdgcn_raw_buffer_load_b32(ro, lane * 4, 0, 0);
+  };
+  const uint32_t vzero = (uint32_t)opaque_zero();
+  auto range_of = [&](int t, uint32_t& j0, uint32_t& j1) {   // per-lane loads (scalar base), made scalar when used
+    const uint32_t* tsb = tile_start + t;
+    j0 = tsb[vzero];
+    j1 = tsb[vzero + 1];
+  };
+  int tile = slab * S;
+  int nslab = slab;
+  int nts = ts;
+  advance(nslab, nts);
+  bool have_next = nslab < nslabs;
+  int nxt = have_next ? nslab * S + nts : tile;            // past the end: reload the current tile (unused)
+  uint32_t cj0v, cj1v, nj0v, nj1v;
+  range_of(tile, cj0v, cj1v);
+  range_of(nxt, nj0v, nj1v);
+  uint32_t cj0 = __builtin_amdgcn_readfirstlane(cj0v), cj1 = __builtin_amdgcn_readfirstlane(cj1v);
+  issue(tile, cj0, cj1);
+  v16f acc2;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc2[r] = 0.f;
+  while (true) {
+    const uint32_t e_base = (uint32_t)tile * tile_elems;        // I < 2^31
+    wave_sync();                                               // previous tile's LDS reads are done
+    asm volatile("" : "+v"(my_om));
+#pragma unroll
+    for (int i = 0; i < TB; ++i) asm volatile("" : "+v"(raw[i]));   // one wait for the whole batch
+#pragma unroll
+    for (int i = 0; i < TB; ++i) BufPair<DT>::commit(sW + i * 256, raw[i]);
+    __builtin_amdgcn_sched_barrier(0);                         // (loads moved above these writes would need register copies)
+    // second-stage factor operands of this tile: small, cache-resident; before the next tile's loads
+    float2 f2s[16];
+    {
+      const float4* fp = reinterpret_cast<const float4*>(fz.fpad) + (size_t)ts * 8 * 64;
+#pragma unroll
+      for (int rp = 0; rp < 8; ++rp) {
+        const float4 f = fp[rp * 64 + lane];
+        f2s[2 * rp] = make_float2(f.x, f.y);
+        f2s[2 * rp + 1] = make_float2(f.z, f.w);
+      }
+    }
+    // the staging registers are free: the next tile's loads go in flight right away
+    const int32_t cur_om = my_om;
+    int nnslab = nslab;
+    int nnts = nts;
+    advance(nnslab, nnts);
+    const bool have_nn = have_next && nnslab < nslabs;
+    const int nn = have_nn ? nnslab * S + nnts : nxt;
+    const uint32_t nj0 = __builtin_amdgcn_readfirstlane(nj0v), nj1 = __builtin_amdgcn_readfirstlane(nj1v);
+    issue(nxt, nj0, nj1);
+    uint32_t nnj0v, nnj1v;
+    range_of(nn, nnj0v, nnj1v);
+    wave_sync();
+    // Sparse(G, Omega) of this tile: hand the values over, then remove them
+    {
+      float2* gsb = gs + cj0;
+      const uint32_t cnt = cj1 - cj0;
+      if ((uint32_t)lane < cnt) {
+        const uint32_t e = (uint32_t)cur_om - e_base;            // the entry lies in this tile
+        float2* p = reinterpret_cast<float2*>(sX + 2 * e);
+        gsb[lane] = *p;
+        *p = make_float2(0.f, 0.f);
+      }
+      if (cnt > 64u)
+        for (uint32_t j = 64u + lane; j < cnt; j += 64) {
+          const uint32_t e = (uint32_t)omega[cj0 + j] - e_base;
+          float2* p = reinterpret_cast<float2*>(sX + 2 * e);
+          gsb[j] = *p;
+          *p = make_float2(0.f, 0.f);
+        }
+    }
+    wave_sync();
+    // ---- the 32 rows through the matrix cores ----
+    __builtin_amdgcn_s_setprio(1);
+    v16f acc;
+    {
+      // CP row pairs, straight-line, A operands fetched kJUnroll pairs ahead at constant offsets.  Pairs
+      // past J meet zero coefficients; what they read lies in the wavefront's own slice (the host
+      // checks 62 K + 4 CP <= TB x 256) and is tile data or zeros, so it is finite.
+      float2 a2[kJUnroll];
+#pragma unroll
+      for (int u = 0; u < kJUnroll; ++u) a2[u] = *reinterpret_cast<const float2*>(xa + 4 * u);
+#pragma unroll
+      for (int jj = 0; jj < CP; ++jj) {
+        const float2 a = a2[jj % kJUnroll];
+        if (jj + kJUnroll < CP) a2[jj % kJUnroll] = *reinterpret_cast<const float2*>(xa + 4 * (jj + kJUnroll));
+        if (jj == 0) {
+          v16f zero;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) zero[r] = 0.f;
+          acc = mfma32(a.x, creg[0].x, zero);
+        } else {
+          acc = mfma32(a.x, creg[jj].x, acc);
+        }
+        acc = mfma32(a.y, creg[jj].y, acc);
+      }
+    }
+    asm volatile("" : "+v"(f2s[0].x));                         // the factor operands are claimed here
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const float y = acc[r];
+      const float sw = __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(y), 0xB1, 0xF, 0xF, true));
+      const float yj = sw * sgn;
+      acc2 = mfma32(f2s[r].x, y, acc2);
+      acc2 = mfma32(f2s[r].y, yj, acc2);
+    }
+    if (ts == S - 1) {                                         // slab complete: D2 -> out[slab, m2, c]
+      float* ob = fz.out + (size_t)slab * fz.M2 * N2;
+      if (full_out) {                                          // scalar row bases + one invariant lane offset
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          float* orow = ob + ((r & 3) + 8 * (r >> 2)) * N2;
+          orow[voff_out] = acc2[r];
+          acc2[r] = 0.f;
+        }
+      } else {                                                 // narrower ranks: guarded, addresses made on the spot
+        int lane_now = lane;                                   // (opaque: nothing of this is kept in registers across tiles)
+        asm volatile("" : "+v"(lane_now));
+        const int c2 = lane_now & 31, h2 = lane_now >> 5;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int m2 = d_row(r, h2);
+          if (m2 < fz.M2 && c2 < N2) ob[m2 * N2 + c2] = acc2[r];
+          acc2[r] = 0.f;
+        }
+      }
+    }
+    __builtin_amdgcn_s_setprio(0);
+    if (!have_next) break;
+    tile = nxt;
+    slab = nslab;
+    ts = nts;
+    nxt = nn;
+    nslab = nnslab;
+    nts = nnts;
+    have_next = have_nn;
+    cj0 = nj0;
+    cj1 = nj1;
+    nj0v = nnj0v;
+    nj1v = nnj1v;
+  }
+}
+
 // k_lupdate: tile = c_alpha * (z x_N U) + c_lambda * scatter(N_S);  W <- decay * W + tile,
 // with c_alpha = -lr alpha, c_lambda = -lr lambda, decay = 1 - lr wd (Algorithm 1: "Reconstruct
 // low-rank part", "Add scaled sparse tensor", weight update; AdamUpdate on the sparse values
@@ -938,7 +1218,7 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate(const float* __restrict__
     }
   };
 
-  const int vzero = tid >> 30;                                 // 0, but not known to be uniform (see k_lproj)
+  const int vzero = opaque_zero();                             // see k_lproj
   int64_t nxt = tile + step;
   uint32_t cj0 = sp.tile_start[tile + vzero], cj1 = sp.tile_start[tile + 1 + vzero];
   uint32_t nj0 = 0, nj1 = 0;
@@ -1151,7 +1431,7 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate_fused(const float2* __res
     asm volatile("" : "+v"(my_om), "+v"(my_g.x), "+v"(my_g.y), "+v"(my_m.x), "+v"(my_m.y), "+v"(my_v));
   };
 
-  const int vzero = tid >> 30;
+  const int vzero = opaque_zero();
   int64_t tile = slab * S;
   int64_t nslab = slab;
   int nts = ts;
@@ -1593,7 +1873,25 @@ void launch_lproj(hipStream_t s, const void* g, int dtype, const int32_t* omega,
   do {                                                                                                   \
     if (W == 4) TGRAD_LP_F4(DT_, NTB_); else if (W == 2) TGRAD_LP_F(DT_, 2, NTB_); else TGRAD_LP_F(DT_, 1, NTB_); \
   } while (0)
-  if (fuse) {                                   // the host only fuses with W == 4 and one column tile
+#define TGRAD_LPF_C(DT_, CP_, TB_)                                                                       \
+  do {                                                                                                   \
+    const size_t ldsf = (size_t)4 * lproj_flat_slice(K, TB_) * 4 + (size_t)2 * ((K + 1) / 2) * 16 * 8;   \
+    allow_lds(k_lproj_flat<DT_, CP_, TB_>, ldsf);                                                        \
+    grid.x = (unsigned)grid_for_tiles(ngroups, resident_blocks(k_lproj_flat<DT_, CP_, TB_>, 256, ldsf)); \
+    k_lproj_flat<DT_, CP_, TB_><<<grid, block, ldsf, s>>>(g, omega, tile_start, gs, U, rn, A, K, M,      \
+                                                          ntiles, fz);                                   \
+  } while (0)
+#define TGRAD_LPF(DT_)                                                                                   \
+  do {                                                                                                   \
+    if ((K + 1) / 2 > kCoefPairsShort) TGRAD_LPF_C(DT_, kCoefPairs, kTileBatch);                         \
+    else if (tb == 5) TGRAD_LPF_C(DT_, kCoefPairsShort, 5);                                              \
+    else TGRAD_LPF_C(DT_, kCoefPairsShort, 9);                                                           \
+  } while (0)
+  static const bool no_flat = [] { const char* e = getenv("TGRAD_LPROJ_FLAT"); return e && e[0] == '0'; }();
+  const int cp = (K + 1) / 2 > kCoefPairsShort ? kCoefPairs : kCoefPairsShort;
+  if (fuse && (K & 1) && !no_flat && tb * 64 >= 16 * K && 62 * K + 4 * cp <= tb * 256) {   // odd last extent: the staging phase without vector ALU work
+    if (dtype == TGRAD_C64) TGRAD_LPF(TGRAD_C64); else TGRAD_LPF(TGRAD_CBF16);
+  } else if (fuse) {                            // the host only fuses with W == 4 and one column tile
     if (dtype == TGRAD_C64) {
       if (K & 1) TGRAD_LP_FUSED(TGRAD_C64, true); else TGRAD_LP_FUSED(TGRAD_C64, false);
     } else {
@@ -1604,6 +1902,8 @@ void launch_lproj(hipStream_t s, const void* g, int dtype, const int32_t* omega,
   } else {
     if (ntb == 2) TGRAD_LP_W(TGRAD_CBF16, 2); else TGRAD_LP_W(TGRAD_CBF16, 1);
   }
+#undef TGRAD_LPF
+#undef TGRAD_LPF_C
 #undef TGRAD_LP_F4
 #undef TGRAD_LP_W
 #undef TGRAD_LP_F
