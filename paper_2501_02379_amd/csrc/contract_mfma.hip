@@ -867,6 +867,8 @@ __global__ __launch_bounds__(256, 2) void k_lproj_flat(const void* __restrict__ 
   typedef typename BufPair<DT>::type Raw;
   constexpr int W = 4, T = 64 * W;
   constexpr int kPiece = (int)sizeof(Raw);                     // bytes of G per lane and load (2 elements)
+  constexpr int kLoadEvery = (CP - 1) / (TB - 1) >= 2 ? 2 : 1; // row pairs of the first stage per load of the next tile
+  static_assert((TB - 1) * kLoadEvery < CP, "the first stage issues all TB loads");
   extern __shared__ float smem[];
   const int stride = 2 * K;                                    // floats per LDS row; K is odd
   const int slice = lproj_flat_slice(K, TB);
@@ -920,16 +922,15 @@ __global__ __launch_bounds__(256, 2) void k_lproj_flat(const void* __restrict__ 
     const uint32_t done = (uint32_t)(k * 4 * 64 * kPiece);
     rest[k] = __builtin_amdgcn_readfirstlane(tile_bytes > done ? tile_bytes - done : 0u);
   }
-  // tile t (support range [j0, j1)) -> raw / my_om; nothing here uses the vector ALU
-  auto issue = [&](int t, uint32_t j0, uint32_t j1) {
+  // piece i of tile t -> raw[i]; the first 64 support entries of a tile -> my_om.  Nothing here uses
+  // the vector ALU.  (A descriptor per 4 pieces: immediate offsets reach 4 KB.)
+  auto issue_piece = [&](int t, int i) {
     const char* tb = reinterpret_cast<const char*>(g) + (int64_t)t * (int64_t)tile_bytes;
-#pragma unroll
-    for (int i0 = 0; i0 < TB; i0 += 4) {                       // a descriptor per 4 loads: immediates reach 4 KB
-      const uint32_t done = (uint32_t)(i0 * 64 * kPiece);
-      const __amdgpu_buffer_rsrc_t r = raw_buffer(tb + done, rest[i0 / 4]);
-#pragma unroll
-      for (int i = i0; i < i0 + 4 && i < TB; ++i) raw[i] = BufPair<DT>::load(r, voff_g + (i - i0) * 64 * kPiece);
-    }
+    const int k = i / 4;
+    const __amdgpu_buffer_rsrc_t r = raw_buffer(tb + (uint32_t)(k * 4 * 64 * kPiece), rest[k]);
+    raw[i] = BufPair<DT>::load(r, voff_g + (i - 4 * k) * 64 * kPiece);
+  };
+  auto issue_support = [&](uint32_t j0, uint32_t j1) {
     const uint32_t cnt = j1 - j0;                              // (s_min_u32: scalar)
     const __amdgpu_buffer_rsrc_t ro = raw_buffer(omega + j0, (cnt < 64u ? cnt : 64u) * 4u);
     my_om = (int32_t)__builtin_amdgcn_raw_buffer_load_b32(ro, lane * 4, 0, 0);
@@ -950,10 +951,38 @@ __global__ __launch_bounds__(256, 2) void k_lproj_flat(const void* __restrict__ 
   range_of(tile, cj0v, cj1v);
   range_of(nxt, nj0v, nj1v);
   uint32_t cj0 = __builtin_amdgcn_readfirstlane(cj0v), cj1 = __builtin_amdgcn_readfirstlane(cj1v);
-  issue(tile, cj0, cj1);
+#pragma unroll
+  for (int i = 0; i < TB; ++i) issue_piece(tile, i);
+  issue_support(cj0, cj1);
   v16f acc2;
 #pragma unroll
   for (int r = 0; r < 16; ++r) acc2[r] = 0.f;
+  // D2 of a complete slab -> out[slab, m2, c].  Issued at the start of the NEXT tile's staging phase,
+  // not after the last matrix-core instruction: the wait that opens a tile covers every vector-memory
+  // operation before it, and stores issued just before it would be waited for in full.
+  auto store_slab = [&](int sl) {
+    float* ob = fz.out + (size_t)sl * fz.M2 * N2;
+    if (full_out) {                                            // scalar row bases + one invariant lane offset
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float* orow = ob + ((r & 3) + 8 * (r >> 2)) * N2;
+        orow[voff_out] = acc2[r];
+        acc2[r] = 0.f;
+      }
+    } else {                                                   // narrower ranks: guarded, addresses made on the spot
+      int lane_now = lane;                                     // (opaque: nothing of this is kept in registers across tiles)
+      asm volatile("" : "+v"(lane_now));
+      const int c2 = lane_now & 31, h2 = lane_now >> 5;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m2 = d_row(r, h2);
+        if (m2 < fz.M2 && c2 < N2) ob[m2 * N2 + c2] = acc2[r];
+        acc2[r] = 0.f;
+      }
+    }
+  };
+  bool pending = false;
+  int pending_slab = 0;
   while (true) {
     const uint32_t e_base = (uint32_t)tile * tile_elems;        // I < 2^31
     wave_sync();                                               // previous tile's LDS reads are done
@@ -963,6 +992,7 @@ __global__ __launch_bounds__(256, 2) void k_lproj_flat(const void* __restrict__ 
 #pragma unroll
     for (int i = 0; i < TB; ++i) BufPair<DT>::commit(sW + i * 256, raw[i]);
     __builtin_amdgcn_sched_barrier(0);                         // (loads moved above these writes would need register copies)
+    if (pending) store_slab(pending_slab);
     // second-stage factor operands of this tile: small, cache-resident; before the next tile's loads
     float2 f2s[16];
     {
@@ -974,7 +1004,6 @@ __global__ __launch_bounds__(256, 2) void k_lproj_flat(const void* __restrict__ 
         f2s[2 * rp + 1] = make_float2(f.z, f.w);
       }
     }
-    // the staging registers are free: the next tile's loads go in flight right away
     const int32_t cur_om = my_om;
     int nnslab = nslab;
     int nnts = nts;
@@ -982,9 +1011,6 @@ __global__ __launch_bounds__(256, 2) void k_lproj_flat(const void* __restrict__ 
     const bool have_nn = have_next && nnslab < nslabs;
     const int nn = have_nn ? nnslab * S + nnts : nxt;
     const uint32_t nj0 = __builtin_amdgcn_readfirstlane(nj0v), nj1 = __builtin_amdgcn_readfirstlane(nj1v);
-    issue(nxt, nj0, nj1);
-    uint32_t nnj0v, nnj1v;
-    range_of(nn, nnj0v, nnj1v);
     wave_sync();
     // Sparse(G, Omega) of this tile: hand the values over, then remove them
     {
@@ -1028,8 +1054,19 @@ __global__ __launch_bounds__(256, 2) void k_lproj_flat(const void* __restrict__ 
           acc = mfma32(a.x, creg[jj].x, acc);
         }
         acc = mfma32(a.y, creg[jj].y, acc);
+        // The next tile's loads, one per row pair: a load instruction waits at issue until the memory
+        // pipeline takes it (at the rate memory delivers when every wavefront streams), and here that
+        // wait lies under the matrix-core instructions instead of in front of them.
+        if (jj % kLoadEvery == 0 && jj / kLoadEvery < TB) {
+          __builtin_amdgcn_sched_barrier(0);
+          issue_piece(nxt, jj / kLoadEvery);
+          __builtin_amdgcn_sched_barrier(0);
+        }
       }
     }
+    issue_support(nj0, nj1);
+    uint32_t nnj0v, nnj1v;
+    range_of(nn, nnj0v, nnj1v);
     asm volatile("" : "+v"(f2s[0].x));                         // the factor operands are claimed here
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
@@ -1039,28 +1076,11 @@ __global__ __launch_bounds__(256, 2) void k_lproj_flat(const void* __restrict__ 
       acc2 = mfma32(f2s[r].x, y, acc2);
       acc2 = mfma32(f2s[r].y, yj, acc2);
     }
-    if (ts == S - 1) {                                         // slab complete: D2 -> out[slab, m2, c]
-      float* ob = fz.out + (size_t)slab * fz.M2 * N2;
-      if (full_out) {                                          // scalar row bases + one invariant lane offset
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          float* orow = ob + ((r & 3) + 8 * (r >> 2)) * N2;
-          orow[voff_out] = acc2[r];
-          acc2[r] = 0.f;
-        }
-      } else {                                                 // narrower ranks: guarded, addresses made on the spot
-        int lane_now = lane;                                   // (opaque: nothing of this is kept in registers across tiles)
-        asm volatile("" : "+v"(lane_now));
-        const int c2 = lane_now & 31, h2 = lane_now >> 5;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int m2 = d_row(r, h2);
-          if (m2 < fz.M2 && c2 < N2) ob[m2 * N2 + c2] = acc2[r];
-          acc2[r] = 0.f;
-        }
-      }
-    }
+    const bool slab_done = ts == S - 1;
+    const int done_slab = slab;
     __builtin_amdgcn_s_setprio(0);
+    pending = slab_done;
+    pending_slab = done_slab;
     if (!have_next) break;
     tile = nxt;
     slab = nslab;
@@ -1074,6 +1094,7 @@ __global__ __launch_bounds__(256, 2) void k_lproj_flat(const void* __restrict__ 
     nj0v = nnj0v;
     nj1v = nnj1v;
   }
+  if (pending) store_slab(pending_slab);
 }
 
 // k_lupdate: tile = c_alpha * (z x_N U) + c_lambda * scatter(N_S);  W <- decay * W + tile,
