@@ -16,7 +16,7 @@
 //             flat tile of rows is staged in LDS, the entries of the support Omega that fall
 //             in the tile are handed to the sparse branch (gather) and zeroed (this is
 //             G - Sparse(G, Omega) without a second pass over G), then 32 rows per wavefront
-//             go through the matrix cores.
+//             go through the matrix cores.  k_lproj_flat is its fused form for odd last extents.
 //  k_lupdate  the last reconstruction stage fused with everything that touches W: expands the
 //             last mode into an LDS tile, runs AdamUpdate on the sparse values of the tile
 //             and adds lambda N_S into it, then streams W <- W (1 - lr wd) - lr tile with
