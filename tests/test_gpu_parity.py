@@ -133,6 +133,10 @@ def test_exact_low_rank_gradient_gives_planted_subspace():
 FUSED_SHAPES = [
     ((16, 32, 32, 9), (4, 8, 8, 4), 300),          # one tile per slab
     ((16, 32, 64, 5), (4, 8, 16, 2), 200),         # two tiles per slab
+    ((16, 32, 32, 33), (4, 8, 8, 8), 500),         # odd last extent, 9 pieces per lane and tile
+    ((8, 64, 32, 35), (4, 8, 8, 6), 500),          # odd last extent, the long-row variant (17 pieces, 33 row pairs)
+    ((16, 32, 32, 8), (4, 8, 8, 4), 300),          # even last extent: padded LDS rows
+    ((16, 32, 32, 9), (4, 8, 8, 4), 45000),        # more than 64 support entries in every tile
 ]
 
 
