@@ -20,7 +20,7 @@ typedef double v4d __attribute__((ext_vector_type(4)));
 
 constexpr int kSuper = 128;          // rows of the output handled by one workgroup, per side
 constexpr int kTC = 16;              // tensor columns staged per tile
-constexpr int kLd = kTC + 1;         // padded LDS row stride (float2 units), odd -> conflict-free
+constexpr int kRowD = 4 * kTC + 2;   // doubles per staged row: 4 per element + a pad of 16 bytes (conflict-free reads)
 constexpr int kGramThreads = 1024;   // 16 wavefronts: a 4 x 4 grid of 32 x 32 output blocks
 
 // Gram of the tensor viewed as (A, In, B): gram[i, j] = sum_{a, b} x[a, i, b] conj(x[a, j, b]).
@@ -34,6 +34,10 @@ constexpr int kGramThreads = 1024;   // 16 wavefronts: a 4 x 4 grid of 32 x 32 o
 // of them off the diagonal, the 36 on or below it on the diagonal - dealt round-robin to its 16
 // wavefronts (tile t to wavefront t % 16: 9 tiles per SIMD in the diagonal case).  The next
 // 16 columns are fetched into registers while the current ones are in the matrix cores.
+// A staged element is converted to float64 once, when it is committed to LDS, and stored as the four
+// operands it can be asked for: (xr, xi, xi, -xr).  The f64 matrix instructions run on the SIMD's
+// vector ALU; a conversion and a select per operand fetch in the inner loop (each element is an
+// operand of up to 8 tiles) took as many of its cycles as the matrix instructions themselves.
 constexpr int kGramMaxTiles = 4;     // tiles per wavefront: 64 / 16
 
 template <int DT>
@@ -41,20 +45,20 @@ __global__ __launch_bounds__(kGramThreads) void k_gram(const void* __restrict__ 
                                                         const uint32_t* __restrict__ mask, int64_t A,
                                                         int In, int64_t B, int64_t cols_per_chunk,
                                                         double* __restrict__ partials) {
-  __shared__ float2 sI[kSuper * kLd];
-  __shared__ float2 sJ[kSuper * kLd];
+  extern __shared__ double sG[];
+  double* sI = sG;                                    // [row][column][xr, xi, xi, -xr]
+  double* sJ = sG + kSuper * kRowD;
   const int nsup = (In + kSuper - 1) / kSuper;
   const int si = blockIdx.y / nsup, sj = blockIdx.y % nsup;
   if (si < sj) return;                                // upper super blocks: mirrored by the reduction
   const bool diag = si == sj;
-  const float2* sJp = diag ? sI : sJ;
   const int64_t J = A * B;
   const int64_t c_begin = (int64_t)blockIdx.x * cols_per_chunk;
   const int64_t c_end = c_begin + cols_per_chunk < J ? c_begin + cols_per_chunk : J;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int part = (lane >> 4) & 1;
   const int ccol = lane >> 5;
   const int lrow = lane & 15;
@@ -101,14 +105,24 @@ __global__ __launch_bounds__(kGramThreads) void k_gram(const void* __restrict__ 
       cl = e % kTC;
     }
   };
-  auto fetch = [&](int s, int64_t c0, int e) -> float2 {
+  // (a0, b0) = (c0 / B, c0 % B) of the tile's first column, kept up to date by the caller: a 64-bit
+  // division per fetched element would cost the vector ALU - which the f64 matrix instructions
+  // also run on - more cycles than the tile's matrix instructions.
+  auto fetch = [&](int s, int64_t c0, int64_t a0, int64_t b0, int e) -> float2 {
     int il, cl;
     locate(e, il, cl);
     const int i = s * kSuper + il;
     const int64_t c = c0 + cl;
     float2 v = make_float2(0.f, 0.f);
     if (i < In && c < c_end) {
-      const int64_t a = c / B, b = c - a * B;
+      int64_t a = a0, b = b0 + cl;
+      if (B >= kTC) {                                 // at most one wrap inside a tile
+        if (b >= B) { b -= B; a += 1; }
+      } else {                                        // tiny trailing extent: b0 + cl < 32
+        const uint32_t q = (uint32_t)b / (uint32_t)B;
+        a += q;
+        b -= (int64_t)q * B;
+      }
       const int64_t idx = (a * In + i) * B + b;
       // both loads are issued together (a load that waits for the mask bit would double the latency)
       const uint32_t mw = mask ? mask[idx >> 5] : 0u;
@@ -119,44 +133,89 @@ __global__ __launch_bounds__(kGramThreads) void k_gram(const void* __restrict__ 
   };
 
   float2 preI[kPer], preJ[kPer];                      // next tile of the row side / the column side
+  int64_t pa0 = c_begin / B, pb0 = c_begin - pa0 * B; // of the tile being fetched (workgroup-uniform)
+  auto next_tile = [&]() {                            // (a0, b0) of the tile kTC columns further on
+    pb0 += kTC;
+    if (B >= kTC) {
+      if (pb0 >= B) { pb0 -= B; pa0 += 1; }
+    } else {
+      const uint32_t q = (uint32_t)pb0 / (uint32_t)B;
+      pa0 += q;
+      pb0 -= (int64_t)q * B;
+    }
+  };
 #pragma unroll
   for (int u = 0; u < kPer; ++u) {
-    preI[u] = fetch(si, c_begin, tid + u * kGramThreads);
-    preJ[u] = diag ? make_float2(0.f, 0.f) : fetch(sj, c_begin, tid + u * kGramThreads);
+    preI[u] = fetch(si, c_begin, pa0, pb0, tid + u * kGramThreads);
+    preJ[u] = diag ? make_float2(0.f, 0.f) : fetch(sj, c_begin, pa0, pb0, tid + u * kGramThreads);
   }
 
-  for (int64_t c0 = c_begin; c0 < c_end; c0 += kTC) {
-    __syncthreads();                                  // previous tile fully consumed
+  // pre -> one staged tile (row side into dI; column side into dJ when the super block is off the diagonal)
+  auto commit = [&](double* dI, double* dJ) {
 #pragma unroll
     for (int u = 0; u < kPer; ++u) {
       int il, cl;
       locate(tid + u * kGramThreads, il, cl);
-      sI[il * kLd + cl] = preI[u];
-      if (!diag) sJ[il * kLd + cl] = preJ[u];
-    }
-    __syncthreads();
-    if (c0 + kTC < c_end) {                           // next 16 columns go in flight
-#pragma unroll
-      for (int u = 0; u < kPer; ++u) {
-        preI[u] = fetch(si, c0 + kTC, tid + u * kGramThreads);
-        if (!diag) preJ[u] = fetch(sj, c0 + kTC, tid + u * kGramThreads);
+      {
+        const double xr = (double)preI[u].x, xi = (double)preI[u].y;
+        double2* d = reinterpret_cast<double2*>(dI + il * kRowD + 4 * cl);
+        d[0] = make_double2(xr, xi);
+        d[1] = make_double2(xi, -xr);
+      }
+      if (!diag) {
+        const double xr = (double)preJ[u].x, xi = (double)preJ[u].y;
+        *reinterpret_cast<double2*>(dJ + il * kRowD + 4 * cl) = make_double2(xr, xi);
       }
     }
+  };
+  auto prefetch = [&](int64_t c0) {                   // the tile that starts at column c0 -> pre
+    next_tile();
+#pragma unroll
+    for (int u = 0; u < kPer; ++u) {
+      preI[u] = fetch(si, c0, pa0, pb0, tid + u * kGramThreads);
+      if (!diag) preJ[u] = fetch(sj, c0, pa0, pb0, tid + u * kGramThreads);
+    }
+  };
+  auto multiply = [&](const double* bI, const double* bJ) {
 #pragma unroll 1
     for (int s2 = 0; s2 < kTC / 2; ++s2) {
       const int cc = 2 * s2 + ccol;
 #pragma unroll
       for (int k = 0; k < kGramMaxTiles; ++k) {
         if (mine[k]) {
-          const float2 xa = sI[(16 * ti[k] + lrow) * kLd + cc];
-          const float2 xb = sJp[(16 * tj[k] + lrow) * kLd + cc];
-          const double aRe = part ? (double)xa.y : (double)xa.x;
-          const double aIm = part ? -(double)xa.x : (double)xa.y;
-          const double bop = part ? (double)xb.y : (double)xb.x;
+          const double* pa = bI + (16 * ti[k] + lrow) * kRowD + 4 * cc + part;
+          const double aRe = pa[0];                   // part ? xi : xr
+          const double aIm = pa[2];                   // part ? -xr : xi
+          const double bop = bJ[(16 * tj[k] + lrow) * kRowD + 4 * cc + part];
           accRe[k] = __builtin_amdgcn_mfma_f64_16x16x4f64(aRe, bop, accRe[k], 0, 0, 0);
           accIm[k] = __builtin_amdgcn_mfma_f64_16x16x4f64(aIm, bop, accIm[k], 0, 0, 0);
         }
       }
+    }
+  };
+  if (diag) {
+    // One staged side only, so the two LDS areas take turns: while the wavefronts multiply tile t out
+    // of one, tile t + 1 is committed into the other (it was read last for tile t - 1, before the
+    // barrier that ended that tile) and tile t + 2 is fetched into registers.  One barrier per tile.
+    commit(sI, sI);
+    if (c_begin + kTC < c_end) prefetch(c_begin + kTC);
+    __syncthreads();
+    int it = 0;
+    for (int64_t c0 = c_begin; c0 < c_end; c0 += kTC, ++it) {
+      double* cur = (it & 1) ? sJ : sI;
+      double* nxt = (it & 1) ? sI : sJ;
+      if (c0 + kTC < c_end) commit(nxt, nxt);
+      if (c0 + 2 * kTC < c_end) prefetch(c0 + 2 * kTC);
+      multiply(cur, cur);
+      __syncthreads();
+    }
+  } else {
+    for (int64_t c0 = c_begin; c0 < c_end; c0 += kTC) {
+      __syncthreads();                                // previous tile fully consumed
+      commit(sI, sJ);
+      __syncthreads();
+      if (c0 + kTC < c_end) prefetch(c0 + kTC);       // next 16 columns go in flight
+      multiply(sI, sJ);
     }
   }
   double2* out = reinterpret_cast<double2*>(partials) + (int64_t)blockIdx.x * In * In;
@@ -694,10 +753,16 @@ void launch_gram(hipStream_t s, const void* g, int dtype, const uint32_t* mask, 
   const int64_t cols_per_chunk = tiles_per_chunk * kTC;
   const int nsup = (In + kSuper - 1) / kSuper;
   dim3 grid((unsigned)nchunks, (unsigned)(nsup * nsup)), block(kGramThreads);
-  if (dtype == TGRAD_C64)
-    k_gram<TGRAD_C64><<<grid, block, 0, s>>>(g, mask, A, In, B, cols_per_chunk, partials);
-  else
-    k_gram<TGRAD_CBF16><<<grid, block, 0, s>>>(g, mask, A, In, B, cols_per_chunk, partials);
+  const size_t lds = (size_t)2 * kSuper * kRowD * sizeof(double);   // 132 KB: more than the default limit
+  if (dtype == TGRAD_C64) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_gram<TGRAD_C64>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    k_gram<TGRAD_C64><<<grid, block, lds, s>>>(g, mask, A, In, B, cols_per_chunk, partials);
+  } else {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_gram<TGRAD_CBF16>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    k_gram<TGRAD_CBF16><<<grid, block, lds, s>>>(g, mask, A, In, B, cols_per_chunk, partials);
+  }
 }
 
 void launch_gram_reduce(hipStream_t s, const double* partials, int nchunks, int In, double* gram) {
