@@ -176,17 +176,26 @@ __global__ __launch_bounds__(kGramThreads) void k_gram(const void* __restrict__ 
       if (!diag) preJ[u] = fetch(sj, c0, pa0, pb0, tid + u * kGramThreads);
     }
   };
-  auto multiply = [&](const double* bI, const double* bJ) {
-#pragma unroll 1
-    for (int s2 = 0; s2 < kTC / 2; ++s2) {
-      const int cc = 2 * s2 + ccol;
+  // Operand addresses are invariant lane offsets plus constants: a wavefront takes its tiles one after
+  // the other and, per tile, the 8 column pairs of the staged tile unrolled, so that nothing in the
+  // loop but the matrix instructions needs the vector ALU (which they occupy).
+  int offA[kGramMaxTiles], offB[kGramMaxTiles];       // doubles, from the start of a staged area
 #pragma unroll
-      for (int k = 0; k < kGramMaxTiles; ++k) {
-        if (mine[k]) {
-          const double* pa = bI + (16 * ti[k] + lrow) * kRowD + 4 * cc + part;
-          const double aRe = pa[0];                   // part ? xi : xr
-          const double aIm = pa[2];                   // part ? -xr : xi
-          const double bop = bJ[(16 * tj[k] + lrow) * kRowD + 4 * cc + part];
+  for (int k = 0; k < kGramMaxTiles; ++k) {
+    offA[k] = (16 * ti[k] + lrow) * kRowD + 4 * ccol + part;
+    offB[k] = (16 * tj[k] + lrow) * kRowD + 4 * ccol + part;
+  }
+  auto multiply = [&](const double* bI, const double* bJ) {
+#pragma unroll
+    for (int k = 0; k < kGramMaxTiles; ++k) {
+      if (mine[k]) {
+        const double* pa = bI + offA[k];
+        const double* pb = bJ + offB[k];
+#pragma unroll
+        for (int s2 = 0; s2 < kTC / 2; ++s2) {        // column 2 s2 + ccol: 4 doubles per column
+          const double aRe = pa[8 * s2];              // part ? xi : xr
+          const double aIm = pa[8 * s2 + 2];          // part ? -xr : xi
+          const double bop = pb[8 * s2];
           accRe[k] = __builtin_amdgcn_mfma_f64_16x16x4f64(aRe, bop, accRe[k], 0, 0, 0);
           accIm[k] = __builtin_amdgcn_mfma_f64_16x16x4f64(aIm, bop, accIm[k], 0, 0, 0);
         }
