@@ -11,7 +11,8 @@ The oracle cannot afford whole runs at these sizes, so:
    sparse values exactly, and the updated weights on sampled entries that the oracle rebuilds
    one by one from the core (entries inside and outside the support, first / last elements and
    tile boundaries included).
-Progress is appended to gpurun_out/fullsize_progress.txt (pytest holds stdout until a test ends).
+Progress lines are also appended to a text file in the run's output folder (pytest holds stdout
+until a test ends).
 """
 import os
 import time
