@@ -94,9 +94,17 @@ __global__ __launch_bounds__(kGramThreads) void k_gram(const void* __restrict__ 
     accIm[k] = (v4d){0., 0., 0., 0.};
   }
 
-  // element e (0 .. 2047) of a staged tile: (row il, column cl) and the value at tensor column c0 + cl
+  // A thread stages elements e = tid + u * 1024 (u < kPer) of a tile: row il, column cl.  Which ones
+  // they are does not depend on the tile, so everything that can be is computed once: the LDS slot,
+  // the tensor offset of (row, cl) inside a tile, and whether the row exists.
   constexpr int kPer = kSuper * kTC / kGramThreads;   // 2 elements per thread and side
-  auto locate = [&](int e, int& il, int& cl) {
+  int e_cl[kPer], e_lds[kPer];
+  int64_t e_offI[kPer], e_offJ[kPer];                 // (row * B + cl) for the row side / the column side
+  bool e_okI[kPer], e_okJ[kPer];
+#pragma unroll
+  for (int u = 0; u < kPer; ++u) {
+    const int e = tid + u * kGramThreads;
+    int il, cl;
     if (B == 1) {                                     // rows are the fastest index in memory
       il = e % kSuper;
       cl = e / kSuper;
@@ -104,26 +112,31 @@ __global__ __launch_bounds__(kGramThreads) void k_gram(const void* __restrict__ 
       il = e / kTC;
       cl = e % kTC;
     }
-  };
-  // (a0, b0) = (c0 / B, c0 % B) of the tile's first column, kept up to date by the caller: a 64-bit
-  // division per fetched element would cost the vector ALU - which the f64 matrix instructions
-  // also run on - more cycles than the tile's matrix instructions.
-  auto fetch = [&](int s, int64_t c0, int64_t a0, int64_t b0, int e) -> float2 {
-    int il, cl;
-    locate(e, il, cl);
-    const int i = s * kSuper + il;
-    const int64_t c = c0 + cl;
+    e_cl[u] = cl;
+    e_lds[u] = il * kRowD + 4 * cl;
+    e_okI[u] = si * kSuper + il < In;
+    e_okJ[u] = sj * kSuper + il < In;
+    e_offI[u] = (int64_t)(si * kSuper + il) * B + cl;
+    e_offJ[u] = (int64_t)(sj * kSuper + il) * B + cl;
+  }
+  // Column c = c0 + cl of the unfolding is tensor index (a, b) = (c / B, c % B); with (a0, b0) those
+  // of the tile's first column (kept up to date by the caller) the element (row i, column c) lies at
+  //   (a0 In + i) B + b0 + cl            if b0 + cl < B,
+  //   ... + (In - 1) B                   if the column has wrapped into the next a (at most once
+  //                                      per tile when B >= 16; smaller B take the general form).
+  // A 64-bit division per fetched element would cost the vector ALU - which the f64 matrix
+  // instructions also run on - more cycles than the tile's matrix instructions.
+  const int64_t wrap_add = (int64_t)(In - 1) * B;
+  auto fetch = [&](bool row_ok, int64_t off, int cl, int64_t c0, int64_t a0, int64_t b0) -> float2 {
     float2 v = make_float2(0.f, 0.f);
-    if (i < In && c < c_end) {
-      int64_t a = a0, b = b0 + cl;
-      if (B >= kTC) {                                 // at most one wrap inside a tile
-        if (b >= B) { b -= B; a += 1; }
+    if (row_ok && c0 + cl < c_end) {
+      int64_t idx;
+      if (B >= kTC) {
+        idx = a0 * In * B + b0 + off + (b0 + cl >= B ? wrap_add : (int64_t)0);
       } else {                                        // tiny trailing extent: b0 + cl < 32
-        const uint32_t q = (uint32_t)b / (uint32_t)B;
-        a += q;
-        b -= (int64_t)q * B;
+        const uint32_t q = (uint32_t)(b0 + cl) / (uint32_t)B;
+        idx = a0 * In * B + b0 + off + (int64_t)q * wrap_add;
       }
-      const int64_t idx = (a * In + i) * B + b;
       // both loads are issued together (a load that waits for the mask bit would double the latency)
       const uint32_t mw = mask ? mask[idx >> 5] : 0u;
       const float2 xv = load_elem<DT>(x, idx);
@@ -146,25 +159,23 @@ __global__ __launch_bounds__(kGramThreads) void k_gram(const void* __restrict__ 
   };
 #pragma unroll
   for (int u = 0; u < kPer; ++u) {
-    preI[u] = fetch(si, c_begin, pa0, pb0, tid + u * kGramThreads);
-    preJ[u] = diag ? make_float2(0.f, 0.f) : fetch(sj, c_begin, pa0, pb0, tid + u * kGramThreads);
+    preI[u] = fetch(e_okI[u], e_offI[u], e_cl[u], c_begin, pa0, pb0);
+    preJ[u] = diag ? make_float2(0.f, 0.f) : fetch(e_okJ[u], e_offJ[u], e_cl[u], c_begin, pa0, pb0);
   }
 
   // pre -> one staged tile (row side into dI; column side into dJ when the super block is off the diagonal)
   auto commit = [&](double* dI, double* dJ) {
 #pragma unroll
     for (int u = 0; u < kPer; ++u) {
-      int il, cl;
-      locate(tid + u * kGramThreads, il, cl);
       {
         const double xr = (double)preI[u].x, xi = (double)preI[u].y;
-        double2* d = reinterpret_cast<double2*>(dI + il * kRowD + 4 * cl);
+        double2* d = reinterpret_cast<double2*>(dI + e_lds[u]);
         d[0] = make_double2(xr, xi);
         d[1] = make_double2(xi, -xr);
       }
       if (!diag) {
         const double xr = (double)preJ[u].x, xi = (double)preJ[u].y;
-        *reinterpret_cast<double2*>(dJ + il * kRowD + 4 * cl) = make_double2(xr, xi);
+        *reinterpret_cast<double2*>(dJ + e_lds[u]) = make_double2(xr, xi);
       }
     }
   };
@@ -172,8 +183,8 @@ __global__ __launch_bounds__(kGramThreads) void k_gram(const void* __restrict__ 
     next_tile();
 #pragma unroll
     for (int u = 0; u < kPer; ++u) {
-      preI[u] = fetch(si, c0, pa0, pb0, tid + u * kGramThreads);
-      if (!diag) preJ[u] = fetch(sj, c0, pa0, pb0, tid + u * kGramThreads);
+      preI[u] = fetch(e_okI[u], e_offI[u], e_cl[u], c0, pa0, pb0);
+      if (!diag) preJ[u] = fetch(e_okJ[u], e_offJ[u], e_cl[u], c0, pa0, pb0);
     }
   };
   // Operand addresses are invariant lane offsets plus constants: a wavefront takes its tiles one after
