@@ -831,14 +831,14 @@ template <int DT> struct BufPair;
 template <> struct BufPair<TGRAD_C64> {
   typedef u32x4 type;
   static __device__ __forceinline__ type load(__amdgpu_buffer_rsrc_t r, int voff) {
-    return __builtin_amdgcn_raw_buffer_load_b128(r, voff, 0, 0);
+    return __builtin_amdgcn_raw_buffer_load_b128(r, voff, 0, 2);   // cache policy: non-temporal
   }
   static __device__ __forceinline__ void commit(float* dst, const type& v) { *reinterpret_cast<type*>(dst) = v; }
 };
 template <> struct BufPair<TGRAD_CBF16> {
   typedef u32x2 type;
   static __device__ __forceinline__ type load(__amdgpu_buffer_rsrc_t r, int voff) {
-    return __builtin_amdgcn_raw_buffer_load_b64(r, voff, 0, 0);
+    return __builtin_amdgcn_raw_buffer_load_b64(r, voff, 0, 2);    // cache policy: non-temporal
   }
   static __device__ __forceinline__ void commit(float* dst, const type& v) {   // a bf16 is the upper half of a float32
     u32x4 w;
@@ -1183,6 +1183,15 @@ template <> struct WStore<TGRAD_CBF16> {
   }
 };
 __device__ __forceinline__ void claim_raw(uint4& r) { asm volatile("" : "+v"(r.x), "+v"(r.y), "+v"(r.z), "+v"(r.w)); }
+typedef float f32x4nt __attribute__((ext_vector_type(4)));
+template <typename R>
+__device__ __forceinline__ R nt_load(const R* p) {
+  return __builtin_bit_cast(R, __builtin_nontemporal_load(reinterpret_cast<const f32x4nt*>(p)));
+}
+template <typename R>
+__device__ __forceinline__ void nt_store(R* p, const R& v) {
+  __builtin_nontemporal_store(__builtin_bit_cast(f32x4nt, v), reinterpret_cast<f32x4nt*>(p));
+}
 
 template <int WDT, int W, int NTB, int JT, int UP>
 __global__ __launch_bounds__(64 * W, 2) void k_lupdate(const float* __restrict__ z,
@@ -1509,7 +1518,7 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate_fused(const float2* __res
 #pragma unroll
     for (int i = 0; i < kPre; ++i) {
       const int q = lane_now + i * 64;
-      wpre[i] = w4[q < n4 ? q : n4 - 1];
+      wpre[i] = nt_load(&w4[q < n4 ? q : n4 - 1]);
     }
     // The stage-A operands are claimed here: the asm statements pin every load above them (memory
     // clobber) and every use below them, so the scheduler cannot interleave load - wait - MFMA.
@@ -1624,7 +1633,7 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate_fused(const float2* __res
 #pragma unroll
     for (int i = 0; i < kPre; ++i) {
       const int q = lane_now + i * 64;
-      if (i < nfull || q < n4) w4[q] = WS::apply(wpre[i], sD, q, decay);
+      if (i < nfull || q < n4) nt_store(&w4[q], WS::apply(wpre[i], sD, q, decay));
     }
     for (int q = lane + kPre * 64; q < n4; q += 64) w4[q] = WS::apply(w4[q], sD, q, decay);
     if (!have_next) break;
