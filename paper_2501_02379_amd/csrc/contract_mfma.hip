@@ -477,9 +477,27 @@ template <int DT> struct RawPair;
 template <> struct RawPair<TGRAD_C64> { typedef float4 type; };
 template <> struct RawPair<TGRAD_CBF16> { typedef uint2 type; };
 
+// Streaming accesses.  G is read once per step and W is read and written once per step; marked
+// non-temporal they neither push the small reused operands (factor tables, intermediate tensors) out
+// of the caches nor leave a cache full of dirty lines behind for the next kernel to wait on.
+typedef float f32x4nt __attribute__((ext_vector_type(4)));
+typedef float f32x2nt __attribute__((ext_vector_type(2)));
+template <typename R>
+__device__ __forceinline__ R nt_load(const R* p) {
+  if constexpr (sizeof(R) == 16)
+    return __builtin_bit_cast(R, __builtin_nontemporal_load(reinterpret_cast<const f32x4nt*>(p)));
+  else
+    return __builtin_bit_cast(R, __builtin_nontemporal_load(reinterpret_cast<const f32x2nt*>(p)));
+}
+template <typename R>
+__device__ __forceinline__ void nt_store(R* p, const R& v) {
+  static_assert(sizeof(R) == 16, "16-byte pieces");
+  __builtin_nontemporal_store(__builtin_bit_cast(f32x4nt, v), reinterpret_cast<f32x4nt*>(p));
+}
+
 template <int DT>
 __device__ __forceinline__ typename RawPair<DT>::type load_raw_pair(const void* g, int64_t p) {
-  return reinterpret_cast<const typename RawPair<DT>::type*>(g)[p];
+  return nt_load(reinterpret_cast<const typename RawPair<DT>::type*>(g) + p);
 }
 template <int DT>
 __device__ __forceinline__ void decode_raw(const typename RawPair<DT>::type& raw, float2& e0, float2& e1) {
@@ -1183,15 +1201,6 @@ template <> struct WStore<TGRAD_CBF16> {
   }
 };
 __device__ __forceinline__ void claim_raw(uint4& r) { asm volatile("" : "+v"(r.x), "+v"(r.y), "+v"(r.z), "+v"(r.w)); }
-typedef float f32x4nt __attribute__((ext_vector_type(4)));
-template <typename R>
-__device__ __forceinline__ R nt_load(const R* p) {
-  return __builtin_bit_cast(R, __builtin_nontemporal_load(reinterpret_cast<const f32x4nt*>(p)));
-}
-template <typename R>
-__device__ __forceinline__ void nt_store(R* p, const R& v) {
-  __builtin_nontemporal_store(__builtin_bit_cast(f32x4nt, v), reinterpret_cast<f32x4nt*>(p));
-}
 
 template <int WDT, int W, int NTB, int JT, int UP>
 __global__ __launch_bounds__(64 * W, 2) void k_lupdate(const float* __restrict__ z,
@@ -1297,7 +1306,7 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate(const float* __restrict__
 #pragma unroll                                                 // piece (the host keeps n4 >= 1 for every tile)
     for (int i = 0; i < kPre; ++i) {
       const int q = lane_now + i * 64;
-      wpre[i] = w4[q < n4 ? q : n4 - 1];
+      wpre[i] = nt_load(&w4[q < n4 ? q : n4 - 1]);
     }
     wave_sync();                                               // previous tile's LDS reads are done
     // ---- expand the 32 rows: sD[row, c] = sum_k (c_alpha U)[c, k] z[row, k], NTB column tiles at a time ----
@@ -1361,7 +1370,7 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate(const float* __restrict__
 #pragma unroll
     for (int i = 0; i < kPre; ++i) {
       const int q = lane_now + i * 64;
-      if (i < nfull || q < n4) w4[q] = WS::apply(wpre[i], sD, q, decay);
+      if (i < nfull || q < n4) nt_store(&w4[q], WS::apply(wpre[i], sD, q, decay));
     }
     for (int q = lane + kPre * 64; q < n4; q += 64) w4[q] = WS::apply(w4[q], sD, q, decay);
     {                                                          // elements past the last whole piece
