@@ -1201,6 +1201,32 @@ template <> struct WStore<TGRAD_CBF16> {
   }
 };
 __device__ __forceinline__ void claim_raw(uint4& r) { asm volatile("" : "+v"(r.x), "+v"(r.y), "+v"(r.z), "+v"(r.w)); }
+// 16-byte pieces of W through a buffer descriptor (range-checked by the hardware: no clamps, no lane
+// masks), non-temporal
+__device__ __forceinline__ void buffer_piece_load(float4& d, __amdgpu_buffer_rsrc_t r, int voff) {
+  const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, voff, 0, 2);
+  d = make_float4(__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w));
+}
+__device__ __forceinline__ void buffer_piece_load(uint4& d, __amdgpu_buffer_rsrc_t r, int voff) {
+  const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, voff, 0, 2);
+  d = make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void buffer_piece_store(const float4& d, __amdgpu_buffer_rsrc_t r, int voff) {
+  u32x4 v;
+  v.x = __float_as_uint(d.x);
+  v.y = __float_as_uint(d.y);
+  v.z = __float_as_uint(d.z);
+  v.w = __float_as_uint(d.w);
+  __builtin_amdgcn_raw_buffer_store_b128(v, r, voff, 0, 2);
+}
+__device__ __forceinline__ void buffer_piece_store(const uint4& d, __amdgpu_buffer_rsrc_t r, int voff) {
+  u32x4 v;
+  v.x = d.x;
+  v.y = d.y;
+  v.z = d.z;
+  v.w = d.w;
+  __builtin_amdgcn_raw_buffer_store_b128(v, r, voff, 0, 2);
+}
 
 template <int WDT, int W, int NTB, int JT, int UP>
 __global__ __launch_bounds__(64 * W, 2) void k_lupdate(const float* __restrict__ z,
@@ -1471,6 +1497,17 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate_fused(const float2* __res
   };
 
   const int vzero = opaque_zero();
+  // W goes through buffer descriptors (one per 4 pieces), range-checked by the hardware: no clamps
+  // and no lane masks in the streaming phase.  Bytes of a tile from the first piece of each group on:
+  constexpr int kWGroups = (kPre + 3) / 4;
+  const uint32_t w_tile_bytes = (uint32_t)tile_w * (uint32_t)(16 / WS::kElems);
+  uint32_t w_rest[kWGroups];
+#pragma unroll
+  for (int k = 0; k < kWGroups; ++k) {
+    const uint32_t done = (uint32_t)(k * 4 * 64 * 16);
+    w_rest[k] = __builtin_amdgcn_readfirstlane(w_tile_bytes > done ? w_tile_bytes - done : 0u);
+  }
+  const int voff_w = lane * 16;
   int64_t tile = slab * S;
   int64_t nslab = slab;
   int nts = ts;
@@ -1524,10 +1561,12 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate_fused(const float2* __res
     }
     // ---- this tile's W pieces go in flight ----
     wraw wpre[kPre];
+    const char* w_tile = reinterpret_cast<const char*>(w4);
 #pragma unroll
-    for (int i = 0; i < kPre; ++i) {
-      const int q = lane_now + i * 64;
-      wpre[i] = nt_load(&w4[q < n4 ? q : n4 - 1]);
+    for (int k = 0; k < kWGroups; ++k) {                       // a descriptor per 4 pieces: immediates reach 4 KB
+      const __amdgpu_buffer_rsrc_t r = raw_buffer(w_tile + k * 4 * 64 * 16, w_rest[k]);
+#pragma unroll
+      for (int i = 4 * k; i < 4 * k + 4 && i < kPre; ++i) buffer_piece_load(wpre[i], r, voff_w + (i - 4 * k) * 64 * 16);
     }
     // The stage-A operands are claimed here: the asm statements pin every load above them (memory
     // clobber) and every use below them, so the scheduler cannot interleave load - wait - MFMA.
@@ -1638,11 +1677,14 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate_fused(const float2* __res
     claim_sparse();
 #pragma unroll
     for (int i = 0; i < kPre; ++i) claim_raw(wpre[i]);
-    const int nfull = n4 >> 6;
 #pragma unroll
-    for (int i = 0; i < kPre; ++i) {
-      const int q = lane_now + i * 64;
-      if (i < nfull || q < n4) nt_store(&w4[q], WS::apply(wpre[i], sD, q, decay));
+    for (int k = 0; k < kWGroups; ++k) {                       // (pieces past the tile's end are dropped by the range check)
+      const __amdgpu_buffer_rsrc_t r = raw_buffer(w_tile + k * 4 * 64 * 16, w_rest[k]);
+#pragma unroll
+      for (int i = 4 * k; i < 4 * k + 4 && i < kPre; ++i) {
+        const int q = lane_now + i * 64;                       // (the LDS read stays inside the tile)
+        buffer_piece_store(WS::apply(wpre[i], sD, q < n4 ? q : n4 - 1, decay), r, voff_w + (i - 4 * k) * 64 * 16);
+      }
     }
     for (int q = lane + kPre * 64; q < n4; q += 64) w4[q] = WS::apply(w4[q], sD, q, decay);
     if (!have_next) break;
