@@ -49,7 +49,13 @@ the design notes of this repository):
 * The gradient argument is the ordinary gradient dphi/dW; the paper's
   G = -grad and W <- W + eta * G~ is the same update because every operation
   applied to G is odd.
-* AdamW decay is decoupled: W <- W (1 - lr wd) - lr * D.
+* AdamW decay is decoupled: W <- W (1 - lr wd) - lr * D (pinned to torch.optim.AdamW).
+* The appendix algorithm "Adam with low-rank tensor decomposition" assigns the
+  bias-corrected moments to the same symbols M_t, V_t it carries to the next
+  step.  Read literally that would divide the stored moments by (1 - beta^t)
+  again at every step; it is read here as standard Adam: the corrected values
+  are temporaries of the step, the stored moments are the raw ones (this is what
+  torch.optim.Adam does, which pins `adam_update` over several steps).
 * Composition orders other than Algorithm 1's (paragraph "Residual and
   composition", ablation on combinations): "lr_us" compresses the full gradient
   to low rank first and gives the sparse part the residual of that low-rank
