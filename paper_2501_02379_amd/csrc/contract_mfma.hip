@@ -25,7 +25,7 @@
 // Operand layout of v_mfma_f32_32x32x2f32 (D = A B + C, A 32 x 2, B 2 x 32, 64 lanes):
 //   lane l supplies A[l % 32][l / 32] and B[l / 32][l % 32];
 //   register r of lane l receives D[(r % 4) + 8 (r / 4) + 4 (l / 32)][l % 32].
-#include <cstdlib>
+#include <atomic>
 #include <map>
 #include <mutex>
 #include <type_traits>
@@ -1770,8 +1770,21 @@ int resident_blocks(Kern kern, int threads, size_t lds) {
   return nb;
 }
 
+// Compute units of the current device (256 on an MI355X), asked of the runtime once per device.
+int compute_units() {
+  constexpr int kMaxDev = 64;
+  static std::atomic<int> cached[kMaxDev];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDev) dev = 0;
+  int n = cached[dev].load(std::memory_order_relaxed);
+  if (n > 0) return n;
+  if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
+  cached[dev].store(n, std::memory_order_relaxed);
+  return n;
+}
+
 int grid_for_tiles(int64_t ntiles, int blocks_per_cu) {
-  const int64_t cap = (int64_t)256 * blocks_per_cu;
+  const int64_t cap = (int64_t)compute_units() * blocks_per_cu;
   return (int)(ntiles < cap ? ntiles : cap);
 }
 
@@ -1840,7 +1853,7 @@ void launch_mid(hipStream_t s, const float2* x, const float2* U, int rn, bool pr
   const int mt0 = M > 32 ? 2 : 1;
   const int64_t wgs0 = ((ncv + 127) / 128) * ((M + 32 * mt0 - 1) / (32 * mt0));
   int mode = 0;
-  if (wgs0 < 256) mode = M > 32 ? 2 : 1;
+  if (wgs0 < compute_units()) mode = M > 32 ? 2 : 1;
   const int mt = mode == 0 ? mt0 : 1;
   const int tl = mode == 2 ? 4 : mt;
   const int64_t gx = mode == 0 ? (ncv + 127) / 128 : (ncv + 31) / 32;
@@ -1968,9 +1981,8 @@ void launch_lproj(hipStream_t s, const void* g, int dtype, const int32_t* omega,
     else if (tb == 5) TGRAD_LPF_C(DT_, kCoefPairsShort, 5);                                              \
     else TGRAD_LPF_C(DT_, kCoefPairsShort, 9);                                                           \
   } while (0)
-  static const bool no_flat = [] { const char* e = getenv("TGRAD_LPROJ_FLAT"); return e && e[0] == '0'; }();
   const int cp = (K + 1) / 2 > kCoefPairsShort ? kCoefPairs : kCoefPairsShort;
-  if (fuse && (K & 1) && !no_flat && tb * 64 >= 16 * K && 62 * K + 4 * cp <= tb * 256) {   // odd last extent: the staging phase without vector ALU work
+  if (fuse && (K & 1) && tb * 64 >= 16 * K && 62 * K + 4 * cp <= tb * 256) {   // odd last extent: the staging phase without vector ALU work
     if (dtype == TGRAD_C64) TGRAD_LPF(TGRAD_C64); else TGRAD_LPF(TGRAD_CBF16);
   } else if (fuse) {                            // the host only fuses with W == 4 and one column tile
     if (dtype == TGRAD_C64) {

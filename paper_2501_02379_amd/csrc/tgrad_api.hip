@@ -2,7 +2,6 @@
 // caller's state / workspace buffers, and the sequencing of kernels on the caller's stream for
 // the two branches of Algorithm 1 (refresh and step).
 #include <cmath>
-#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -163,10 +162,8 @@ void make_plan(const tgrad_config* c, Plan* p) {
   p->nseg = (p->I + kSegElems - 1) / kSegElems;
   p->mask_words = (p->I + 31) / 32;
   {
-    int prefer = 4;
-    if (const char* e = std::getenv("TGRAD_TILE_WAVES")) prefer = std::atoi(e);   // tuning knob: 0, 1, 2, 4
     const int last = N - 1;
-    p->tile_waves = prefer > 0 ? choose_tile_waves((int)p->shape[last], p->rank[last], prefer) : 0;
+    p->tile_waves = choose_tile_waves((int)p->shape[last], p->rank[last], 4);
     if (c->weight_dtype == TGRAD_CBF16 && p->I < 4) p->tile_waves = 0;   // a bf16 tile needs one whole 16-byte piece
     const int64_t rows = p->I / p->shape[last];
     p->ntiles = (rows + 31) / 32;                 // last-mode kernels: flat tiles of 32 rows
@@ -174,16 +171,13 @@ void make_plan(const tgrad_config* c, Plan* p) {
     // Fusion of the mode-(N-1) stages into the last-mode kernels: needs whole 32-row tiles per slab,
     // one column tile of the last mode (r_N <= 16), r_(N-1) <= 32, and enough slabs to fill the chip.
     bool fuse = p->tile_waves == 4 && N >= 3;
-    if (const char* e = std::getenv("TGRAD_FUSE")) fuse = fuse && std::atoi(e) != 0;       // tuning knob
     if (fuse) {
       const int64_t I2 = p->shape[last - 1];
       fuse = (I2 % 32 == 0) && I2 <= TGRAD_MAX_EXTENT && p->rank[last - 1] <= 32 && 2 * p->rank[last] <= 32 &&
              rows / I2 >= 512 && p->shape[last] <= fused_max_last_extent();
     }
     p->fuse_next = fuse;
-    bool fc = core_kernel_fits((int)p->shape[0], p->rank[0]);
-    if (const char* e = std::getenv("TGRAD_FUSE_CORE")) fc = fc && std::atoi(e) != 0;     // tuning knob
-    p->fuse_core = fc;
+    p->fuse_core = core_kernel_fits((int)p->shape[0], p->rank[0]);
   }
 
   size_t o = 0;

@@ -20,10 +20,53 @@ def rel_err(a: np.ndarray, b: np.ndarray) -> float:
     return float(np.linalg.norm(np.asarray(a, dtype=np.complex128) - b) / (den if den > 0 else 1.0))
 
 
+def max_abs_err(a: np.ndarray, b: np.ndarray) -> float:
+    return float(np.max(np.abs(np.asarray(a, dtype=np.complex128) - b))) if np.size(b) else 0.0
+
+
+# Element-wise bar on the update.  One step moves an entry by lr * |D| with |D| of order one (Adam's
+# normalised direction), so an entry that is wrong in kind - a mis-scattered sparse value, a tile
+# column from the wrong slab, a missed decay - is off by about lr; float32 arithmetic against the
+# float64 oracle leaves about 1e-6 * lr per step.  1e-2 * lr * sqrt(steps) separates the two by
+# orders of magnitude on both sides.
+ENTRY_TOL = 1e-2
+W_TOL = 1e-4          # || W_g - W_o ||_F / || W_o ||_F   (the stated bar)
+DW_TOL = 1e-4         # the same on W_t - W_0: sensitive to the optimizer and not to W_0
+
+
+def check_parity(info, W0, moments=True):
+    """Weights as tensors (Frobenius, on W and on W - W0) AND entry by entry; Adam moments entry by
+    entry relative to their largest entry."""
+    Wg = np.asarray(info["W_gpu"], dtype=np.complex128)
+    Wo = info["W_oracle"]
+    lr, steps = info["lr"], info["steps"]
+    assert np.all(np.isfinite(Wg.view(np.float64)))
+    assert rel_err(Wg, Wo) < W_TOL
+    dg, do = Wg - W0, Wo - W0
+    assert rel_err(dg, do) < DW_TOL, rel_err(dg, do)
+    worst = max_abs_err(dg, do)
+    assert worst <= ENTRY_TOL * lr * max(1.0, np.sqrt(steps)), worst
+    if moments:
+        from paper_2501_02379_amd import tgrad as T
+        ctx, st = info["ctx"], info["state"]
+        for what, ref in ((T.STATE_CORE_M, st.M_L), (T.STATE_CORE_V, st.V_L),
+                          (T.STATE_SPARSE_M, st.M_S), (T.STATE_SPARSE_V, st.V_S)):
+            if ref.size == 0:
+                continue
+            got = ctx.tgrad_get_state(what).astype(ref.dtype)
+            scale = float(np.max(np.abs(ref)))
+            assert max_abs_err(got, ref) <= 1e-4 * scale + 1e-30, (what, max_abs_err(got, ref), scale)
+
+
 def oracle_hyper(shape, ranks, k, **kw) -> O.Hyper:
-    return O.Hyper(ranks=tuple(ranks), k=int(k), lr=kw.get("lr", 1e-3), beta1=kw.get("beta1", 0.9),
-                   beta2=kw.get("beta2", 0.999), eps=kw.get("eps", 1e-8), alpha=kw.get("alpha", 1.0),
-                   lam=kw.get("lam", 1.0), weight_decay=kw.get("weight_decay", 0.0),
+    """The oracle's hyper-parameters for a library configuration.  The ABI carries lr, the decay
+    rates, eps, alpha, lambda and the weight decay as float32, so the oracle is given exactly those
+    values (as float64 numbers): both sides then solve the same problem."""
+    def f32(name, default):
+        return float(np.float32(kw.get(name, default)))
+    return O.Hyper(ranks=tuple(ranks), k=int(k), lr=f32("lr", 1e-3), beta1=f32("beta1", 0.9),
+                   beta2=f32("beta2", 0.999), eps=f32("eps", 1e-8), alpha=f32("alpha", 1.0),
+                   lam=f32("lam", 1.0), weight_decay=f32("weight_decay", 0.0),
                    T=kw.get("refresh_every", 1), hooi_sweeps=kw.get("hooi_sweeps", 0),
                    warm_restart=bool(kw.get("warm_restart", False)),
                    order={0: "us_lr", 1: "lr_us", 2: "sum"}[kw.get("order", 0)],
@@ -45,8 +88,9 @@ def run_both(T, shape, ranks, k, grads, W0, grad_dtype=0, check_every_refresh=Tr
     Wd = T.to_device_weight(W0)
     Wo = W0.astype(np.complex128)
     Tper = kw.get("refresh_every", 1)
-    info = {"omega_equal": [], "proj_dist": []}
+    info = {"omega_equal": [], "proj_dist": [], "lr": kw.get("lr", 1e-3), "steps": 0}
     for t, g in enumerate(grads):
+        info["steps"] = t + 1
         gd = T.to_device_grad(g)
         ctx.tgrad_step(Wd, gd)
         Wo = O.step(st, Wo, g)
