@@ -4,13 +4,25 @@
 //
 // Order: (|g|^2 descending, linear index ascending); Omega is written ascending.
 //
-// Method: most-significant-digit radix select on the 32-bit pattern of the float32 key
-// (digits of 12, 12 and 8 bits -> three histogram passes), which yields the key T of the k-th
-// largest entry and the number `need_eq` of entries equal to T that belong to the support (the
-// ones with the lowest indices).  A count pass and an emit pass then place every selected entry:
-// the position of entry i inside Omega is
-//     #(key > T before i) + min(#(key == T before i), need_eq),
-// so two independent exclusive prefix counts are enough and no atomics decide an output slot.
+// Method: most-significant-digit radix select on the 32-bit pattern of the float32 key (digits of
+// 12, 12 and 8 bits), arranged so that the gradient is streamed only TWICE:
+//   1. k_select_hist    reads G: histogram of the leading 12 key bits -> the bin b1 that holds the
+//                       k-th largest key.
+//   2. k_select_split   reads G: one bit per element into two bitmasks: "sure" (leading digit above
+//                       b1: certainly in the support) and "cand" (leading digit equal to b1: the
+//                       candidates among which the remaining digits decide).
+//   3. k_select_hist_cand (twice) walks the candidate mask and fetches only the candidates' keys:
+//                       histograms of the middle 12 and the last 8 bits -> the key T of the k-th
+//                       largest entry and the number `need_eq` of entries equal to T that belong to
+//                       the support (the ones with the lowest indices).
+//   4. k_select_count / k_select_scan / k_select_emit walk the two masks (and the candidates' keys):
+//                       the position of entry i inside Omega is
+//                           #(key > T before i) + min(#(key == T before i), need_eq),
+//                       two exclusive prefix counts, so no atomics decide an output slot.  The emit
+//                       kernel also turns the "sure" mask into the support bitmask.
+// The candidates are the entries of ONE of 4096 key bins (16 per octave of |g|^2), a fraction of a
+// percent of the tensor for any smooth distribution; on a degenerate input (all keys equal) every
+// element is a candidate and steps 3 and 4 read all of G through the same code, only slower.
 // Everything is integer work: the result is bit-exact and run-to-run deterministic.
 //
 // Uniform random selection (rand-k, the alternative rule the same section names) runs through the
@@ -27,6 +39,7 @@ constexpr int kSelThreads = 256;
 constexpr int kWavesPerBlock = kSelThreads / kWave;
 constexpr int kPairsPerIter = kWave;                       // one pair (2 elements) per lane
 constexpr int kSegIters = kSegElems / (2 * kPairsPerIter); // 16 iterations of 128 elements
+constexpr int kChunkWords = kSelChunkElems / 32;           // mask words one wavefront counts / emits in order
 
 __device__ __forceinline__ uint32_t digit_of(uint32_t key, int pass) {
   return pass == 0 ? (key >> 20) : pass == 1 ? ((key >> 8) & 0xFFFu) : (key & 0xFFu);
@@ -73,27 +86,22 @@ __device__ __forceinline__ uint32_t elem_key(const KeySource& src, int64_t i) {
     return select_key(load_elem<KS>(src.g, i));
 }
 
+// Histogram of the leading 12 key bits of every element.
 template <int DT>
 __global__ __launch_bounds__(kSelThreads) void k_select_hist(const KeySource g, int64_t I,
-                                                             int pass,
-                                                             const SelectScalars* __restrict__ sc,
                                                              uint32_t* __restrict__ hist) {
   __shared__ uint32_t h[kHistBins];
   for (int b = threadIdx.x; b < kHistBins; b += kSelThreads) h[b] = 0;
   __syncthreads();
-  const uint32_t prefix = pass == 0 ? 0u : sc->prefix;
   const int64_t npairs = I >> 1;
   const int64_t stride = (int64_t)gridDim.x * kSelThreads;
   for (int64_t p = (int64_t)blockIdx.x * kSelThreads + threadIdx.x; p < npairs; p += stride) {
     uint32_t k0, k1;
     pair_keys<DT>(g, p, k0, k1);
-    if (in_prefix(k0, pass, prefix)) atomicAdd(&h[digit_of(k0, pass)], 1u);
-    if (in_prefix(k1, pass, prefix)) atomicAdd(&h[digit_of(k1, pass)], 1u);
+    atomicAdd(&h[digit_of(k0, 0)], 1u);
+    atomicAdd(&h[digit_of(k1, 0)], 1u);
   }
-  if ((I & 1) && blockIdx.x == 0 && threadIdx.x == 0) {
-    uint32_t k0 = elem_key<DT>(g, I - 1);
-    if (in_prefix(k0, pass, prefix)) atomicAdd(&h[digit_of(k0, pass)], 1u);
-  }
+  if ((I & 1) && blockIdx.x == 0 && threadIdx.x == 0) atomicAdd(&h[digit_of(elem_key<DT>(g, I - 1), 0)], 1u);
   __syncthreads();
   for (int b = threadIdx.x; b < kHistBins; b += kSelThreads)
     if (h[b]) atomicAdd(&hist[b], h[b]);
@@ -139,7 +147,7 @@ __global__ __launch_bounds__(1024) void k_select_pick(int pass, uint32_t k, Sele
   }
 }
 
-// Flags of the (up to) two elements a lane holds in iteration `it` of segment `seg`.
+// Keys of the (up to) two elements a lane holds in iteration `it` of segment `seg`.
 template <int DT>
 __device__ __forceinline__ void seg_keys(const KeySource& g, int64_t I, int64_t seg, int it, int lane,
                                          int64_t& i0, bool& v0, bool& v1, uint32_t& k0, uint32_t& k1) {
@@ -155,32 +163,123 @@ __device__ __forceinline__ void seg_keys(const KeySource& g, int64_t I, int64_t 
   }
 }
 
+// Spread the low 16 bits of x to the even bit positions of a 32-bit word.
+__device__ __forceinline__ uint32_t spread16(uint32_t x) {
+  x &= 0xFFFFu;
+  x = (x | (x << 8)) & 0x00FF00FFu;
+  x = (x | (x << 4)) & 0x0F0F0F0Fu;
+  x = (x | (x << 2)) & 0x33333333u;
+  x = (x | (x << 1)) & 0x55555555u;
+  return x;
+}
+
+// One bit per element into the two masks (bit b of word w = element 32 w + b): `sure` where the
+// leading key digit lies above the bin b1 of the first pick, `cand` where it equals b1.  Bits past
+// the end of the tensor are written as zero; every word that covers an element is written.
 template <int DT>
-__global__ __launch_bounds__(kSelThreads) void k_select_count(const KeySource g, int64_t I,
+__global__ __launch_bounds__(kSelThreads) void k_select_split(const KeySource g, int64_t I,
                                                               const SelectScalars* __restrict__ sc,
-                                                              uint32_t* __restrict__ seg_gt,
-                                                              uint32_t* __restrict__ seg_eq,
-                                                              int64_t nseg) {
+                                                              uint32_t* __restrict__ sure,
+                                                              uint32_t* __restrict__ cand, int64_t nseg) {
   const int lane = lane_id();
   const int64_t seg = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x / kWave);
   if (seg >= nseg) return;                           // whole wave leaves together
-  const uint32_t T = sc->threshold;
-  uint32_t ngt = 0, neq = 0;
+  const uint32_t b1 = sc->prefix;                    // after the first pick: the leading digit of T
   for (int it = 0; it < kSegIters; ++it) {
     int64_t i0;
     bool v0, v1;
     uint32_t k0, k1;
     seg_keys<DT>(g, I, seg, it, lane, i0, v0, v1, k0, k1);
-    ngt += __popcll(__ballot(v0 && k0 > T)) + __popcll(__ballot(v1 && k1 > T));
-    neq += __popcll(__ballot(v0 && k0 == T)) + __popcll(__ballot(v1 && k1 == T));
-  }
-  if (lane == 0) {
-    seg_gt[seg] = ngt;
-    seg_eq[seg] = neq;
+    const uint32_t d0 = k0 >> 20, d1 = k1 >> 20;
+    const uint64_t S0 = __ballot(v0 && d0 > b1), S1 = __ballot(v1 && d1 > b1);
+    const uint64_t C0 = __ballot(v0 && d0 == b1), C1 = __ballot(v1 && d1 == b1);
+    if ((lane & 15) == 0 && i0 < I) {
+      sure[i0 >> 5] = spread16((uint32_t)(S0 >> lane)) | (spread16((uint32_t)(S1 >> lane)) << 1);
+      cand[i0 >> 5] = spread16((uint32_t)(C0 >> lane)) | (spread16((uint32_t)(C1 >> lane)) << 1);
+    }
   }
 }
 
-// In-place exclusive prefix sums of both per-segment count arrays; one block of 16 wavefronts.
+// Histogram of the next digit over the candidates only (pass 1: bits 19..8 of the keys whose
+// leading digit is the picked one - every candidate; pass 2: bits 7..0 of the keys whose leading
+// 24 bits are the picked ones).  A lane owns one mask word per iteration and fetches the keys of
+// its set bits.
+template <int DT>
+__global__ __launch_bounds__(kSelThreads) void k_select_hist_cand(const KeySource g, int pass,
+                                                                  const SelectScalars* __restrict__ sc,
+                                                                  const uint32_t* __restrict__ cand,
+                                                                  int64_t nwords, uint32_t* __restrict__ hist) {
+  __shared__ uint32_t h[kHistBins];
+  for (int b = threadIdx.x; b < kHistBins; b += kSelThreads) h[b] = 0;
+  __syncthreads();
+  const uint32_t prefix = sc->prefix;
+  const int64_t stride = (int64_t)gridDim.x * kSelThreads;
+  for (int64_t w = (int64_t)blockIdx.x * kSelThreads + threadIdx.x; w < nwords; w += stride) {
+    uint32_t c = cand[w];
+    while (c) {
+      const int b = __builtin_ctz(c);
+      c &= c - 1u;
+      const uint32_t key = elem_key<DT>(g, (w << 5) + b);
+      if (in_prefix(key, pass, prefix)) atomicAdd(&h[digit_of(key, pass)], 1u);
+    }
+  }
+  __syncthreads();
+  for (int b = threadIdx.x; b < kHistBins; b += kSelThreads)
+    if (h[b]) atomicAdd(&hist[b], h[b]);
+}
+
+__device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
+#pragma unroll
+  for (int off = kWave / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+  return v;
+}
+
+// Candidate bits of one mask word sorted by their key against the threshold T.
+template <int DT>
+__device__ __forceinline__ void classify_candidates(const KeySource& g, int64_t w, uint32_t c, uint32_t T,
+                                                    uint32_t& above, uint32_t& equal) {
+  above = 0u;
+  equal = 0u;
+  while (c) {
+    const int b = __builtin_ctz(c);
+    c &= c - 1u;
+    const uint32_t key = elem_key<DT>(g, (w << 5) + b);
+    if (key > T) above |= 1u << b;
+    else if (key == T) equal |= 1u << b;
+  }
+}
+
+// Per chunk of kChunkWords mask words (one wavefront each): entries above T and entries equal to T.
+template <int DT>
+__global__ __launch_bounds__(kSelThreads) void k_select_count(const KeySource g,
+                                                              const SelectScalars* __restrict__ sc,
+                                                              const uint32_t* __restrict__ sure,
+                                                              const uint32_t* __restrict__ cand, int64_t nwords,
+                                                              uint32_t* __restrict__ chunk_gt,
+                                                              uint32_t* __restrict__ chunk_eq, int64_t nchunks) {
+  const int lane = lane_id();
+  const int64_t chunk = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x / kWave);
+  if (chunk >= nchunks) return;
+  const uint32_t T = sc->threshold;
+  uint32_t ngt = 0, neq = 0;
+  for (int it = 0; it < kChunkWords / kWave; ++it) {
+    const int64_t w = chunk * kChunkWords + (int64_t)it * kWave + lane;
+    if (w < nwords) {
+      uint32_t above, equal;
+      classify_candidates<DT>(g, w, cand[w], T, above, equal);
+      ngt += __popc(sure[w]) + __popc(above);
+      neq += __popc(equal);
+    }
+  }
+  ngt = wave_sum(ngt);
+  neq = wave_sum(neq);
+  if (lane == 0) {
+    chunk_gt[chunk] = ngt;
+    chunk_eq[chunk] = neq;
+  }
+}
+
+// In-place exclusive prefix sums of both per-chunk count arrays; one block of 16 wavefronts.
 // Wavefront w owns the contiguous range [w * per, (w + 1) * per): it first adds the range up
 // (coalesced 64-entry reads), the 16 totals are scanned through LDS, then the range is walked again
 // and every 64-entry group is scanned with lane shuffles on top of the running offset.
@@ -230,64 +329,55 @@ __global__ __launch_bounds__(1024) void k_select_scan(uint32_t* seg_gt, uint32_t
   }
 }
 
-// Spread the low 16 bits of x to the even bit positions of a 32-bit word.
-__device__ __forceinline__ uint32_t spread16(uint32_t x) {
-  x &= 0xFFFFu;
-  x = (x | (x << 8)) & 0x00FF00FFu;
-  x = (x | (x << 4)) & 0x0F0F0F0Fu;
-  x = (x | (x << 2)) & 0x33333333u;
-  x = (x | (x << 1)) & 0x55555555u;
-  return x;
-}
-
+// Ordered compaction: a wavefront walks its chunk of mask words in index order (lane = word inside
+// a group of 64, bits ascending inside a word) and writes every selected index to its final slot.
+// `sure` comes in as the mask of the entries whose leading digit lies above the picked bin and goes
+// out as the support bitmask (those, the candidates above T and the first need_eq candidates equal
+// to T).
 template <int DT>
-__global__ __launch_bounds__(kSelThreads) void k_select_emit(const KeySource g, int64_t I,
+__global__ __launch_bounds__(kSelThreads) void k_select_emit(const KeySource g,
                                                              const SelectScalars* __restrict__ sc,
-                                                             const uint32_t* __restrict__ seg_gt,
-                                                             const uint32_t* __restrict__ seg_eq,
-                                                             int64_t nseg, int32_t* __restrict__ omega,
-                                                             uint32_t* __restrict__ mask) {
+                                                             const uint32_t* __restrict__ chunk_gt,
+                                                             const uint32_t* __restrict__ chunk_eq,
+                                                             int64_t nchunks, uint32_t* __restrict__ sure,
+                                                             const uint32_t* __restrict__ cand, int64_t nwords,
+                                                             int32_t* __restrict__ omega) {
   const int lane = lane_id();
-  const int64_t seg = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x / kWave);
-  if (seg >= nseg) return;
+  const int64_t chunk = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x / kWave);
+  if (chunk >= nchunks) return;
   const uint32_t T = sc->threshold;
   const uint32_t need = sc->need_eq;
-  uint32_t run_gt = seg_gt[seg], run_eq = seg_eq[seg];
-  for (int it = 0; it < kSegIters; ++it) {
-    int64_t i0;
-    bool v0, v1;
-    uint32_t k0, k1;
-    seg_keys<DT>(g, I, seg, it, lane, i0, v0, v1, k0, k1);
-    const bool g0 = v0 && k0 > T, g1 = v1 && k1 > T;
-    const bool e0 = v0 && k0 == T, e1 = v1 && k1 == T;
-    const uint64_t Bg0 = __ballot(g0), Bg1 = __ballot(g1), Be0 = __ballot(e0), Be1 = __ballot(e1);
-    // entries before element i0 (in index order: lower lanes hold lower indices)
-    uint32_t gtb = run_gt + popc_below(Bg0, lane) + popc_below(Bg1, lane);
-    uint32_t eqb = run_eq + popc_below(Be0, lane) + popc_below(Be1, lane);
-    bool s0 = false, s1 = false;
-    if (g0) {
-      s0 = true;
-      omega[gtb + (eqb < need ? eqb : need)] = (int32_t)i0;
-    } else if (e0 && eqb < need) {
-      s0 = true;
-      omega[gtb + eqb] = (int32_t)i0;
+  uint32_t run_gt = chunk_gt[chunk], run_eq = chunk_eq[chunk];
+  for (int it = 0; it < kChunkWords / kWave; ++it) {
+    const int64_t w = chunk * kChunkWords + (int64_t)it * kWave + lane;
+    uint32_t take = 0u, equal = 0u;                   // bits taken for certain; bits equal to T
+    if (w < nwords) {
+      uint32_t above;
+      classify_candidates<DT>(g, w, cand[w], T, above, equal);
+      take = sure[w] | above;
     }
-    gtb += g0 ? 1u : 0u;                               // element i0 + 1 comes after element i0
-    eqb += e0 ? 1u : 0u;
-    if (g1) {
-      s1 = true;
-      omega[gtb + (eqb < need ? eqb : need)] = (int32_t)(i0 + 1);
-    } else if (e1 && eqb < need) {
-      s1 = true;
-      omega[gtb + eqb] = (int32_t)(i0 + 1);
+    const uint32_t ng = __popc(take), ne = __popc(equal);
+    const uint32_t sg = wave_inclusive_scan(ng, lane), se = wave_inclusive_scan(ne, lane);
+    uint32_t gtb = run_gt + sg - ng, eqb = run_eq + se - ne;   // entries before this word
+    uint32_t todo = take | equal, chosen = take;
+    while (todo) {
+      const int b = __builtin_ctz(todo);
+      todo &= todo - 1u;
+      const int32_t idx = (int32_t)((w << 5) + b);
+      if (take & (1u << b)) {
+        omega[gtb + (eqb < need ? eqb : need)] = idx;
+        ++gtb;
+      } else {
+        if (eqb < need) {
+          omega[gtb + eqb] = idx;
+          chosen |= 1u << b;
+        }
+        ++eqb;
+      }
     }
-    const uint64_t S0 = __ballot(s0), S1 = __ballot(s1);
-    if ((lane & 15) == 0 && i0 < I) {
-      uint32_t w = spread16((uint32_t)(S0 >> lane)) | (spread16((uint32_t)(S1 >> lane)) << 1);
-      mask[i0 >> 5] = w;
-    }
-    run_gt += __popcll(Bg0) + __popcll(Bg1);
-    run_eq += __popcll(Be0) + __popcll(Be1);
+    if (w < nwords) sure[w] = chosen;
+    run_gt += __shfl(sg, kWave - 1, kWave);
+    run_eq += __shfl(se, kWave - 1, kWave);
   }
 }
 
@@ -326,55 +416,66 @@ void zero_u32(hipStream_t s, uint32_t* p, int64_t n) {
   k_zero_u32<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(p, n);
 }
 
+#define TGRAD_SEL_DISPATCH(KERN, GRID, BLOCK, ...)                                                    \
+  do {                                                                                                \
+    if (keys.random) KERN<kKeyRandom><<<dim3(GRID), dim3(BLOCK), 0, s>>>(__VA_ARGS__);                \
+    else if (dtype == TGRAD_C64) KERN<TGRAD_C64><<<dim3(GRID), dim3(BLOCK), 0, s>>>(__VA_ARGS__);     \
+    else KERN<TGRAD_CBF16><<<dim3(GRID), dim3(BLOCK), 0, s>>>(__VA_ARGS__);                           \
+  } while (0)
+
 void launch_select_hist(hipStream_t s, const void* g, int dtype, const SelectKeys& keys, int64_t I,
-                        int pass, const SelectScalars* sc, uint32_t* hist) {
+                        uint32_t* hist) {
   int64_t npairs = I >> 1;
   int64_t want = (npairs + kSelThreads - 1) / kSelThreads;
   unsigned grid = (unsigned)(want < 1 ? 1 : want > 4096 ? 4096 : want);
   const KeySource src{g, keys.s0, keys.s1};
-  if (keys.random)
-    k_select_hist<kKeyRandom><<<dim3(grid), dim3(kSelThreads), 0, s>>>(src, I, pass, sc, hist);
-  else if (dtype == TGRAD_C64)
-    k_select_hist<TGRAD_C64><<<dim3(grid), dim3(kSelThreads), 0, s>>>(src, I, pass, sc, hist);
-  else
-    k_select_hist<TGRAD_CBF16><<<dim3(grid), dim3(kSelThreads), 0, s>>>(src, I, pass, sc, hist);
+  TGRAD_SEL_DISPATCH(k_select_hist, grid, kSelThreads, src, I, hist);
 }
 
 void launch_select_pick(hipStream_t s, int pass, uint32_t k, SelectScalars* sc, const uint32_t* hist) {
   k_select_pick<<<dim3(1), dim3(1024), 0, s>>>(pass, k, sc, hist);
 }
 
-void launch_select_count(hipStream_t s, const void* g, int dtype, const SelectKeys& keys, int64_t I,
-                         const SelectScalars* sc, uint32_t* seg_gt, uint32_t* seg_eq, int64_t nseg) {
+void launch_select_split(hipStream_t s, const void* g, int dtype, const SelectKeys& keys, int64_t I,
+                         const SelectScalars* sc, uint32_t* sure, uint32_t* cand) {
+  const int64_t nseg = (I + kSegElems - 1) / kSegElems;
   unsigned grid = (unsigned)((nseg + kWavesPerBlock - 1) / kWavesPerBlock);
   const KeySource src{g, keys.s0, keys.s1};
-  if (keys.random)
-    k_select_count<kKeyRandom><<<dim3(grid), dim3(kSelThreads), 0, s>>>(src, I, sc, seg_gt, seg_eq, nseg);
-  else if (dtype == TGRAD_C64)
-    k_select_count<TGRAD_C64><<<dim3(grid), dim3(kSelThreads), 0, s>>>(src, I, sc, seg_gt, seg_eq, nseg);
-  else
-    k_select_count<TGRAD_CBF16><<<dim3(grid), dim3(kSelThreads), 0, s>>>(src, I, sc, seg_gt, seg_eq, nseg);
+  TGRAD_SEL_DISPATCH(k_select_split, grid, kSelThreads, src, I, sc, sure, cand, nseg);
 }
 
-void launch_select_scan(hipStream_t s, uint32_t* seg_gt, uint32_t* seg_eq, int64_t nseg) {
-  k_select_scan<<<dim3(1), dim3(1024), 0, s>>>(seg_gt, seg_eq, nseg);
+void launch_select_hist_cand(hipStream_t s, const void* g, int dtype, const SelectKeys& keys, int64_t I,
+                             int pass, const SelectScalars* sc, const uint32_t* cand, uint32_t* hist) {
+  const int64_t nwords = (I + 31) / 32;
+  int64_t want = (nwords + kSelThreads - 1) / kSelThreads;
+  unsigned grid = (unsigned)(want < 1 ? 1 : want > 2048 ? 2048 : want);
+  const KeySource src{g, keys.s0, keys.s1};
+  TGRAD_SEL_DISPATCH(k_select_hist_cand, grid, kSelThreads, src, pass, sc, cand, nwords, hist);
+}
+
+void launch_select_count(hipStream_t s, const void* g, int dtype, const SelectKeys& keys, int64_t I,
+                         const SelectScalars* sc, const uint32_t* sure, const uint32_t* cand,
+                         uint32_t* chunk_gt, uint32_t* chunk_eq, int64_t nchunks) {
+  const int64_t nwords = (I + 31) / 32;
+  unsigned grid = (unsigned)((nchunks + kWavesPerBlock - 1) / kWavesPerBlock);
+  const KeySource src{g, keys.s0, keys.s1};
+  TGRAD_SEL_DISPATCH(k_select_count, grid, kSelThreads, src, sc, sure, cand, nwords, chunk_gt, chunk_eq, nchunks);
+}
+
+void launch_select_scan(hipStream_t s, uint32_t* chunk_gt, uint32_t* chunk_eq, int64_t nchunks) {
+  k_select_scan<<<dim3(1), dim3(1024), 0, s>>>(chunk_gt, chunk_eq, nchunks);
 }
 
 void launch_select_emit(hipStream_t s, const void* g, int dtype, const SelectKeys& keys, int64_t I,
-                        const SelectScalars* sc, const uint32_t* seg_gt, const uint32_t* seg_eq,
-                        int64_t nseg, int32_t* omega, uint32_t* mask) {
-  unsigned grid = (unsigned)((nseg + kWavesPerBlock - 1) / kWavesPerBlock);
+                        const SelectScalars* sc, const uint32_t* chunk_gt, const uint32_t* chunk_eq,
+                        int64_t nchunks, uint32_t* sure, const uint32_t* cand, int32_t* omega) {
+  const int64_t nwords = (I + 31) / 32;
+  unsigned grid = (unsigned)((nchunks + kWavesPerBlock - 1) / kWavesPerBlock);
   const KeySource src{g, keys.s0, keys.s1};
-  if (keys.random)
-    k_select_emit<kKeyRandom><<<dim3(grid), dim3(kSelThreads), 0, s>>>(src, I, sc, seg_gt, seg_eq, nseg,
-                                                                       omega, mask);
-  else if (dtype == TGRAD_C64)
-    k_select_emit<TGRAD_C64><<<dim3(grid), dim3(kSelThreads), 0, s>>>(src, I, sc, seg_gt, seg_eq, nseg,
-                                                                      omega, mask);
-  else
-    k_select_emit<TGRAD_CBF16><<<dim3(grid), dim3(kSelThreads), 0, s>>>(src, I, sc, seg_gt, seg_eq, nseg,
-                                                                        omega, mask);
+  TGRAD_SEL_DISPATCH(k_select_emit, grid, kSelThreads, src, sc, chunk_gt, chunk_eq, nchunks, sure, cand, nwords,
+                     omega);
 }
+#undef TGRAD_SEL_DISPATCH
 
 void launch_mask_from_indices(hipStream_t s, const int32_t* omega, int64_t k, uint32_t* mask,
                               int64_t mask_words) {

@@ -24,7 +24,8 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 const char* const kKernelNames[KID_COUNT] = {
-    "select_hist", "select_pick", "select_count", "select_scan", "select_emit", "mask_from_indices",
+    "select_hist", "select_pick", "select_split", "select_hist_cand", "select_count", "select_scan", "select_emit",
+    "mask_from_indices",
     "tile_offsets", "gram", "gram_reduce", "eig_jacobi", "factor_pack",
     "gather", "project_first", "project", "adam_core", "backproject", "update", "sparse_update",
     "hooi_project", "core", "residual"};
@@ -38,7 +39,7 @@ struct Plan {
   int rank[kMaxNdim];
   Stage proj[kMaxNdim];          // proj[s]: s-th projection stage; contracts mode N-1-s
   Stage back[kMaxNdim];          // back[s]: s-th reconstruction stage; expands mode s
-  int64_t nseg = 0;
+  int64_t nchunks = 0;           // selection: runs of kSelChunkElems elements counted / emitted by one wavefront
   int64_t mask_words = 0;
   int tile_waves = 0;            // last-mode kernels: wavefronts per workgroup; 0 = generic kernels
   int64_t ntiles = 0;            // tiles of the tensor seen as (I / I_N rows, I_N)
@@ -48,7 +49,7 @@ struct Plan {
   // byte offsets into state
   size_t st_omega, st_ms, st_vs, st_ml, st_vl, st_U[kMaxNdim], state_bytes;
   // byte offsets into workspace
-  size_t ws_sel, ws_hist, ws_seg_gt, ws_seg_eq, ws_mask, ws_tile_start, ws_fpad, ws_ut, ws_partials, ws_gram[kMaxNdim],
+  size_t ws_sel, ws_hist, ws_chunk_gt, ws_chunk_eq, ws_mask, ws_cand, ws_tile_start, ws_fpad, ws_ut, ws_partials, ws_gram[kMaxNdim],
       ws_eig_a[kMaxNdim], ws_eig_v[kMaxNdim], ws_gs, ws_core_g, ws_core_n, ws_buf[2], workspace_bytes;
   int gram_chunks[kMaxNdim];
   int order = 0;                   // TGRAD_ORDER_*
@@ -159,7 +160,7 @@ void make_plan(const tgrad_config* c, Plan* p) {
     st.K = p->rank[s];
     st.M = (int)p->shape[s];
   }
-  p->nseg = (p->I + kSegElems - 1) / kSegElems;
+  p->nchunks = (p->I + kSelChunkElems - 1) / kSelChunkElems;
   p->mask_words = (p->I + 31) / 32;
   {
     const int last = N - 1;
@@ -197,9 +198,10 @@ void make_plan(const tgrad_config* c, Plan* p) {
   o = 0;
   p->ws_sel = take(sizeof(SelectScalars));
   p->ws_hist = take(3 * kHistBins * 4);
-  p->ws_seg_gt = take((size_t)p->nseg * 4);
-  p->ws_seg_eq = take((size_t)p->nseg * 4);
+  p->ws_chunk_gt = take((size_t)p->nchunks * 4);
+  p->ws_chunk_eq = take((size_t)p->nchunks * 4);
   p->ws_mask = take((size_t)p->mask_words * 4);
+  p->ws_cand = take((size_t)p->mask_words * 4);
   p->ws_tile_start = take((size_t)(p->ntiles + 1) * 4);
   p->ws_fpad = take(p->fuse_next ? (size_t)p->shape[N - 2] * 32 * 8 : 0);
   p->ws_ut = take(p->fuse_next ? (size_t)p->shape[N - 2] * 32 * 8 : 0);
@@ -357,9 +359,10 @@ void select_support(tgrad_ctx* c, const void* x, int dt) {
   hipStream_t s = c->stream;
   SelectScalars* sc = c->w<SelectScalars>(p.ws_sel);
   uint32_t* hist = c->w<uint32_t>(p.ws_hist);
-  uint32_t* seg_gt = c->w<uint32_t>(p.ws_seg_gt);
-  uint32_t* seg_eq = c->w<uint32_t>(p.ws_seg_eq);
-  uint32_t* mask = c->w<uint32_t>(p.ws_mask);
+  uint32_t* chunk_gt = c->w<uint32_t>(p.ws_chunk_gt);
+  uint32_t* chunk_eq = c->w<uint32_t>(p.ws_chunk_eq);
+  uint32_t* mask = c->w<uint32_t>(p.ws_mask);          // "sure" bits first, the support bitmask in the end
+  uint32_t* cand = c->w<uint32_t>(p.ws_cand);
   int32_t* omega = c->st<int32_t>(p.st_omega);
   SelectKeys keys{false, 0u, 0u};
   if (c->cfg.select_rule == TGRAD_SELECT_RANDOM) {
@@ -371,13 +374,18 @@ void select_support(tgrad_ctx* c, const void* x, int dt) {
   }
   if (p.k > 0) {
     zero_u32(s, hist, 3 * kHistBins);
-    for (int pass = 0; pass < 3; ++pass) {
-      { Scope sc_(c, KID_SEL_HIST); launch_select_hist(s, x, dt, keys, p.I, pass, sc, hist + pass * kHistBins); }
+    // two streaming passes over x: leading-digit histogram, then the two bitmasks
+    { Scope sc_(c, KID_SEL_HIST); launch_select_hist(s, x, dt, keys, p.I, hist); }
+    { Scope sc_(c, KID_SEL_PICK); launch_select_pick(s, 0, (uint32_t)p.k, sc, hist); }
+    { Scope sc_(c, KID_SEL_SPLIT); launch_select_split(s, x, dt, keys, p.I, sc, mask, cand); }
+    // the remaining digits are decided among the candidates only
+    for (int pass = 1; pass < 3; ++pass) {
+      { Scope sc_(c, KID_SEL_HIST_CAND); launch_select_hist_cand(s, x, dt, keys, p.I, pass, sc, cand, hist + pass * kHistBins); }
       { Scope sc_(c, KID_SEL_PICK); launch_select_pick(s, pass, (uint32_t)p.k, sc, hist + pass * kHistBins); }
     }
-    { Scope sc_(c, KID_SEL_COUNT); launch_select_count(s, x, dt, keys, p.I, sc, seg_gt, seg_eq, p.nseg); }
-    { Scope sc_(c, KID_SEL_SCAN); launch_select_scan(s, seg_gt, seg_eq, p.nseg); }
-    { Scope sc_(c, KID_SEL_EMIT); launch_select_emit(s, x, dt, keys, p.I, sc, seg_gt, seg_eq, p.nseg, omega, mask); }
+    { Scope sc_(c, KID_SEL_COUNT); launch_select_count(s, x, dt, keys, p.I, sc, mask, cand, chunk_gt, chunk_eq, p.nchunks); }
+    { Scope sc_(c, KID_SEL_SCAN); launch_select_scan(s, chunk_gt, chunk_eq, p.nchunks); }
+    { Scope sc_(c, KID_SEL_EMIT); launch_select_emit(s, x, dt, keys, p.I, sc, chunk_gt, chunk_eq, p.nchunks, mask, cand, omega); }
   }
   {
     Scope sc_(c, KID_TILE_OFFSETS);

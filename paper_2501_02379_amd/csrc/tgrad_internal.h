@@ -12,8 +12,10 @@ namespace tgrad {
 constexpr int kMaxNdim = TGRAD_MAX_NDIM;
 
 // ---- selection (Algorithm 1: SparseIndices) -------------------------------------------------
-// A "segment" is the run of consecutive elements one wavefront counts/emits in order.
+// A "segment" is the run of consecutive elements one wavefront turns into mask bits; a "chunk" is
+// the run one wavefront counts and emits in order from the masks.
 constexpr int kSegElems = 2048;
+constexpr int kSelChunkElems = 32768;
 constexpr int kHistBins = 4096;            // 12-bit digits; the three digits are 12 + 12 + 8 bits
 
 struct SelectScalars {                     // lives in workspace, written by the pick kernel
@@ -34,7 +36,8 @@ struct Stage {
 
 // Names of the profiled kernels (index into the per-context timing table).
 enum KernelId {
-  KID_SEL_HIST = 0, KID_SEL_PICK, KID_SEL_COUNT, KID_SEL_SCAN, KID_SEL_EMIT, KID_MASK_FROM_IDX,
+  KID_SEL_HIST = 0, KID_SEL_PICK, KID_SEL_SPLIT, KID_SEL_HIST_CAND, KID_SEL_COUNT, KID_SEL_SCAN, KID_SEL_EMIT,
+  KID_MASK_FROM_IDX,
   KID_TILE_OFFSETS, KID_GRAM, KID_GRAM_REDUCE, KID_EIG, KID_FACTOR_PACK,
   KID_GATHER, KID_PROJECT_FIRST, KID_PROJECT, KID_ADAM_CORE, KID_BACKPROJECT, KID_UPDATE,
   KID_SPARSE_UPDATE, KID_HOOI_PROJECT, KID_CORE, KID_RESIDUAL, KID_COUNT
@@ -51,14 +54,19 @@ struct SelectKeys {
   uint32_t s0, s1;
 };
 void launch_select_hist(hipStream_t s, const void* g, int dtype, const SelectKeys& keys, int64_t I,
-                        int pass, const SelectScalars* sc, uint32_t* hist);
+                        uint32_t* hist);
 void launch_select_pick(hipStream_t s, int pass, uint32_t k, SelectScalars* sc, const uint32_t* hist);
+void launch_select_split(hipStream_t s, const void* g, int dtype, const SelectKeys& keys, int64_t I,
+                         const SelectScalars* sc, uint32_t* sure, uint32_t* cand);
+void launch_select_hist_cand(hipStream_t s, const void* g, int dtype, const SelectKeys& keys, int64_t I,
+                             int pass, const SelectScalars* sc, const uint32_t* cand, uint32_t* hist);
 void launch_select_count(hipStream_t s, const void* g, int dtype, const SelectKeys& keys, int64_t I,
-                         const SelectScalars* sc, uint32_t* seg_gt, uint32_t* seg_eq, int64_t nseg);
-void launch_select_scan(hipStream_t s, uint32_t* seg_gt, uint32_t* seg_eq, int64_t nseg);
+                         const SelectScalars* sc, const uint32_t* sure, const uint32_t* cand,
+                         uint32_t* chunk_gt, uint32_t* chunk_eq, int64_t nchunks);
+void launch_select_scan(hipStream_t s, uint32_t* chunk_gt, uint32_t* chunk_eq, int64_t nchunks);
 void launch_select_emit(hipStream_t s, const void* g, int dtype, const SelectKeys& keys, int64_t I,
-                        const SelectScalars* sc, const uint32_t* seg_gt, const uint32_t* seg_eq,
-                        int64_t nseg, int32_t* omega, uint32_t* mask);
+                        const SelectScalars* sc, const uint32_t* chunk_gt, const uint32_t* chunk_eq,
+                        int64_t nchunks, uint32_t* sure, const uint32_t* cand, int32_t* omega);
 void launch_mask_from_indices(hipStream_t s, const int32_t* omega, int64_t k, uint32_t* mask,
                               int64_t mask_words);
 
