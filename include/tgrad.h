@@ -39,6 +39,7 @@ extern "C" {
 #define TGRAD_MAX_NDIM 6
 #define TGRAD_MAX_HOOI_SWEEPS 64
 #define TGRAD_MAX_EXTENT 256          /* largest I_n the factor refresh accepts */
+#define TGRAD_STATIC_WORKSPACE_BYTES (32u << 20)   /* scratch of tgrad_step_static, per GPU */
 
 typedef struct tgrad_ctx tgrad_ctx;   /* opaque; host memory owned by the library */
 
@@ -168,6 +169,32 @@ int tgrad_refresh_factors(tgrad_ctx* ctx, const void* grad_dev);
  * Errors: INVALID_ARG, NOT_READY (refresh_every == 0 and no refresh yet), HIP.
  */
 int tgrad_step(tgrad_ctx* ctx, void* weight_dev, const void* grad_dev);
+
+/*
+ * tgrad_step for callers that cannot allocate device memory and cannot hold a context: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  It does what
+ * `tgrad_step` does for a context at step count t (refresh first when t % cfg.refresh_every == 0,
+ * then the loop body), but allocates nothing, neither on the device nor on the host: there is no
+ * context, and the scratch that `workspace_dev` provides elsewhere is a fixed array inside the
+ * library, TGRAD_STATIC_WORKSPACE_BYTES per GPU, which every GPU that runs the library holds until
+ * the process ends.  A configuration whose `tgrad_query_sizes` workspace exceeds that size is
+ * rejected with TGRAD_ERR_UNSUPPORTED and nothing is launched.
+ *  cfg         host pointer; refresh_every must be >= 1 (INVALID_ARG otherwise).
+ *  state_dev   device pointer, >= state_bytes of `tgrad_query_sizes`, 256-byte aligned: the optimizer
+ *              state (Omega, M_S, V_S, M_L, V_L, U^(n)).  The caller zero-fills it before the call
+ *              with t = 0 and passes the same buffer, untouched, to the calls with t = 1, 2, ...; a
+ *              call with t % refresh_every != 0 on a state that no earlier call has refreshed is
+ *              not detected.
+ *  t           the number of steps this state has taken so far.
+ *  weight_dev, grad_dev  as for `tgrad_step`.
+ *  hip_stream  stream to enqueue on (NULL = the default stream).  Does not wait.
+ * All calls on one GPU share that GPU's array, which keeps the last call's contents: every call
+ * rebuilds what it reads from there, and calls that overlap in time on one GPU (two streams, two
+ * threads) race.  The device must be the current one.
+ * Errors: INVALID_ARG, UNSUPPORTED, HIP.
+ */
+int tgrad_step_static(const tgrad_config* cfg, void* state_dev, int64_t t, void* weight_dev,
+                      const void* grad_dev, void* hip_stream);
 
 /*
  * Copy one state item to the host (waits for the stream first).

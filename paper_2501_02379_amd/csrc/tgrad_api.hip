@@ -3,6 +3,7 @@
 // the two branches of Algorithm 1 (refresh and step).
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -706,6 +707,29 @@ int locate(tgrad_ctx* c, int what, Item* it) {
   return TGRAD_ERR_INVALID_ARG;
 }
 
+// ---- workspace of tgrad_step_static ------------------------------------------------------------
+// One fixed array per GPU (every GPU the code object is loaded on holds its own copy until the
+// process ends).  In host code the array's name is only a handle for hipGetSymbolAddress: the
+// device address is looked up once per device and every kernel receives that address.
+__device__ __align__(256) unsigned char g_static_workspace[TGRAD_STATIC_WORKSPACE_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mu;
+void* g_static_ptr[kMaxDevices];          // device address of g_static_workspace, per device; null = not looked up yet
+
+int static_workspace(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return TGRAD_ERR_HIP;
+  std::lock_guard<std::mutex> lock(g_static_mu);
+  if (!g_static_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_static_workspace)) != hipSuccess || !ptr) return TGRAD_ERR_HIP;
+    g_static_ptr[dev] = ptr;
+  }
+  *out = g_static_ptr[dev];
+  return TGRAD_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -772,6 +796,47 @@ int tgrad_step(tgrad_ctx* ctx, void* weight_dev, const void* grad_dev) {
   }
   if (!ctx->ready()) return TGRAD_ERR_NOT_READY;
   return do_step(ctx, weight_dev, grad_dev);
+}
+
+int tgrad_step_static(const tgrad_config* cfg, void* state_dev, int64_t t, void* weight_dev,
+                      const void* grad_dev, void* hip_stream) {
+  int rc = validate(cfg);
+  if (rc != TGRAD_OK) return rc;
+  if (!state_dev || !weight_dev || !grad_dev || t < 0) return TGRAD_ERR_INVALID_ARG;
+  if (((uintptr_t)state_dev % kAlign) || ((uintptr_t)grad_dev % 16) || ((uintptr_t)weight_dev % 16) ||
+      weight_dev == grad_dev)
+    return TGRAD_ERR_INVALID_ARG;
+  if (cfg->refresh_every < 1) return TGRAD_ERR_INVALID_ARG;      // nobody else could refresh this state
+  tgrad_ctx c;                                                    // on the stack: nothing is allocated
+  c.cfg = *cfg;
+  make_plan(cfg, &c.plan);
+  if (c.plan.workspace_bytes > (size_t)TGRAD_STATIC_WORKSPACE_BYTES) return TGRAD_ERR_UNSUPPORTED;
+  void* ws = nullptr;
+  rc = static_workspace(&ws);
+  if (rc != TGRAD_OK) return rc;
+  c.state = static_cast<char*>(state_dev);
+  c.ws = static_cast<char*>(ws);
+  c.stream = static_cast<hipStream_t>(hip_stream);
+  c.t = t;
+  c.have_indices = true;                                          // the caller's contract for t % T != 0
+  for (int n = 0; n < kMaxNdim; ++n) c.have_factor[n] = true;
+  c.profiling = false;
+  Plan& p = c.plan;
+  if (p.order != TGRAD_ORDER_US_LR) zero_u32(c.stream, c.w<uint32_t>(p.ws_tile_zero), p.ntiles + 1);
+  if (t % cfg->refresh_every == 0) {
+    rc = do_refresh(&c, grad_dev);
+    if (rc != TGRAD_OK) return rc;
+  } else {
+    // The array is shared by every call on this GPU and may hold another tensor's data: whatever a
+    // context keeps in its workspace between a refresh and the steps after it is derived again
+    // from the state (the support bitmask, the tile offsets, the factor copies of the fused kernels).
+    if (p.k > 0 && p.tile_waves == 0)
+      launch_mask_from_indices(c.stream, c.st<int32_t>(p.st_omega), p.k, c.w<uint32_t>(p.ws_mask), p.mask_words);
+    launch_tile_offsets(c.stream, c.st<int32_t>(p.st_omega), p.k, p.tile_elems, p.ntiles,
+                        c.w<uint32_t>(p.ws_tile_start));
+    pack_fused_factor(&c);
+  }
+  return do_step(&c, weight_dev, grad_dev);
 }
 
 int tgrad_get_state(tgrad_ctx* ctx, int what, void* host_out, size_t cap) {

@@ -34,7 +34,7 @@ STATE_GRAM0, STATE_FACTOR0 = 32, 64
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libtgrad.so")
 
 EXPORTS = (
-    "tgrad_query_sizes", "tgrad_init", "tgrad_refresh_factors", "tgrad_step", "tgrad_get_state",
+    "tgrad_query_sizes", "tgrad_init", "tgrad_refresh_factors", "tgrad_step", "tgrad_step_static", "tgrad_get_state",
     "tgrad_set_state", "tgrad_set_profiling", "tgrad_get_kernel_times", "tgrad_calibration_copy",
     "tgrad_destroy", "tgrad_strerror",
 )
@@ -88,6 +88,7 @@ def load():
     lib.tgrad_init.argtypes = [C.POINTER(vp), C.POINTER(tgrad_config), vp, vp, vp]
     lib.tgrad_refresh_factors.argtypes = [vp, vp]
     lib.tgrad_step.argtypes = [vp, vp, vp]
+    lib.tgrad_step_static.argtypes = [C.POINTER(tgrad_config), vp, C.c_int64, vp, vp, vp]
     lib.tgrad_get_state.argtypes = [vp, i32, vp, sz]
     lib.tgrad_set_state.argtypes = [vp, i32, vp, sz]
     lib.tgrad_set_profiling.argtypes = [vp, i32]
@@ -258,6 +259,21 @@ class Context:
             self.tgrad_destroy()
         except Exception:
             pass
+
+
+STATIC_WORKSPACE_BYTES = 32 << 20
+
+
+def tgrad_step_static(cfg: tgrad_config, state, t: int, weight, grad, stream=None) -> None:
+    """The allocation-free step: `state` is the caller's state buffer (a torch uint8 tensor of
+    state_bytes, zero-filled before t = 0); scratch is the library's fixed per-GPU array."""
+    import torch
+    st = stream if stream is not None else torch.cuda.current_stream(weight.device)
+    with torch.cuda.device(weight.device):
+        rc = load().tgrad_step_static(C.byref(cfg), _ptr(state), int(t), _ptr(weight), _ptr(grad),
+                                      C.c_void_p(st.cuda_stream))
+    if rc != TGRAD_OK:
+        raise TgradError(rc, "tgrad_step_static")
 
 
 def tgrad_calibration_copy(dst, src, stream=None) -> None:

@@ -101,3 +101,23 @@ def test_caller_side_sizes():
         assert T.sparse_count(Fraction(*w.density), w.numel) == w.k
         assert tuple(T.rank_from_ratio(Fraction(1, 2) if w.name == "cfg1" else Fraction(1, 4), i)
                      for i in w.shape) == w.ranks
+
+
+def test_static_step_argument_checks_need_no_gpu():
+    """Everything `tgrad_step_static` refuses is refused before it looks at the device."""
+    lib = T.load()
+    big = synth.WORKLOADS["cfg4"]
+    cfg = T.make_config(big.shape, big.ranks, big.k, refresh_every=big.T)
+    rc, _, wb = T.tgrad_query_sizes(cfg)
+    assert rc == T.TGRAD_OK and wb > T.STATIC_WORKSPACE_BYTES
+    assert lib.tgrad_step_static(C.byref(cfg), 256, 0, 512, 1024, None) == T.TGRAD_ERR_UNSUPPORTED
+    small = T.make_config((16, 16, 8, 5), (8, 8, 4, 3), 103, refresh_every=5)
+    assert lib.tgrad_step_static(None, 256, 0, 512, 1024, None) == T.TGRAD_ERR_INVALID_ARG
+    assert lib.tgrad_step_static(C.byref(small), None, 0, 512, 1024, None) == T.TGRAD_ERR_INVALID_ARG
+    assert lib.tgrad_step_static(C.byref(small), 256, 0, None, 1024, None) == T.TGRAD_ERR_INVALID_ARG
+    assert lib.tgrad_step_static(C.byref(small), 256, 0, 512, None, None) == T.TGRAD_ERR_INVALID_ARG
+    assert lib.tgrad_step_static(C.byref(small), 264, 0, 512, 1024, None) == T.TGRAD_ERR_INVALID_ARG   # state alignment
+    assert lib.tgrad_step_static(C.byref(small), 256, 0, 512, 512, None) == T.TGRAD_ERR_INVALID_ARG    # W aliases G
+    assert lib.tgrad_step_static(C.byref(small), 256, -1, 512, 1024, None) == T.TGRAD_ERR_INVALID_ARG
+    small.refresh_every = 0
+    assert lib.tgrad_step_static(C.byref(small), 256, 0, 512, 1024, None) == T.TGRAD_ERR_INVALID_ARG
