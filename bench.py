@@ -103,9 +103,12 @@ def kernel_model(w, fused, weight_bytes=8, core_fused=False):
     m["gather"] = {"bytes": k * (4 + gb + 8), "flops": 0, "bound": "hbm"}
     m["adam_core"] = {"bytes": C * (8 + 12 + 12 + 8), "flops": 12 * C, "bound": "hbm"}
     m["sparse_update"] = {"bytes": k * (8 + 4 + 12 + 12 + 16), "flops": 14 * k, "bound": "hbm"}
+    # selection: two streaming reads of G (leading-digit histogram; the pass that writes the two
+    # bitmasks, I/8 bytes each); the later kernels read the masks and the candidates' keys only
     m["select_hist"] = {"bytes": I * gb, "flops": 3 * I, "bound": "hbm"}
-    m["select_count"] = {"bytes": I * gb, "flops": 3 * I, "bound": "hbm"}
-    m["select_emit"] = {"bytes": I * gb + I // 8 + 4 * k, "flops": 3 * I, "bound": "hbm"}
+    m["select_split"] = {"bytes": I * gb + 2 * (I // 8), "flops": 3 * I, "bound": "hbm"}
+    m["select_count"] = {"bytes": 2 * (I // 8), "flops": 0, "bound": "hbm"}
+    m["select_emit"] = {"bytes": 3 * (I // 8) + 4 * k, "flops": 0, "bound": "hbm"}
     gram_fl = sum(8 * I * shape[n] for n in range(N) if ranks[n] < shape[n])
     ngram = sum(1 for n in range(N) if ranks[n] < shape[n])
     m["gram"] = {"bytes": ngram * I * gb, "flops": gram_fl, "bound": "mfma64", "launches_per_step": ngram}
@@ -126,59 +129,40 @@ def measured_traffic(workload, kernel):
     return int(m.group(1)) if m else None
 
 
-def cpu_baseline(w, budget_hint_s=20.0):
-    """The oracle, as it stands, on a bounded sample of the same workload: the leading
-    channel block of the gradient (all Fourier modes kept), one refresh + 3 steps, amortised
-    over the workload's refresh period exactly like the GPU figure."""
-    from fractions import Fraction
+def cpu_baseline(w):
+    """The oracle, as it stands, on the workload itself: the gradient of layer 0 from the same
+    seeded generator the GPU run uses, one refresh + 3 steps (the steps after the first run on the
+    old support), amortised over the workload's refresh period exactly like the GPU figure.  A
+    workload of several layers is timed on one layer (every layer costs the same)."""
     from oracle import tgrad_oracle as O
     from paper_2501_02379_amd import synth
-    shape = list(w.shape)
-    ranks = list(w.ranks)
-    # shrink the two channel modes until the sample is at most ~40M elements (10-30 s of CPU work)
-    while int(np.prod(shape)) > 40_000_000 and shape[0] > 8:
-        shape[0] //= 2
-        shape[1] //= 2
-        ranks[0] = max(1, ranks[0] // 2)
-        ranks[1] = max(1, ranks[1] // 2)
-    shape, ranks = tuple(shape), tuple(ranks)
-    I = int(np.prod(shape))
-    k = O.sparse_count(Fraction(*w.density), I)
-    sl = tuple(slice(0, s) for s in shape)
-    rng = np.random.default_rng(0)
-
-    def sample_grad(t):
-        g = rng.standard_normal(shape + (2,), dtype=np.float32).view(np.complex64).reshape(shape)
-        g *= np.float32(np.sqrt(0.5))
-        pos = synth.outlier_positions(I, w.outlier_frac, 97 + w.config_id)
-        g.reshape(-1)[pos] *= np.float32(20.0)
-        if w.grad_dtype == "cbf16":
-            return synth.complex64_to_bf16_pairs(g)
-        return g
-
-    st = O.State(shape, O.Hyper(ranks=ranks, k=k, lr=w.lr, T=0))
-    W = np.zeros(shape, dtype=np.complex128)
-    g = sample_grad(0)
+    I = w.numel
+    grads = [synth.gradient(w, t) for t in range(2)]
+    st = O.State(w.shape, O.Hyper(ranks=w.ranks, k=w.k, lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps,
+                                  alpha=w.alpha, lam=w.lam, weight_decay=w.weight_decay, T=0))
+    W = synth.initial_weight(w).astype(np.complex128)
     t0 = time.perf_counter()
-    O.refresh(st, g)
+    O.refresh(st, grads[0])
     t_refresh = time.perf_counter() - t0
-    t0 = time.perf_counter()
     nsteps = 3
+    t0 = time.perf_counter()
     for t in range(nsteps):
-        W = O.step(st, W, g)
+        W = O.step(st, W, grads[t & 1])
     t_step = (time.perf_counter() - t0) / nsteps
     per_step = t_step + t_refresh / max(1, w.T)
+    cores = len(os.sched_getaffinity(0))
     try:
         from threadpoolctl import threadpool_info
-        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        blas = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
-        threads = len(os.sched_getaffinity(0))
+        blas = None
     return {
-        "value": I / per_step / 1e9, "unit": "Gelem/s", "cores": int(threads), "kind": "oracle",
-        "sample": "leading %s block of the %s gradient, ranks %s, k=%d; 1 refresh (%.2f s) + %d steps "
-                  "(%.2f s each), amortised over T=%d" % ("x".join(map(str, shape)), w.name,
-                                                         ",".join(map(str, ranks)), k, t_refresh, nsteps,
-                                                         t_step, w.T),
+        "value": I / per_step / 1e9, "unit": "Gelem/s", "cores": int(cores), "blas_threads": blas, "kind": "oracle",
+        "sample": "the %s gradient itself (%s, %d elements, one layer), ranks %s, k=%d; 1 refresh (%.2f s) + %d "
+                  "steps (%.2f s each), amortised over T=%d" % (w.name, "x".join(map(str, w.shape)), I,
+                                                               ",".join(map(str, w.ranks)), w.k, t_refresh, nsteps,
+                                                               t_step, w.T),
+        "refresh_s": round(t_refresh, 3), "step_s": round(t_step, 3),
     }
 
 
@@ -257,6 +241,24 @@ def main():
     run_steps(Wm, 0)
     torch.cuda.synchronize()
 
+    # ---- achievable HBM rate on this machine, in this run: the library's plain copy kernel on a
+    # gradient-sized buffer (bytes read + bytes written over the HIP-event time)
+    nb = min(w.numel * 8, 1 << 30) // 16 * 16
+    csrc = torch.empty(nb, dtype=torch.uint8, device=dev)
+    cdst = torch.empty_like(csrc)
+    csrc.zero_()
+    ce0, ce1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for _ in range(3):
+        T.tgrad_calibration_copy(cdst, csrc)
+    ncopy = 10
+    ce0.record()
+    for _ in range(ncopy):
+        T.tgrad_calibration_copy(cdst, csrc)
+    ce1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 2.0 * nb * ncopy / (ce0.elapsed_time(ce1) * 1e-3) / 1e9
+    del csrc, cdst
+
     # ---- region A: the timed K steps (no per-kernel events) ----
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
@@ -278,25 +280,35 @@ def main():
     e1.record()
     torch.cuda.synchronize()
     ms_per_step_profiled = e0.elapsed_time(e1) / K
-    refreshes_b = sum(1 for t in range(Wm + K, Wm + 2 * K) if t % w.T == 0)
     times = {}
     for c in ctxs:
         for name, v in c.tgrad_get_kernel_times().items():
             d = times.setdefault(name, {"total_ms": 0.0, "launches": 0})
             d["total_ms"] += v["total_ms"]
             d["launches"] += v["launches"]
-    # one more explicit refresh so refresh kernels are always covered
-    refresh_ms = None
-    if refreshes_b == 0:
-        for c in ctxs:
-            c.tgrad_set_profiling(False)
-        torch.cuda.synchronize()
-        e0.record()
-        for layer in range(w.layers):
-            ctxs[layer].tgrad_refresh_factors(Gs[layer][0])
-        e1.record()
-        torch.cuda.synchronize()
-        refresh_ms = e0.elapsed_time(e1)
+    # one explicit refresh, timed as a whole without events, then once more with per-kernel events so
+    # that the refresh kernels are always covered
+    for c in ctxs:
+        c.tgrad_set_profiling(False)
+    torch.cuda.synchronize()
+    e0.record()
+    for layer in range(w.layers):
+        ctxs[layer].tgrad_refresh_factors(Gs[layer][0])
+    e1.record()
+    torch.cuda.synchronize()
+    refresh_ms = e0.elapsed_time(e1)
+    for c in ctxs:
+        c.tgrad_set_profiling(True)
+    for layer in range(w.layers):
+        ctxs[layer].tgrad_refresh_factors(Gs[layer][0])
+    torch.cuda.synchronize()
+    rtimes = {}
+    for c in ctxs:
+        for name, v in c.tgrad_get_kernel_times().items():
+            d = rtimes.setdefault(name, {"total_ms": 0.0, "launches": 0})
+            d["total_ms"] += v["total_ms"]
+            d["launches"] += v["launches"]
+    times.update(rtimes)          # refresh kernels: the explicit refresh (step kernels never run in it)
 
     # the library fuses the mode-(N-1) stages when the shape allows: then k_mid runs N - 2 times each way
     nstep = max(1, times.get("project_first", {}).get("launches", 1))
@@ -311,10 +323,22 @@ def main():
         mm = model.get(name)
         if mm:
             lp = mm.get("launches_per_step", 1)
-            ent["GBps"] = round(mm["bytes"] / lp / (avg * 1e-3) / 1e9, 1)
-            ent["TFLOPs"] = round(mm["flops"] / lp / (avg * 1e-3) / 1e12, 2)
+            gbs = mm["bytes"] / lp / (avg * 1e-3) / 1e9
+            tfl = mm["flops"] / lp / (avg * 1e-3) / 1e12
+            ent["GBps"] = round(gbs, 1)
+            ent["TFLOPs"] = round(tfl, 2)
+            if mm["bound"] == "hbm":
+                ent["frac_hbm_peak"] = round(gbs / HBM_PEAK_GBS, 4)
+                ent["frac_hbm_achievable"] = round(gbs / copy_gbs, 4)
+            elif mm["bound"] == "mfma64":
+                ent["frac_mfma_fp64_peak"] = round(tfl / MFMA_FP64_PEAK_TF, 4)
+            else:
+                ent["frac_mfma_fp32_peak"] = round(tfl / MFMA_FP32_PEAK_TF, 4)
+            if name == "project_first":          # straddles the ridge: both fractions
+                ent["frac_mfma_fp32_peak"] = round(tfl / MFMA_FP32_PEAK_TF, 4)
         kernels[name] = ent
-    step_kernels = [n for n in kernels if not n.startswith(("select", "gram", "eig", "mask", "factor", "hooi", "tile", "residual", "gather"))]
+    refresh_names = ("select", "gram", "eig", "mask", "factor", "hooi", "tile", "residual", "gather")
+    step_kernels = [n for n in kernels if not n.startswith(refresh_names)]
     dom = max(step_kernels, key=lambda n: kernels[n]["total_ms"]) if step_kernels else None
     roofline = None
     if dom and dom in model:
@@ -325,11 +349,33 @@ def main():
             ach, peak, unit = mm["bytes"] / lp / avg_s / 1e9, HBM_PEAK_GBS, "GB/s"
         else:
             ach, peak, unit = mm["flops"] / lp / avg_s / 1e12, MFMA_FP32_PEAK_TF, "TFLOP/s"
+        traffic = measured_traffic(w.name, dom) if args.weights == "c64" else None
         roofline = {"kernel": dom, "bound": "hbm" if mm["bound"] == "hbm" else "mfma",
                     "achieved": round(ach, 2), "peak": peak, "unit": unit, "frac": round(ach / peak, 4),
-                    "traffic": measured_traffic(w.name, dom) if args.weights == "c64" else None,
+                    "traffic": traffic,
+                    "traffic_source": ("profiles/hbm_traffic_%s.txt (rocprofv3 --pmc passes recorded earlier, not "
+                                       "measured by this run)" % w.name) if traffic is not None else None,
                     "algorithmic_bytes_per_launch": mm["bytes"] // lp,
                     "avg_launch_ms": kernels[dom]["avg_ms"]}
+        if mm["bound"] == "hbm":
+            # what a plain copy kernel reaches on this machine in this run (read + write bytes per second)
+            roofline["achievable_peak"] = round(copy_gbs, 1)
+            roofline["frac_vs_achievable"] = round(ach / copy_gbs, 4)
+    # selection as a whole: one read of G is what the method needs (8 or 4 bytes per element)
+    sel_ms = sum(v["total_ms"] for n, v in rtimes.items() if n.startswith("select")) / max(1, w.layers)
+    gbytes = w.numel * (8 if w.grad_dtype == "c64" else 4)
+    select_summary = None
+    if sel_ms > 0 and args.select == "topk":
+        select_summary = {"ms_per_refresh": round(sel_ms, 4), "algorithmic_bytes": gbytes,
+                          "GBps": round(gbytes / (sel_ms * 1e-3) / 1e9, 1),
+                          "frac_hbm_peak": round(gbytes / (sel_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                          "frac_hbm_achievable": round(gbytes / (sel_ms * 1e-3) / 1e9 / copy_gbs, 4)}
+    ms_amortised = None
+    steady = ms_per_step if refreshes == 0 else None
+    if refreshes == 0:
+        ms_amortised = ms_per_step + refresh_ms / w.T
+    elif K == w.T and refreshes == 1:
+        ms_amortised = ms_per_step                      # exactly one period inside the timed region
 
     out = {
         "metric": "gradient elements compressed+updated/sec (Gelem/s) per step; % HBM roofline",
@@ -342,8 +388,13 @@ def main():
                    "refreshes_in_timed_region": refreshes, "fused_mode_stages": bool(fused), "fused_core_stage": bool(core_fused),
                    "order": args.order, "weights": args.weights, "select": args.select, "hooi_sweeps": args.hooi_sweeps, "warm_restart": bool(args.warm_restart)},
         "roofline": roofline,
+        "ms_per_step_steady": round(steady, 4) if steady is not None else None,
+        "ms_per_step_amortised": round(ms_amortised, 4) if ms_amortised is not None else None,
+        "value_amortised": round(I / (ms_amortised * 1e-3) / 1e9, 4) if ms_amortised is not None else None,
         "ms_per_step_with_kernel_events": round(ms_per_step_profiled, 4),
-        "refresh_ms": refresh_ms,
+        "refresh_ms": round(refresh_ms, 4),
+        "copy_kernel_GBps": round(copy_gbs, 1),
+        "select": select_summary,
         "kernels": kernels,
     }
     if not args.no_cpu_baseline:

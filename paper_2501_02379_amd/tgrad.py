@@ -9,7 +9,6 @@ from __future__ import annotations
 import ctypes as C
 import os
 from dataclasses import dataclass, field
-from fractions import Fraction
 from typing import Optional, Sequence
 
 import numpy as np
@@ -107,19 +106,6 @@ def load():
 
 def strerror(status: int) -> str:
     return load().tgrad_strerror(int(status)).decode()
-
-
-def sparse_count(density: Fraction, numel: int) -> int:
-    """k = ceil(rho I) in exact integer arithmetic (what the caller passes as k_sparse)."""
-    d = Fraction(density)
-    q, r = divmod(d.numerator * int(numel), d.denominator)
-    return int(q + (1 if r else 0))
-
-
-def rank_from_ratio(ratio: Fraction, extent: int) -> int:
-    """Round-half-up rank for a per-mode ratio, at least 1."""
-    ratio = Fraction(ratio)
-    return max(1, int((2 * ratio.numerator * extent + ratio.denominator) // (2 * ratio.denominator)))
 
 
 def make_config(shape: Sequence[int], rank: Sequence[int], k_sparse: int, *, grad_dtype=TGRAD_C64,

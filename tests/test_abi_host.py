@@ -7,7 +7,7 @@ from fractions import Fraction
 
 import pytest
 
-from paper_2501_02379_amd import synth, tgrad as T
+from paper_2501_02379_amd import sizing, synth, tgrad as T
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -98,8 +98,8 @@ def test_null_and_misaligned_pointers():
 
 def test_caller_side_sizes():
     for w in synth.WORKLOADS.values():
-        assert T.sparse_count(Fraction(*w.density), w.numel) == w.k
-        assert tuple(T.rank_from_ratio(Fraction(1, 2) if w.name == "cfg1" else Fraction(1, 4), i)
+        assert sizing.sparse_count(Fraction(*w.density), w.numel) == w.k
+        assert tuple(sizing.rank_from_ratio(Fraction(1, 2) if w.name == "cfg1" else Fraction(1, 4), i)
                      for i in w.shape) == w.ranks
 
 

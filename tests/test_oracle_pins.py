@@ -822,3 +822,22 @@ def test_synthetic_inputs_are_seeded_and_shaped():
     back = (bits.astype(np.uint32) << 16).view(np.float32)
     assert back[0] == 1.0 and back[1] == 1.0 and back[2] == 1.015625 and back[3] == -2.5
     assert abs(back[4] - 3.1415927) <= 2.0 ** -7
+
+
+def test_planted_low_rank_recipe_really_carries_its_outliers():
+    """cfg2's recipe: planted Tucker-rank signal of unit variance + CN(0, 0.1) noise + Student-t
+    (nu = 2) outliers of scale 10 at 1 % of the positions.  The outliers are added through a flat
+    view of the tensor; this checks that they arrive (heavy tail at exactly the seeded positions,
+    ordinary entries elsewhere)."""
+    w = synth.WORKLOADS["cfg2"]
+    g = synth.gradient(w, 3)
+    assert g.flags.c_contiguous and g.shape == w.shape
+    pos = synth.outlier_positions(w.numel, w.outlier_frac, 97 + w.config_id)
+    assert len(pos) == round(w.numel / 100)
+    mag = np.abs(g.reshape(-1))
+    rest = np.ones(w.numel, dtype=bool)
+    rest[pos] = False
+    assert np.median(mag[pos]) > 8 * np.median(mag[rest])      # scale 10 against unit variance
+    assert mag[pos].max() > 300 and mag[rest].max() < 10        # the t(2) tail; Gaussian elsewhere
+    # signal + noise without the outliers: variance 1 + 0.1
+    assert abs(np.mean(mag[rest] ** 2) - 1.1) < 0.05
