@@ -109,7 +109,8 @@ def kernel_model(w, fused, weight_bytes=8, core_fused=False):
     m["select_split"] = {"bytes": I * gb + 2 * (I // 8), "flops": 3 * I, "bound": "hbm"}
     m["select_count"] = {"bytes": 2 * (I // 8), "flops": 0, "bound": "hbm"}
     m["select_emit"] = {"bytes": 3 * (I // 8) + 4 * k, "flops": 0, "bound": "hbm"}
-    gram_fl = sum(8 * I * shape[n] for n in range(N) if ranks[n] < shape[n])
+    # a Gram matrix is Hermitian: I (I_n + 1) / 2 complex multiply-adds give all of it
+    gram_fl = sum(8 * I * (shape[n] + 1) // 2 for n in range(N) if ranks[n] < shape[n])
     ngram = sum(1 for n in range(N) if ranks[n] < shape[n])
     m["gram"] = {"bytes": ngram * I * gb, "flops": gram_fl, "bound": "mfma64", "launches_per_step": ngram}
     return m
