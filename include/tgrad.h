@@ -18,6 +18,12 @@
  *  - All device work is enqueued on the one HIP stream given at init.  Neither
  *    `tgrad_step` nor `tgrad_refresh_factors` waits for the device; only
  *    `tgrad_get_state`, `tgrad_set_state` and `tgrad_get_kernel_times` do.
+ *  - Every kernel launch is checked where it happens.  A HIP error that is already pending when
+ *    `tgrad_step`, `tgrad_step_static` or `tgrad_refresh_factors` is entered belongs to the caller:
+ *    the call returns TGRAD_ERR_HIP, launches nothing and leaves the error in place.
+ *  - Which kernels serve a configuration is a function of the configuration alone (no environment
+ *    switches): matrix-core kernels for the shapes they cover (last-mode rank <= 32 and last extent
+ *    >= 2; two modes per pass when the shape allows), one-thread-per-output kernels for the rest.
  *  - A context is used from one host thread at a time.
  *  - Tensors are dense, row-major (last mode fastest).  TGRAD_C64 elements are
  *    interleaved (re, im) float32 pairs (8 bytes); TGRAD_CBF16 elements are
@@ -38,6 +44,7 @@ extern "C" {
 
 #define TGRAD_MAX_NDIM 6
 #define TGRAD_MAX_HOOI_SWEEPS 64
+#define TGRAD_MAX_EIG_SWEEPS 30       /* Jacobi sweeps an eigen-solve may take */
 #define TGRAD_MAX_EXTENT 256          /* largest I_n the factor refresh accepts */
 #define TGRAD_STATIC_WORKSPACE_BYTES (32u << 20)   /* scratch of tgrad_step_static, per GPU */
 
@@ -53,7 +60,9 @@ enum {
   TGRAD_ERR_UNSUPPORTED = -2,   /* valid in the paper's terms, but not built (see field comments) */
   TGRAD_ERR_NOT_READY = -3,     /* step or state read before any refresh / factor injection */
   TGRAD_ERR_HIP = -4,           /* a HIP runtime call or kernel launch failed */
-  TGRAD_ERR_TOO_SMALL = -5      /* host buffer smaller than the requested item */
+  TGRAD_ERR_TOO_SMALL = -5,     /* host buffer smaller than the requested item */
+  TGRAD_ERR_NOT_CONVERGED = -6  /* tgrad_get_state of a factor whose eigen-solve stopped at its sweep limit
+                                   with rotations still to do (the factor is delivered all the same) */
 };
 
 /* Items of `tgrad_get_state` / `tgrad_set_state` (host-side formats in the comments). */
@@ -67,7 +76,9 @@ enum {
   TGRAD_STATE_SPARSE_G = 6,     /* float32[2*k]: values gathered at Omega by the last step (read-only) */
   TGRAD_STATE_CORE_G = 7,       /* float32[2*C]: compressed gradient of the last step (read-only) */
   TGRAD_STATE_GRAM0 = 32,       /* + n: float64[2*I_n*I_n] mode-n Gram of the last refresh (read-only) */
-  TGRAD_STATE_FACTOR0 = 64      /* + n: float32[2*I_n*r_n]: U^(n), row-major I_n x r_n, interleaved complex */
+  TGRAD_STATE_FACTOR0 = 64,     /* + n: float32[2*I_n*r_n]: U^(n), row-major I_n x r_n, interleaved complex */
+  TGRAD_STATE_EIG_INFO0 = 96    /* + n: int32[2] of mode n's last eigen-solve: {1 if it stopped at the sweep limit
+                                   else 0, sweeps run} (read-only; compressed modes only) */
 };
 
 /*
@@ -120,6 +131,9 @@ typedef struct {
                                          that finds every factor present (from an earlier refresh or
                                          tgrad_set_state) starts its sweeps from those factors instead
                                          of from HOSVD (the warm restart of the same appendix) */
+  int32_t eig_max_sweeps;             /* cyclic-Jacobi sweeps an eigen-solve of the refresh may take:
+                                         1..TGRAD_MAX_EIG_SWEEPS, or 0 = that maximum.  A solve that uses
+                                         them up is reported by tgrad_get_state (NOT_CONVERGED) */
 } tgrad_config;
 
 /*
@@ -146,11 +160,14 @@ int tgrad_init(tgrad_ctx** out, const tgrad_config* cfg, void* state_dev, void* 
                void* hip_stream);
 
 /*
- * Algorithm 1, the `t mod T = 0` branch: Omega <- SparseIndices(G, rho, top-k magnitude);
- * R_L <- G - Sparse(G, Omega); {U^(n)} <- TuckerFactors(R_L, r) (HOSVD: eigenvectors of the r_n
- * largest eigenvalues of each mode-n Gram matrix R_L(n) R_L(n)^H, descending, every column
- * multiplied by the unit phase that makes its largest-modulus entry real and positive).
- * Selection order: (|g|^2 descending, linear index ascending), |g|^2 evaluated in float32 as
+ * Algorithm 1, the `t mod T = 0` branch, for cfg.order == TGRAD_ORDER_US_LR:
+ * Omega <- SparseIndices(G, rho, cfg.select_rule); R_L <- G - Sparse(G, Omega);
+ * {U^(n)} <- TuckerFactors(R_L, r): HOSVD (eigenvectors of the r_n largest eigenvalues of each mode-n
+ * Gram matrix R_L(n) R_L(n)^H, descending, every column multiplied by the unit phase that makes its
+ * largest-modulus entry real and positive), then cfg.hooi_sweeps HOOI sweeps (from the factors in
+ * place instead of from HOSVD when cfg.warm_restart applies).  The two other composition orders
+ * take the factors from the full G and (TGRAD_ORDER_LR_US) the support from G - G~_L; see cfg.order.
+ * Top-k order: (|g|^2 descending, linear index ascending), |g|^2 evaluated in float32 as
  * fl(fl(re*re) + fl(im*im)).  Touches neither the moments nor t.
  *  grad_dev   device pointer to G (cfg.grad_dtype), read only.
  * Errors: INVALID_ARG, HIP.
@@ -204,6 +221,17 @@ int tgrad_step_static(const tgrad_config* cfg, void* state_dev, int64_t t, void*
  * Errors: INVALID_ARG, TOO_SMALL, NOT_READY (indices/factors before any refresh), HIP.
  */
 int tgrad_get_state(tgrad_ctx* ctx, int what, void* host_out, size_t cap);
+
+/*
+ * Non-finite gradient entries seen by the last refresh (waits for the stream).  The top-k selection
+ * already builds a histogram of the leading bits of |g|^2 for every refresh; the entries whose
+ * |g|^2 is inf or NaN (a non-finite part, or a magnitude above 1.8e19) are its top bins, so this
+ * costs no extra pass over the gradient.  Algorithm 1 is undefined on such a gradient.
+ *  nonfinite  host pointer, out: their number.
+ * Errors: INVALID_ARG; UNSUPPORTED (rand-k selection or k_sparse == 0: no such histogram exists);
+ *         NOT_READY (no refresh yet); HIP.
+ */
+int tgrad_check(tgrad_ctx* ctx, int64_t* nonfinite);
 
 /*
  * Overwrite one state item from the host (checkpoint restore, or injecting externally computed

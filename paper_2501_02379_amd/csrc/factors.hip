@@ -278,8 +278,11 @@ struct EigJob {
   double* A;            // work copy
   double* V;            // eigenvector accumulator
   float* U;             // out: n x r complex float32, row-major
+  int* status;          // out: [0] = 1 if the solve stopped at the sweep limit with rotations left, else 0;
+                        //      [1] = sweeps run
   int n;
   int r;
+  int max_sweeps;
 };
 struct EigJobs {
   EigJob job[kMaxNdim];
@@ -416,7 +419,8 @@ __global__ __launch_bounds__(kEigThreads) void k_eig(EigJobs jobs) {
   const int m = n + (n & 1);                                             // even player count
   const int half = m / 2;
 
-  for (int sweep = 0; sweep < kEigMaxSweeps; ++sweep) {
+  int sweeps_run = 0, converged = 0;
+  for (int sweep = 0; sweep < jb.max_sweeps; ++sweep) {
     if (tid == 0) nrot = 0;
     __syncthreads();
     for (int round = 0; round < m - 1; ++round) {
@@ -510,7 +514,15 @@ __global__ __launch_bounds__(kEigThreads) void k_eig(EigJobs jobs) {
     }
     const int done = (nrot == 0);
     __syncthreads();
-    if (done) break;
+    ++sweeps_run;
+    if (done) {
+      converged = 1;
+      break;
+    }
+  }
+  if (tid == 0) {
+    jb.status[0] = converged ? 0 : 1;
+    jb.status[1] = sweeps_run;
   }
 
   for (int i = tid; i < n; i += kEigThreads) lam[i] = A[i * n + i].x;
@@ -536,7 +548,7 @@ __device__ __forceinline__ void tri_put(double2* T, int i, int j, double2 v) {
 __global__ __launch_bounds__(kEigThreads) void k_eig_tri(EigJobs jobs) {
   extern __shared__ double2 T[];                // lower triangle of the work matrix
   const EigJob jb = jobs.job[blockIdx.x];
-  const int n = jb.n, r = jb.r;
+  const int n = jb.n;
   const int tid = threadIdx.x;
   const double2* G = reinterpret_cast<const double2*>(jb.gram);
   EigLogHeader* hdr = reinterpret_cast<EigLogHeader*>(jb.A);
@@ -631,7 +643,8 @@ __global__ __launch_bounds__(kEigThreads) void k_eig_tri(EigJobs jobs) {
     }
   };
 
-  for (int sweep = 0; sweep < kEigMaxSweeps; ++sweep) {
+  int sweeps_run = 0, converged = 0;
+  for (int sweep = 0; sweep < jb.max_sweeps; ++sweep) {
     if (tid == 0) nrot = 0;
     __syncthreads();
     for (int round = 0; round < m - 1; ++round) {
@@ -678,10 +691,18 @@ __global__ __launch_bounds__(kEigThreads) void k_eig_tri(EigJobs jobs) {
     }
     const int done = (nrot == 0);
     __syncthreads();
-    if (done) break;
+    ++sweeps_run;
+    if (done) {
+      converged = 1;
+      break;
+    }
   }
   for (int i = tid; i < n; i += kEigThreads) hdr->lam[i] = T[tri_idx(i, i)].x;
-  if (tid == 0) hdr->rounds = nlogged;
+  if (tid == 0) {
+    hdr->rounds = nlogged;
+    jb.status[0] = converged ? 0 : 1;
+    jb.status[1] = sweeps_run;
+  }
 }
 
 // Eigenvector accumulator from the rotation log: V = R_1 R_2 ... (every round's rotations act on
@@ -791,7 +812,9 @@ void launch_gram_reduce(hipStream_t s, const double* partials, int nchunks, int 
 }
 
 void launch_eig_batch(hipStream_t s, int njobs, const double* const* gram, double* const* work_a,
-                      double* const* work_v, const int* In, const int* r, float* const* U) {
+                      double* const* work_v, const int* In, const int* r, float* const* U, int* const* status,
+                      int max_sweeps) {
+  if (max_sweeps <= 0 || max_sweeps > kEigMaxSweeps) max_sweeps = kEigMaxSweeps;   // the log is sized for kEigMaxSweeps
   if (njobs <= 0) return;
   EigJobs small, large;                          // n <= 128: work matrix in LDS; larger: in memory
   int nsmall = 0, nlarge = 0, nmax = 0;
@@ -801,8 +824,10 @@ void launch_eig_batch(hipStream_t s, int njobs, const double* const* gram, doubl
     jb.A = work_a[i];
     jb.V = work_v[i];
     jb.U = U[i];
+    jb.status = status[i];
     jb.n = In[i];
     jb.r = r[i];
+    jb.max_sweeps = max_sweeps;
     if (In[i] <= kEigTriMaxN) {
       small.job[nsmall++] = jb;
       if (In[i] > nmax) nmax = In[i];

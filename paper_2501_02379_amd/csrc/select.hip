@@ -389,11 +389,26 @@ __global__ void k_mask_from_indices(const int32_t* __restrict__ omega, int64_t k
   }
 }
 
-// Plain streaming copy (16 bytes per lane per step), the reference point for memory counters.
-__global__ __launch_bounds__(256) void k_copy16(float4* __restrict__ dst, const float4* __restrict__ src,
+// Plain streaming copy, the reference point for memory counters and for the copy rate this box
+// reaches: every lane keeps four 16-byte pieces in flight (the same depth the optimizer's streaming
+// kernels use), loads and stores marked non-temporal like theirs.
+typedef float f32x4c __attribute__((ext_vector_type(4)));
+constexpr int kCopyDepth = 4;
+__global__ __launch_bounds__(256) void k_copy16(f32x4c* __restrict__ dst, const f32x4c* __restrict__ src,
                                                 int64_t n16) {
-  const int64_t stride = (int64_t)gridDim.x * 256;
-  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+  // a workgroup moves contiguous runs of 256 * kCopyDepth pieces (16 KB), run after run
+  constexpr int64_t kRun = 256 * kCopyDepth;
+  const int64_t nruns = n16 / kRun;
+  for (int64_t r = blockIdx.x; r < nruns; r += gridDim.x) {
+    const int64_t base = r * kRun + threadIdx.x;
+    f32x4c v[kCopyDepth];
+#pragma unroll
+    for (int u = 0; u < kCopyDepth; ++u) v[u] = __builtin_nontemporal_load(src + base + u * 256);
+#pragma unroll
+    for (int u = 0; u < kCopyDepth; ++u) __builtin_nontemporal_store(v[u], dst + base + u * 256);
+  }
+  for (int64_t i = nruns * kRun + (int64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (int64_t)gridDim.x * 256)
+    __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
 
 __global__ void k_zero_u32(uint32_t* p, int64_t n) {
@@ -406,9 +421,8 @@ __global__ void k_zero_u32(uint32_t* p, int64_t n) {
 void launch_copy16(hipStream_t s, void* dst, const void* src, int64_t n16) {
   if (n16 <= 0) return;
   const int64_t want = (n16 + 255) / 256;
-  const unsigned grid = (unsigned)(want < 256 * 16 ? want : 256 * 16);
-  k_copy16<<<dim3(grid), dim3(256), 0, s>>>(reinterpret_cast<float4*>(dst), reinterpret_cast<const float4*>(src),
-                                            n16);
+  const unsigned grid = (unsigned)(want < 256 * 8 ? want : 256 * 8);
+  k_copy16<<<dim3(grid), dim3(256), 0, s>>>(reinterpret_cast<f32x4c*>(dst), reinterpret_cast<const f32x4c*>(src), n16);
 }
 
 void zero_u32(hipStream_t s, uint32_t* p, int64_t n) {

@@ -13,7 +13,8 @@ namespace tgrad {
 void zero_u32(hipStream_t s, uint32_t* p, int64_t n);
 void launch_copy16(hipStream_t s, void* dst, const void* src, int64_t n16);
 void launch_eig_batch(hipStream_t s, int njobs, const double* const* gram, double* const* work_a,
-                      double* const* work_v, const int* In, const int* r, float* const* U);
+                      double* const* work_v, const int* In, const int* r, float* const* U, int* const* status,
+                      int max_sweeps);
 void launch_identity_factor(hipStream_t s, float* U, int n);
 }  // namespace tgrad
 
@@ -50,7 +51,7 @@ struct Plan {
   // byte offsets into state
   size_t st_omega, st_ms, st_vs, st_ml, st_vl, st_U[kMaxNdim], state_bytes;
   // byte offsets into workspace
-  size_t ws_sel, ws_hist, ws_chunk_gt, ws_chunk_eq, ws_mask, ws_cand, ws_tile_start, ws_fpad, ws_ut, ws_partials, ws_gram[kMaxNdim],
+  size_t ws_sel, ws_hist, ws_eig_status, ws_chunk_gt, ws_chunk_eq, ws_mask, ws_cand, ws_tile_start, ws_fpad, ws_ut, ws_partials, ws_gram[kMaxNdim],
       ws_eig_a[kMaxNdim], ws_eig_v[kMaxNdim], ws_gs, ws_core_g, ws_core_n, ws_buf[2], workspace_bytes;
   int gram_chunks[kMaxNdim];
   int order = 0;                   // TGRAD_ORDER_*
@@ -118,6 +119,7 @@ int validate(const tgrad_config* c) {
   if (c->hooi_sweeps < 0 || c->hooi_sweeps > TGRAD_MAX_HOOI_SWEEPS) return TGRAD_ERR_INVALID_ARG;
   if (c->order != TGRAD_ORDER_US_LR && c->order != TGRAD_ORDER_LR_US && c->order != TGRAD_ORDER_SUM)
     return TGRAD_ERR_INVALID_ARG;
+  if (c->eig_max_sweeps < 0 || c->eig_max_sweeps > TGRAD_MAX_EIG_SWEEPS) return TGRAD_ERR_INVALID_ARG;
   if (c->warm_restart != 0 && c->warm_restart != 1) return TGRAD_ERR_INVALID_ARG;
   if (c->warm_restart == 1 && c->hooi_sweeps < 1) return TGRAD_ERR_INVALID_ARG;
   if (c->select_rule != TGRAD_SELECT_TOPK_MAG && c->select_rule != TGRAD_SELECT_RANDOM)
@@ -199,6 +201,7 @@ void make_plan(const tgrad_config* c, Plan* p) {
   o = 0;
   p->ws_sel = take(sizeof(SelectScalars));
   p->ws_hist = take(3 * kHistBins * 4);
+  p->ws_eig_status = take(2 * kMaxNdim * sizeof(int));   // per mode: 1 if the last solve stopped at the sweep limit, sweeps run
   p->ws_chunk_gt = take((size_t)p->nchunks * 4);
   p->ws_chunk_eq = take((size_t)p->nchunks * 4);
   p->ws_mask = take((size_t)p->mask_words * 4);
@@ -286,6 +289,8 @@ struct tgrad_ctx {
   int64_t t;
   bool have_indices;
   bool have_factor[kMaxNdim];
+  bool have_hist;                 // the leading-digit histogram of the last refresh's gradient is in the workspace
+  int launch_status;              // first failed kernel launch of the current call (TGRAD_OK = none)
   bool profiling;
   std::vector<EventPair> events;
   double total_ms[KID_COUNT];
@@ -320,6 +325,9 @@ struct Scope {
     }
   }
   ~Scope() {
+    // every launch is checked where it happens, so a failure is charged to the call (and kernel)
+    // that caused it
+    if (hipGetLastError() != hipSuccess && c->launch_status == TGRAD_OK) c->launch_status = TGRAD_ERR_HIP;
     if (a && b) {
       (void)hipEventRecord(b, c->stream);
       c->events.push_back({a, b, kid});
@@ -343,6 +351,19 @@ int drain_events(tgrad_ctx* c) {
 }
 
 int check_launch() { return hipGetLastError() == hipSuccess ? TGRAD_OK : TGRAD_ERR_HIP; }
+
+// Status of the launches of the call that is ending: the first failure a Scope saw, else whatever the
+// runtime still reports (launches outside a Scope); the per-call record is cleared.
+int finish_call(tgrad_ctx* c) {
+  const int tail = check_launch();
+  const int rc = c->launch_status != TGRAD_OK ? c->launch_status : tail;
+  c->launch_status = TGRAD_OK;
+  return rc;
+}
+
+// An error that was pending in the runtime BEFORE this library launched anything belongs to the
+// caller: it is reported (not cleared, so the caller still finds it) and nothing is launched.
+bool error_pending_on_entry() { return hipPeekAtLastError() != hipSuccess; }
 
 // Kernel-ready copies of U^(N-1) for the fused kernels; rebuilt whenever that factor changes
 // (refresh, HOOI sweep, tgrad_set_state), never on the step path.
@@ -388,6 +409,7 @@ void select_support(tgrad_ctx* c, const void* x, int dt) {
     { Scope sc_(c, KID_SEL_SCAN); launch_select_scan(s, chunk_gt, chunk_eq, p.nchunks); }
     { Scope sc_(c, KID_SEL_EMIT); launch_select_emit(s, x, dt, keys, p.I, sc, chunk_gt, chunk_eq, p.nchunks, mask, cand, omega); }
   }
+  c->have_hist = p.k > 0 && !keys.random;
   {
     Scope sc_(c, KID_TILE_OFFSETS);
     launch_tile_offsets(s, omega, p.k, p.tile_elems, p.ntiles, c->w<uint32_t>(p.ws_tile_start));
@@ -422,6 +444,7 @@ void compute_factors(tgrad_ctx* c, const void* g, const uint32_t* tile_start, co
   double* wv[kMaxNdim];
   int In[kMaxNdim], rr[kMaxNdim];
   float* Us[kMaxNdim];
+  int* stat[kMaxNdim];
   int njobs = 0;
   for (int n = 0; n < p.N; ++n) {
     float* U = c->st<float>(p.st_U[n]);
@@ -442,13 +465,14 @@ void compute_factors(tgrad_ctx* c, const void* g, const uint32_t* tile_start, co
       In[njobs] = (int)p.shape[n];
       rr[njobs] = p.rank[n];
       Us[njobs] = U;
+      stat[njobs] = c->w<int>(p.ws_eig_status) + 2 * n;
       ++njobs;
     }
     c->have_factor[n] = true;
   }
   if (njobs > 0) {
     Scope sc_(c, KID_EIG);
-    launch_eig_batch(s, njobs, grams, wa, wv, In, rr, Us);
+    launch_eig_batch(s, njobs, grams, wa, wv, In, rr, Us, stat, c->cfg.eig_max_sweeps);
   }
 
   // --- HOOI sweeps: mode n re-solved on the tensor compressed in every other mode ---
@@ -478,8 +502,9 @@ void compute_factors(tgrad_ctx* c, const void* g, const uint32_t* tile_start, co
       double* v1[1] = {c->w<double>(p.ws_eig_v[n])};
       int i1[1] = {(int)p.shape[n]}, r1[1] = {p.rank[n]};
       float* u1[1] = {c->st<float>(p.st_U[n])};
+      int* s1[1] = {c->w<int>(p.ws_eig_status) + 2 * n};
       Scope sc_(c, KID_EIG);
-      launch_eig_batch(s, 1, g1, a1, v1, i1, r1, u1);
+      launch_eig_batch(s, 1, g1, a1, v1, i1, r1, u1, s1, c->cfg.eig_max_sweeps);
     }
   }
   pack_fused_factor(c);
@@ -510,14 +535,14 @@ int do_refresh(tgrad_ctx* c, const void* g) {
     // Algorithm 1: support from G, factors from G with the support removed
     select_support(c, g, dt);
     compute_factors(c, g, real_ts, p.k > 0 ? c->w<uint32_t>(p.ws_mask) : nullptr);
-    return check_launch();
+    return finish_call(c);
   }
   const uint32_t* zero_ts = c->w<uint32_t>(p.ws_tile_zero);
   if (p.order == TGRAD_ORDER_SUM) {
     // both components see the full gradient
     select_support(c, g, dt);
     compute_factors(c, g, zero_ts, nullptr);
-    return check_launch();
+    return finish_call(c);
   }
   // low rank first: factors of the full gradient, then the support from R = G - G~_L
   compute_factors(c, g, zero_ts, nullptr);
@@ -541,7 +566,7 @@ int do_refresh(tgrad_ctx* c, const void* g) {
     launch_residual(s, g, dt, z, c->st<float2>(p.st_U[p.N - 1]), p.rank[p.N - 1], sg.A, sg.M, c->w<float2>(p.ws_resid));
   }
   select_support(c, c->w<float2>(p.ws_resid), TGRAD_C64);
-  return check_launch();
+  return finish_call(c);
 }
 
 int do_step(tgrad_ctx* c, void* weight, const void* g) {
@@ -661,7 +686,7 @@ int do_step(tgrad_ctx* c, void* weight, const void* g) {
     }
   }
   c->t += 1;
-  return check_launch();
+  return finish_call(c);
 }
 
 struct Item {
@@ -690,6 +715,16 @@ int locate(tgrad_ctx* c, int what, Item* it) {
     const int n = what - TGRAD_STATE_FACTOR0;
     it->dev = c->state + p.st_U[n];
     it->bytes = (size_t)p.shape[n] * p.rank[n] * 8;
+    it->needs_factor = true;
+    it->mode = n;
+    return TGRAD_OK;
+  }
+  if (what >= TGRAD_STATE_EIG_INFO0 && what < TGRAD_STATE_EIG_INFO0 + p.N) {
+    const int n = what - TGRAD_STATE_EIG_INFO0;
+    if (p.rank[n] == p.shape[n]) return TGRAD_ERR_INVALID_ARG;     // identity factor: nothing is solved
+    it->dev = c->ws + p.ws_eig_status + (size_t)2 * n * sizeof(int);
+    it->bytes = 2 * sizeof(int);
+    it->writable = false;
     it->needs_factor = true;
     it->mode = n;
     return TGRAD_OK;
@@ -763,11 +798,15 @@ int tgrad_init(tgrad_ctx** out, const tgrad_config* cfg, void* state_dev, void* 
   c->t = 0;
   c->have_indices = false;
   for (int n = 0; n < kMaxNdim; ++n) c->have_factor[n] = false;
+  c->have_hist = false;
+  c->launch_status = TGRAD_OK;
   c->profiling = false;
   for (int i = 0; i < KID_COUNT; ++i) {
     c->total_ms[i] = 0.;
     c->launches[i] = 0;
   }
+  // no solve has hit its sweep limit yet (a factor injected with tgrad_set_state never does)
+  zero_u32(c->stream, c->w<uint32_t>(c->plan.ws_eig_status), 2 * kMaxNdim);
   // moments <- 0 (and everything else in the state block), with a fill kernel
   zero_u32(c->stream, reinterpret_cast<uint32_t*>(c->state), (int64_t)(c->plan.state_bytes / 4));
   if (c->plan.order != TGRAD_ORDER_US_LR)
@@ -783,6 +822,7 @@ int tgrad_init(tgrad_ctx** out, const tgrad_config* cfg, void* state_dev, void* 
 int tgrad_refresh_factors(tgrad_ctx* ctx, const void* grad_dev) {
   if (!ctx || !grad_dev) return TGRAD_ERR_INVALID_ARG;
   if ((uintptr_t)grad_dev % 16) return TGRAD_ERR_INVALID_ARG;
+  if (error_pending_on_entry()) return TGRAD_ERR_HIP;
   return do_refresh(ctx, grad_dev);
 }
 
@@ -790,6 +830,7 @@ int tgrad_step(tgrad_ctx* ctx, void* weight_dev, const void* grad_dev) {
   if (!ctx || !weight_dev || !grad_dev) return TGRAD_ERR_INVALID_ARG;
   if (((uintptr_t)grad_dev % 16) || ((uintptr_t)weight_dev % 16) || weight_dev == grad_dev)
     return TGRAD_ERR_INVALID_ARG;
+  if (error_pending_on_entry()) return TGRAD_ERR_HIP;
   if (ctx->cfg.refresh_every > 0 && ctx->t % ctx->cfg.refresh_every == 0) {
     int rc = do_refresh(ctx, grad_dev);
     if (rc != TGRAD_OK) return rc;
@@ -820,7 +861,10 @@ int tgrad_step_static(const tgrad_config* cfg, void* state_dev, int64_t t, void*
   c.t = t;
   c.have_indices = true;                                          // the caller's contract for t % T != 0
   for (int n = 0; n < kMaxNdim; ++n) c.have_factor[n] = true;
+  c.have_hist = false;
+  c.launch_status = TGRAD_OK;
   c.profiling = false;
+  if (error_pending_on_entry()) return TGRAD_ERR_HIP;
   Plan& p = c.plan;
   if (p.order != TGRAD_ORDER_US_LR) zero_u32(c.stream, c.w<uint32_t>(p.ws_tile_zero), p.ntiles + 1);
   if (t % cfg->refresh_every == 0) {
@@ -865,6 +909,32 @@ int tgrad_get_state(tgrad_ctx* ctx, int what, void* host_out, size_t cap) {
   if (cap < it.bytes) return TGRAD_ERR_TOO_SMALL;
   if (hipStreamSynchronize(ctx->stream) != hipSuccess) return TGRAD_ERR_HIP;
   if (it.bytes && hipMemcpy(host_out, it.dev, it.bytes, hipMemcpyDeviceToHost) != hipSuccess) return TGRAD_ERR_HIP;
+  if (what >= TGRAD_STATE_FACTOR0 && what < TGRAD_STATE_FACTOR0 + p.N && p.rank[it.mode] < p.shape[it.mode]) {
+    // the factor is delivered either way; the status says whether its eigen-solve ran to the end
+    int info[2] = {0, 0};
+    if (hipMemcpy(info, ctx->ws + p.ws_eig_status + (size_t)2 * it.mode * sizeof(int), sizeof(info),
+                  hipMemcpyDeviceToHost) != hipSuccess)
+      return TGRAD_ERR_HIP;
+    if (info[0] != 0) return TGRAD_ERR_NOT_CONVERGED;
+  }
+  return TGRAD_OK;
+}
+
+int tgrad_check(tgrad_ctx* ctx, int64_t* nonfinite) {
+  if (!ctx || !nonfinite) return TGRAD_ERR_INVALID_ARG;
+  *nonfinite = -1;
+  const Plan& p = ctx->plan;
+  if (ctx->cfg.select_rule != TGRAD_SELECT_TOPK_MAG || p.k == 0) return TGRAD_ERR_UNSUPPORTED;
+  if (!ctx->have_hist) return TGRAD_ERR_NOT_READY;
+  if (hipStreamSynchronize(ctx->stream) != hipSuccess) return TGRAD_ERR_HIP;
+  // |g|^2 = inf or NaN has all exponent bits set: leading 12-bit digit 0x7F8 or above
+  constexpr int kFirst = 0x7F8;
+  uint32_t tail[kHistBins - kFirst];
+  if (hipMemcpy(tail, ctx->ws + p.ws_hist + (size_t)kFirst * 4, sizeof(tail), hipMemcpyDeviceToHost) != hipSuccess)
+    return TGRAD_ERR_HIP;
+  int64_t n = 0;
+  for (uint32_t v : tail) n += v;
+  *nonfinite = n;
   return TGRAD_OK;
 }
 
@@ -976,6 +1046,7 @@ const char* tgrad_strerror(int status) {
     case TGRAD_ERR_NOT_READY: return "no sparse support / Tucker factors yet (refresh first)";
     case TGRAD_ERR_HIP: return "HIP runtime call or kernel launch failed";
     case TGRAD_ERR_TOO_SMALL: return "host buffer too small";
+    case TGRAD_ERR_NOT_CONVERGED: return "eigen-solve of a factor stopped at its sweep limit";
     default: return "unknown status";
   }
 }

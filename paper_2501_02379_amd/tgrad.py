@@ -25,15 +25,16 @@ TGRAD_ERR_UNSUPPORTED = -2
 TGRAD_ERR_NOT_READY = -3
 TGRAD_ERR_HIP = -4
 TGRAD_ERR_TOO_SMALL = -5
+TGRAD_ERR_NOT_CONVERGED = -6
 
 STATE_STEP, STATE_INDICES, STATE_CORE_M, STATE_CORE_V = 0, 1, 2, 3
 STATE_SPARSE_M, STATE_SPARSE_V, STATE_SPARSE_G, STATE_CORE_G = 4, 5, 6, 7
-STATE_GRAM0, STATE_FACTOR0 = 32, 64
+STATE_GRAM0, STATE_FACTOR0, STATE_EIG_INFO0 = 32, 64, 96
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libtgrad.so")
 
 EXPORTS = (
-    "tgrad_query_sizes", "tgrad_init", "tgrad_refresh_factors", "tgrad_step", "tgrad_step_static", "tgrad_get_state",
+    "tgrad_query_sizes", "tgrad_init", "tgrad_refresh_factors", "tgrad_step", "tgrad_step_static", "tgrad_get_state", "tgrad_check",
     "tgrad_set_state", "tgrad_set_profiling", "tgrad_get_kernel_times", "tgrad_calibration_copy",
     "tgrad_destroy", "tgrad_strerror",
 )
@@ -60,6 +61,7 @@ class tgrad_config(C.Structure):
         ("select_seed", C.c_uint64),
         ("order", C.c_int32),
         ("warm_restart", C.c_int32),
+        ("eig_max_sweeps", C.c_int32),
     ]
 
 
@@ -90,6 +92,7 @@ def load():
     lib.tgrad_step_static.argtypes = [C.POINTER(tgrad_config), vp, C.c_int64, vp, vp, vp]
     lib.tgrad_get_state.argtypes = [vp, i32, vp, sz]
     lib.tgrad_set_state.argtypes = [vp, i32, vp, sz]
+    lib.tgrad_check.argtypes = [vp, C.POINTER(C.c_int64)]
     lib.tgrad_set_profiling.argtypes = [vp, i32]
     lib.tgrad_get_kernel_times.argtypes = [vp, C.POINTER(C.c_char_p), C.POINTER(C.c_double),
                                            C.POINTER(C.c_int64), i32]
@@ -112,7 +115,7 @@ def make_config(shape: Sequence[int], rank: Sequence[int], k_sparse: int, *, gra
                 weight_dtype=TGRAD_C64, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, alpha=1.0,
                 lam=1.0, weight_decay=0.0, refresh_every=1, hooi_sweeps=0,
                 select_rule=TGRAD_SELECT_TOPK_MAG, select_seed=0, warm_restart=False,
-                order=TGRAD_ORDER_US_LR) -> tgrad_config:
+                order=TGRAD_ORDER_US_LR, eig_max_sweeps=0) -> tgrad_config:
     cfg = tgrad_config()
     cfg.ndim = len(shape)
     if len(shape) <= MAX_NDIM and len(rank) == len(shape):
@@ -128,6 +131,7 @@ def make_config(shape: Sequence[int], rank: Sequence[int], k_sparse: int, *, gra
     cfg.select_seed = int(select_seed) & 0xFFFFFFFFFFFFFFFF
     cfg.warm_restart = int(warm_restart)
     cfg.order = int(order)
+    cfg.eig_max_sweeps = int(eig_max_sweeps)
     return cfg
 
 
@@ -196,6 +200,8 @@ class Context:
         if STATE_FACTOR0 <= what < STATE_FACTOR0 + len(self.shape):
             n = what - STATE_FACTOR0
             return np.zeros((self.shape[n], self.rank[n]), dtype=np.complex64)
+        if STATE_EIG_INFO0 <= what < STATE_EIG_INFO0 + len(self.shape):
+            return np.zeros(2, dtype=np.int32)
         if STATE_GRAM0 <= what < STATE_GRAM0 + len(self.shape):
             n = what - STATE_GRAM0
             return np.zeros((self.shape[n], self.shape[n]), dtype=np.complex128)
@@ -207,6 +213,14 @@ class Context:
         if rc != TGRAD_OK:
             raise TgradError(rc, "tgrad_get_state")
         return out
+
+    def tgrad_check(self) -> int:
+        """Non-finite gradient entries seen by the last refresh."""
+        n = C.c_int64(-1)
+        rc = self.lib.tgrad_check(self.handle, C.byref(n))
+        if rc != TGRAD_OK:
+            raise TgradError(rc, "tgrad_check")
+        return int(n.value)
 
     def tgrad_set_state(self, what: int, value) -> None:
         ref = self._item_array(what)

@@ -28,11 +28,11 @@ def test_library_exports_every_declared_symbol():
 
 def test_strerror_names_every_status():
     seen = set()
-    for code in (0, -1, -2, -3, -4, -5):
+    for code in (0, -1, -2, -3, -4, -5, -6):
         s = T.strerror(code)
         assert s and s != "unknown status"
         seen.add(s)
-    assert len(seen) == 6
+    assert len(seen) == 7
     assert T.strerror(-99) == "unknown status"
 
 
@@ -69,6 +69,8 @@ def test_query_sizes_counts_the_compressed_state():
     (lambda c: (setattr(c, "hooi_sweeps", 1), setattr(c, "warm_restart", 2)), T.TGRAD_ERR_INVALID_ARG),
     (lambda c: setattr(c, "select_rule", 2), T.TGRAD_ERR_INVALID_ARG),
     (lambda c: setattr(c, "order", 3), T.TGRAD_ERR_INVALID_ARG),
+    (lambda c: setattr(c, "eig_max_sweeps", -1), T.TGRAD_ERR_INVALID_ARG),
+    (lambda c: setattr(c, "eig_max_sweeps", 31), T.TGRAD_ERR_INVALID_ARG),
     (lambda c: setattr(c, "select_rule", -1), T.TGRAD_ERR_INVALID_ARG),
     (lambda c: c.shape.__setitem__(0, 1 << 31), T.TGRAD_ERR_UNSUPPORTED),
 ])

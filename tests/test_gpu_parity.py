@@ -540,3 +540,78 @@ def test_set_state_rejects_bad_indices():
             ctx.tgrad_set_state(T.STATE_INDICES, np.array(bad, dtype=np.int64))
     with pytest.raises(T.TgradError):
         ctx.tgrad_set_state(T.STATE_SPARSE_G, np.zeros(3, np.complex64))     # read-only item
+
+
+# ------------------------------------------------------------------ failure detection
+def test_eigen_solve_reports_convergence_and_a_forced_sweep_limit():
+    """Every compressed mode's solve reports (stalled, sweeps).  With the library's limit a solve
+    ends by itself; with a limit of one sweep (forced from the host) it stops with rotations left:
+    the factor is still delivered and tgrad_get_state says NOT_CONVERGED."""
+    shape, ranks, k = (24, 18, 10), (5, 4, 3), 20
+    g = synth.small_case(shape, 905)
+    ctx = make_gpu_ctx(T, shape, ranks, k, refresh_every=0)
+    ctx.tgrad_refresh_factors(T.to_device_grad(g))
+    for n in range(3):
+        stalled, sweeps = ctx.tgrad_get_state(T.STATE_EIG_INFO0 + n)
+        assert stalled == 0 and 2 <= sweeps <= 30
+        ctx.tgrad_get_state(T.STATE_FACTOR0 + n)                       # no error
+    ctx.tgrad_destroy()
+    ctx = make_gpu_ctx(T, shape, ranks, k, refresh_every=0, eig_max_sweeps=1)
+    ctx.tgrad_refresh_factors(T.to_device_grad(g))
+    for n in range(3):
+        stalled, sweeps = ctx.tgrad_get_state(T.STATE_EIG_INFO0 + n)
+        assert stalled == 1 and sweeps == 1
+        U = np.zeros((shape[n], ranks[n]), dtype=np.complex64)
+        rc = ctx.lib.tgrad_get_state(ctx.handle, T.STATE_FACTOR0 + n, U.ctypes.data, U.nbytes)
+        assert rc == T.TGRAD_ERR_NOT_CONVERGED
+        assert np.all(np.isfinite(U.view(np.float32))) and np.linalg.norm(U) > 0   # delivered all the same
+    # an injected factor is nobody's failed solve
+    ctx.tgrad_set_state(T.STATE_FACTOR0, np.eye(shape[0], ranks[0], dtype=np.complex64))
+    ctx.tgrad_destroy()
+
+
+def test_eigen_solve_on_degenerate_clusters():
+    """A gradient whose mode Gram matrices have exactly repeated eigenvalues (multiplicities 4, 2, 2
+    and a simple tail) up to a perturbation at rounding level.  Any basis of a cluster is correct, so
+    the check is what is unique: the solve ends by itself, the factor is orthonormal, and the energy
+    it captures equals the sum of the leading eigenvalues (the rank does not cut a cluster)."""
+    rng = np.random.default_rng(77)
+    shape = (12, 12)
+    sv = np.array([5, 5, 5, 5, 3, 3, 2, 2, 1, 0.5, 0.25, 0.125])
+    Q1 = np.linalg.qr(rng.standard_normal((12, 12)) + 1j * rng.standard_normal((12, 12)))[0]
+    Q2 = np.linalg.qr(rng.standard_normal((12, 12)) + 1j * rng.standard_normal((12, 12)))[0]
+    g = ((Q1 * sv) @ Q2.conj().T).astype(np.complex64)
+    for r in (4, 6, 8):
+        ctx = make_gpu_ctx(T, shape, (r, r), 0, refresh_every=0)
+        ctx.tgrad_refresh_factors(T.to_device_grad(g))
+        X = O.to_complex128(g)
+        for n in range(2):
+            stalled, sweeps = ctx.tgrad_get_state(T.STATE_EIG_INFO0 + n)
+            assert stalled == 0 and sweeps <= 30
+            U = ctx.tgrad_get_state(T.STATE_FACTOR0 + n).astype(np.complex128)
+            assert np.max(np.abs(U.conj().T @ U - np.eye(r))) < 1e-5
+            Xn = X if n == 0 else X.T
+            captured = np.linalg.norm(U.conj().T @ Xn) ** 2
+            assert abs(captured - np.sum(sv[:r] ** 2)) <= 1e-5 * np.sum(sv ** 2)
+        ctx.tgrad_destroy()
+
+
+def test_check_counts_non_finite_gradient_entries():
+    shape, ranks, k = (16, 16, 8, 5), (8, 8, 4, 3), 103
+    g = synth.small_case(shape, 31).copy()
+    ctx = make_gpu_ctx(T, shape, ranks, k, refresh_every=0)
+    import ctypes
+    n = ctypes.c_int64(0)
+    assert ctx.lib.tgrad_check(ctx.handle, ctypes.byref(n)) == T.TGRAD_ERR_NOT_READY
+    ctx.tgrad_refresh_factors(T.to_device_grad(g))
+    assert ctx.tgrad_check() == 0
+    flat = g.reshape(-1)
+    flat[5] = complex(np.inf, 0.0)
+    flat[77] = complex(0.0, np.nan)
+    flat[1234] = complex(3e19, 3e19)                       # finite parts, |g|^2 overflows float32
+    ctx.tgrad_refresh_factors(T.to_device_grad(g))
+    assert ctx.tgrad_check() == 3
+    ctx.tgrad_destroy()
+    ctx = make_gpu_ctx(T, shape, ranks, k, refresh_every=0, select_rule=T.TGRAD_SELECT_RANDOM)
+    ctx.tgrad_refresh_factors(T.to_device_grad(g))
+    assert ctx.lib.tgrad_check(ctx.handle, ctypes.byref(n)) == T.TGRAD_ERR_UNSUPPORTED
