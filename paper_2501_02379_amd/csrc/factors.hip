@@ -10,6 +10,8 @@
 // float64 is used because Adam in core space is not invariant to the basis inside the subspace:
 // noise-like gradients have relative eigenvalue gaps near 1e-4, and float32 accumulation error
 // divided by such a gap would move the individual eigenvectors far more than the update tolerates.
+#include <type_traits>
+
 #include "device_common.h"
 
 namespace tgrad {
@@ -251,23 +253,320 @@ __global__ __launch_bounds__(kGramThreads) void k_gram(const void* __restrict__ 
   }
 }
 
-// gram[i, j] = sum over chunks of partials[chunk][i, j] for i >= j, in chunk order (deterministic);
-// the upper triangle is the conjugate mirror (k_gram leaves it unwritten).
-__global__ void k_gram_reduce(const double* __restrict__ partials, int nchunks, int In,
-                              double* __restrict__ gram) {
-  const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+// -------------------------------------------------------------------------------------------------
+// k_gram128: the same Gram for extents In <= 128 - one super block, on the diagonal - which is every
+// mode of the FNO shapes.  Same staging scheme and the same arithmetic as k_gram's diagonal case (the
+// two LDS areas take turns, one barrier per staged tile of 16 columns); what differs is what runs
+// next to the f64 matrix instructions, which occupy the SIMD's vector ALU as well:
+//  * 8 wavefronts instead of 16 (256 registers each): the accumulators of 6 tiles and a fetched tile
+//    stay in registers with nothing spilled.  (A spill reload is a vector-memory load: it waits for
+//    every prefetch in flight and puts the memory latency back in front of the matrix phase.)
+//  * Fetch: the element and its support-mask word come through two buffer descriptors (the tile's
+//    first column as base, rebuilt in scalar registers per tile).  A lane's offset is invariant -
+//    row * B + column, plus the wrap into the next leading index - and lanes without an element
+//    (row >= In, column past the chunk) use an offset that the hardware range check answers with
+//    zero: no branches, no 64-bit vector arithmetic.  The mask is applied when the tile is
+//    committed to LDS, so nothing waits for the loads before the matrix phase.
+//  * Matrix phase: a wavefront's tiles are runs inside one tile ROW, so the row-side operands
+//    (xr | xi) and (xi | -xr) are fetched from LDS once per run and column pair (62 operand fetches
+//    per column pair instead of 108), three column pairs ahead of the matrix instructions that use
+//    them; the main loop exists once per shape of tile set, chosen outside the loop, so inside it
+//    the accumulators live in fixed registers.
+// With fewer than 8 tile rows (In <= 112) the tiles are dealt one by one as in k_gram.
+struct GramRuns {                    // a wavefront's tiles when all 8 tile rows exist: run A = (ra, a0 .. a0 + na - 1),
+  signed char ra, a0, na, rb, b0, nb;  // run B = (rb, b0 .. b0 + nb - 1), every run inside one tile row
+};
+// 36 tiles of the lower triangle over 8 wavefronts: 5 tiles for wavefronts 0..3, 4 tiles for 4..7
+// (wavefronts w and w + 4 share a SIMD: 9 tiles per SIMD).  Wavefronts 5..7 hold one run of 4.
+__constant__ GramRuns kGramRuns[8] = {
+    {2, 0, 3, 1, 0, 2}, {4, 0, 3, 3, 0, 2}, {5, 0, 3, 3, 2, 2}, {5, 3, 3, 4, 3, 2},
+    {6, 0, 3, 0, 0, 1}, {6, 3, 2, 6, 5, 2}, {7, 0, 2, 7, 2, 2}, {7, 4, 2, 7, 6, 2}};
+
+constexpr int kGram128Threads = 512;
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t gram_buffer(const void* base, uint32_t bytes) {
+  // untyped buffer, stride 0: a load at an offset >= bytes returns zero
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), (short)0, (int)bytes, 0x00020000);
+}
+
+template <int DT, bool SMALLB>
+__global__ __launch_bounds__(kGram128Threads) void k_gram128(const void* __restrict__ x,
+                                                             const uint32_t* __restrict__ mask, int64_t A, int In,
+                                                             int64_t B64, int64_t cols_per_chunk, uint32_t magicB,
+                                                             double* __restrict__ partials) {
+  extern __shared__ double sG[];
+  constexpr int kEs = DT == TGRAD_C64 ? 8 : 4;        // bytes per element
+  constexpr uint32_t kNowhere = 0xFFFFFFF0u;          // an offset beyond every descriptor: the load returns zero
+  double* buf0 = sG;
+  double* buf1 = sG + kSuper * kRowD;
+  const uint32_t B = (uint32_t)B64;                   // the host takes this kernel only when In * B < 2^28
+  const int64_t J = A * B64;
+  const int64_t c_begin = (int64_t)blockIdx.x * cols_per_chunk;
+  const int64_t c_end = c_begin + cols_per_chunk < J ? c_begin + cols_per_chunk : J;
+  const bool empty = c_begin >= c_end;                // (workgroup-uniform) a trailing chunk without columns writes zeros
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int part = (lane >> 4) & 1, ccol = lane >> 5, lrow = lane & 15;
+  const int ntr = (In + 15) >> 4;                     // tile rows present
+
+  // ---- staging: a thread owns kPer elements (il, cl) of every staged tile ----
+  constexpr int kPer = kSuper * kTC / kGram128Threads;   // 4
+  // lane-invariant offset (elements) of (il, cl) from the tile's first column, before any wrap of the
+  // column into the next leading index; rows that do not exist point nowhere
+  const uint32_t wrap_add = (uint32_t)(In - 1) * B;
+  uint32_t off0[kPer];
+  int cl[kPer], lds_slot[kPer];
+#pragma unroll
+  for (int u = 0; u < kPer; ++u) {
+    const int e = tid + u * kGram128Threads;
+    int il;
+    if (B == 1) { il = e % kSuper; cl[u] = e / kSuper; } else { il = e / kTC; cl[u] = e % kTC; }
+    off0[u] = il < In ? (uint32_t)il * B + (uint32_t)cl[u] : kNowhere;
+    lds_slot[u] = il * kRowD + 4 * cl[u];
+  }
+  const uint64_t total_bytes = (uint64_t)J * (uint64_t)In * kEs;
+  const __amdgpu_buffer_rsrc_t rmask = gram_buffer(mask, mask ? (uint32_t)((((uint64_t)J * In + 31) >> 5) * 4) : 0u);
+
+  // the tile being fetched: first column c = (a0, b0) (workgroup-uniform, scalar registers)
+  uint32_t pa0 = (uint32_t)(c_begin / B64), pb0 = (uint32_t)(c_begin - (int64_t)pa0 * B64);
+  uint32_t pre0[kPer], pre1[kPer];                    // the fetched elements as they lie in memory
+  uint32_t pre_m[kPer], pre_g[kPer];                  // their mask words and global element indices
+  auto fetch_tile = [&](int64_t c0) {                 // the tile that starts at column c0 = (pa0, pb0) -> pre
+    const uint64_t base_e = (uint64_t)pa0 * (uint64_t)In * B + pb0;          // < 2^31 elements
+    const uint64_t base_b = base_e * kEs;
+    const uint64_t left = total_bytes - base_b;       // bytes of the tensor from the tile's first element on
+    const __amdgpu_buffer_rsrc_t rx =
+        gram_buffer(reinterpret_cast<const char*>(x) + base_b, left > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)left);
+    const uint32_t lim = (uint32_t)(c_end - c0 < kTC ? c_end - c0 : kTC);    // columns of this tile inside the chunk
+    const uint32_t base32 = (uint32_t)base_e;
+#pragma unroll
+    for (int u = 0; u < kPer; ++u) {
+      uint32_t off;
+      if constexpr (SMALLB) {                         // B < 16: (b0 + cl) / B wraps, b0 + cl < 32
+        const uint32_t n = pb0 + (uint32_t)cl[u];
+        const uint32_t q = magicB ? __umulhi(n, magicB) : n;
+        off = off0[u] + q * wrap_add;
+      } else {                                        // B >= 16: at most one wrap
+        off = off0[u] + ((pb0 + (uint32_t)cl[u] >= B) ? wrap_add : 0u);
+      }
+      if (off0[u] == kNowhere || (uint32_t)cl[u] >= lim) off = kNowhere;
+      const uint32_t gi = base32 + off;               // global element index (unused where off points nowhere)
+      pre_g[u] = gi;
+      const uint32_t voff = off == kNowhere ? kNowhere : off * kEs;
+      if constexpr (DT == TGRAD_C64) {
+        typedef uint32_t u2 __attribute__((ext_vector_type(2)));
+        const u2 r = __builtin_amdgcn_raw_buffer_load_b64(rx, voff, 0, 0);
+        pre0[u] = r.x;
+        pre1[u] = r.y;
+      } else {
+        pre0[u] = __builtin_amdgcn_raw_buffer_load_b32(rx, voff, 0, 0);
+        pre1[u] = 0u;
+      }
+      pre_m[u] = __builtin_amdgcn_raw_buffer_load_b32(rmask, off == kNowhere ? kNowhere : ((gi >> 5) << 2), 0, 0);
+    }
+  };
+  auto next_tile = [&]() {
+    pb0 += kTC;
+    if constexpr (SMALLB) {
+      const uint32_t q = magicB ? __umulhi(pb0, magicB) : pb0;
+      pa0 += q;
+      pb0 -= q * B;
+    } else {
+      if (pb0 >= B) { pb0 -= B; pa0 += 1; }
+    }
+  };
+  auto commit = [&](double* d) {                      // pre -> one staged tile, as (xr, xi, xi, -xr) per element
+#pragma unroll
+    for (int u = 0; u < kPer; ++u) {
+      float fr, fi;
+      if constexpr (DT == TGRAD_C64) {
+        fr = __uint_as_float(pre0[u]);
+        fi = __uint_as_float(pre1[u]);
+      } else {                                        // a bf16 is the upper half of a float32
+        fr = __uint_as_float(pre0[u] << 16);
+        fi = __uint_as_float(pre0[u] & 0xFFFF0000u);
+      }
+      const bool masked = (pre_m[u] >> (pre_g[u] & 31u)) & 1u;
+      const double xr = (double)(masked ? 0.f : fr), xi = (double)(masked ? 0.f : fi);
+      double2* q = reinterpret_cast<double2*>(d + lds_slot[u]);
+      q[0] = make_double2(xr, xi);
+      q[1] = make_double2(xi, -xr);
+    }
+  };
+
+  // ---- this wavefront's tiles ----
+  constexpr int kMaxT = 6;
+  int ti[kMaxT], tj[kMaxT];
+  bool mine[kMaxT];
+  if (ntr == 8) {
+    const GramRuns g = kGramRuns[wave];
+#pragma unroll
+    for (int k = 0; k < kMaxT; ++k) {
+      const bool in_a = k < g.na;
+      mine[k] = k < g.na + g.nb;
+      ti[k] = in_a ? g.ra : g.rb;
+      tj[k] = !mine[k] ? 0 : in_a ? g.a0 + k : g.b0 + (k - g.na);
+    }
+  } else {                                            // fewer tile rows: tile t of the lower triangle to wavefront t % 8
+    const int ntl = ntr * (ntr + 1) / 2;
+#pragma unroll
+    for (int k = 0; k < kMaxT; ++k) {
+      const int t = wave + 8 * k;
+      int a = (int)((sqrtf(8.f * (float)t + 1.f) - 1.f) * 0.5f);
+      while (a * (a + 1) / 2 > t) --a;
+      while ((a + 1) * (a + 2) / 2 <= t) ++a;
+      mine[k] = t < ntl;
+      ti[k] = mine[k] ? a : 0;
+      tj[k] = mine[k] ? t - a * (a + 1) / 2 : 0;
+    }
+  }
+  v4d accRe[kMaxT], accIm[kMaxT];
+#pragma unroll
+  for (int k = 0; k < kMaxT; ++k) {
+    accRe[k] = (v4d){0., 0., 0., 0.};
+    accIm[k] = (v4d){0., 0., 0., 0.};
+  }
+  const int lane_off = lrow * kRowD + 4 * ccol + part;   // doubles, within a tile row of a staged area
+  // A run of NT tiles of one tile row in accumulator slots S0 ..: the row-side operands are fetched
+  // once per column pair for the whole run, kAhead - 1 column pairs ahead of the matrix instructions
+  // (an LDS fetch right in front of its use leaves the matrix core idle for the LDS latency whenever
+  // the SIMD's other wavefront is not ready).
+  constexpr int kAhead = 3;
+  auto multiply_run = [&](const double* b, auto s0_c, auto nt_c) {
+    constexpr int S0 = decltype(s0_c)::value;
+    constexpr int NT = decltype(nt_c)::value;
+    const double* pa = b + 16 * ti[S0] * kRowD + lane_off;
+    const double* pb[NT];
+#pragma unroll
+    for (int k = 0; k < NT; ++k) pb[k] = b + 16 * tj[S0 + k] * kRowD + lane_off;
+    double ar[kAhead], ai[kAhead], bo[kAhead][NT];
+    auto fetch_ops = [&](int s2) {                    // column 2 s2 + ccol: 4 doubles per column
+      const int slot = s2 % kAhead;
+      ar[slot] = pa[8 * s2];                          // part ? xi : xr
+      ai[slot] = pa[8 * s2 + 2];                      // part ? -xr : xi
+#pragma unroll
+      for (int k = 0; k < NT; ++k) bo[slot][k] = pb[k][8 * s2];
+    };
+#pragma unroll
+    for (int s2 = 0; s2 < kAhead - 1; ++s2) fetch_ops(s2);
+#pragma unroll
+    for (int s2 = 0; s2 < kTC / 2; ++s2) {
+      if (s2 + kAhead - 1 < kTC / 2) fetch_ops(s2 + kAhead - 1);
+      __builtin_amdgcn_sched_barrier(0);
+      const int slot = s2 % kAhead;
+#pragma unroll
+      for (int k = 0; k < NT; ++k) {
+        accRe[S0 + k] = __builtin_amdgcn_mfma_f64_16x16x4f64(ar[slot], bo[slot][k], accRe[S0 + k], 0, 0, 0);
+        accIm[S0 + k] = __builtin_amdgcn_mfma_f64_16x16x4f64(ai[slot], bo[slot][k], accIm[S0 + k], 0, 0, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  auto multiply_single = [&](const double* b) {       // fewer than 8 tile rows: tile by tile
+#pragma unroll
+    for (int k = 0; k < kMaxT; ++k) {
+      if (mine[k]) {
+        const double* pa = b + 16 * ti[k] * kRowD + lane_off;
+        const double* pb = b + 16 * tj[k] * kRowD + lane_off;
+#pragma unroll
+        for (int s2 = 0; s2 < kTC / 2; ++s2) {
+          const double aRe = pa[8 * s2];
+          const double aIm = pa[8 * s2 + 2];
+          const double bop = pb[8 * s2];
+          accRe[k] = __builtin_amdgcn_mfma_f64_16x16x4f64(aRe, bop, accRe[k], 0, 0, 0);
+          accIm[k] = __builtin_amdgcn_mfma_f64_16x16x4f64(aIm, bop, accIm[k], 0, 0, 0);
+        }
+      }
+    }
+  };
+  using I0 = std::integral_constant<int, 0>;
+  using I1 = std::integral_constant<int, 1>;
+  using I2 = std::integral_constant<int, 2>;
+  using I3 = std::integral_constant<int, 3>;
+  using I4 = std::integral_constant<int, 4>;
+
+  // ---- main loop: while the wavefronts multiply tile t out of one LDS area, tile t + 1 is committed
+  // into the other (read last for tile t - 1, before the barrier that ended it) and tile t + 2 is
+  // fetched.  One instance of the loop per shape of a wavefront's tile set; every instance passes the
+  // same barriers. ----
+  auto main_loop = [&](auto na_c, auto nb_c) {        // (NA, NB): runs of NA and NB tiles; (0, 0): tile by tile
+    constexpr int NA = decltype(na_c)::value;
+    constexpr int NB = decltype(nb_c)::value;
+    fetch_tile(c_begin);
+    commit(buf0);
+    if (c_begin + kTC < c_end) { next_tile(); fetch_tile(c_begin + kTC); }
+    __syncthreads();
+    int it = 0;
+    for (int64_t c0 = c_begin; c0 < c_end; c0 += kTC, ++it) {
+      double* cur = (it & 1) ? buf1 : buf0;
+      double* nxt = (it & 1) ? buf0 : buf1;
+      if (c0 + kTC < c_end) commit(nxt);
+      if (c0 + 2 * kTC < c_end) { next_tile(); fetch_tile(c0 + 2 * kTC); }
+      if constexpr (NA == 0) {
+        multiply_single(cur);
+      } else {
+        multiply_run(cur, I0{}, na_c);
+        if constexpr (NB > 0) multiply_run(cur, na_c, nb_c);
+      }
+      __syncthreads();
+    }
+  };
+  if (!empty) {
+    if (ntr != 8) main_loop(I0{}, I0{});
+    else if (wave < 4) main_loop(I3{}, I2{});
+    else if (wave == 4) main_loop(I3{}, I1{});
+    else main_loop(I4{}, I0{});                        // both runs lie in one tile row: a run of 4
+  }
+  double2* out = reinterpret_cast<double2*>(partials) + (int64_t)blockIdx.x * In * In;
+#pragma unroll
+  for (int k = 0; k < kMaxT; ++k) {
+    if (mine[k]) {
+      for (int r = 0; r < 4; ++r) {
+        const int i = 16 * ti[k] + 4 * r + (lane >> 4);
+        const int j = 16 * tj[k] + (lane & 15);
+        if (i < In && j < In) out[(int64_t)i * In + j] = make_double2(accRe[k][r], accIm[k][r]);
+      }
+    }
+  }
+}
+
+// gram[i, j] = sum over chunks of partials[chunk][i, j] for i >= j; the upper triangle is the
+// conjugate mirror (the Gram kernels leave it unwritten).  The chunks of one entry are summed by 8
+// threads, each over a contiguous eighth of the chunks in order, and the 8 partial sums are added in
+// order: the result does not depend on the launch, and 8 times as many loads are in flight.
+constexpr int kReduceSplit = 8;
+constexpr int kReduceElems = 256 / kReduceSplit;     // entries per workgroup
+__global__ __launch_bounds__(256) void k_gram_reduce(const double* __restrict__ partials, int nchunks, int In,
+                                                     double* __restrict__ gram) {
+  __shared__ double2 part[kReduceSplit][kReduceElems];
+  const int el = threadIdx.x % kReduceElems, sub = threadIdx.x / kReduceElems;
+  const int64_t e = (int64_t)blockIdx.x * kReduceElems + el;
   const int64_t n2 = (int64_t)In * In;
-  if (e >= n2) return;
-  const int i = (int)(e / In), j = (int)(e - (int64_t)i * In);
-  const int64_t src = i >= j ? e : (int64_t)j * In + i;
+  const bool in = e < n2;
+  const int i = in ? (int)(e / In) : 0, j = in ? (int)(e - (int64_t)i * In) : 0;
+  const int64_t src = i >= j ? (int64_t)i * In + j : (int64_t)j * In + i;
+  const int per = (nchunks + kReduceSplit - 1) / kReduceSplit;
+  const int c0 = sub * per, c1 = c0 + per < nchunks ? c0 + per : nchunks;
   const double2* p2 = reinterpret_cast<const double2*>(partials);
   double re = 0., im = 0.;
-  for (int c = 0; c < nchunks; ++c) {
-    const double2 v = p2[(int64_t)c * n2 + src];
-    re += v.x;
-    im += v.y;
+  if (in)
+    for (int c = c0; c < c1; ++c) {
+      const double2 v = p2[(int64_t)c * n2 + src];
+      re += v.x;
+      im += v.y;
+    }
+  part[sub][el] = make_double2(re, im);
+  __syncthreads();
+  if (sub == 0 && in) {
+    double sr = 0., si = 0.;
+#pragma unroll
+    for (int q = 0; q < kReduceSplit; ++q) {
+      sr += part[q][el].x;
+      si += part[q][el].y;
+    }
+    reinterpret_cast<double2*>(gram)[e] = make_double2(sr, i >= j ? si : -si);
   }
-  reinterpret_cast<double2*>(gram)[e] = make_double2(re, i >= j ? im : -im);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -793,8 +1092,25 @@ void launch_gram(hipStream_t s, const void* g, int dtype, const uint32_t* mask, 
   const int64_t tiles_per_chunk = (tiles + nchunks - 1) / nchunks;
   const int64_t cols_per_chunk = tiles_per_chunk * kTC;
   const int nsup = (In + kSuper - 1) / kSuper;
-  dim3 grid((unsigned)nchunks, (unsigned)(nsup * nsup)), block(kGramThreads);
   const size_t lds = (size_t)2 * kSuper * kRowD * sizeof(double);   // 132 KB: more than the default limit
+  // One super block (every FNO extent) and lane offsets that fit 32 bits: the kernel with the lean fetch.
+  // Its offsets reach two leading indices ahead: 2 In B elements of at most 8 bytes.
+  if (nsup == 1 && (int64_t)In * B < ((int64_t)1 << 28)) {
+    dim3 grid((unsigned)nchunks), block(kGram128Threads);
+    const bool smallb = B < kTC;
+    const uint32_t magic = B <= 1 ? 0u : (uint32_t)((0x100000000ull + (uint64_t)B - 1) / (uint64_t)B);
+#define TGRAD_GRAM128(DT_, SB_)                                                                         \
+  do {                                                                                                  \
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_gram128<DT_, SB_>),                       \
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                    \
+    k_gram128<DT_, SB_><<<grid, block, lds, s>>>(g, mask, A, In, B, cols_per_chunk, magic, partials);   \
+  } while (0)
+    if (dtype == TGRAD_C64) { if (smallb) TGRAD_GRAM128(TGRAD_C64, true); else TGRAD_GRAM128(TGRAD_C64, false); }
+    else { if (smallb) TGRAD_GRAM128(TGRAD_CBF16, true); else TGRAD_GRAM128(TGRAD_CBF16, false); }
+#undef TGRAD_GRAM128
+    return;
+  }
+  dim3 grid((unsigned)nchunks, (unsigned)(nsup * nsup)), block(kGramThreads);
   if (dtype == TGRAD_C64) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_gram<TGRAD_C64>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -808,7 +1124,8 @@ void launch_gram(hipStream_t s, const void* g, int dtype, const uint32_t* mask, 
 
 void launch_gram_reduce(hipStream_t s, const double* partials, int nchunks, int In, double* gram) {
   const int64_t n2 = (int64_t)In * In;
-  k_gram_reduce<<<dim3((unsigned)((n2 + 255) / 256)), dim3(256), 0, s>>>(partials, nchunks, In, gram);
+  k_gram_reduce<<<dim3((unsigned)((n2 + kReduceElems - 1) / kReduceElems)), dim3(256), 0, s>>>(partials, nchunks, In,
+                                                                                          gram);
 }
 
 void launch_eig_batch(hipStream_t s, int njobs, const double* const* gram, double* const* work_a,
