@@ -175,9 +175,6 @@ def main():
                     help="untimed steps first (the clocks take some tens of steps to settle; step 0 refreshes)")
     ap.add_argument("--workload", default="cfg4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--calibrate-copy", type=int, default=0,
-                    help="also launch the library's plain copy kernel this many times on a gradient-sized "
-                         "buffer (a known number of HBM bytes, for scaling rocprofv3 --pmc counters)")
     ap.add_argument("--hooi-sweeps", type=int, default=0,
                     help="HOOI refinement sweeps per refresh (default 0 = HOSVD factors, the headline configuration)")
     ap.add_argument("--warm-restart", action="store_true", help="with --hooi-sweeps: refreshes restart from the factors in place")
@@ -228,23 +225,13 @@ def main():
             for layer in range(w.layers):
                 ctxs[layer].tgrad_step(Ws[layer], Gs[layer][t & 1])
 
-    if args.calibrate_copy > 0:
-        src = torch.empty(w.numel * 8, dtype=torch.uint8, device=dev)
-        dst = torch.empty_like(src)
-        src.zero_()
-        for _ in range(args.calibrate_copy):
-            T.tgrad_calibration_copy(dst, src)
-        torch.cuda.synchronize()
-        log("calibration copy: %d launches of %d bytes read + %d bytes written" % (args.calibrate_copy, src.numel(), src.numel()))
-        del src, dst
-
     log("warmup %d steps ..." % Wm)
     run_steps(Wm, 0)
     torch.cuda.synchronize()
 
     # ---- achievable HBM rate on this machine, in this run: the library's plain copy kernel on a
     # gradient-sized buffer (bytes read + bytes written over the HIP-event time)
-    nb = min(w.numel * 8, 1 << 30) // 16 * 16
+    nb = w.numel * 8 // 16 * 16          # (also the known-size launch that scales the profiler's HBM counters)
     csrc = torch.empty(nb, dtype=torch.uint8, device=dev)
     cdst = torch.empty_like(csrc)
     csrc.zero_()
