@@ -77,8 +77,9 @@ enum {
   TGRAD_STATE_CORE_G = 7,       /* float32[2*C]: compressed gradient of the last step (read-only) */
   TGRAD_STATE_GRAM0 = 32,       /* + n: float64[2*I_n*I_n] mode-n Gram of the last refresh (read-only) */
   TGRAD_STATE_FACTOR0 = 64,     /* + n: float32[2*I_n*r_n]: U^(n), row-major I_n x r_n, interleaved complex */
-  TGRAD_STATE_EIG_INFO0 = 96    /* + n: int32[2] of mode n's last eigen-solve: {1 if it stopped at the sweep limit
-                                   else 0, sweeps run} (read-only; compressed modes only) */
+  TGRAD_STATE_EIG_INFO0 = 96    /* + n: int32[3] of mode n's last eigen-solve: {1 if it stopped at the sweep limit
+                                   else 0, Jacobi sweeps run, 1 if the Jacobi solver ran because the tridiagonal
+                                   one declined (close eigenvalues) else 0} (read-only; compressed modes only) */
 };
 
 /*
@@ -131,9 +132,13 @@ typedef struct {
                                          that finds every factor present (from an earlier refresh or
                                          tgrad_set_state) starts its sweeps from those factors instead
                                          of from HOSVD (the warm restart of the same appendix) */
-  int32_t eig_max_sweeps;             /* cyclic-Jacobi sweeps an eigen-solve of the refresh may take:
-                                         1..TGRAD_MAX_EIG_SWEEPS, or 0 = that maximum.  A solve that uses
-                                         them up is reported by tgrad_get_state (NOT_CONVERGED) */
+  int32_t eig_max_sweeps;             /* which eigen-solver the refresh uses for extents up to 128:
+                                         0 = Householder tridiagonalisation + bisection + inverse iteration,
+                                         and cyclic Jacobi (up to TGRAD_MAX_EIG_SWEEPS sweeps) only for a matrix
+                                         whose leading eigenvalues are too close for inverse iteration;
+                                         1..TGRAD_MAX_EIG_SWEEPS = cyclic Jacobi with that many sweeps at most
+                                         for every solve (extents above 128 always use Jacobi).  A Jacobi solve
+                                         that uses its sweeps up is reported by tgrad_get_state (NOT_CONVERGED) */
 } tgrad_config;
 
 /*

@@ -578,10 +578,12 @@ struct EigJob {
   double* V;            // eigenvector accumulator
   float* U;             // out: n x r complex float32, row-major
   int* status;          // out: [0] = 1 if the solve stopped at the sweep limit with rotations left, else 0;
-                        //      [1] = sweeps run
+                        //      [1] = Jacobi sweeps run; [2] = 1 if the tridiagonal path declined (close eigenvalues)
   int n;
   int r;
   int max_sweeps;
+  int use_fast;         // 1: Householder tridiagonalisation + bisection + inverse iteration first (n <= 128), the
+                        //    Jacobi kernels run only if that path declines (status[2] != 0); 0: Jacobi
 };
 struct EigJobs {
   EigJob job[kMaxNdim];
@@ -847,6 +849,7 @@ __device__ __forceinline__ void tri_put(double2* T, int i, int j, double2 v) {
 __global__ __launch_bounds__(kEigThreads) void k_eig_tri(EigJobs jobs) {
   extern __shared__ double2 T[];                // lower triangle of the work matrix
   const EigJob jb = jobs.job[blockIdx.x];
+  if (jb.use_fast && jb.status[2] == 0) return;   // the tridiagonal path has delivered this factor
   const int n = jb.n;
   const int tid = threadIdx.x;
   const double2* G = reinterpret_cast<const double2*>(jb.gram);
@@ -1011,6 +1014,7 @@ constexpr int kLogAhead = 4;                     // rounds whose log entries are
 
 __global__ __launch_bounds__(64) void k_eig_apply(EigJobs jobs) {
   const EigJob jb = jobs.job[blockIdx.y];
+  if (jb.use_fast && jb.status[2] == 0) return;
   const int n = jb.n;
   const int row = blockIdx.x;
   if (row >= n) return;
@@ -1053,6 +1057,7 @@ __global__ __launch_bounds__(64) void k_eig_apply(EigJobs jobs) {
 // Ordering, phase convention and the float32 factor, from the eigenvalues in the log header and V.
 __global__ __launch_bounds__(kEigThreads) void k_eig_finish(EigJobs jobs) {
   const EigJob jb = jobs.job[blockIdx.x];
+  if (jb.use_fast && jb.status[2] == 0) return;
   __shared__ double lam[kEigTriMaxN];
   __shared__ int col_of[kEigTriMaxN];
   __shared__ double2 phase[kEigTriMaxN];
@@ -1061,6 +1066,391 @@ __global__ __launch_bounds__(kEigThreads) void k_eig_finish(EigJobs jobs) {
   __syncthreads();
   eig_finish(jb.n, jb.r, threadIdx.x, lam, col_of, phase, reinterpret_cast<const double2*>(jb.V),
              reinterpret_cast<float2*>(jb.U));
+}
+
+// ---------------------------------------------------------------------------------------------
+// The same eigenvectors by the classical three-stage route, for n <= 128 (one workgroup per matrix):
+//   (1) Householder tridiagonalisation  A = Q T Q^H  of the Hermitian matrix (packed lower triangle
+//       in LDS; reflector i annihilates column i below the subdiagonal; T real symmetric tridiagonal),
+//   (2) the r largest eigenvalues of T by multisection on Sturm counts (32 lanes per eigenvalue, 32
+//       points per step: 13 steps from the Gershgorin interval down to rounding),
+//   (3) their eigenvectors by inverse iteration (Gaussian elimination with partial pivoting on
+//       T - lambda I, three solves from a fixed pseudo-random start vector, one thread per vector),
+//   (4) back-transformation with the reflectors, phase convention and the float32 factor (k_trid_back,
+//       one wavefront per eigenvector).
+// A cyclic Jacobi sweep reads and writes the whole matrix in every one of its n - 1 rounds, about
+// ten sweeps long; the tridiagonalisation touches the trailing block once per step: 15 times less
+// LDS traffic, which is what bounds both.
+// Inverse iteration separates eigenvectors only as well as their eigenvalues are separated: if two
+// of the r leading eigenvalues, or the r-th and the (r+1)-th, lie within 1e-7 of the spectral radius
+// (exactly repeated eigenvalues, a zero matrix), this path declines (status[2] = 1) and the Jacobi
+// kernels, which handle clusters gracefully, solve the matrix instead.
+constexpr int kTridThreads = 1024;
+constexpr int kInvBatch = 32;          // eigenvectors per inverse-iteration batch (LDS: 4 arrays of n x 32 doubles)
+constexpr int kMultiSteps = 13;        // 33^13 > 2^64
+constexpr double kClusterTol = 1e-7;
+
+__device__ __forceinline__ double2* trid_tau(const EigJob& jb) { return reinterpret_cast<double2*>(jb.A); }
+__device__ __forceinline__ double* trid_Z(const EigJob& jb) { return jb.A + 2 * jb.n; }   // r vectors of n doubles
+
+__device__ __forceinline__ double wave_sum_d(double v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+
+// eigenvalues of the tridiagonal (d, e2 = e^2) below x
+__device__ __forceinline__ int sturm_count(const double* d, const double* e2, int n, double x, double pivmin) {
+  double q = d[0] - x;
+  if (fabs(q) < pivmin) q = -pivmin;
+  int c = q < 0. ? 1 : 0;
+  for (int i = 1; i < n; ++i) {
+    q = d[i] - x - e2[i - 1] / q;
+    if (fabs(q) < pivmin) q = -pivmin;
+    c += q < 0. ? 1 : 0;
+  }
+  return c;
+}
+
+__device__ __forceinline__ uint32_t trid_mix(uint32_t x) {
+  x ^= x >> 16;
+  x *= 0x7FEB352Du;
+  x ^= x >> 15;
+  x *= 0x846CA68Bu;
+  x ^= x >> 16;
+  return x;
+}
+
+__global__ __launch_bounds__(kTridThreads) void k_trid(EigJobs jobs) {
+  extern __shared__ double2 T[];                // packed lower triangle; reused by the inverse iteration
+  const EigJob jb = jobs.job[blockIdx.x];
+  const int n = jb.n, r = jb.r;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const double2* G = reinterpret_cast<const double2*>(jb.gram);
+  double2* Vg = reinterpret_cast<double2*>(jb.V);   // reflector i: Vg[i * n + row], rows i + 1 .. n - 1
+  double2* tauG = trid_tau(jb);
+  __shared__ double2 sv[kEigTriMaxN], sw[kEigTriMaxN];
+  __shared__ double sd[kEigTriMaxN], se[kEigTriMaxN], se2[kEigTriMaxN], slam[kEigTriMaxN];
+  __shared__ double2 s_tau, s_scale, s_alpha2;
+  __shared__ double s_gl, s_gu, s_pivmin;
+  __shared__ int s_decline;
+
+  for (int e = tid; e < n * n; e += kTridThreads) {
+    const int i = e / n, j = e - i * n;
+    if (i >= j) T[tri_idx(i, j)] = G[e];
+  }
+  if (tid == 0) s_decline = 0;
+  __syncthreads();
+
+  // ---- (1) tridiagonalisation ----
+  for (int i = 0; i + 1 < n; ++i) {
+    const int m = n - i - 1;                     // trailing block: rows / columns i + 1 .. n - 1 (local 0 .. m - 1)
+    if (wave == 0) {
+      double xn2 = 0.;
+      for (int j = 1 + lane; j < m; j += 64) {
+        const double2 x = T[tri_idx(i + 1 + j, i)];
+        xn2 += x.x * x.x + x.y * x.y;
+      }
+      xn2 = wave_sum_d(xn2);
+      if (lane == 0) {
+        const double2 alpha = T[tri_idx(i + 1, i)];
+        double2 tau = make_double2(0., 0.), scale = make_double2(0., 0.);
+        double beta = alpha.x;
+        if (!(xn2 == 0. && alpha.y == 0.)) {
+          beta = -copysign(sqrt(alpha.x * alpha.x + alpha.y * alpha.y + xn2), alpha.x);
+          tau = make_double2((beta - alpha.x) / beta, -alpha.y / beta);
+          const double2 z = make_double2(alpha.x - beta, alpha.y);          // 1 / (alpha - beta)
+          const double inv = 1. / (z.x * z.x + z.y * z.y);
+          scale = make_double2(z.x * inv, -z.y * inv);
+        }
+        s_tau = tau;
+        s_scale = scale;
+        se[i] = beta;
+        sd[i] = T[tri_idx(i, i)].x;
+        tauG[i] = tau;
+      }
+    }
+    __syncthreads();
+    const double2 tau = s_tau;
+    const bool reflect = tau.x != 0. || tau.y != 0.;           // (workgroup-uniform)
+    for (int j = tid; j < m; j += kTridThreads) {
+      double2 v = make_double2(j == 0 ? 1. : 0., 0.);
+      if (j > 0 && reflect) v = cmuld(T[tri_idx(i + 1 + j, i)], s_scale);
+      sv[j] = v;
+      Vg[(size_t)i * n + i + 1 + j] = v;
+    }
+    __syncthreads();
+    if (!reflect) continue;
+    // p = tau S v: 8 threads per row, each over the columns c = q, q + 8, ..; summed in a fixed order
+    {
+      const int rr = tid >> 3, q = tid & 7;
+      double2 acc = make_double2(0., 0.);
+      if (rr < m)
+        for (int c = q; c < m; c += 8) {
+          const double2 sv_c = sv[c];
+          const double2 a = c <= rr ? T[tri_idx(i + 1 + rr, i + 1 + c)] : conjd(T[tri_idx(i + 1 + c, i + 1 + rr)]);
+          const double2 t = cmuld(a, sv_c);
+          acc.x += t.x;
+          acc.y += t.y;
+        }
+#pragma unroll
+      for (int off = 1; off < 8; off <<= 1) {
+        acc.x += __shfl_xor(acc.x, off, 64);
+        acc.y += __shfl_xor(acc.y, off, 64);
+      }
+      if (q == 0 && rr < m) sw[rr] = cmuld(tau, acc);
+    }
+    __syncthreads();
+    // alpha2 = -1/2 tau (p^H v);  w = p + alpha2 v
+    if (wave == 0) {
+      double ax = 0., ay = 0.;
+      for (int j = lane; j < m; j += 64) {
+        const double2 t = cmuld(conjd(sw[j]), sv[j]);
+        ax += t.x;
+        ay += t.y;
+      }
+      ax = wave_sum_d(ax);
+      ay = wave_sum_d(ay);
+      if (lane == 0) {
+        const double2 t = cmuld(tau, make_double2(ax, ay));
+        s_alpha2 = make_double2(-0.5 * t.x, -0.5 * t.y);
+      }
+    }
+    __syncthreads();
+    for (int j = tid; j < m; j += kTridThreads) {
+      const double2 t = cmuld(s_alpha2, sv[j]);
+      sw[j] = make_double2(sw[j].x + t.x, sw[j].y + t.y);
+    }
+    __syncthreads();
+    // S <- S - v w^H - w v^H on the lower triangle
+    {
+      const int ty = tid >> 5, tx = tid & 31;
+      for (int rr = ty; rr < m; rr += 32) {
+        const double2 vr = sv[rr], wr = sw[rr];
+        for (int c = tx; c <= rr; c += 32) {
+          const double2 t1 = cmuld(vr, conjd(sw[c])), t2 = cmuld(wr, conjd(sv[c]));
+          double2* p = &T[tri_idx(i + 1 + rr, i + 1 + c)];
+          *p = make_double2(p->x - t1.x - t2.x, p->y - t1.y - t2.y);
+        }
+      }
+    }
+    __syncthreads();
+  }
+  if (tid == 0) {
+    sd[n - 1] = T[tri_idx(n - 1, n - 1)].x;
+    se[n - 1] = 0.;
+  }
+  __syncthreads();
+  for (int i = tid; i < n; i += kTridThreads) se2[i] = se[i] * se[i];
+  __syncthreads();
+
+  // ---- (2) the r largest eigenvalues: Gershgorin interval, then multisection on Sturm counts ----
+  if (wave == 0) {
+    double lo = 1e300, hi = -1e300, em = 0.;
+    for (int i = lane; i < n; i += 64) {
+      const double rad = (i > 0 ? fabs(se[i - 1]) : 0.) + (i + 1 < n ? fabs(se[i]) : 0.);
+      lo = fmin(lo, sd[i] - rad);
+      hi = fmax(hi, sd[i] + rad);
+      em = fmax(em, se2[i]);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+      lo = fmin(lo, __shfl_xor(lo, off, 64));
+      hi = fmax(hi, __shfl_xor(hi, off, 64));
+      em = fmax(em, __shfl_xor(em, off, 64));
+    }
+    if (lane == 0) {
+      const double tn = fmax(fabs(lo), fabs(hi));
+      const double pivmin = 2.2250738585072014e-308 * fmax(1., em);
+      const double slack = 2.1 * tn * 2.220446049250313e-16 * n + 2.1 * pivmin;
+      s_gl = lo - slack;
+      s_gu = hi + slack;
+      s_pivmin = pivmin;
+    }
+  }
+  __syncthreads();
+  const double pivmin = s_pivmin;
+  const double tnorm = fmax(fabs(s_gl), fabs(s_gu));
+  {
+    const int g = tid >> 5, j = tid & 31;
+    for (int kk = g; kk < r; kk += kTridThreads / 32) {
+      const int kasc = n - 1 - kk;                 // kk-th largest = kasc-th smallest (0-based)
+      double lo = s_gl, hi = s_gu;
+      for (int step = 0; step < kMultiSteps; ++step) {
+        const double h = (hi - lo) / 33.;
+        const double x = lo + (j + 1) * h;
+        const bool above = sturm_count(sd, se2, n, x, pivmin) > kasc;     // more than kasc eigenvalues below x
+        const uint64_t bal = __ballot(above);
+        const uint32_t mk = (uint32_t)(bal >> (lane & 32));
+        // first point with `above`: the eigenvalue lies between it and the point before
+        const int jf = mk ? __builtin_ctz(mk) : 32;
+        const double nlo = jf == 0 ? lo : lo + jf * h;
+        const double nhi = jf == 32 ? hi : lo + (jf + 1) * h;
+        lo = nlo;
+        hi = nhi;
+      }
+      if (j == 0) slam[kk] = 0.5 * (lo + hi);
+    }
+  }
+  __syncthreads();
+  // close eigenvalues: decline
+  if (tid == 0) {
+    const double delta = kClusterTol * tnorm;
+    int bad = 0;
+    for (int k = 0; k < r; ++k) {
+      if (!(fabs(slam[k]) <= 1e300)) bad = 1;                          // NaN / inf
+      if (k + 1 < r && !(slam[k] - slam[k + 1] >= delta)) bad = 1;
+    }
+    if (!bad && r < n && sturm_count(sd, se2, n, slam[r - 1] - delta, pivmin) != n - r) bad = 1;
+    if (!(tnorm > 0.)) bad = 1;                                         // zero matrix
+    s_decline = bad;
+    jb.status[0] = 0;
+    jb.status[1] = 0;
+    jb.status[2] = bad;
+  }
+  __syncthreads();
+  if (s_decline) return;
+
+  // ---- (3) inverse iteration, kInvBatch eigenvectors at a time, one thread each ----
+  double* pivA = reinterpret_cast<double*>(T);     // [i][t]: pivots of the elimination
+  double* U1 = pivA + n * kInvBatch;               //         first super-diagonal of the upper factor
+  double* Y = U1 + n * kInvBatch;                  //         right-hand side after the forward sweep
+  double* Zv = Y + n * kInvBatch;                  //         current iterate
+  double* Zg = trid_Z(jb);
+  const double tol = 2.220446049250313e-16 * tnorm;
+  for (int b0 = 0; b0 < r; b0 += kInvBatch) {
+    const int t = tid;
+    if (t < kInvBatch && b0 + t < r) {
+      const int k = b0 + t;
+      const double lam = slam[k];
+      for (int i = 0; i < n; ++i) {
+        const uint32_t u = trid_mix((uint32_t)i * 0x9E3779B9u + (uint32_t)k * 0x85EBCA6Bu + 0x1234567u);
+        Zv[i * kInvBatch + t] = (double)u * (1. / 2147483648.) - 1.;
+      }
+      for (int it = 0; it < 3; ++it) {
+        uint64_t pv_lo = 0ull, pv_hi = 0ull;                           // bit i: rows interchanged at step i
+        // forward: elimination with partial pivoting and the forward substitution in one sweep
+        double a = sd[0] - lam, du = se[0], y = Zv[t];
+        for (int i = 0; i + 1 < n; ++i) {
+          const double sub = se[i], dn = sd[i + 1] - lam, en = i + 2 < n ? se[i + 1] : 0.;
+          const double rhs = Zv[(i + 1) * kInvBatch + t];
+          if (fabs(a) >= fabs(sub)) {
+            if (a == 0.) a = tol;
+            const double f = sub / a;
+            pivA[i * kInvBatch + t] = a;
+            U1[i * kInvBatch + t] = du;
+            Y[i * kInvBatch + t] = y;
+            a = dn - f * du;
+            du = en;
+            y = rhs - f * y;
+          } else {
+            const double f = a / sub;
+            if (i < 64) pv_lo |= 1ull << i; else pv_hi |= 1ull << (i - 64);
+            pivA[i * kInvBatch + t] = sub;
+            U1[i * kInvBatch + t] = dn;
+            Y[i * kInvBatch + t] = rhs;
+            a = du - f * dn;
+            du = -f * en;
+            y = y - f * rhs;
+          }
+        }
+        if (a == 0.) a = tol;
+        pivA[(n - 1) * kInvBatch + t] = a;
+        Y[(n - 1) * kInvBatch + t] = y;
+        // backward substitution; second super-diagonal: e[i + 1] where rows were interchanged
+        double z1 = 0., z2 = 0., zmax = 0.;
+        for (int i = n - 1; i >= 0; --i) {
+          double p = pivA[i * kInvBatch + t];
+          if (fabs(p) < tol) p = p < 0. ? -tol : tol;
+          double sacc = Y[i * kInvBatch + t];
+          if (i + 1 < n) sacc -= U1[i * kInvBatch + t] * z1;
+          const bool swapped = i < 64 ? ((pv_lo >> i) & 1ull) : ((pv_hi >> (i - 64)) & 1ull);
+          if (i + 2 < n && swapped) sacc -= se[i + 1] * z2;
+          const double z = sacc / p;
+          Zv[i * kInvBatch + t] = z;
+          zmax = fmax(zmax, fabs(z));
+          z2 = z1;
+          z1 = z;
+        }
+        const double sc = zmax > 0. ? 1. / zmax : 1.;
+        for (int i = 0; i < n; ++i) Zv[i * kInvBatch + t] *= sc;
+      }
+      double nrm2 = 0.;
+      for (int i = 0; i < n; ++i) nrm2 += Zv[i * kInvBatch + t] * Zv[i * kInvBatch + t];
+      const double inv = nrm2 > 0. ? rsqrt(nrm2) : 0.;
+      for (int i = 0; i < n; ++i) Zg[(size_t)k * n + i] = Zv[i * kInvBatch + t] * inv;
+    }
+    __syncthreads();
+  }
+}
+
+// (4) U[:, k] = H_0 H_1 .. H_{n-2} z_k, the phase convention and the float32 factor: one wavefront per
+// eigenvector, the vector in registers (rows lane and lane + 64), the reflectors read kAheadRefl ahead.
+constexpr int kAheadRefl = 4;
+__global__ __launch_bounds__(64) void k_trid_back(EigJobs jobs) {
+  const EigJob jb = jobs.job[blockIdx.y];
+  const int n = jb.n, r = jb.r;
+  const int k = blockIdx.x;
+  if (k >= r || jb.status[2] != 0) return;
+  const int lane = threadIdx.x;
+  const double2* Vg = reinterpret_cast<const double2*>(jb.V);
+  const double2* tauG = trid_tau(jb);
+  const double* Zg = trid_Z(jb);
+  const int r0 = lane, r1 = lane + 64;
+  double2 x0 = make_double2(r0 < n ? Zg[(size_t)k * n + r0] : 0., 0.);
+  double2 x1 = make_double2(r1 < n ? Zg[(size_t)k * n + r1] : 0., 0.);
+  double2 pv0[kAheadRefl], pv1[kAheadRefl], ptau[kAheadRefl];
+  auto issue = [&](int i, int slot) {
+    const double2 zero = make_double2(0., 0.);
+    const int ic = i >= 0 ? i : 0;
+    ptau[slot] = tauG[ic];
+    pv0[slot] = (i >= 0 && r0 > i && r0 < n) ? Vg[(size_t)ic * n + r0] : zero;
+    pv1[slot] = (i >= 0 && r1 > i && r1 < n) ? Vg[(size_t)ic * n + r1] : zero;
+  };
+#pragma unroll
+  for (int d = 0; d < kAheadRefl; ++d) issue(n - 2 - d, d);
+  for (int base = n - 2; base >= 0; base -= kAheadRefl) {
+#pragma unroll
+    for (int d = 0; d < kAheadRefl; ++d) {
+      const int i = base - d;
+      const double2 tau = ptau[d], v0 = pv0[d], v1 = pv1[d];
+      issue(i - kAheadRefl, d);
+      if (i >= 0) {
+        const double2 t0 = cmuld(conjd(v0), x0), t1 = cmuld(conjd(v1), x1);
+        const double dx = wave_sum_d(t0.x + t1.x), dy = wave_sum_d(t0.y + t1.y);
+        const double2 sfac = cmuld(tau, make_double2(dx, dy));
+        const double2 u0 = cmuld(sfac, v0), u1 = cmuld(sfac, v1);
+        x0 = make_double2(x0.x - u0.x, x0.y - u0.y);
+        x1 = make_double2(x1.x - u1.x, x1.y - u1.y);
+      }
+    }
+  }
+  // unit phase that makes the largest-modulus entry (lowest row on ties) real and positive
+  double best = r0 < n ? x0.x * x0.x + x0.y * x0.y : -1.;
+  int brow = r0;
+  double2 bval = x0;
+  {
+    const double a1 = r1 < n ? x1.x * x1.x + x1.y * x1.y : -1.;
+    if (a1 > best) { best = a1; brow = r1; bval = x1; }
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    const double ob = __shfl_xor(best, off, 64);
+    const int orow = __shfl_xor(brow, off, 64);
+    const double ovx = __shfl_xor(bval.x, off, 64), ovy = __shfl_xor(bval.y, off, 64);
+    if (ob > best || (ob == best && orow < brow)) { best = ob; brow = orow; bval = make_double2(ovx, ovy); }
+  }
+  const double mag = sqrt(best);
+  const double2 ph = mag > 0. ? make_double2(bval.x / mag, -bval.y / mag) : make_double2(1., 0.);
+  float2* U = reinterpret_cast<float2*>(jb.U);
+  if (r0 < n) {
+    const double2 v = cmuld(x0, ph);
+    U[(size_t)r0 * r + k] = make_float2((float)v.x, (float)v.y);
+  }
+  if (r1 < n) {
+    const double2 v = cmuld(x1, ph);
+    U[(size_t)r1 * r + k] = make_float2((float)v.x, (float)v.y);
+  }
 }
 
 __global__ void k_identity_factor(float2* U, int n) {
@@ -1131,6 +1521,9 @@ void launch_gram_reduce(hipStream_t s, const double* partials, int nchunks, int 
 void launch_eig_batch(hipStream_t s, int njobs, const double* const* gram, double* const* work_a,
                       double* const* work_v, const int* In, const int* r, float* const* U, int* const* status,
                       int max_sweeps) {
+  // max_sweeps == 0: the tridiagonal path first, Jacobi (full sweep budget) where it declines;
+  // 1 .. kEigMaxSweeps: Jacobi with that budget for every solve
+  const int use_fast = max_sweeps <= 0 ? 1 : 0;
   if (max_sweeps <= 0 || max_sweeps > kEigMaxSweeps) max_sweeps = kEigMaxSweeps;   // the log is sized for kEigMaxSweeps
   if (njobs <= 0) return;
   EigJobs small, large;                          // n <= 128: work matrix in LDS; larger: in memory
@@ -1145,6 +1538,7 @@ void launch_eig_batch(hipStream_t s, int njobs, const double* const* gram, doubl
     jb.n = In[i];
     jb.r = r[i];
     jb.max_sweeps = max_sweeps;
+    jb.use_fast = In[i] <= kEigTriMaxN ? use_fast : 0;
     if (In[i] <= kEigTriMaxN) {
       small.job[nsmall++] = jb;
       if (In[i] > nmax) nmax = In[i];
@@ -1159,6 +1553,20 @@ void launch_eig_batch(hipStream_t s, int njobs, const double* const* gram, doubl
       (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_eig_tri), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 kEigTriMaxN * (kEigTriMaxN + 1) / 2 * (int)sizeof(double2));
       attr_set = true;
+    }
+    if (use_fast) {
+      int rmax = 1;
+      for (int i = 0; i < nsmall; ++i) rmax = small.job[i].r > rmax ? small.job[i].r : rmax;
+      const size_t inv = (size_t)4 * nmax * kInvBatch * sizeof(double);
+      const size_t lds_t = lds > inv ? lds : inv;
+      static bool attr_t = false;
+      if (!attr_t) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_trid), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  kEigTriMaxN * (kEigTriMaxN + 1) / 2 * (int)sizeof(double2));
+        attr_t = true;
+      }
+      k_trid<<<dim3((unsigned)nsmall), dim3(kTridThreads), lds_t, s>>>(small);
+      k_trid_back<<<dim3((unsigned)rmax, (unsigned)nsmall), dim3(64), 0, s>>>(small);
     }
     k_eig_tri<<<dim3((unsigned)nsmall), dim3(kEigThreads), lds, s>>>(small);
     k_eig_apply<<<dim3((unsigned)nmax, (unsigned)nsmall), dim3(64), 0, s>>>(small);

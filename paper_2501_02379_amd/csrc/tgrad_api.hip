@@ -201,7 +201,8 @@ void make_plan(const tgrad_config* c, Plan* p) {
   o = 0;
   p->ws_sel = take(sizeof(SelectScalars));
   p->ws_hist = take(3 * kHistBins * 4);
-  p->ws_eig_status = take(2 * kMaxNdim * sizeof(int));   // per mode: 1 if the last solve stopped at the sweep limit, sweeps run
+  p->ws_eig_status = take(4 * kMaxNdim * sizeof(int));   // per mode: 1 if the last solve stopped at the sweep limit,
+                                                         // Jacobi sweeps run, 1 if the tridiagonal path declined, spare
   p->ws_chunk_gt = take((size_t)p->nchunks * 4);
   p->ws_chunk_eq = take((size_t)p->nchunks * 4);
   p->ws_mask = take((size_t)p->mask_words * 4);
@@ -465,7 +466,7 @@ void compute_factors(tgrad_ctx* c, const void* g, const uint32_t* tile_start, co
       In[njobs] = (int)p.shape[n];
       rr[njobs] = p.rank[n];
       Us[njobs] = U;
-      stat[njobs] = c->w<int>(p.ws_eig_status) + 2 * n;
+      stat[njobs] = c->w<int>(p.ws_eig_status) + 4 * n;
       ++njobs;
     }
     c->have_factor[n] = true;
@@ -502,7 +503,7 @@ void compute_factors(tgrad_ctx* c, const void* g, const uint32_t* tile_start, co
       double* v1[1] = {c->w<double>(p.ws_eig_v[n])};
       int i1[1] = {(int)p.shape[n]}, r1[1] = {p.rank[n]};
       float* u1[1] = {c->st<float>(p.st_U[n])};
-      int* s1[1] = {c->w<int>(p.ws_eig_status) + 2 * n};
+      int* s1[1] = {c->w<int>(p.ws_eig_status) + 4 * n};
       Scope sc_(c, KID_EIG);
       launch_eig_batch(s, 1, g1, a1, v1, i1, r1, u1, s1, c->cfg.eig_max_sweeps);
     }
@@ -722,8 +723,8 @@ int locate(tgrad_ctx* c, int what, Item* it) {
   if (what >= TGRAD_STATE_EIG_INFO0 && what < TGRAD_STATE_EIG_INFO0 + p.N) {
     const int n = what - TGRAD_STATE_EIG_INFO0;
     if (p.rank[n] == p.shape[n]) return TGRAD_ERR_INVALID_ARG;     // identity factor: nothing is solved
-    it->dev = c->ws + p.ws_eig_status + (size_t)2 * n * sizeof(int);
-    it->bytes = 2 * sizeof(int);
+    it->dev = c->ws + p.ws_eig_status + (size_t)4 * n * sizeof(int);
+    it->bytes = 3 * sizeof(int);
     it->writable = false;
     it->needs_factor = true;
     it->mode = n;
@@ -806,7 +807,7 @@ int tgrad_init(tgrad_ctx** out, const tgrad_config* cfg, void* state_dev, void* 
     c->launches[i] = 0;
   }
   // no solve has hit its sweep limit yet (a factor injected with tgrad_set_state never does)
-  zero_u32(c->stream, c->w<uint32_t>(c->plan.ws_eig_status), 2 * kMaxNdim);
+  zero_u32(c->stream, c->w<uint32_t>(c->plan.ws_eig_status), 4 * kMaxNdim);
   // moments <- 0 (and everything else in the state block), with a fill kernel
   zero_u32(c->stream, reinterpret_cast<uint32_t*>(c->state), (int64_t)(c->plan.state_bytes / 4));
   if (c->plan.order != TGRAD_ORDER_US_LR)
@@ -912,7 +913,7 @@ int tgrad_get_state(tgrad_ctx* ctx, int what, void* host_out, size_t cap) {
   if (what >= TGRAD_STATE_FACTOR0 && what < TGRAD_STATE_FACTOR0 + p.N && p.rank[it.mode] < p.shape[it.mode]) {
     // the factor is delivered either way; the status says whether its eigen-solve ran to the end
     int info[2] = {0, 0};
-    if (hipMemcpy(info, ctx->ws + p.ws_eig_status + (size_t)2 * it.mode * sizeof(int), sizeof(info),
+    if (hipMemcpy(info, ctx->ws + p.ws_eig_status + (size_t)4 * it.mode * sizeof(int), sizeof(info),
                   hipMemcpyDeviceToHost) != hipSuccess)
       return TGRAD_ERR_HIP;
     if (info[0] != 0) return TGRAD_ERR_NOT_CONVERGED;

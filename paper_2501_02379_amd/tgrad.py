@@ -201,7 +201,7 @@ class Context:
             n = what - STATE_FACTOR0
             return np.zeros((self.shape[n], self.rank[n]), dtype=np.complex64)
         if STATE_EIG_INFO0 <= what < STATE_EIG_INFO0 + len(self.shape):
-            return np.zeros(2, dtype=np.int32)
+            return np.zeros(3, dtype=np.int32)
         if STATE_GRAM0 <= what < STATE_GRAM0 + len(self.shape):
             n = what - STATE_GRAM0
             return np.zeros((self.shape[n], self.shape[n]), dtype=np.complex128)

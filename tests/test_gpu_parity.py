@@ -544,22 +544,33 @@ def test_set_state_rejects_bad_indices():
 
 # ------------------------------------------------------------------ failure detection
 def test_eigen_solve_reports_convergence_and_a_forced_sweep_limit():
-    """Every compressed mode's solve reports (stalled, sweeps).  With the library's limit a solve
-    ends by itself; with a limit of one sweep (forced from the host) it stops with rotations left:
-    the factor is still delivered and tgrad_get_state says NOT_CONVERGED."""
+    """Every compressed mode's solve reports (stalled, Jacobi sweeps, declined).  By default the
+    tridiagonal solver delivers the factor (no Jacobi sweep); asked for by its sweep budget, the
+    Jacobi solver ends by itself within the budget and gives the same factors; with a budget of
+    one sweep (forced from the host) it stops with rotations left: the factor is still delivered
+    and tgrad_get_state says NOT_CONVERGED."""
     shape, ranks, k = (24, 18, 10), (5, 4, 3), 20
     g = synth.small_case(shape, 905)
     ctx = make_gpu_ctx(T, shape, ranks, k, refresh_every=0)
     ctx.tgrad_refresh_factors(T.to_device_grad(g))
+    fast = []
     for n in range(3):
-        stalled, sweeps = ctx.tgrad_get_state(T.STATE_EIG_INFO0 + n)
+        stalled, sweeps, declined = ctx.tgrad_get_state(T.STATE_EIG_INFO0 + n)
+        assert (stalled, sweeps, declined) == (0, 0, 0)
+        fast.append(ctx.tgrad_get_state(T.STATE_FACTOR0 + n))
+    ctx.tgrad_destroy()
+    ctx = make_gpu_ctx(T, shape, ranks, k, refresh_every=0, eig_max_sweeps=30)
+    ctx.tgrad_refresh_factors(T.to_device_grad(g))
+    for n in range(3):
+        stalled, sweeps, declined = ctx.tgrad_get_state(T.STATE_EIG_INFO0 + n)
         assert stalled == 0 and 2 <= sweeps <= 30
-        ctx.tgrad_get_state(T.STATE_FACTOR0 + n)                       # no error
+        U = ctx.tgrad_get_state(T.STATE_FACTOR0 + n)
+        assert np.max(np.abs(U - fast[n])) < 1e-6                      # two solvers, one answer
     ctx.tgrad_destroy()
     ctx = make_gpu_ctx(T, shape, ranks, k, refresh_every=0, eig_max_sweeps=1)
     ctx.tgrad_refresh_factors(T.to_device_grad(g))
     for n in range(3):
-        stalled, sweeps = ctx.tgrad_get_state(T.STATE_EIG_INFO0 + n)
+        stalled, sweeps, declined = ctx.tgrad_get_state(T.STATE_EIG_INFO0 + n)
         assert stalled == 1 and sweeps == 1
         U = np.zeros((shape[n], ranks[n]), dtype=np.complex64)
         rc = ctx.lib.tgrad_get_state(ctx.handle, T.STATE_FACTOR0 + n, U.ctypes.data, U.nbytes)
@@ -586,14 +597,39 @@ def test_eigen_solve_on_degenerate_clusters():
         ctx.tgrad_refresh_factors(T.to_device_grad(g))
         X = O.to_complex128(g)
         for n in range(2):
-            stalled, sweeps = ctx.tgrad_get_state(T.STATE_EIG_INFO0 + n)
+            stalled, sweeps, declined = ctx.tgrad_get_state(T.STATE_EIG_INFO0 + n)
             assert stalled == 0 and sweeps <= 30
+            assert declined in (0, 1)       # the clusters are split at float32 rounding level: either solver may take it
             U = ctx.tgrad_get_state(T.STATE_FACTOR0 + n).astype(np.complex128)
             assert np.max(np.abs(U.conj().T @ U - np.eye(r))) < 1e-5
             Xn = X if n == 0 else X.T
             captured = np.linalg.norm(U.conj().T @ Xn) ** 2
             assert abs(captured - np.sum(sv[:r] ** 2)) <= 1e-5 * np.sum(sv ** 2)
         ctx.tgrad_destroy()
+
+
+def test_exactly_repeated_eigenvalues_go_to_the_jacobi_solver():
+    """A diagonal gradient with repeated entries: the Gram matrices are exactly diagonal with exactly
+    repeated eigenvalues.  Inverse iteration cannot separate those, so the tridiagonal solver must
+    decline and the Jacobi solver deliver: unit vectors, ordered by (eigenvalue descending, index
+    ascending)."""
+    sv = np.array([5, 5, 5, 5, 3, 3, 2, 2, 1, 0.5, 0.25, 0.125], dtype=np.float32)
+    g = np.diag(sv).astype(np.complex64)
+    for r in (3, 4, 7):
+        ctx = make_gpu_ctx(T, (12, 12), (r, r), 0, refresh_every=0)
+        ctx.tgrad_refresh_factors(T.to_device_grad(g))
+        for n in range(2):
+            stalled, sweeps, declined = ctx.tgrad_get_state(T.STATE_EIG_INFO0 + n)
+            assert (stalled, declined) == (0, 1) and sweeps >= 1
+            U = ctx.tgrad_get_state(T.STATE_FACTOR0 + n)
+            assert np.array_equal(U, np.eye(12, r, dtype=np.complex64))
+        ctx.tgrad_destroy()
+    # and a zero gradient: nothing to separate at all
+    ctx = make_gpu_ctx(T, (12, 12), (3, 3), 0, refresh_every=0)
+    ctx.tgrad_refresh_factors(T.to_device_grad(np.zeros((12, 12), dtype=np.complex64)))
+    assert tuple(ctx.tgrad_get_state(T.STATE_EIG_INFO0))[2] == 1
+    assert np.array_equal(ctx.tgrad_get_state(T.STATE_FACTOR0), np.eye(12, 3, dtype=np.complex64))
+    ctx.tgrad_destroy()
 
 
 def test_check_counts_non_finite_gradient_entries():
