@@ -417,6 +417,309 @@ __global__ __launch_bounds__(kMidThreads) void k_core(const float* x, const floa
 }
 
 // -------------------------------------------------------------------------------------------
+// k_core2: everything between the fused first projection and the fused update when exactly two
+// modes (the two leading ones) are left to compress: y is (I0 = 128, I1, Cc), its Cc complex
+// columns contiguous.  Every column c goes through
+//   g_L[m0, m1, c] = sum_{i0, i1} conj(U0[i0, m0]) conj(U1[i1, m1]) y[i0, i1, c]   last two compression stages
+//   N_L            = AdamUpdate(g_L)                (appendix algorithm "Adam with low-rank tensor decomposition")
+//   z[i0, i1, c]   = sum_{m0, m1} U0[i0, m0] U1[i1, m1] N_L[m0, m1, c]             first two reconstruction stages
+// on its own, so a workgroup that owns two neighbouring columns (16 bytes per (i0, i1)) runs the whole
+// chain between workgroup barriers: nothing travels through memory between the five steps and the
+// launches, prologues and tails of three kernels become one.  Wavefront w owns the rows
+// i0 = 32 w .. 32 w + 31.  The accumulator layout of one stage is the operand layout of the next
+// (register r of lane (col, half) holds row d_row(r, half) of the tile, and a matrix-core step pairs
+// exactly the rows d_row(r, 0) and d_row(r, 1)), so no stage transposes anything:
+//   1  T[i0, m1]   = sum_i1 y[i0, i1] conj(U1[i1, m1])   data = A operand (lane = i0), U1 from LDS;  D: i0 in registers, m1 in lanes
+//   2  P[m0, m1]   = sum_i0 conj(U0[i0, m0]) T[i0, m1]   U0 = A operand, T = B operand straight from the accumulators;
+//                                                        the four wavefronts' partial sums meet in LDS, fixed order
+//   -  AdamUpdate on the 32 x 32 x 2 core entries of the two columns, N_L back into LDS in accumulator layout
+//   3  R[m1, i0]   = sum_m0 N_L[m0, m1] U0[i0, m0]       N_L = A operand (LDS), U0 = B operand;  D: m1 in registers, i0 in lanes
+//   4  z[i0, i1]   = sum_m1 R[m1, i0] U1[i1, m1]         R = A operand straight from the accumulators, U1 from LDS;
+//                                                        D: i0 in registers, i1 in lanes
+// The factor operands of all four stages come from a table in operand order that is built once per
+// refresh (k_pack_core2): the prologue is a straight copy with every load in flight at once.
+// The result is written one column pair at a time, z[pair][i0][i1] in 16-byte units, because in
+// stage 4 neighbouring lanes hold neighbouring i1: the stores of a wavefront are then 512 contiguous
+// bytes instead of 64 pieces of 16 bytes each in a cache line of its own (the fused update reads its
+// operand rows through strides, see FusedPrev).  Workgroups that share cache lines of y (8 column
+// pairs per 128 bytes) get consecutive blockIdx / 8, i.e. the same XCD under round-robin dispatch.
+struct Core2Args {
+  const float* y;       // (128, I1, Cc) complex
+  float* z;             // (Cc / 2, 128, I1) units of two complex, not the same buffer
+  const float2* tab;    // core2_table_elems(I1) operands from k_pack_core2
+  int I1, M0, M1;
+  int64_t Cc;           // even
+};
+constexpr int kCore2Rows = 128;              // extent of the first mode: 4 wavefronts x 32 rows
+constexpr int kCore2Batch = 8;               // row pairs of y per lane in flight (twice that while a batch is computed)
+
+// Operand table: [J1][64] stage 1, [NT1][16][64] stage 4, [4][16][64] stage 2, [4][16][64] stage 3 (float2 each);
+// J1 = row pairs of mode 2, NT1 = 32-row tiles of mode 2.
+__host__ __device__ inline int core2_table_elems(int I1) { return ((I1 + 1) / 2) * 64 + ((I1 + 31) / 32) * 1024 + 8192; }
+
+__global__ void k_pack_core2(const float2* __restrict__ U0, int rn0, int M0, const float2* __restrict__ U1,
+                             int rn1, int M1, int I1, float2* __restrict__ tab) {
+  const int J1 = (I1 + 1) >> 1, NT1 = (I1 + 31) >> 5;
+  const int n1 = J1 * 64, n4 = NT1 * 1024;
+  const int e = (int)(blockIdx.x * blockDim.x + threadIdx.x);
+  if (e >= n1 + n4 + 8192) return;
+  const int l = e & 63, col = l & 31, half = l >> 5;
+  float2 u = make_float2(0.f, 0.f);
+  if (e < n1) {                                    // stage 1: U1[2 j + half][col]
+    const int i1 = 2 * (e >> 6) + half;
+    if (i1 < I1 && col < M1) u = U1[(int64_t)i1 * rn1 + col];
+  } else if (e < n1 + n4) {                        // stage 4: U1[32 tile + col][d_row(r, half)]
+    const int q = (e - n1) >> 6, r = q & 15, tile = q >> 4;
+    const int i1 = 32 * tile + col, m1 = d_row(r, half);
+    if (i1 < I1 && m1 < M1) u = U1[(int64_t)i1 * rn1 + m1];
+  } else if (e < n1 + n4 + 4096) {                 // stage 2: U0[32 w + d_row(r, half)][col]
+    const int q = (e - n1 - n4) >> 6, r = q & 15, w = q >> 4;
+    if (col < M0) u = U0[(int64_t)(32 * w + d_row(r, half)) * rn0 + col];
+  } else {                                         // stage 3: U0[32 w + col][d_row(r, half)]
+    const int q = (e - n1 - n4 - 4096) >> 6, r = q & 15, w = q >> 4;
+    const int m0 = d_row(r, half);
+    if (m0 < M0) u = U0[(int64_t)(32 * w + col) * rn0 + m0];
+  }
+  tab[e] = u;
+}
+
+__global__ __launch_bounds__(kMidThreads) void k_core2(Core2Args a, CoreAdam ad) {
+  extern __shared__ float2 sF[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int col = lane & 31, half = lane >> 5;
+  const int planes = (int)(a.Cc >> 1);
+  const int b = (int)blockIdx.x;
+  const int plane = (planes & 7) == 0 ? (b & 7) * (planes >> 3) + (b >> 3) : b;
+  const int I1 = a.I1, M0 = a.M0, M1 = a.M1;
+  const int J1 = (I1 + 1) >> 1, NT1 = (I1 + 31) >> 5;
+  const int64_t row = a.Cc * 2;              // floats between consecutive i1 of y
+  const int64_t slab = row * I1;             // floats between consecutive i0 of y
+  // LDS: [0, 64 KB) stage-1 operands (J1 x 64 float2), afterwards the partial sums of stage 2
+  //      ([wave][t][r][lane] floats) and then N_L ([t][r][lane]); [64 KB, 64 KB + NT1 x 8 KB) stage-4 operands
+  float2* sT1 = sF;
+  float* red = reinterpret_cast<float*>(sF);
+  float2* sT4 = sF + 8192;
+
+  // the first rows of y go in flight, then the stage-1 operands
+  const float* xp = a.y + (int64_t)(32 * wave + col) * slab + 4 * plane;
+  auto load_pair_row = [&](int j) -> float4 {
+    const int jc = j < J1 ? j : J1 - 1;
+    const int k = 2 * jc + half;
+    return *reinterpret_cast<const float4*>(xp + (int64_t)(k < I1 ? k : I1 - 1) * row);
+  };
+  float4 cur[kCore2Batch];
+#pragma unroll
+  for (int u = 0; u < kCore2Batch; ++u) cur[u] = load_pair_row(u);
+  {
+    // stage-1 operands -> LDS: 16-byte pieces, 8 per thread (the table holds a multiple of 64 float2)
+    const float4* t1 = reinterpret_cast<const float4*>(a.tab);
+    float4* d1 = reinterpret_cast<float4*>(sT1);
+    const int n1 = J1 * 32;
+    float4 p1[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int e = tid + u * kMidThreads;
+      p1[u] = t1[e < n1 ? e : 0];
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int e = tid + u * kMidThreads;
+      if (e < n1) d1[e] = p1[u];
+    }
+  }
+  __syncthreads();
+  // What the later stages need travels while stage 1 runs: U0 as the operands of stages 2 and 3
+  // (registers) and the moments of this thread's core entries: rows d_row(4 wave + q, half), column col,
+  // both columns of the pair.  (The stage-4 operands travel during stage 2.)
+  float2 f2[16], f3[16];
+  {
+    const float2* t2 = a.tab + J1 * 64 + NT1 * 1024 + wave * 1024 + lane;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      f2[r] = t2[r * 64];
+      f3[r] = t2[4096 + r * 64];
+    }
+  }
+  float4 mm[4];
+  float2 vv[4];
+  int64_t cidx[4];
+  bool live[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int m0 = d_row(4 * wave + q, half);
+    live[q] = m0 < M0 && col < M1;
+    cidx[q] = live[q] ? ((int64_t)m0 * M1 + col) * a.Cc + 2 * plane : 0;
+    mm[q] = *reinterpret_cast<const float4*>(ad.m + cidx[q]);
+    vv[q] = *reinterpret_cast<const float2*>(ad.v + cidx[q]);
+  }
+
+  // ---- stage 1: T = y conj(U1); tiles (column of the pair, re / im) ----
+  v16f t0r, t0i, t1r, t1i;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) t0r[r] = t0i[r] = t1r[r] = t1i[r] = 0.f;
+  auto stage1 = [&](const float4& v, int j) {
+    const float2 f = sT1[j * 64 + lane];
+    const float nfy = -f.y;
+    t0r = mfma32(v.x, f.x, t0r);             // re: yr ur + yi ui;  im: yi ur - yr ui
+    t0i = mfma32(v.y, f.x, t0i);
+    t1r = mfma32(v.z, f.x, t1r);
+    t1i = mfma32(v.w, f.x, t1i);
+    t0r = mfma32(v.y, f.y, t0r);
+    t0i = mfma32(v.x, nfy, t0i);
+    t1r = mfma32(v.w, f.y, t1r);
+    t1i = mfma32(v.z, nfy, t1i);
+  };
+  {
+    int j = 0;
+    for (; j + kCore2Batch <= J1; j += kCore2Batch) {
+      float4 nxt[kCore2Batch];
+#pragma unroll
+      for (int u = 0; u < kCore2Batch; ++u) nxt[u] = load_pair_row(j + kCore2Batch + u);
+      __builtin_amdgcn_sched_barrier(0);                       // the loads stay in front of the batch they overlap
+#pragma unroll
+      for (int u = 0; u < kCore2Batch; ++u) stage1(cur[u], j + u);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int u = 0; u < kCore2Batch; ++u) cur[u] = nxt[u];
+    }
+#pragma unroll
+    for (int u = 0; u < kCore2Batch; ++u)
+      if (j + u < J1) stage1(cur[u], j + u);
+  }
+  // ---- stage 2: this wavefront's part of P = conj(U0)^T T over its 32 rows; the stage-4 operands go in flight ----
+  const int n4 = NT1 * 512;
+  float4 p4[8];
+  {
+    const float4* t4 = reinterpret_cast<const float4*>(a.tab + J1 * 64);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int e = tid + u * kMidThreads;
+      p4[u] = t4[e < n4 ? e : 0];
+    }
+  }
+  v16f p0r, p0i, p1r, p1i;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) p0r[r] = p0i[r] = p1r[r] = p1i[r] = 0.f;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const float2 f = f2[r];
+    const float nfy = -f.y;
+    p0r = mfma32(f.x, t0r[r], p0r);          // re: ur tr + ui ti;  im: ur ti - ui tr
+    p0i = mfma32(f.x, t0i[r], p0i);
+    p1r = mfma32(f.x, t1r[r], p1r);
+    p1i = mfma32(f.x, t1i[r], p1i);
+    p0r = mfma32(f.y, t0i[r], p0r);
+    p0i = mfma32(nfy, t0r[r], p0i);
+    p1r = mfma32(f.y, t1i[r], p1r);
+    p1i = mfma32(nfy, t1r[r], p1i);
+  }
+  {
+    float4* d4 = reinterpret_cast<float4*>(sT4);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int e = tid + u * kMidThreads;
+      if (e < n4) d4[e] = p4[u];
+    }
+  }
+  __syncthreads();                                             // every wavefront is through with the stage-1 operands
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    red[((wave * 4 + 0) * 16 + r) * 64 + lane] = p0r[r];
+    red[((wave * 4 + 1) * 16 + r) * 64 + lane] = p0i[r];
+    red[((wave * 4 + 2) * 16 + r) * 64 + lane] = p1r[r];
+    red[((wave * 4 + 3) * 16 + r) * 64 + lane] = p1i[r];
+  }
+  __syncthreads();
+  // ---- AdamUpdate: wavefront w takes registers 4 w .. 4 w + 3 of the tile, partial sums added in wavefront order ----
+  float nn[4][4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int r = 4 * wave + q;
+    float g[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      g[t] = 0.f;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) g[t] += red[((w * 4 + t) * 16 + r) * 64 + lane];
+    }
+    float4 m = mm[q];
+    float2 v = vv[q];
+    m.x = ad.beta1 * m.x + (1.f - ad.beta1) * g[0];
+    m.y = ad.beta1 * m.y + (1.f - ad.beta1) * g[1];
+    m.z = ad.beta1 * m.z + (1.f - ad.beta1) * g[2];
+    m.w = ad.beta1 * m.w + (1.f - ad.beta1) * g[3];
+    v.x = ad.beta2 * v.x + (1.f - ad.beta2) * (g[0] * g[0] + g[1] * g[1]);
+    v.y = ad.beta2 * v.y + (1.f - ad.beta2) * (g[2] * g[2] + g[3] * g[3]);
+    const float d0 = 1.f / (sqrtf(v.x * ad.inv_c2) + ad.eps);
+    const float d1 = 1.f / (sqrtf(v.y * ad.inv_c2) + ad.eps);
+    nn[q][0] = nn[q][1] = nn[q][2] = nn[q][3] = 0.f;
+    if (live[q]) {
+      *reinterpret_cast<float4*>(ad.m + cidx[q]) = m;
+      *reinterpret_cast<float2*>(ad.v + cidx[q]) = v;
+      *reinterpret_cast<float4*>(ad.g_out + cidx[q]) = make_float4(g[0], g[1], g[2], g[3]);
+      nn[q][0] = m.x * ad.inv_c1 * d0;
+      nn[q][1] = m.y * ad.inv_c1 * d0;
+      nn[q][2] = m.z * ad.inv_c1 * d1;
+      nn[q][3] = m.w * ad.inv_c1 * d1;
+    }
+  }
+  __syncthreads();                                             // every partial sum has been read
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+#pragma unroll
+    for (int t = 0; t < 4; ++t) red[(t * 16 + 4 * wave + q) * 64 + lane] = nn[q][t];
+  __syncthreads();
+  // ---- stage 3: R = N_L^T U0^T for this wavefront's 32 rows i0 ----
+  v16f r0r, r0i, r1r, r1i;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) r0r[r] = r0i[r] = r1r[r] = r1i[r] = 0.f;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const float2 f = f3[r];
+    const float nfy = -f.y;
+    const float n0r = red[(0 * 16 + r) * 64 + lane], n0i = red[(1 * 16 + r) * 64 + lane];
+    const float n1r = red[(2 * 16 + r) * 64 + lane], n1i = red[(3 * 16 + r) * 64 + lane];
+    r0r = mfma32(n0r, f.x, r0r);             // re: nr ur - ni ui;  im: ni ur + nr ui
+    r0i = mfma32(n0i, f.x, r0i);
+    r1r = mfma32(n1r, f.x, r1r);
+    r1i = mfma32(n1i, f.x, r1i);
+    r0r = mfma32(n0i, nfy, r0r);
+    r0i = mfma32(n0r, f.y, r0i);
+    r1r = mfma32(n1i, nfy, r1r);
+    r1i = mfma32(n1r, f.y, r1i);
+  }
+  // ---- stage 4: z = R^T U1^T, one tile of 32 columns i1 at a time; z[plane][i0][i1], 4 floats each ----
+  float* zp = a.z + (((int64_t)plane * kCore2Rows + 32 * wave + 4 * half) * I1 + col) * 4;
+  for (int tile = 0; tile < NT1; ++tile) {
+    v16f z0r, z0i, z1r, z1i;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) z0r[r] = z0i[r] = z1r[r] = z1i[r] = 0.f;
+    const float2* ft = sT4 + tile * 16 * 64 + lane;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const float2 f = ft[r * 64];
+      const float nfy = -f.y;
+      z0r = mfma32(r0r[r], f.x, z0r);        // re: rr ur - ri ui;  im: rr ui + ri ur
+      z0i = mfma32(r0r[r], f.y, z0i);
+      z1r = mfma32(r1r[r], f.x, z1r);
+      z1i = mfma32(r1r[r], f.y, z1i);
+      z0r = mfma32(r0i[r], nfy, z0r);
+      z0i = mfma32(r0i[r], f.x, z0i);
+      z1r = mfma32(r1i[r], nfy, z1r);
+      z1i = mfma32(r1i[r], f.x, z1i);
+    }
+    if (32 * tile + col < I1) {
+      float* zt = zp + 32 * tile * 4;
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        *reinterpret_cast<float4*>(zt + (int64_t)((r & 3) + 8 * (r >> 2)) * I1 * 4) =
+            make_float4(z0r[r], z0i[r], z1r[r], z1i[r]);
+    }
+  }
+}
+
+// -------------------------------------------------------------------------------------------
 // Shared by the two last-mode kernels.  The tensor seen as (A rows, L complex per row) is cut
 // into flat tiles of 32 rows (one matrix-core tile); tile t holds elements [32 t L, 32 (t + 1) L).
 // `tile_start[t]` = number of support entries below 32 t L (Omega is ascending), so tile t owns
@@ -1425,10 +1728,12 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate(const float* __restrict__
 //             of row i2, so step (u, part) pairs elements k(u, 0) and k(u, 1) and the coefficient
 //             table is read at those rows.  Everything after that is k_lupdate.
 struct FusedPrev {
-  const float2* y1;     // (slabs, K2, K) complex: input of the fused stage
+  const float2* y1;     // input of the fused stage: element (slab, m2, m3) of the (slabs, K2, K) complex tensor lies at
+                        // y1[slab * s_slab + m2 * s_m2 + (m3 / 2) * s_pair + (m3 & 1)]
   const float2* ut;     // U^(N-1)[i2, m2], zero for m2 >= K2, in operand order (k_pack_fused_factor)
   int S;                // tiles per slab
   int K2;               // rank of mode N-1
+  int64_t s_slab, s_m2, s_pair;   // row-major: K2 K, K, 2; one column pair at a time (k_core2): 2, (K / 2) slabs 2, slabs 2
 };
 
 template <int WDT, int W, int NTB, int JT2, int UP>
@@ -1518,9 +1823,23 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate_fused(const float2* __res
   uint32_t nj0 = sp.tile_start[nxt + vzero], nj1 = sp.tile_start[nxt + 1 + vzero];
   issue_sparse(cj0, cj1);
   claim_sparse();
-  float2 y1[JT2];                                              // stage-A operand rows of the current slab
+  // Stage-A operand rows (the slab's Y1) stay in registers for all S tiles of a slab.  Those of the NEXT slab
+  // are requested right after stage A of a slab's last tile, when the registers have just been used
+  // for the last time: they then have a whole stage B and W phase to arrive, however the tensor is laid
+  // out (one column pair at a time, a lane's 16 loads touch 16 cache lines each).  Unconditional
+  // loads with clamped indices: clamped rows / columns meet zero coefficients.
+  float2 y1[JT2];
+  auto fetch_y1 = [&](int64_t sl, int ln) {
+    const int c2 = ln & 31, h2 = ln >> 5;
+    const int m3 = (c2 >> 1) < K ? (c2 >> 1) : K - 1;
+    const float2* yp = fz.y1 + sl * fz.s_slab + (int64_t)(m3 >> 1) * fz.s_pair + (m3 & 1);
 #pragma unroll
-  for (int jj = 0; jj < JT2; ++jj) y1[jj] = make_float2(0.f, 0.f);
+    for (int jj = 0; jj < JT2; ++jj) {
+      const int m2 = 2 * jj + h2;
+      y1[jj] = yp[(int64_t)(m2 < fz.K2 ? m2 : fz.K2 - 1) * fz.s_m2];
+    }
+  };
+  fetch_y1(slab, lane);
   while (true) {
     int lane_now = lane;                                       // opaque per-tile copy (see k_lproj)
     asm volatile("" : "+v"(lane_now));
@@ -1533,24 +1852,10 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate_fused(const float2* __res
     const int32_t c_om = my_om;
     const float2 c_g = my_g, c_m = my_m;
     const float c_v = my_v;
-    // ---- stage-A operands of this tile (small, cache-resident: the slab's Y1 and 32 columns of the
-    //      factor copy), issued BEFORE the W pieces so that waiting for them leaves those in flight.
-    //      Unconditional loads with clamped indices: clamped rows / columns meet zero coefficients. ----
-    // The slab's Y1 rows stay in registers for all S tiles of the slab: they are fetched on its first
-    // tile only.  On the other tiles the same instructions read one fixed, cache-resident element and
-    // the old value is kept by a select - a branch around the loads would end in a wait and a copy.
+    // ---- this tile's 32 columns of the factor copy (small, cache-resident), issued BEFORE the W pieces so
+    //      that waiting for them leaves those in flight ----
     float2 u2[JT2];
     {
-      const bool first = ts == 0;
-      const int m3 = (col >> 1) < K ? (col >> 1) : K - 1;
-      const float2* yp = fz.y1 + (first ? (size_t)slab * fz.K2 * K + m3 : (size_t)0);
-#pragma unroll
-      for (int jj = 0; jj < JT2; ++jj) {
-        const int m2 = 2 * jj + half;
-        const float2 v = yp[first ? (size_t)(m2 < fz.K2 ? m2 : fz.K2 - 1) * K : (size_t)0];
-        y1[jj].x = first ? v.x : y1[jj].x;
-        y1[jj].y = first ? v.y : y1[jj].y;
-      }
       const float4* up = reinterpret_cast<const float4*>(fz.ut) + (size_t)ts * 8 * 64 + lane_now;
 #pragma unroll
       for (int jp = 0; jp < JT2 / 2; ++jp) {                   // two operand rows per 16-byte load
@@ -1584,6 +1889,7 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate_fused(const float2* __res
       dz = mfma32(a1, u2[jj].x, dz);
       dz = mfma32(a2, u2[jj].y, dz);
     }
+    if (nts == 0 && have_next) fetch_y1(nslab, lane_now);      // (wave-uniform) the next tile opens a new slab
     // ---- the next tile's sparse state goes in flight ----
     int64_t nnslab = nslab;
     int nnts = nts;
@@ -1914,6 +2220,38 @@ void launch_core(hipStream_t s, const float2* x, const float2* U, int rn, int K,
   }
 }
 
+// Limits of k_core2: first extent 128 (one 32-row tile per wavefront), ranks within one tile, the second
+// extent within four tiles, an even rank of the last mode (a column pair then lies inside one row of the
+// mode before it), and enough column pairs (one workgroup each) to occupy three quarters of the chip:
+// below that the three separate kernels, which spread over it, are faster.
+bool core2_kernel_fits(int I0, int I1, int M0, int M1, int K2, int K) {
+  const int64_t Cc = (int64_t)K2 * K;
+  return I0 == kCore2Rows && I1 >= 1 && I1 <= 128 && M0 >= 1 && M0 <= 32 && M1 >= 1 && M1 <= 32 && K % 2 == 0 &&
+         Cc / 2 >= (int64_t)compute_units() * 3 / 4 && (int64_t)I0 * I1 * Cc < ((int64_t)1 << 28);
+}
+
+size_t core2_table_bytes(int I1) { return (size_t)core2_table_elems(I1) * 8; }
+
+// The factors of the two leading modes in the operand order of k_core2's four stages (once per refresh).
+void launch_pack_core2(hipStream_t s, const float2* U0, int rn0, int M0, const float2* U1, int rn1, int M1, int I1,
+                       float2* tab) {
+  const int n = core2_table_elems(I1);
+  k_pack_core2<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(U0, rn0, M0, U1, rn1, M1, I1, tab);
+}
+
+// The two leading modes compressed, AdamUpdate on the core, the two leading modes reconstructed:
+// x (128, I1, Cc) -> z (Cc / 2, 128, I1) units of two complex, the core (M0, M1, Cc) in between.
+void launch_core2(hipStream_t s, const float2* x, const float2* tab, int I1, int M0, int M1, int64_t Cc, float2* m,
+                  float* v, float2* g_out, float beta1, float beta2, float inv_c1, float inv_c2, float eps,
+                  float2* z) {
+  const int NT1 = (I1 + 31) / 32;
+  const size_t lds = (size_t)64 * 1024 + (size_t)NT1 * 16 * 64 * 8;
+  Core2Args a{reinterpret_cast<const float*>(x), reinterpret_cast<float*>(z), tab, I1, M0, M1, Cc};
+  CoreAdam ad{m, v, g_out, beta1, beta2, inv_c1, inv_c2, eps};
+  allow_lds(k_core2, lds);
+  k_core2<<<dim3((unsigned)(Cc / 2)), dim3(kMidThreads), lds, s>>>(a, ad);
+}
+
 void launch_pack_fused_factor(hipStream_t s, const float2* U, int I2, int r, float2* fpad, float2* ut) {
   k_pack_fused_factor<<<dim3((unsigned)((I2 * 32 + 255) / 256)), dim3(256), 0, s>>>(U, I2, r, fpad, ut);
 }
@@ -2050,11 +2388,13 @@ void launch_lupdate(hipStream_t s, const float2* z, const float2* U, const Stage
 }
 
 // k_lupdate with the reconstruction stage of mode N-1 in front (see k_lupdate_fused): `y1` is the
-// tensor before that stage, (slabs, K2, K) complex; `ut` the transposed factor copy; I2 = 32 S.
+// tensor before that stage, (slabs, K2, K) complex - or, with `pair_major` (K even), the same tensor
+// as (K2 K / 2, slabs) units of two neighbouring complex numbers; `ut` the transposed factor copy; I2 = 32 S.
 void launch_lupdate_fused(hipStream_t s, const float2* y1, const float2* ut, int I2, int K2, const float2* U,
                           const Stage& st, void* w, int wdtype, float decay, float c_alpha, const int32_t* omega,
                           const uint32_t* tile_start, int64_t k, const float2* gs, float2* ms, float* vs,
-                          float beta1, float beta2, float inv_c1, float inv_c2, float eps, float c_lambda) {
+                          float beta1, float beta2, float inv_c1, float inv_c2, float eps, float c_lambda,
+                          bool pair_major) {
   const int64_t A = st.A;
   const int K = st.K, M = st.M;
   if (A * M <= 0) return;
@@ -2068,7 +2408,12 @@ void launch_lupdate_fused(hipStream_t s, const float2* y1, const float2* ut, int
   dim3 grid(1), block(64 * W);
   SparseAdam sp{omega, tile_start, gs, ms, vs, beta1, beta2, inv_c1, inv_c2, eps, c_lambda,
                 (int)(k > 0 ? k - 1 : 0)};
-  FusedPrev fz{y1, ut, S, K2};
+  FusedPrev fz{y1, ut, S, K2, (int64_t)K2 * K, (int64_t)K, 2};
+  if (pair_major) {                              // (K2 K / 2, slabs) units of two complex: what k_core2 writes
+    fz.s_slab = 2;
+    fz.s_pair = nslabs * 2;
+    fz.s_m2 = (int64_t)(K / 2) * nslabs * 2;
+  }
   const int up = (M + 3) / 4 <= 5 ? 5 : (M + 3) / 4 <= 9 ? 9 : kUpdPrefetch;
 #define TGRAD_LUF_U(JT2_, UP_)                                                                           \
   do {                                                                                                   \

@@ -48,10 +48,11 @@ struct Plan {
   int64_t tile_elems = 0;
   bool fuse_next = false;        // the last-mode kernels also handle mode N-1 (see make_plan)
   bool fuse_core = false;        // last compression stage + AdamUpdate + first reconstruction stage in one kernel
+  bool fuse_core2 = false;       // both leading modes, both ways, and AdamUpdate in one kernel (N = 4, see k_core2)
   // byte offsets into state
   size_t st_omega, st_ms, st_vs, st_ml, st_vl, st_U[kMaxNdim], state_bytes;
   // byte offsets into workspace
-  size_t ws_sel, ws_hist, ws_eig_status, ws_chunk_gt, ws_chunk_eq, ws_mask, ws_cand, ws_tile_start, ws_fpad, ws_ut, ws_partials, ws_gram[kMaxNdim],
+  size_t ws_sel, ws_hist, ws_eig_status, ws_chunk_gt, ws_chunk_eq, ws_mask, ws_cand, ws_tile_start, ws_fpad, ws_ut, ws_core2, ws_partials, ws_gram[kMaxNdim],
       ws_eig_a[kMaxNdim], ws_eig_v[kMaxNdim], ws_gs, ws_core_g, ws_core_n, ws_buf[2], workspace_bytes;
   int gram_chunks[kMaxNdim];
   int order = 0;                   // TGRAD_ORDER_*
@@ -182,6 +183,8 @@ void make_plan(const tgrad_config* c, Plan* p) {
     }
     p->fuse_next = fuse;
     p->fuse_core = core_kernel_fits((int)p->shape[0], p->rank[0]);
+    p->fuse_core2 = fuse && N == 4 &&
+                    core2_kernel_fits((int)p->shape[0], (int)p->shape[1], p->rank[0], p->rank[1], p->rank[2], p->rank[3]);
   }
 
   size_t o = 0;
@@ -210,6 +213,7 @@ void make_plan(const tgrad_config* c, Plan* p) {
   p->ws_tile_start = take((size_t)(p->ntiles + 1) * 4);
   p->ws_fpad = take(p->fuse_next ? (size_t)p->shape[N - 2] * 32 * 8 : 0);
   p->ws_ut = take(p->fuse_next ? (size_t)p->shape[N - 2] * 32 * 8 : 0);
+  p->ws_core2 = take(p->fuse_core2 ? core2_table_bytes((int)p->shape[1]) : 0);
   size_t partial_max = 0;
   for (int n = 0; n < N; ++n) {
     int64_t A = 1, B = 1;
@@ -366,14 +370,17 @@ int finish_call(tgrad_ctx* c) {
 // caller: it is reported (not cleared, so the caller still finds it) and nothing is launched.
 bool error_pending_on_entry() { return hipPeekAtLastError() != hipSuccess; }
 
-// Kernel-ready copies of U^(N-1) for the fused kernels; rebuilt whenever that factor changes
-// (refresh, HOOI sweep, tgrad_set_state), never on the step path.
+// Kernel-ready copies of U^(N-1) for the fused kernels, and of U^(1), U^(2) for the two-mode core kernel;
+// rebuilt whenever a factor changes (refresh, HOOI sweep, tgrad_set_state), never on the step path.
 void pack_fused_factor(tgrad_ctx* c) {
   Plan& p = c->plan;
   if (!p.fuse_next) return;
   Scope sc_(c, KID_FACTOR_PACK);
   launch_pack_fused_factor(c->stream, c->st<float2>(p.st_U[p.N - 2]), (int)p.shape[p.N - 2], p.rank[p.N - 2],
                            c->w<float2>(p.ws_fpad), c->w<float2>(p.ws_ut));
+  if (p.fuse_core2)
+    launch_pack_core2(c->stream, c->st<float2>(p.st_U[0]), p.rank[0], p.rank[0], c->st<float2>(p.st_U[1]), p.rank[1],
+                      p.rank[1], (int)p.shape[1], c->w<float2>(p.ws_core2));
 }
 
 // Omega <- SparseIndices(x, rho, top-k | rand-k), plus the support bitmask and the tile offsets.
@@ -607,6 +614,7 @@ int do_step(tgrad_ctx* c, void* weight, const void* g) {
       st = 1;
       continue;
     }
+    if (st == N - 2 && p.fuse_core2) break;                    // modes 2 and 1 are contracted inside k_core2 below
     if (st == N - 1 && p.fuse_core) break;                     // mode 1 is contracted inside k_core below
     Scope sc_(c, st == 0 ? KID_PROJECT_FIRST : KID_PROJECT);
     if (st == 0) {
@@ -627,7 +635,15 @@ int do_step(tgrad_ctx* c, void* weight, const void* g) {
   const float inv_c2 = (float)(1.0 / (1.0 - std::pow((double)cf.beta2, tau)));
   const float2* zsrc = core_n;
   int first_back = 0;
-  if (p.fuse_core) {
+  if (p.fuse_core2) {
+    // the last two compression stages, AdamUpdate on the core and the first two reconstruction stages
+    Scope sc_(c, KID_CORE);
+    launch_core2(s, src, c->w<float2>(p.ws_core2), (int)p.shape[1], p.rank[0], p.rank[1],
+                 (int64_t)p.rank[2] * p.rank[3], c->st<float2>(p.st_ml), c->st<float>(p.st_vl), core_g, cf.beta1,
+                 cf.beta2, inv_c1, inv_c2, cf.eps, buf[0]);
+    zsrc = buf[0];
+    first_back = 2;
+  } else if (p.fuse_core) {
     // last compression stage, AdamUpdate on the core and first reconstruction stage (all mode 1)
     const Stage& sg = p.proj[N - 1];
     Scope sc_(c, KID_CORE);
@@ -669,7 +685,7 @@ int do_step(tgrad_ctx* c, void* weight, const void* g) {
       launch_lupdate_fused(s, zsrc, c->w<float2>(p.ws_ut), (int)p.shape[N - 2], p.rank[N - 2], U, sg,
                            weight, cf.weight_dtype, decay, -cf.lr * cf.alpha, omega, tile_start, p.k, gs,
                            c->st<float2>(p.st_ms), c->st<float>(p.st_vs), cf.beta1, cf.beta2, inv_c1, inv_c2,
-                           cf.eps, -cf.lr * cf.lambda);
+                           cf.eps, -cf.lr * cf.lambda, p.fuse_core2);
     } else if (mfma_last) {
       Scope sc_(c, KID_UPDATE);
       launch_lupdate(s, zsrc, U, sg, p.tile_waves, weight, cf.weight_dtype, decay, -cf.lr * cf.alpha,

@@ -161,6 +161,34 @@ def test_fused_tier_small_shapes(shape, ranks, k):
     assert times["project"]["launches"] == len(shape) - 3 and times["backproject"]["launches"] == len(shape) - 3
 
 
+CORE2_SHAPES = [
+    ((128, 40, 32, 13), (8, 6, 32, 12), 4000, "us_lr"),      # second extent: one full tile + a ragged one
+    ((128, 41, 32, 13), (32, 32, 32, 12), 4000, "us_lr"),    # odd second extent, full ranks in the two leading modes
+    ((128, 128, 32, 13), (32, 32, 32, 12), 30000, "lr_us"),  # the headline's leading modes, low rank first
+]
+
+
+@pytest.mark.parametrize("shape,ranks,k,order", CORE2_SHAPES)
+def test_two_mode_core_kernel_tier(shape, ranks, k, order):
+    """Four-way tensors with a first extent of 128 and at least 192 column pairs behind the two leading
+    modes: both leading modes (both ways) and AdamUpdate on the core run as ONE launch between the
+    fused first projection and the fused update."""
+    _announce("two-mode core kernel", shape, ranks, k)
+    grads = [synth.small_case(shape, 900 + t, outlier_frac=(1, 200)) for t in range(5)]
+    rng = np.random.default_rng(8)
+    W0 = ((rng.standard_normal(shape) + 1j * rng.standard_normal(shape)) * 0.02).astype(np.complex64)
+    info = run_both(T, shape, ranks, k, grads, W0, refresh_every=3, lr=2e-3, weight_decay=0.01,
+                    order=getattr(T, "TGRAD_ORDER_" + order.upper()))
+    assert all(info["omega_equal"])
+    check_parity(info, W0)
+    ctx = info["ctx"]
+    ctx.tgrad_set_profiling(True)
+    ctx.tgrad_step(T.to_device_weight(W0), T.to_device_grad(grads[0]))
+    times = ctx.tgrad_get_kernel_times()
+    assert times["core"]["launches"] == 1
+    assert "project" not in times and "backproject" not in times          # kernels that never ran are not listed
+
+
 # ------------------------------------------------------------------ weights stored as bf16 pairs
 def _bf16_weights(shape, seed):
     rng = np.random.default_rng(seed)
