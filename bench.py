@@ -30,12 +30,13 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def kernel_model(w, fused, weight_bytes=8, core_fused=False):
+def kernel_model(w, fused, weight_bytes=8, core_fused=0):
     """Algorithmic bytes and flops per launch of every kernel, from the tensor shapes alone
     (8 real flops per complex multiply-add; a complex64 element is 8 bytes).  `fused`: the library
     ran the mode-(N-1) compression / reconstruction stages inside the first-stage and the
     weight-update kernels (it does whenever the shape allows), so the tensors between them are
-    neither written nor read.  `weight_bytes`: 8 for complex64 weights, 4 for bf16 pairs."""
+    neither written nor read.  `weight_bytes`: 8 for complex64 weights, 4 for bf16 pairs.
+    `core_fused`: how many leading modes the kernel around the core handles both ways (0, 1 or 2)."""
     shape, ranks, k = w.shape, w.ranks, w.k
     N = len(shape)
     I = int(np.prod(shape))
@@ -67,10 +68,10 @@ def kernel_model(w, fused, weight_bytes=8, core_fused=False):
         fl += 8 * A1 * K1 * M1 * B1
         first_mid = 2
     m["project_first"] = {"bytes": by, "flops": fl, "bound": "hbm"}
-    # `core_fused`: the last compression stage, AdamUpdate on the core and the first reconstruction
-    # stage (all three on mode 1) run as one kernel: reads its input tensor, writes a tensor of the
+    # `core_fused`: the last 1 or 2 compression stages, AdamUpdate on the core and the first 1 or 2
+    # reconstruction stages run as one kernel: reads its input tensor, writes a tensor of the
     # same size, reads and writes the moments and writes the core gradient
-    proj_end = N - 1 if core_fused else N
+    proj_end = N - core_fused
     by = fl = 0
     for s in range(first_mid, proj_end):
         b_, f_ = vol(*stage_dims(True, s))
@@ -79,7 +80,7 @@ def kernel_model(w, fused, weight_bytes=8, core_fused=False):
     if proj_end > first_mid:
         m["project"] = {"bytes": by, "flops": fl, "bound": "mfma", "launches_per_step": proj_end - first_mid}
     last_mid = N - 2 if fused else N - 1                  # reconstruction stages 0 .. last_mid - 1 run alone
-    back_start = 1 if core_fused else 0
+    back_start = core_fused
     by = fl = 0
     for s in range(back_start, last_mid):
         b_, f_ = vol(*stage_dims(False, s))
@@ -88,8 +89,9 @@ def kernel_model(w, fused, weight_bytes=8, core_fused=False):
     if last_mid > back_start:
         m["backproject"] = {"bytes": by, "flops": fl, "bound": "mfma", "launches_per_step": last_mid - back_start}
     if core_fused:
-        A0, K0, M0, B0 = stage_dims(True, N - 1)
-        m["core"] = {"bytes": 2 * K0 * B0 * 8 + C * (8 + 12 + 12), "flops": 16 * K0 * M0 * B0 + 12 * C, "bound": "mfma"}
+        A0, K0, M0, B0 = stage_dims(True, N - core_fused)    # the kernel's input: (A0, K0, B0), A0 = I_1 with two modes
+        fl = sum(2 * vol(*stage_dims(True, s))[1] for s in range(N - core_fused, N))
+        m["core"] = {"bytes": 2 * A0 * K0 * B0 * 8 + C * (8 + 12 + 12), "flops": fl + 12 * C, "bound": "mfma"}
     # last reconstruction stage fused with the sparse AdamUpdate, the scatter-add and the weight
     # update: reads its input tensor and W, writes W; per sparse entry its index, gathered value
     # and both moments are read and the moments written back
@@ -175,6 +177,8 @@ def main():
                     help="untimed steps first (the clocks take some tens of steps to settle; step 0 refreshes)")
     ap.add_argument("--workload", default="cfg4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--probe-copies", type=int, default=50,
+                    help="launches of the copy kernel that measure the achievable HBM rate (they run right before the timed steps)")
     ap.add_argument("--hooi-sweeps", type=int, default=0,
                     help="HOOI refinement sweeps per refresh (default 0 = HOSVD factors, the headline configuration)")
     ap.add_argument("--warm-restart", action="store_true", help="with --hooi-sweeps: refreshes restart from the factors in place")
@@ -238,7 +242,7 @@ def main():
     ce0, ce1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     for _ in range(3):
         T.tgrad_calibration_copy(cdst, csrc)
-    ncopy = 10
+    ncopy = max(1, args.probe_copies)
     ce0.record()
     for _ in range(ncopy):
         T.tgrad_calibration_copy(cdst, csrc)
@@ -300,9 +304,12 @@ def main():
 
     # the library fuses the mode-(N-1) stages when the shape allows: then k_mid runs N - 2 times each way
     nstep = max(1, times.get("project_first", {}).get("launches", 1))
-    core_fused = "core" in times
-    nproj = times.get("project", {}).get("launches", 0) + (nstep if core_fused else 0)
-    fused = len(w.shape) >= 3 and nproj == (len(w.shape) - 2) * nstep
+    # and the kernel around the core takes one leading mode, or two (four-way tensors, first extent 128):
+    # the stages that k_mid does not launch are the ones that were absorbed
+    nmid = times.get("project", {}).get("launches", 0) // nstep
+    absorbed = (len(w.shape) - 1) - nmid - (1 if "core" in times else 0)
+    fused = len(w.shape) >= 3 and absorbed >= 1
+    core_fused = (2 if absorbed >= 2 else 1) if "core" in times else 0
     model = kernel_model(w, fused, 4 if args.weights == "bf16" else 8, core_fused)
     kernels = {}
     for name, v in sorted(times.items(), key=lambda kv: -kv[1]["total_ms"]):
@@ -373,7 +380,7 @@ def main():
         "config": {"workload": "%s: %d x %s %s gradient, Tucker ranks %s, k=%d sparse, refresh every %d"
                                % (w.name, w.layers, "x".join(map(str, w.shape)), w.grad_dtype,
                                   ",".join(map(str, w.ranks)), w.k, w.T),
-                   "refreshes_in_timed_region": refreshes, "fused_mode_stages": bool(fused), "fused_core_stage": bool(core_fused),
+                   "refreshes_in_timed_region": refreshes, "fused_mode_stages": bool(fused), "core_kernel_modes": int(core_fused),
                    "order": args.order, "weights": args.weights, "select": args.select, "hooi_sweeps": args.hooi_sweeps, "warm_restart": bool(args.warm_restart)},
         "roofline": roofline,
         "ms_per_step_steady": round(steady, 4) if steady is not None else None,
