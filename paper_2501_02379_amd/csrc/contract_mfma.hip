@@ -1777,6 +1777,13 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate_fused(const float2* __res
   const int64_t nslabs = ntiles / S;                           // A = slabs * 32 S exactly
   const int64_t nw = (int64_t)gridDim.x * W;
   int64_t slab = (int64_t)blockIdx.x * W + wave;
+  if (W == 4 && fz.s_slab == 2 && (gridDim.x & 15) == 0) {
+    // One column pair at a time, a 128-byte line of the operand tensor holds 8 consecutive slabs: the two
+    // workgroups that share it are given block indices 8 apart, i.e. the same XCD under round-robin
+    // dispatch, so that one L2 fetches the line for both (otherwise two do: 1.03 x the kernel's traffic).
+    const int64_t b = blockIdx.x;
+    slab = 8 * (8 * (b >> 4) + (b & 7)) + 4 * ((b >> 3) & 1) + wave;
+  }
   int ts = 0;
   if (slab >= nslabs) return;
   auto advance = [&](int64_t& sl, int& t) {
