@@ -636,6 +636,45 @@ def test_eigen_solve_on_degenerate_clusters():
         ctx.tgrad_destroy()
 
 
+def _matrix_with_singular_values(n, sv, seed):
+    rng = np.random.default_rng(seed)
+    Q1 = np.linalg.qr(rng.standard_normal((n, n)) + 1j * rng.standard_normal((n, n)))[0]
+    Q2 = np.linalg.qr(rng.standard_normal((n, n)) + 1j * rng.standard_normal((n, n)))[0]
+    return ((Q1 * sv) @ Q2.conj().T).astype(np.complex64)
+
+
+@pytest.mark.parametrize("n", [2, 3, 5, 16, 17, 31, 33, 64, 65, 96, 127, 128])
+def test_eigen_solve_over_extents_ranks_and_spectra(n):
+    """The solver for extents up to 128 against the oracle's factors, column by column, on square
+    matrices with prescribed singular values: a geometric decay over two decades (Gram eigenvalues
+    over four: their smallest gap is still 5e-6 of the spectral radius at n = 128), a flat noise-like spectrum with gaps of 1e-3, and a pair of leading singular values
+    1e-4 apart (a Gram gap of 2e-4 of the spectral radius: far above the threshold at which the
+    tridiagonal path declines, small enough to stress inverse iteration).  Ranks 1, n / 4 and n - 1."""
+    _announce("eigen-solve sweep", n)
+    spectra = {
+        "geometric": 10.0 ** (-2.0 * np.arange(n) / max(1, n - 1)),
+        "flat": 1.0 - 1e-3 * np.arange(n),
+        "close pair": np.concatenate(([1.0, 1.0 - 1e-4], 0.9 - 0.5 * np.arange(max(0, n - 2)) / max(1, n))),
+    }
+    for name, sv in spectra.items():
+        g = _matrix_with_singular_values(n, sv[:n], 100 + n)
+        X = O.to_complex128(g)
+        for r in sorted({1, max(1, n // 4), n - 1}):
+            ctx = make_gpu_ctx(T, (n, n), (r, r), 0, refresh_every=0)
+            ctx.tgrad_refresh_factors(T.to_device_grad(g))
+            Uo = O.tucker_factors(X, (r, r))
+            for mode in range(2):
+                stalled, sweeps, declined = ctx.tgrad_get_state(T.STATE_EIG_INFO0 + mode)
+                assert (stalled, declined) == (0, 0), (name, r, mode)
+                U = ctx.tgrad_get_state(T.STATE_FACTOR0 + mode).astype(np.complex128)
+                assert np.max(np.abs(U.conj().T @ U - np.eye(r))) < 1e-5, (name, r, mode)
+                assert projector_distance(U, Uo[mode]) < PROJ_TOL, (name, r, mode)
+                # (both sides see the same float32 matrix and accumulate its Gram in float64: the pair's gap
+                # divides errors of 1e-16, not of 1e-7)
+                assert np.max(np.abs(U - Uo[mode])) < 1e-4, (name, r, mode)
+            ctx.tgrad_destroy()
+
+
 def test_exactly_repeated_eigenvalues_go_to_the_jacobi_solver():
     """A diagonal gradient with repeated entries: the Gram matrices are exactly diagonal with exactly
     repeated eigenvalues.  Inverse iteration cannot separate those, so the tridiagonal solver must
