@@ -1736,7 +1736,7 @@ struct FusedPrev {
   int64_t s_slab, s_m2, s_pair;   // row-major: K2 K, K, 2; one column pair at a time (k_core2): 2, (K / 2) slabs 2, slabs 2
 };
 
-template <int WDT, int W, int NTB, int JT2, int UP>
+template <int WDT, int W, int MS, int JT2, int UP>
 __global__ __launch_bounds__(64 * W, 2) void k_lupdate_fused(const float2* __restrict__ U, int64_t A, int K,
                                                              int M, int64_t ntiles, void* __restrict__ w,
                                                              float decay, float c_alpha, SparseAdam sp,
@@ -1746,7 +1746,9 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate_fused(const float2* __res
   constexpr int kPre = WS::kElems == 2 ? UP : (UP + 1) / 2;   // 16-byte pieces of the W tile per lane in flight
   constexpr int T = 64 * W;
   extern __shared__ float smem[];
-  const int N2 = 2 * M;
+  // MS > 0: the extent of the last mode is the compile-time constant MS (the host passes M == MS): stage B
+  // then runs without a single vector-ALU instruction between its matrix instructions (see below).
+  const int N2 = MS > 0 ? 2 * MS : 2 * M;
   const int NT = (N2 + 31) >> 5;
   const int ld = 16 * NT;
   const int slice = (kTileRows * N2 + 3) & ~3;                 // floats per wavefront: flat image of its W tile
@@ -1763,11 +1765,24 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate_fused(const float2* __res
   // two halves of the wavefront are added with one lane exchange.
   const bool vtail = (N2 & 31) == 2;
   const int NTm = vtail ? NT - 1 : NT;                         // column tiles that go through the matrix cores
-  float2 ctail[8];
-#pragma unroll
+  float2 ctail[8];                                             // (MS > 0: read from the table when used; the registers
+#pragma unroll                                                 //  hold the matrix-core coefficients instead)
   for (int u = 0; u < 8; ++u) {
     const int k = (u & 1) + 4 * (u >> 1) + 2 * (lane >> 5);
-    ctail[u] = vtail ? sF[k * ld + (M - 1)] : make_float2(0.f, 0.f);
+    ctail[u] = (MS == 0 && vtail) ? sF[k * ld + (M - 1)] : make_float2(0.f, 0.f);
+  }
+
+  // MS > 0: the stage-B coefficients of every column tile, already in the form the lane's column needs
+  // (they do not depend on the tile), in registers for the whole kernel.
+  constexpr int kNTmS = MS > 0 ? ((2 * MS) & 31) == 2 ? (2 * MS + 31) / 32 - 1 : (2 * MS + 31) / 32 : 1;
+  float2 cregB[kNTmS][8];
+  if constexpr (MS > 0) {
+    const float2* fl0 = sF + (2 * (lane >> 5)) * ld + ((lane & 31) >> 1);
+#pragma unroll
+    for (int i = 0; i < kNTmS; ++i)
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        cregB[i][u] = column_coef(fl0[((u & 1) + 4 * (u >> 1)) * ld + 16 * i], lane & 1);
   }
 
   const int64_t Iw = A * M;
@@ -1889,12 +1904,20 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate_fused(const float2* __res
     v16f dz;
 #pragma unroll
     for (int r = 0; r < 16; ++r) dz[r] = 0.f;
+    if (ts == 0) {
+      // (wave-uniform) first tile of a slab: the rows just claimed become the two A operands of the lane's
+      // row (rho = 2 m3 + p): re(u y) = ur yr - ui yi, im(u y) = ur yi + ui yr; once per slab, not per tile
+#pragma unroll
+      for (int jj = 0; jj < JT2; ++jj) {
+        const float2 y = y1[jj];
+        y1[jj].x = part ? y.y : y.x;
+        y1[jj].y = part ? y.x : -y.y;
+      }
+    }
 #pragma unroll
     for (int jj = 0; jj < JT2; ++jj) {
-      const float a1 = part ? y1[jj].y : y1[jj].x;
-      const float a2 = part ? y1[jj].x : -y1[jj].y;
-      dz = mfma32(a1, u2[jj].x, dz);
-      dz = mfma32(a2, u2[jj].y, dz);
+      dz = mfma32(y1[jj].x, u2[jj].x, dz);
+      dz = mfma32(y1[jj].y, u2[jj].y, dz);
     }
     if (nts == 0 && have_next) fetch_y1(nslab, lane_now);      // (wave-uniform) the next tile opens a new slab
     // ---- the next tile's sparse state goes in flight ----
@@ -1908,33 +1931,34 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate_fused(const float2* __res
     wave_sync();                                               // previous tile's LDS reads are done
     // ---- stage B: expand the last mode: sD[row, c] = sum_k (c_alpha U)[c, k] ..., NTB column tiles at a time ----
     const float2* fl = sF + (2 * half) * ld + (col >> 1);      // row k(u, half) = (u & 1) + 4 (u >> 1) + 2 half
-    auto block = [&](int nt0, auto ntile_count) {
-      constexpr int N = decltype(ntile_count)::value;
-      v16f acc[N];
+    if constexpr (MS > 0) {
+      // Straight-line: 16 matrix instructions per column tile with coefficients from registers, then the tile's
+      // 16 result rows written at constant offsets from one lane address.  (A vector-ALU instruction between two fp32 matrix instructions waits for the matrix
+      // pipe: selects, zeroing and register copies in this stage cost more than its matrix work.)
+      constexpr int N2s = 2 * MS;
+      float* sDl = sD + (4 * half) * N2s + col;
+      auto chain = [&](int i) -> v16f {
+        v16f zero;
 #pragma unroll
-      for (int i = 0; i < N; ++i)
+        for (int r = 0; r < 16; ++r) zero[r] = 0.f;
+        v16f acc = mfma32(dz[0], cregB[i][0].x, zero);
+        acc = mfma32(dz[1], cregB[i][0].y, acc);
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
-      const float2* fb = fl + 16 * nt0;
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
-#pragma unroll
-        for (int i = 0; i < N; ++i) {
-          const float2 b2 = column_coef(fb[((u & 1) + 4 * (u >> 1)) * ld + 16 * i], part);
-          acc[i] = mfma32(dz[2 * u], b2.x, acc[i]);
-          acc[i] = mfma32(dz[2 * u + 1], b2.y, acc[i]);
+        for (int u = 1; u < 8; ++u) {
+          acc = mfma32(dz[2 * u], cregB[i][u].x, acc);
+          acc = mfma32(dz[2 * u + 1], cregB[i][u].y, acc);
         }
-      }
+        return acc;
+      };
+      auto put = [&](const v16f& acc, int i) {
+        if (32 * (i + 1) <= N2s || 32 * i + col < N2s) {
 #pragma unroll
-      for (int i = 0; i < N; ++i) {
-        const int c = 32 * (nt0 + i) + col;
-        if (c < N2) {
-#pragma unroll
-          for (int r = 0; r < 16; ++r) sD[d_row(r, half) * N2 + c] = acc[i][r];
+          for (int r = 0; r < 16; ++r) sDl[((r & 3) + 8 * (r >> 2)) * N2s + 32 * i] = acc[r];
         }
-      }
-    };
-    if constexpr (NTB == 1) {
+      };
+#pragma unroll
+      for (int i = 0; i < kNTmS; ++i) put(chain(i), i);
+    } else {
       // one column tile at a time, its 8 coefficient pairs fetched while the previous tile is in the
       // matrix cores (the last tile re-reads itself)
       float2 cf[8];
@@ -1962,18 +1986,15 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate_fused(const float2* __res
 #pragma unroll
         for (int u = 0; u < 8; ++u) cf[u] = cn[u];
       }
-    } else {
-      int nt0 = 0;
-      for (; nt0 + NTB <= NTm; nt0 += NTB) block(nt0, std::integral_constant<int, NTB>());
-      for (; nt0 < NTm; ++nt0) block(nt0, std::integral_constant<int, 1>());
     }
     if (vtail) {                                               // the last complex column, without the matrix cores
       float pre = 0.f, pim = 0.f;
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
         const float zr = dz[2 * u], zi = dz[2 * u + 1];
-        pre += zr * ctail[u].x - zi * ctail[u].y;
-        pim += zr * ctail[u].y + zi * ctail[u].x;
+        const float2 ct = MS > 0 ? sF[((u & 1) + 4 * (u >> 1) + 2 * half) * ld + (MS - 1)] : ctail[u];
+        pre += zr * ct.x - zi * ct.y;
+        pim += zr * ct.y + zi * ct.x;
       }
       pre += __shfl_xor(pre, 32, 64);
       pim += __shfl_xor(pim, 32, 64);
@@ -2422,24 +2443,31 @@ void launch_lupdate_fused(hipStream_t s, const float2* y1, const float2* ut, int
     fz.s_m2 = (int64_t)(K / 2) * nslabs * 2;
   }
   const int up = (M + 3) / 4 <= 5 ? 5 : (M + 3) / 4 <= 9 ? 9 : kUpdPrefetch;
-#define TGRAD_LUF_U(JT2_, UP_)                                                                           \
+#define TGRAD_LUF_M(JT2_, UP_, MS_)                                                                      \
   do {                                                                                                   \
     if (wdtype == TGRAD_C64) {                                                                           \
-      allow_lds(k_lupdate_fused<TGRAD_C64, W, 1, JT2_, UP_>, lds);   \
-      grid.x = (unsigned)grid_for_tiles(ngroups, resident_blocks(k_lupdate_fused<TGRAD_C64, W, 1, JT2_, UP_>, 64 * W, lds));                                       \
-      k_lupdate_fused<TGRAD_C64, W, 1, JT2_, UP_><<<grid, block, lds, s>>>(U, A, K, M, ntiles, w, decay, c_alpha, sp, fz); \
+      allow_lds(k_lupdate_fused<TGRAD_C64, W, MS_, JT2_, UP_>, lds);                                     \
+      grid.x = (unsigned)grid_for_tiles(ngroups, resident_blocks(k_lupdate_fused<TGRAD_C64, W, MS_, JT2_, UP_>, 64 * W, lds)); \
+      k_lupdate_fused<TGRAD_C64, W, MS_, JT2_, UP_><<<grid, block, lds, s>>>(U, A, K, M, ntiles, w, decay, c_alpha, sp, fz); \
     } else {                                                                                             \
-      allow_lds(k_lupdate_fused<TGRAD_CBF16, W, 1, JT2_, UP_>, lds);   \
-      grid.x = (unsigned)grid_for_tiles(ngroups, resident_blocks(k_lupdate_fused<TGRAD_CBF16, W, 1, JT2_, UP_>, 64 * W, lds));                                     \
-      k_lupdate_fused<TGRAD_CBF16, W, 1, JT2_, UP_><<<grid, block, lds, s>>>(U, A, K, M, ntiles, w, decay, c_alpha, sp, fz); \
+      allow_lds(k_lupdate_fused<TGRAD_CBF16, W, MS_, JT2_, UP_>, lds);                                   \
+      grid.x = (unsigned)grid_for_tiles(ngroups, resident_blocks(k_lupdate_fused<TGRAD_CBF16, W, MS_, JT2_, UP_>, 64 * W, lds)); \
+      k_lupdate_fused<TGRAD_CBF16, W, MS_, JT2_, UP_><<<grid, block, lds, s>>>(U, A, K, M, ntiles, w, decay, c_alpha, sp, fz); \
     }                                                                                                    \
+  } while (0)
+  // the half-spectrum extents of FNO layers (2^m + 1) get a stage B with the extent as a compile-time constant
+#define TGRAD_LUF_U(JT2_, UP_, MS_)                                                                      \
+  do {                                                                                                   \
+    if (M == MS_) TGRAD_LUF_M(JT2_, UP_, MS_); else TGRAD_LUF_M(JT2_, UP_, 0);                           \
   } while (0)
 #define TGRAD_LUF(JT2_)                                                                                  \
   do {                                                                                                   \
-    if (up == 5) TGRAD_LUF_U(JT2_, 5); else if (up == 9) TGRAD_LUF_U(JT2_, 9); else TGRAD_LUF_U(JT2_, kUpdPrefetch); \
+    if (up == 5) TGRAD_LUF_U(JT2_, 5, 17); else if (up == 9) TGRAD_LUF_U(JT2_, 9, 33);                   \
+    else TGRAD_LUF_U(JT2_, kUpdPrefetch, 65);                                                            \
   } while (0)
   if (K2 <= 8) TGRAD_LUF(4); else if (K2 <= 16) TGRAD_LUF(8); else TGRAD_LUF(16);
 #undef TGRAD_LUF_U
+#undef TGRAD_LUF_M
 #undef TGRAD_LUF
 }
 
