@@ -1099,13 +1099,23 @@ __device__ __forceinline__ double wave_sum_d(double v) {
   return v;
 }
 
+// 1 / q from the hardware's reciprocal estimate and two Newton steps (relative error a few 1e-16): the
+// sequential recurrences below spend their time in this, and a correctly rounded float64 division
+// is four times as long.  Their results only steer a bisection and an inverse iteration.
+__device__ __forceinline__ double rcp_nr(double q) {
+  double r = __builtin_amdgcn_rcp(q);
+  r = fma(fma(-q, r, 1.), r, r);
+  r = fma(fma(-q, r, 1.), r, r);
+  return r;
+}
+
 // eigenvalues of the tridiagonal (d, e2 = e^2) below x
 __device__ __forceinline__ int sturm_count(const double* d, const double* e2, int n, double x, double pivmin) {
   double q = d[0] - x;
   if (fabs(q) < pivmin) q = -pivmin;
   int c = q < 0. ? 1 : 0;
   for (int i = 1; i < n; ++i) {
-    q = d[i] - x - e2[i - 1] / q;
+    q = (d[i] - x) - e2[i - 1] * rcp_nr(q);
     if (fabs(q) < pivmin) q = -pivmin;
     c += q < 0. ? 1 : 0;
   }
@@ -1312,7 +1322,7 @@ __global__ __launch_bounds__(kTridThreads) void k_trid(EigJobs jobs) {
   if (s_decline) return;
 
   // ---- (3) inverse iteration, kInvBatch eigenvectors at a time, one thread each ----
-  double* pivA = reinterpret_cast<double*>(T);     // [i][t]: pivots of the elimination
+  double* pivA = reinterpret_cast<double*>(T);     // [i][t]: reciprocal pivots of the elimination
   double* U1 = pivA + n * kInvBatch;               //         first super-diagonal of the upper factor
   double* Y = U1 + n * kInvBatch;                  //         right-hand side after the forward sweep
   double* Zv = Y + n * kInvBatch;                  //         current iterate
@@ -1336,17 +1346,19 @@ __global__ __launch_bounds__(kTridThreads) void k_trid(EigJobs jobs) {
           const double rhs = Zv[(i + 1) * kInvBatch + t];
           if (fabs(a) >= fabs(sub)) {
             if (a == 0.) a = tol;
-            const double f = sub / a;
-            pivA[i * kInvBatch + t] = a;
+            const double ra = rcp_nr(fabs(a) < tol ? (a < 0. ? -tol : tol) : a);
+            const double f = sub * ra;
+            pivA[i * kInvBatch + t] = ra;                              // reciprocal pivots: the back substitution multiplies
             U1[i * kInvBatch + t] = du;
             Y[i * kInvBatch + t] = y;
             a = dn - f * du;
             du = en;
             y = rhs - f * y;
           } else {
-            const double f = a / sub;
+            const double rs = rcp_nr(sub);                             // |sub| > |a| >= 0
+            const double f = a * rs;
             if (i < 64) pv_lo |= 1ull << i; else pv_hi |= 1ull << (i - 64);
-            pivA[i * kInvBatch + t] = sub;
+            pivA[i * kInvBatch + t] = fabs(sub) < tol ? (sub < 0. ? -1. / tol : 1. / tol) : rs;
             U1[i * kInvBatch + t] = dn;
             Y[i * kInvBatch + t] = rhs;
             a = du - f * dn;
@@ -1354,19 +1366,18 @@ __global__ __launch_bounds__(kTridThreads) void k_trid(EigJobs jobs) {
             y = y - f * rhs;
           }
         }
-        if (a == 0.) a = tol;
-        pivA[(n - 1) * kInvBatch + t] = a;
+        if (fabs(a) < tol) a = a < 0. ? -tol : tol;
+        pivA[(n - 1) * kInvBatch + t] = rcp_nr(a);
         Y[(n - 1) * kInvBatch + t] = y;
         // backward substitution; second super-diagonal: e[i + 1] where rows were interchanged
         double z1 = 0., z2 = 0., zmax = 0.;
         for (int i = n - 1; i >= 0; --i) {
-          double p = pivA[i * kInvBatch + t];
-          if (fabs(p) < tol) p = p < 0. ? -tol : tol;
+          const double rp = pivA[i * kInvBatch + t];
           double sacc = Y[i * kInvBatch + t];
           if (i + 1 < n) sacc -= U1[i * kInvBatch + t] * z1;
           const bool swapped = i < 64 ? ((pv_lo >> i) & 1ull) : ((pv_hi >> (i - 64)) & 1ull);
           if (i + 2 < n && swapped) sacc -= se[i + 1] * z2;
-          const double z = sacc / p;
+          const double z = sacc * rp;
           Zv[i * kInvBatch + t] = z;
           zmax = fmax(zmax, fabs(z));
           z2 = z1;
