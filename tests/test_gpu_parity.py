@@ -204,6 +204,7 @@ BF16W_CASES = [
     ((9, 7, 6), (3, 3, 2), 11, "c64"),               # tail of 2 elements after the whole pieces
     ((8, 7, 40), (2, 2, 36), 30, "c64"),             # generic kernels (last-mode rank above 32)
     ((5, 4, 3, 1), (2, 2, 2, 1), 3, "c64"),          # generic kernels (last extent 1)
+    ((128, 40, 32, 17), (8, 6, 32, 12), 4000, "c64"),  # fused + two-mode core kernel, last extent 17 (compile-time stage B)
 ]
 
 
@@ -536,10 +537,12 @@ def test_checkpoint_restore_is_bit_identical():
     assert np.array_equal(T.weight_to_host(Wd2), W_a)
 
 
-def test_checkpoint_restore_fused_tier():
-    """The same on a shape that takes the fused kernels: their factor copies must follow
-    tgrad_set_state (they are rebuilt when a factor is written, not on every step)."""
-    shape, ranks, k = FUSED_SHAPES[1]
+@pytest.mark.parametrize("case", [FUSED_SHAPES[1], CORE2_SHAPES[0][:3]])
+def test_checkpoint_restore_fused_tier(case):
+    """The same on shapes that take the fused kernels (and the two-mode core kernel): their factor
+    copies and operand tables must follow tgrad_set_state (they are rebuilt when a factor is written,
+    not on every step)."""
+    shape, ranks, k = case
     grads = [synth.small_case(shape, 700 + t) for t in range(6)]
     rng = np.random.default_rng(9)
     W0 = ((rng.standard_normal(shape) + 1j * rng.standard_normal(shape)) * 0.02).astype(np.complex64)
