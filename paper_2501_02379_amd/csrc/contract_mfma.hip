@@ -423,7 +423,8 @@ __global__ __launch_bounds__(kMidThreads) void k_core(const float* x, const floa
 //   g_L[m0, m1, c] = sum_{i0, i1} conj(U0[i0, m0]) conj(U1[i1, m1]) y[i0, i1, c]   last two compression stages
 //   N_L            = AdamUpdate(g_L)                (appendix algorithm "Adam with low-rank tensor decomposition")
 //   z[i0, i1, c]   = sum_{m0, m1} U0[i0, m0] U1[i1, m1] N_L[m0, m1, c]             first two reconstruction stages
-// on its own, so a workgroup that owns two neighbouring columns (16 bytes per (i0, i1)) runs the whole
+// on its own, so a workgroup that owns VEC = 2 neighbouring columns (16 bytes per (i0, i1); VEC = 1, 8 bytes,
+// where two per workgroup would leave most of the chip without work) runs the whole
 // chain between workgroup barriers: nothing travels through memory between the five steps and the
 // launches, prologues and tails of three kernels become one.  Wavefront w owns the rows
 // i0 = 32 w .. 32 w + 31.  The accumulator layout of one stage is the operand layout of the next
@@ -432,23 +433,24 @@ __global__ __launch_bounds__(kMidThreads) void k_core(const float* x, const floa
 //   1  T[i0, m1]   = sum_i1 y[i0, i1] conj(U1[i1, m1])   data = A operand (lane = i0), U1 from LDS;  D: i0 in registers, m1 in lanes
 //   2  P[m0, m1]   = sum_i0 conj(U0[i0, m0]) T[i0, m1]   U0 = A operand, T = B operand straight from the accumulators;
 //                                                        the four wavefronts' partial sums meet in LDS, fixed order
-//   -  AdamUpdate on the 32 x 32 x 2 core entries of the two columns, N_L back into LDS in accumulator layout
+//   -  AdamUpdate on the 32 x 32 x VEC core entries of the workgroup's columns, N_L back into LDS in accumulator layout
 //   3  R[m1, i0]   = sum_m0 N_L[m0, m1] U0[i0, m0]       N_L = A operand (LDS), U0 = B operand;  D: m1 in registers, i0 in lanes
 //   4  z[i0, i1]   = sum_m1 R[m1, i0] U1[i1, m1]         R = A operand straight from the accumulators, U1 from LDS;
 //                                                        D: i0 in registers, i1 in lanes
 // The factor operands of all four stages come from a table in operand order that is built once per
 // refresh (k_pack_core2): the prologue is a straight copy with every load in flight at once.
-// The result is written one column pair at a time, z[pair][i0][i1] in 16-byte units, because in
-// stage 4 neighbouring lanes hold neighbouring i1: the stores of a wavefront are then 512 contiguous
-// bytes instead of 64 pieces of 16 bytes each in a cache line of its own (the fused update reads its
+// The result is written one column group at a time, z[group][i0][i1] in units of VEC complex, because in
+// stage 4 neighbouring lanes hold neighbouring i1: the stores of a wavefront are then 512 (256)
+// contiguous bytes instead of 64 pieces each in a cache line of its own (the fused update reads its
 // operand rows through strides, see FusedPrev).  Workgroups that share cache lines of y (8 column
 // pairs per 128 bytes) get consecutive blockIdx / 8, i.e. the same XCD under round-robin dispatch.
 struct Core2Args {
   const float* y;       // (128, I1, Cc) complex
-  float* z;             // (Cc / 2, 128, I1) units of two complex, not the same buffer
+  float* z;             // (Cc / G, 128, I1) units of G complex, not the same buffer; G = `zgroup` (2: Cc even)
   const float2* tab;    // core2_table_elems(I1) operands from k_pack_core2
   int I1, M0, M1;
-  int64_t Cc;           // even
+  int64_t Cc;           // a multiple of VEC
+  int zgroup;           // columns per unit of z: VEC, or 2 with VEC = 1 (two workgroups then fill a unit)
 };
 constexpr int kCore2Rows = 128;              // extent of the first mode: 4 wavefronts x 32 rows
 constexpr int kCore2Batch = 8;               // row pairs of y per lane in flight (twice that while a batch is computed)
@@ -483,12 +485,15 @@ __global__ void k_pack_core2(const float2* __restrict__ U0, int rn0, int M0, con
   tab[e] = u;
 }
 
+template <int VEC>
 __global__ __launch_bounds__(kMidThreads) void k_core2(Core2Args a, CoreAdam ad) {
+  typedef typename VecT<VEC>::type V;             // the workgroup's VEC columns of one (i0, i1): 8 or 16 bytes
+  constexpr int NT = 2 * VEC;                     // accumulator tiles: (column, re / im)
   extern __shared__ float2 sF[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int col = lane & 31, half = lane >> 5;
-  const int planes = (int)(a.Cc >> 1);
+  const int planes = (int)(a.Cc / VEC);
   const int b = (int)blockIdx.x;
   const int plane = (planes & 7) == 0 ? (b & 7) * (planes >> 3) + (b >> 3) : b;
   const int I1 = a.I1, M0 = a.M0, M1 = a.M1;
@@ -502,13 +507,20 @@ __global__ __launch_bounds__(kMidThreads) void k_core2(Core2Args a, CoreAdam ad)
   float2* sT4 = sF + 8192;
 
   // the first rows of y go in flight, then the stage-1 operands
-  const float* xp = a.y + (int64_t)(32 * wave + col) * slab + 4 * plane;
-  auto load_pair_row = [&](int j) -> float4 {
+  const float* xp = a.y + (int64_t)(32 * wave + col) * slab + NT * plane;
+  auto load_pair_row = [&](int j) -> V {
     const int jc = j < J1 ? j : J1 - 1;
     const int k = 2 * jc + half;
-    return *reinterpret_cast<const float4*>(xp + (int64_t)(k < I1 ? k : I1 - 1) * row);
+    return *reinterpret_cast<const V*>(xp + (int64_t)(k < I1 ? k : I1 - 1) * row);
   };
-  float4 cur[kCore2Batch];
+  auto parts = [](const V& v, float* x) {        // x[2 c] = re, x[2 c + 1] = im of column c
+    if constexpr (VEC == 1) {
+      x[0] = v.x; x[1] = v.y;
+    } else {
+      x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
+    }
+  };
+  V cur[kCore2Batch];
 #pragma unroll
   for (int u = 0; u < kCore2Batch; ++u) cur[u] = load_pair_row(u);
   {
@@ -531,7 +543,7 @@ __global__ __launch_bounds__(kMidThreads) void k_core2(Core2Args a, CoreAdam ad)
   __syncthreads();
   // What the later stages need travels while stage 1 runs: U0 as the operands of stages 2 and 3
   // (registers) and the moments of this thread's core entries: rows d_row(4 wave + q, half), column col,
-  // both columns of the pair.  (The stage-4 operands travel during stage 2.)
+  // the workgroup's VEC columns.  (The stage-4 operands travel during stage 2.)
   float2 f2[16], f3[16];
   {
     const float2* t2 = a.tab + J1 * 64 + NT1 * 1024 + wave * 1024 + lane;
@@ -541,39 +553,45 @@ __global__ __launch_bounds__(kMidThreads) void k_core2(Core2Args a, CoreAdam ad)
       f3[r] = t2[4096 + r * 64];
     }
   }
-  float4 mm[4];
-  float2 vv[4];
+  float2 mm[4][VEC];
+  float vv[4][VEC];
   int64_t cidx[4];
   bool live[4];
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
     const int m0 = d_row(4 * wave + q, half);
     live[q] = m0 < M0 && col < M1;
-    cidx[q] = live[q] ? ((int64_t)m0 * M1 + col) * a.Cc + 2 * plane : 0;
-    mm[q] = *reinterpret_cast<const float4*>(ad.m + cidx[q]);
-    vv[q] = *reinterpret_cast<const float2*>(ad.v + cidx[q]);
+    cidx[q] = live[q] ? ((int64_t)m0 * M1 + col) * a.Cc + VEC * plane : 0;
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) {
+      mm[q][c] = ad.m[cidx[q] + c];
+      vv[q][c] = ad.v[cidx[q] + c];
+    }
   }
 
-  // ---- stage 1: T = y conj(U1); tiles (column of the pair, re / im) ----
-  v16f t0r, t0i, t1r, t1i;
+  // ---- stage 1: T = y conj(U1); tiles (column, re / im) ----
+  v16f t[NT];
 #pragma unroll
-  for (int r = 0; r < 16; ++r) t0r[r] = t0i[r] = t1r[r] = t1i[r] = 0.f;
-  auto stage1 = [&](const float4& v, int j) {
+  for (int i = 0; i < NT; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) t[i][r] = 0.f;
+  auto stage1 = [&](const V& v, int j) {
     const float2 f = sT1[j * 64 + lane];
     const float nfy = -f.y;
-    t0r = mfma32(v.x, f.x, t0r);             // re: yr ur + yi ui;  im: yi ur - yr ui
-    t0i = mfma32(v.y, f.x, t0i);
-    t1r = mfma32(v.z, f.x, t1r);
-    t1i = mfma32(v.w, f.x, t1i);
-    t0r = mfma32(v.y, f.y, t0r);
-    t0i = mfma32(v.x, nfy, t0i);
-    t1r = mfma32(v.w, f.y, t1r);
-    t1i = mfma32(v.z, nfy, t1i);
+    float x[NT];
+    parts(v, x);
+#pragma unroll
+    for (int i = 0; i < NT; ++i) t[i] = mfma32(x[i], f.x, t[i]);      // re: yr ur + yi ui;  im: yi ur - yr ui
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) {
+      t[2 * c] = mfma32(x[2 * c + 1], f.y, t[2 * c]);
+      t[2 * c + 1] = mfma32(x[2 * c], nfy, t[2 * c + 1]);
+    }
   };
   {
     int j = 0;
     for (; j + kCore2Batch <= J1; j += kCore2Batch) {
-      float4 nxt[kCore2Batch];
+      V nxt[kCore2Batch];
 #pragma unroll
       for (int u = 0; u < kCore2Batch; ++u) nxt[u] = load_pair_row(j + kCore2Batch + u);
       __builtin_amdgcn_sched_barrier(0);                       // the loads stay in front of the batch they overlap
@@ -598,21 +616,22 @@ __global__ __launch_bounds__(kMidThreads) void k_core2(Core2Args a, CoreAdam ad)
       p4[u] = t4[e < n4 ? e : 0];
     }
   }
-  v16f p0r, p0i, p1r, p1i;
+  v16f p[NT];
 #pragma unroll
-  for (int r = 0; r < 16; ++r) p0r[r] = p0i[r] = p1r[r] = p1i[r] = 0.f;
+  for (int i = 0; i < NT; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) p[i][r] = 0.f;
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
     const float2 f = f2[r];
     const float nfy = -f.y;
-    p0r = mfma32(f.x, t0r[r], p0r);          // re: ur tr + ui ti;  im: ur ti - ui tr
-    p0i = mfma32(f.x, t0i[r], p0i);
-    p1r = mfma32(f.x, t1r[r], p1r);
-    p1i = mfma32(f.x, t1i[r], p1i);
-    p0r = mfma32(f.y, t0i[r], p0r);
-    p0i = mfma32(nfy, t0r[r], p0i);
-    p1r = mfma32(f.y, t1i[r], p1r);
-    p1i = mfma32(nfy, t1r[r], p1i);
+#pragma unroll
+    for (int i = 0; i < NT; ++i) p[i] = mfma32(f.x, t[i][r], p[i]);    // re: ur tr + ui ti;  im: ur ti - ui tr
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) {
+      p[2 * c] = mfma32(f.y, t[2 * c + 1][r], p[2 * c]);
+      p[2 * c + 1] = mfma32(nfy, t[2 * c][r], p[2 * c + 1]);
+    }
   }
   {
     float4* d4 = reinterpret_cast<float4*>(sT4);
@@ -624,97 +643,104 @@ __global__ __launch_bounds__(kMidThreads) void k_core2(Core2Args a, CoreAdam ad)
   }
   __syncthreads();                                             // every wavefront is through with the stage-1 operands
 #pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    red[((wave * 4 + 0) * 16 + r) * 64 + lane] = p0r[r];
-    red[((wave * 4 + 1) * 16 + r) * 64 + lane] = p0i[r];
-    red[((wave * 4 + 2) * 16 + r) * 64 + lane] = p1r[r];
-    red[((wave * 4 + 3) * 16 + r) * 64 + lane] = p1i[r];
-  }
+  for (int i = 0; i < NT; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) red[((wave * NT + i) * 16 + r) * 64 + lane] = p[i][r];
   __syncthreads();
   // ---- AdamUpdate: wavefront w takes registers 4 w .. 4 w + 3 of the tile, partial sums added in wavefront order ----
-  float nn[4][4];
+  float nn[4][NT];
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
     const int r = 4 * wave + q;
-    float g[4];
+    float g[NT];
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      g[t] = 0.f;
+    for (int i = 0; i < NT; ++i) {
+      g[i] = 0.f;
 #pragma unroll
-      for (int w = 0; w < 4; ++w) g[t] += red[((w * 4 + t) * 16 + r) * 64 + lane];
+      for (int w = 0; w < 4; ++w) g[i] += red[((w * NT + i) * 16 + r) * 64 + lane];
     }
-    float4 m = mm[q];
-    float2 v = vv[q];
-    m.x = ad.beta1 * m.x + (1.f - ad.beta1) * g[0];
-    m.y = ad.beta1 * m.y + (1.f - ad.beta1) * g[1];
-    m.z = ad.beta1 * m.z + (1.f - ad.beta1) * g[2];
-    m.w = ad.beta1 * m.w + (1.f - ad.beta1) * g[3];
-    v.x = ad.beta2 * v.x + (1.f - ad.beta2) * (g[0] * g[0] + g[1] * g[1]);
-    v.y = ad.beta2 * v.y + (1.f - ad.beta2) * (g[2] * g[2] + g[3] * g[3]);
-    const float d0 = 1.f / (sqrtf(v.x * ad.inv_c2) + ad.eps);
-    const float d1 = 1.f / (sqrtf(v.y * ad.inv_c2) + ad.eps);
-    nn[q][0] = nn[q][1] = nn[q][2] = nn[q][3] = 0.f;
-    if (live[q]) {
-      *reinterpret_cast<float4*>(ad.m + cidx[q]) = m;
-      *reinterpret_cast<float2*>(ad.v + cidx[q]) = v;
-      *reinterpret_cast<float4*>(ad.g_out + cidx[q]) = make_float4(g[0], g[1], g[2], g[3]);
-      nn[q][0] = m.x * ad.inv_c1 * d0;
-      nn[q][1] = m.y * ad.inv_c1 * d0;
-      nn[q][2] = m.z * ad.inv_c1 * d1;
-      nn[q][3] = m.w * ad.inv_c1 * d1;
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) {
+      float2 m = mm[q][c];
+      m.x = ad.beta1 * m.x + (1.f - ad.beta1) * g[2 * c];
+      m.y = ad.beta1 * m.y + (1.f - ad.beta1) * g[2 * c + 1];
+      const float v = ad.beta2 * vv[q][c] + (1.f - ad.beta2) * (g[2 * c] * g[2 * c] + g[2 * c + 1] * g[2 * c + 1]);
+      const float d = 1.f / (sqrtf(v * ad.inv_c2) + ad.eps);
+      nn[q][2 * c] = nn[q][2 * c + 1] = 0.f;
+      if (live[q]) {
+        ad.m[cidx[q] + c] = m;
+        ad.v[cidx[q] + c] = v;
+        ad.g_out[cidx[q] + c] = make_float2(g[2 * c], g[2 * c + 1]);
+        nn[q][2 * c] = m.x * ad.inv_c1 * d;
+        nn[q][2 * c + 1] = m.y * ad.inv_c1 * d;
+      }
     }
   }
   __syncthreads();                                             // every partial sum has been read
 #pragma unroll
   for (int q = 0; q < 4; ++q)
 #pragma unroll
-    for (int t = 0; t < 4; ++t) red[(t * 16 + 4 * wave + q) * 64 + lane] = nn[q][t];
+    for (int i = 0; i < NT; ++i) red[(i * 16 + 4 * wave + q) * 64 + lane] = nn[q][i];
   __syncthreads();
   // ---- stage 3: R = N_L^T U0^T for this wavefront's 32 rows i0 ----
-  v16f r0r, r0i, r1r, r1i;
+  v16f rr[NT];
 #pragma unroll
-  for (int r = 0; r < 16; ++r) r0r[r] = r0i[r] = r1r[r] = r1i[r] = 0.f;
+  for (int i = 0; i < NT; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) rr[i][r] = 0.f;
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
     const float2 f = f3[r];
     const float nfy = -f.y;
-    const float n0r = red[(0 * 16 + r) * 64 + lane], n0i = red[(1 * 16 + r) * 64 + lane];
-    const float n1r = red[(2 * 16 + r) * 64 + lane], n1i = red[(3 * 16 + r) * 64 + lane];
-    r0r = mfma32(n0r, f.x, r0r);             // re: nr ur - ni ui;  im: ni ur + nr ui
-    r0i = mfma32(n0i, f.x, r0i);
-    r1r = mfma32(n1r, f.x, r1r);
-    r1i = mfma32(n1i, f.x, r1i);
-    r0r = mfma32(n0i, nfy, r0r);
-    r0i = mfma32(n0r, f.y, r0i);
-    r1r = mfma32(n1i, nfy, r1r);
-    r1i = mfma32(n1r, f.y, r1i);
-  }
-  // ---- stage 4: z = R^T U1^T, one tile of 32 columns i1 at a time; z[plane][i0][i1], 4 floats each ----
-  float* zp = a.z + (((int64_t)plane * kCore2Rows + 32 * wave + 4 * half) * I1 + col) * 4;
-  for (int tile = 0; tile < NT1; ++tile) {
-    v16f z0r, z0i, z1r, z1i;
+    float n[NT];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) z0r[r] = z0i[r] = z1r[r] = z1i[r] = 0.f;
+    for (int i = 0; i < NT; ++i) n[i] = red[(i * 16 + r) * 64 + lane];
+#pragma unroll
+    for (int i = 0; i < NT; ++i) rr[i] = mfma32(n[i], f.x, rr[i]);     // re: nr ur - ni ui;  im: ni ur + nr ui
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) {
+      rr[2 * c] = mfma32(n[2 * c + 1], nfy, rr[2 * c]);
+      rr[2 * c + 1] = mfma32(n[2 * c], f.y, rr[2 * c + 1]);
+    }
+  }
+  // ---- stage 4: z = R^T U1^T, one tile of 32 columns i1 at a time; z[group][i0][i1], units of zgroup complex ----
+  const int ZU = 2 * a.zgroup;                                 // floats per unit
+  const int zg = VEC == 1 && a.zgroup == 2 ? plane >> 1 : plane;
+  float* zp = a.z + (((int64_t)zg * kCore2Rows + 32 * wave + 4 * half) * I1 + col) * ZU +
+              (VEC == 1 && a.zgroup == 2 ? 2 * (plane & 1) : 0);
+  for (int tile = 0; tile < NT1; ++tile) {
+    v16f z[NT];
+#pragma unroll
+    for (int i = 0; i < NT; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) z[i][r] = 0.f;
     const float2* ft = sT4 + tile * 16 * 64 + lane;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const float2 f = ft[r * 64];
       const float nfy = -f.y;
-      z0r = mfma32(r0r[r], f.x, z0r);        // re: rr ur - ri ui;  im: rr ui + ri ur
-      z0i = mfma32(r0r[r], f.y, z0i);
-      z1r = mfma32(r1r[r], f.x, z1r);
-      z1i = mfma32(r1r[r], f.y, z1i);
-      z0r = mfma32(r0i[r], nfy, z0r);
-      z0i = mfma32(r0i[r], f.x, z0i);
-      z1r = mfma32(r1i[r], nfy, z1r);
-      z1i = mfma32(r1i[r], f.x, z1i);
+#pragma unroll
+      for (int c = 0; c < VEC; ++c) {                          // re: rr ur - ri ui;  im: rr ui + ri ur
+        z[2 * c] = mfma32(rr[2 * c][r], f.x, z[2 * c]);
+        z[2 * c + 1] = mfma32(rr[2 * c][r], f.y, z[2 * c + 1]);
+      }
+#pragma unroll
+      for (int c = 0; c < VEC; ++c) {
+        z[2 * c] = mfma32(rr[2 * c + 1][r], nfy, z[2 * c]);
+        z[2 * c + 1] = mfma32(rr[2 * c + 1][r], f.x, z[2 * c + 1]);
+      }
     }
     if (32 * tile + col < I1) {
-      float* zt = zp + 32 * tile * 4;
+      float* zt = zp + 32 * tile * ZU;
 #pragma unroll
-      for (int r = 0; r < 16; ++r)
-        *reinterpret_cast<float4*>(zt + (int64_t)((r & 3) + 8 * (r >> 2)) * I1 * 4) =
-            make_float4(z0r[r], z0i[r], z1r[r], z1i[r]);
+      for (int r = 0; r < 16; ++r) {
+        float* o = zt + (int64_t)((r & 3) + 8 * (r >> 2)) * I1 * ZU;
+        if constexpr (VEC == 1) {
+          *reinterpret_cast<float2*>(o) = make_float2(z[0][r], z[1][r]);
+        } else {
+          *reinterpret_cast<float4*>(o) = make_float4(z[0][r], z[1][r], z[2][r], z[3][r]);
+        }
+      }
     }
   }
 }
@@ -1729,11 +1755,13 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate(const float* __restrict__
 //             table is read at those rows.  Everything after that is k_lupdate.
 struct FusedPrev {
   const float2* y1;     // input of the fused stage: element (slab, m2, m3) of the (slabs, K2, K) complex tensor lies at
-                        // y1[slab * s_slab + m2 * s_m2 + (m3 / 2) * s_pair + (m3 & 1)]
+                        // y1[slab * s_slab + m2 * s_m2 + (m3 / 2) * s_pair + (m3 & 1) * s_odd]
   const float2* ut;     // U^(N-1)[i2, m2], zero for m2 >= K2, in operand order (k_pack_fused_factor)
   int S;                // tiles per slab
   int K2;               // rank of mode N-1
-  int64_t s_slab, s_m2, s_pair;   // row-major: K2 K, K, 2; one column pair at a time (k_core2): 2, (K / 2) slabs 2, slabs 2
+  int64_t s_slab, s_m2, s_pair, s_odd;   // row-major: K2 K, K, 2, 1; one column pair at a time (k_core2<2>):
+                                         // 2, (K / 2) slabs 2, slabs 2, 1; one column at a time (k_core2<1>):
+                                         // 1, K slabs, 2 slabs, slabs
 };
 
 template <int WDT, int W, int MS, int JT2, int UP>
@@ -1854,7 +1882,7 @@ __global__ __launch_bounds__(64 * W, 2) void k_lupdate_fused(const float2* __res
   auto fetch_y1 = [&](int64_t sl, int ln) {
     const int c2 = ln & 31, h2 = ln >> 5;
     const int m3 = (c2 >> 1) < K ? (c2 >> 1) : K - 1;
-    const float2* yp = fz.y1 + sl * fz.s_slab + (int64_t)(m3 >> 1) * fz.s_pair + (m3 & 1);
+    const float2* yp = fz.y1 + sl * fz.s_slab + (int64_t)(m3 >> 1) * fz.s_pair + (int64_t)(m3 & 1) * fz.s_odd;
 #pragma unroll
     for (int jj = 0; jj < JT2; ++jj) {
       const int m2 = 2 * jj + h2;
@@ -2249,13 +2277,20 @@ void launch_core(hipStream_t s, const float2* x, const float2* U, int rn, int K,
 }
 
 // Limits of k_core2: first extent 128 (one 32-row tile per wavefront), ranks within one tile, the second
-// extent within four tiles, an even rank of the last mode (a column pair then lies inside one row of the
-// mode before it), and enough column pairs (one workgroup each) to occupy three quarters of the chip:
-// below that the three separate kernels, which spread over it, are faster.
-bool core2_kernel_fits(int I0, int I1, int M0, int M1, int K2, int K) {
+// extent within four tiles, and enough column groups (one workgroup each) to occupy the chip: pairs of
+// columns if there are at least 3/4 as many pairs as compute units (the rank of the last mode must then
+// be even: a pair lies inside one row of the mode before it), else single columns if there are at least
+// 3/8 as many columns as compute units.  Below that the three separate kernels, which spread over the
+// chip, are faster.  Returns the columns per workgroup (2 or 1), or 0.
+int core2_kernel_vec(int I0, int I1, int M0, int M1, int K2, int K) {
   const int64_t Cc = (int64_t)K2 * K;
-  return I0 == kCore2Rows && I1 >= 1 && I1 <= 128 && M0 >= 1 && M0 <= 32 && M1 >= 1 && M1 <= 32 && K % 2 == 0 &&
-         Cc / 2 >= (int64_t)compute_units() * 3 / 4 && (int64_t)I0 * I1 * Cc < ((int64_t)1 << 28);
+  if (!(I0 == kCore2Rows && I1 >= 1 && I1 <= 128 && M0 >= 1 && M0 <= 32 && M1 >= 1 && M1 <= 32 &&
+        (int64_t)I0 * I1 * Cc < ((int64_t)1 << 28)))
+    return 0;
+  const int64_t cus = compute_units();
+  if (K % 2 == 0 && Cc / 2 >= cus * 3 / 4) return 2;
+  if (Cc >= cus * 3 / 8) return 1;
+  return 0;
 }
 
 size_t core2_table_bytes(int I1) { return (size_t)core2_table_elems(I1) * 8; }
@@ -2268,16 +2303,22 @@ void launch_pack_core2(hipStream_t s, const float2* U0, int rn0, int M0, const f
 }
 
 // The two leading modes compressed, AdamUpdate on the core, the two leading modes reconstructed:
-// x (128, I1, Cc) -> z (Cc / 2, 128, I1) units of two complex, the core (M0, M1, Cc) in between.
-void launch_core2(hipStream_t s, const float2* x, const float2* tab, int I1, int M0, int M1, int64_t Cc, float2* m,
-                  float* v, float2* g_out, float beta1, float beta2, float inv_c1, float inv_c2, float eps,
-                  float2* z) {
+// x (128, I1, Cc) -> z (Cc / zgroup, 128, I1) units of zgroup complex (zgroup = vec, or 2 with vec = 1 and Cc
+// even), the core (M0, M1, Cc) in between.
+void launch_core2(hipStream_t s, int vec, int zgroup, const float2* x, const float2* tab, int I1, int M0, int M1, int64_t Cc,
+                  float2* m, float* v, float2* g_out, float beta1, float beta2, float inv_c1, float inv_c2,
+                  float eps, float2* z) {
   const int NT1 = (I1 + 31) / 32;
   const size_t lds = (size_t)64 * 1024 + (size_t)NT1 * 16 * 64 * 8;
-  Core2Args a{reinterpret_cast<const float*>(x), reinterpret_cast<float*>(z), tab, I1, M0, M1, Cc};
+  Core2Args a{reinterpret_cast<const float*>(x), reinterpret_cast<float*>(z), tab, I1, M0, M1, Cc, zgroup};
   CoreAdam ad{m, v, g_out, beta1, beta2, inv_c1, inv_c2, eps};
-  allow_lds(k_core2, lds);
-  k_core2<<<dim3((unsigned)(Cc / 2)), dim3(kMidThreads), lds, s>>>(a, ad);
+  if (vec == 2) {
+    allow_lds(k_core2<2>, lds);
+    k_core2<2><<<dim3((unsigned)(Cc / 2)), dim3(kMidThreads), lds, s>>>(a, ad);
+  } else {
+    allow_lds(k_core2<1>, lds);
+    k_core2<1><<<dim3((unsigned)Cc), dim3(kMidThreads), lds, s>>>(a, ad);
+  }
 }
 
 void launch_pack_fused_factor(hipStream_t s, const float2* U, int I2, int r, float2* fpad, float2* ut) {
@@ -2416,13 +2457,14 @@ void launch_lupdate(hipStream_t s, const float2* z, const float2* U, const Stage
 }
 
 // k_lupdate with the reconstruction stage of mode N-1 in front (see k_lupdate_fused): `y1` is the
-// tensor before that stage, (slabs, K2, K) complex - or, with `pair_major` (K even), the same tensor
-// as (K2 K / 2, slabs) units of two neighbouring complex numbers; `ut` the transposed factor copy; I2 = 32 S.
+// tensor before that stage, (slabs, K2, K) complex (`group` = 0) - or the same tensor one column group at
+// a time: (K2 K / group, slabs) units of `group` = 1 or 2 neighbouring complex numbers (2: K even);
+// `ut` the transposed factor copy; I2 = 32 S.
 void launch_lupdate_fused(hipStream_t s, const float2* y1, const float2* ut, int I2, int K2, const float2* U,
                           const Stage& st, void* w, int wdtype, float decay, float c_alpha, const int32_t* omega,
                           const uint32_t* tile_start, int64_t k, const float2* gs, float2* ms, float* vs,
                           float beta1, float beta2, float inv_c1, float inv_c2, float eps, float c_lambda,
-                          bool pair_major) {
+                          int group) {
   const int64_t A = st.A;
   const int K = st.K, M = st.M;
   if (A * M <= 0) return;
@@ -2436,11 +2478,16 @@ void launch_lupdate_fused(hipStream_t s, const float2* y1, const float2* ut, int
   dim3 grid(1), block(64 * W);
   SparseAdam sp{omega, tile_start, gs, ms, vs, beta1, beta2, inv_c1, inv_c2, eps, c_lambda,
                 (int)(k > 0 ? k - 1 : 0)};
-  FusedPrev fz{y1, ut, S, K2, (int64_t)K2 * K, (int64_t)K, 2};
-  if (pair_major) {                              // (K2 K / 2, slabs) units of two complex: what k_core2 writes
+  FusedPrev fz{y1, ut, S, K2, (int64_t)K2 * K, (int64_t)K, 2, 1};
+  if (group == 2) {                              // (K2 K / 2, slabs) units of two complex: what k_core2<2> writes
     fz.s_slab = 2;
     fz.s_pair = nslabs * 2;
     fz.s_m2 = (int64_t)(K / 2) * nslabs * 2;
+  } else if (group == 1) {                       // (K2 K, slabs) complex: what k_core2<1> writes
+    fz.s_slab = 1;
+    fz.s_odd = nslabs;
+    fz.s_pair = nslabs * 2;
+    fz.s_m2 = (int64_t)K * nslabs;
   }
   const int up = (M + 3) / 4 <= 5 ? 5 : (M + 3) / 4 <= 9 ? 9 : kUpdPrefetch;
 #define TGRAD_LUF_M(JT2_, UP_, MS_)                                                                      \

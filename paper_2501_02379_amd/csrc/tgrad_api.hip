@@ -48,7 +48,9 @@ struct Plan {
   int64_t tile_elems = 0;
   bool fuse_next = false;        // the last-mode kernels also handle mode N-1 (see make_plan)
   bool fuse_core = false;        // last compression stage + AdamUpdate + first reconstruction stage in one kernel
-  bool fuse_core2 = false;       // both leading modes, both ways, and AdamUpdate in one kernel (N = 4, see k_core2)
+  int fuse_core2 = 0;            // both leading modes, both ways, and AdamUpdate in one kernel (N = 4, see k_core2):
+                                 // columns per workgroup (2 or 1), 0 = not used
+  int core2_zgroup = 0;          // columns per unit of its result tensor (2 whenever the last rank is even)
   // byte offsets into state
   size_t st_omega, st_ms, st_vs, st_ml, st_vl, st_U[kMaxNdim], state_bytes;
   // byte offsets into workspace
@@ -183,8 +185,10 @@ void make_plan(const tgrad_config* c, Plan* p) {
     }
     p->fuse_next = fuse;
     p->fuse_core = core_kernel_fits((int)p->shape[0], p->rank[0]);
-    p->fuse_core2 = fuse && N == 4 &&
-                    core2_kernel_fits((int)p->shape[0], (int)p->shape[1], p->rank[0], p->rank[1], p->rank[2], p->rank[3]);
+    p->fuse_core2 = fuse && N == 4 ? core2_kernel_vec((int)p->shape[0], (int)p->shape[1], p->rank[0], p->rank[1],
+                                                      p->rank[2], p->rank[3])
+                                   : 0;
+    p->core2_zgroup = p->fuse_core2 == 0 ? 0 : (p->rank[N - 1] % 2 == 0 ? 2 : 1);
   }
 
   size_t o = 0;
@@ -638,7 +642,7 @@ int do_step(tgrad_ctx* c, void* weight, const void* g) {
   if (p.fuse_core2) {
     // the last two compression stages, AdamUpdate on the core and the first two reconstruction stages
     Scope sc_(c, KID_CORE);
-    launch_core2(s, src, c->w<float2>(p.ws_core2), (int)p.shape[1], p.rank[0], p.rank[1],
+    launch_core2(s, p.fuse_core2, p.core2_zgroup, src, c->w<float2>(p.ws_core2), (int)p.shape[1], p.rank[0], p.rank[1],
                  (int64_t)p.rank[2] * p.rank[3], c->st<float2>(p.st_ml), c->st<float>(p.st_vl), core_g, cf.beta1,
                  cf.beta2, inv_c1, inv_c2, cf.eps, buf[0]);
     zsrc = buf[0];
@@ -685,7 +689,7 @@ int do_step(tgrad_ctx* c, void* weight, const void* g) {
       launch_lupdate_fused(s, zsrc, c->w<float2>(p.ws_ut), (int)p.shape[N - 2], p.rank[N - 2], U, sg,
                            weight, cf.weight_dtype, decay, -cf.lr * cf.alpha, omega, tile_start, p.k, gs,
                            c->st<float2>(p.st_ms), c->st<float>(p.st_vs), cf.beta1, cf.beta2, inv_c1, inv_c2,
-                           cf.eps, -cf.lr * cf.lambda, p.fuse_core2);
+                           cf.eps, -cf.lr * cf.lambda, p.core2_zgroup);
     } else if (mfma_last) {
       Scope sc_(c, KID_UPDATE);
       launch_lupdate(s, zsrc, U, sg, p.tile_waves, weight, cf.weight_dtype, decay, -cf.lr * cf.alpha,

@@ -108,13 +108,13 @@ bool core_kernel_fits(int K, int M);
 void launch_core(hipStream_t s, const float2* x, const float2* U, int rn, int K, int M, int64_t B, float2* m,
                  float* v, float2* g_out, float beta1, float beta2, float inv_c1, float inv_c2, float eps,
                  float2* z);
-bool core2_kernel_fits(int I0, int I1, int M0, int M1, int K2, int K);
+int core2_kernel_vec(int I0, int I1, int M0, int M1, int K2, int K);   // columns per workgroup (2, 1) or 0
 size_t core2_table_bytes(int I1);
 void launch_pack_core2(hipStream_t s, const float2* U0, int rn0, int M0, const float2* U1, int rn1, int M1, int I1,
                        float2* tab);
-void launch_core2(hipStream_t s, const float2* x, const float2* tab, int I1, int M0, int M1, int64_t Cc, float2* m,
-                  float* v, float2* g_out, float beta1, float beta2, float inv_c1, float inv_c2, float eps,
-                  float2* z);
+void launch_core2(hipStream_t s, int vec, int zgroup, const float2* x, const float2* tab, int I1, int M0, int M1, int64_t Cc,
+                  float2* m, float* v, float2* g_out, float beta1, float beta2, float inv_c1, float inv_c2,
+                  float eps, float2* z);
 void launch_pack_fused_factor(hipStream_t s, const float2* U, int I2, int r, float2* fpad, float2* ut);
 void launch_lproj(hipStream_t s, const void* g, int dtype, const int32_t* omega, const uint32_t* tile_start,
                   float2* gs, const float2* U, int rn, const Stage& st, int W, float2* out, int fused_I2,
@@ -128,6 +128,6 @@ void launch_lupdate_fused(hipStream_t s, const float2* y1, const float2* ut, int
                           const Stage& st, void* w, int wdtype, float decay, float c_alpha, const int32_t* omega,
                           const uint32_t* tile_start, int64_t k, const float2* gs, float2* ms, float* vs,
                           float beta1, float beta2, float inv_c1, float inv_c2, float eps, float c_lambda,
-                          bool pair_major);
+                          int group);
 
 }  // namespace tgrad

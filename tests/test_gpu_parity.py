@@ -165,14 +165,16 @@ CORE2_SHAPES = [
     ((128, 40, 32, 13), (8, 6, 32, 12), 4000, "us_lr"),      # second extent: one full tile + a ragged one
     ((128, 41, 32, 13), (32, 32, 32, 12), 4000, "us_lr"),    # odd second extent, full ranks in the two leading modes
     ((128, 128, 32, 13), (32, 32, 32, 12), 30000, "lr_us"),  # the headline's leading modes, low rank first
+    ((128, 40, 32, 9), (8, 6, 16, 6), 2000, "us_lr"),        # 96 columns: one column per workgroup
+    ((128, 33, 32, 9), (8, 6, 20, 5), 2000, "sum"),          # one column per workgroup, odd rank of the last mode
 ]
 
 
 @pytest.mark.parametrize("shape,ranks,k,order", CORE2_SHAPES)
 def test_two_mode_core_kernel_tier(shape, ranks, k, order):
-    """Four-way tensors with a first extent of 128 and at least 192 column pairs behind the two leading
-    modes: both leading modes (both ways) and AdamUpdate on the core run as ONE launch between the
-    fused first projection and the fused update."""
+    """Four-way tensors with a first extent of 128 and at least 192 column pairs (or, failing that, 96
+    columns) behind the two leading modes: both leading modes (both ways) and AdamUpdate on the core
+    run as ONE launch between the fused first projection and the fused update."""
     _announce("two-mode core kernel", shape, ranks, k)
     grads = [synth.small_case(shape, 900 + t, outlier_frac=(1, 200)) for t in range(5)]
     rng = np.random.default_rng(8)
