@@ -302,6 +302,23 @@ def main():
             d["launches"] += v["launches"]
     times.update(rtimes)          # refresh kernels: the explicit refresh (step kernels never run in it)
 
+    # ---- what the matrix cores deliver with nothing in the way, on this machine, in this run: the library's
+    # register-resident loops of the float32 (projections) and float64 (Gram) matrix instructions (after
+    # everything that is timed: the float64 loop draws enough power to lower the clocks for a while)
+    sink = torch.zeros(4, dtype=torch.float32, device=dev)
+    mfma_tf = {}
+    for kind, key in ((0, "fp32"), (1, "fp64")):
+        for _ in range(2):
+            T.tgrad_calibration_mfma(kind, 4096, sink)
+        ce0.record()
+        fl = 0.0
+        for _ in range(5):
+            fl += T.tgrad_calibration_mfma(kind, 4096, sink)
+        ce1.record()
+        torch.cuda.synchronize()
+        mfma_tf[key] = fl / (ce0.elapsed_time(ce1) * 1e-3) / 1e12
+
+
     # the library fuses the mode-(N-1) stages when the shape allows: then k_mid runs N - 2 times each way
     nstep = max(1, times.get("project_first", {}).get("launches", 1))
     # and the kernel around the core takes one leading mode, or two (four-way tensors, first extent 128):
@@ -327,10 +344,13 @@ def main():
                 ent["frac_hbm_achievable"] = round(gbs / copy_gbs, 4)
             elif mm["bound"] == "mfma64":
                 ent["frac_mfma_fp64_peak"] = round(tfl / MFMA_FP64_PEAK_TF, 4)
+                ent["frac_mfma_fp64_achievable"] = round(tfl / mfma_tf["fp64"], 4)
             else:
                 ent["frac_mfma_fp32_peak"] = round(tfl / MFMA_FP32_PEAK_TF, 4)
+                ent["frac_mfma_fp32_achievable"] = round(tfl / mfma_tf["fp32"], 4)
             if name == "project_first":          # straddles the ridge: both fractions
                 ent["frac_mfma_fp32_peak"] = round(tfl / MFMA_FP32_PEAK_TF, 4)
+                ent["frac_mfma_fp32_achievable"] = round(tfl / mfma_tf["fp32"], 4)
         kernels[name] = ent
     refresh_names = ("select", "gram", "eig", "mask", "factor", "hooi", "tile", "residual", "gather")
     step_kernels = [n for n in kernels if not n.startswith(refresh_names)]
@@ -389,6 +409,7 @@ def main():
         "ms_per_step_with_kernel_events": round(ms_per_step_profiled, 4),
         "refresh_ms": round(refresh_ms, 4),
         "copy_kernel_GBps": round(copy_gbs, 1),
+        "mfma_loop_TFLOPs": {k: round(v, 1) for k, v in mfma_tf.items()},
         "select": select_summary,
         "kernels": kernels,
     }

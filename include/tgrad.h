@@ -268,6 +268,21 @@ int tgrad_get_kernel_times(tgrad_ctx* ctx, const char** names, double* total_ms,
  */
 int tgrad_calibration_copy(void* dst_dev, const void* src_dev, size_t bytes, void* hip_stream);
 
+/*
+ * Register-resident matrix-core loop over the whole chip, for calibrating the matrix-core fractions that
+ * are reported for the projection and Gram kernels: what the hardware delivers with no memory traffic at all.
+ *  kind        0 = the float32 instruction of the projection kernels (32 x 32 x 2), 1 = the float64
+ *              instruction of the Gram kernels (16 x 16 x 4).
+ *  iterations  loop length per wavefront, >= 1 (each iteration issues four matrix instructions).
+ *  sink_dev    device pointer to at least 4 writable bytes, 4-byte aligned (never written in practice: it
+ *              keeps the loop from being optimised away).
+ *  hip_stream  stream to enqueue on (NULL = the default stream).  Does not wait.
+ *  flops       host pointer: receives the floating-point operations of the launch (2 per multiply-add);
+ *              divide by the launch's duration, measured by the caller on that stream.
+ * Errors: INVALID_ARG, HIP.
+ */
+int tgrad_calibration_mfma(int kind, int64_t iterations, void* sink_dev, void* hip_stream, double* flops);
+
 /* Release the context (host memory only; device buffers stay the caller's). */
 int tgrad_destroy(tgrad_ctx* ctx);
 

@@ -51,6 +51,53 @@ __device__ __forceinline__ uint32_t div_magic(uint32_t n, uint32_t magic) {
 }
 
 // -------------------------------------------------------------------------------------------
+// Register-resident matrix-core loops: what the matrix cores of this chip deliver when nothing else
+// is in the way (no memory, no LDS, operands constant).  The reference point for the matrix-core
+// fractions of the kernels below, next to the published peaks.  Four independent accumulators per
+// wavefront, two wavefronts per SIMD.
+typedef double v4d __attribute__((ext_vector_type(4)));
+constexpr int kProbeChains = 4;
+constexpr int kProbeUnroll = 64;             // rounds per trip of the loop (the loop's own bookkeeping is then negligible)
+__global__ __launch_bounds__(256) void k_mfma_probe_f32(float* sink, int64_t iters, float a, float b) {
+  v16f acc[kProbeChains];
+#pragma unroll
+  for (int c = 0; c < kProbeChains; ++c)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[c][r] = 0.f;
+  for (int64_t i = 0; i < iters; i += kProbeUnroll) {          // (iters is a multiple of kProbeUnroll: host)
+#pragma unroll
+    for (int u = 0; u < kProbeUnroll; ++u)
+#pragma unroll
+      for (int c = 0; c < kProbeChains; ++c) acc[c] = mfma32(a, b, acc[c]);
+  }
+  float t = 0.f;
+#pragma unroll
+  for (int c = 0; c < kProbeChains; ++c)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) t += acc[c][r];
+  if (t == 12345.678f) sink[0] = t;                            // (never: a b iters is not that number; keeps the loop alive)
+}
+__global__ __launch_bounds__(256) void k_mfma_probe_f64(float* sink, int64_t iters, double a, double b) {
+  v4d acc[kProbeChains];
+#pragma unroll
+  for (int c = 0; c < kProbeChains; ++c)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) acc[c][r] = 0.;
+  for (int64_t i = 0; i < iters; i += kProbeUnroll) {
+#pragma unroll
+    for (int u = 0; u < kProbeUnroll; ++u)
+#pragma unroll
+      for (int c = 0; c < kProbeChains; ++c) acc[c] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, acc[c], 0, 0, 0);
+  }
+  double t = 0.;
+#pragma unroll
+  for (int c = 0; c < kProbeChains; ++c)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) t += acc[c][r];
+  if (t == 12345.678) sink[0] = (float)t;
+}
+
+// -------------------------------------------------------------------------------------------
 // k_mid: out[a, m, b] = sum_k F[m, k] x[a, k, b],  F = U^H (PROJECT) or U.
 // Workgroup = 4 wavefronts; a wavefront owns 32 column vectors (VEC complex each) and MT row
 // tiles of 32 output rows; blockIdx.y selects the group of MT row tiles.
@@ -2191,6 +2238,20 @@ int choose_tile_waves(int Klast, int rlast, int prefer) {
     }
   }
   return 0;
+}
+
+// Launches one of the matrix-core loops over the whole chip (two workgroups of four wavefronts per compute
+// unit); returns the real floating-point operations of the launch.
+double launch_mfma_probe(hipStream_t s, int kind, int64_t iters, float* sink) {
+  const int grid = compute_units() * 2;
+  iters = (iters + kProbeUnroll - 1) / kProbeUnroll * kProbeUnroll;
+  const double instr = (double)grid * 4.0 * (double)iters * kProbeChains;
+  if (kind == 0) {
+    k_mfma_probe_f32<<<dim3((unsigned)grid), dim3(256), 0, s>>>(sink, iters, 1.f, 0.5f);
+    return instr * 4096.0;                                     // 32 x 32 x 2 multiply-adds
+  }
+  k_mfma_probe_f64<<<dim3((unsigned)grid), dim3(256), 0, s>>>(sink, iters, 1., 0.5);
+  return instr * 2048.0;                                       // 16 x 16 x 4 multiply-adds
 }
 
 void launch_tile_offsets(hipStream_t s, const int32_t* omega, int64_t k, int64_t tile_elems,

@@ -1052,6 +1052,14 @@ int tgrad_calibration_copy(void* dst_dev, const void* src_dev, size_t bytes, voi
   return check_launch();
 }
 
+int tgrad_calibration_mfma(int kind, int64_t iterations, void* sink_dev, void* hip_stream, double* flops) {
+  if ((kind != 0 && kind != 1) || iterations < 1 || iterations > ((int64_t)1 << 32) || !sink_dev || !flops ||
+      ((uintptr_t)sink_dev % 4))
+    return TGRAD_ERR_INVALID_ARG;
+  *flops = launch_mfma_probe(static_cast<hipStream_t>(hip_stream), kind, iterations, static_cast<float*>(sink_dev));
+  return check_launch();
+}
+
 int tgrad_destroy(tgrad_ctx* ctx) {
   if (!ctx) return TGRAD_ERR_INVALID_ARG;
   (void)drain_events(ctx);

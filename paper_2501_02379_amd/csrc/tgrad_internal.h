@@ -99,6 +99,7 @@ void launch_residual_gather(hipStream_t s, float2* gs, const int32_t* omega, int
 
 // matrix-core kernels of the step (contract_mfma.hip)
 int choose_tile_waves(int Klast, int rlast, int prefer);
+double launch_mfma_probe(hipStream_t s, int kind, int64_t iters, float* sink);   // returns the launch's flops
 int fused_max_last_extent();                       // largest I_N the fused first-stage kernel takes
 void launch_tile_offsets(hipStream_t s, const int32_t* omega, int64_t k, int64_t tile_elems,
                          int64_t ntiles, uint32_t* tile_start);

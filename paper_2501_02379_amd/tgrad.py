@@ -36,6 +36,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libtgrad.so
 EXPORTS = (
     "tgrad_query_sizes", "tgrad_init", "tgrad_refresh_factors", "tgrad_step", "tgrad_step_static", "tgrad_get_state", "tgrad_check",
     "tgrad_set_state", "tgrad_set_profiling", "tgrad_get_kernel_times", "tgrad_calibration_copy",
+    "tgrad_calibration_mfma",
     "tgrad_destroy", "tgrad_strerror",
 )
 
@@ -97,6 +98,7 @@ def load():
     lib.tgrad_get_kernel_times.argtypes = [vp, C.POINTER(C.c_char_p), C.POINTER(C.c_double),
                                            C.POINTER(C.c_int64), i32]
     lib.tgrad_calibration_copy.argtypes = [vp, vp, sz, vp]
+    lib.tgrad_calibration_mfma.argtypes = [C.c_int, C.c_int64, vp, vp, C.POINTER(C.c_double)]
     lib.tgrad_destroy.argtypes = [vp]
     lib.tgrad_strerror.argtypes = [i32]
     lib.tgrad_strerror.restype = C.c_char_p
@@ -286,6 +288,18 @@ def tgrad_calibration_copy(dst, src, stream=None) -> None:
     rc = load().tgrad_calibration_copy(_ptr(dst), _ptr(src), nbytes, C.c_void_p(st.cuda_stream))
     if rc != TGRAD_OK:
         raise TgradError(rc, "tgrad_calibration_copy")
+
+
+def tgrad_calibration_mfma(kind: int, iterations: int, sink, stream=None) -> float:
+    """Register-resident matrix-core loop (kind 0: float32, 1: float64); returns the launch's flops."""
+    import torch
+    st = stream if stream is not None else torch.cuda.current_stream(sink.device)
+    flops = C.c_double(0.0)
+    rc = load().tgrad_calibration_mfma(int(kind), int(iterations), _ptr(sink), C.c_void_p(st.cuda_stream),
+                                       C.byref(flops))
+    if rc != TGRAD_OK:
+        raise TgradError(rc, "tgrad_calibration_mfma")
+    return float(flops.value)
 
 
 def to_device_grad(g: np.ndarray, device="cuda:0"):

@@ -98,6 +98,19 @@ def test_null_and_misaligned_pointers():
     assert lib.tgrad_query_sizes(C.byref(cfg), None, None) == T.TGRAD_ERR_INVALID_ARG
 
 
+def test_calibration_probes_check_their_arguments_before_the_device():
+    lib = T.load()
+    fl = C.c_double(0.0)
+    assert lib.tgrad_calibration_mfma(2, 16, 256, None, C.byref(fl)) == T.TGRAD_ERR_INVALID_ARG     # no such instruction
+    assert lib.tgrad_calibration_mfma(0, 0, 256, None, C.byref(fl)) == T.TGRAD_ERR_INVALID_ARG      # no iterations
+    assert lib.tgrad_calibration_mfma(0, 16, None, None, C.byref(fl)) == T.TGRAD_ERR_INVALID_ARG
+    assert lib.tgrad_calibration_mfma(0, 16, 258, None, C.byref(fl)) == T.TGRAD_ERR_INVALID_ARG     # sink alignment
+    assert lib.tgrad_calibration_mfma(1, 16, 256, None, None) == T.TGRAD_ERR_INVALID_ARG
+    assert lib.tgrad_calibration_copy(256, 512, 24, None) == T.TGRAD_ERR_INVALID_ARG                # not a multiple of 16
+    assert lib.tgrad_calibration_copy(256, 264, 16, None) == T.TGRAD_ERR_INVALID_ARG                # alignment
+    assert lib.tgrad_calibration_copy(256, 512, 512, None) == T.TGRAD_ERR_INVALID_ARG               # overlap
+
+
 def test_caller_side_sizes():
     for w in synth.WORKLOADS.values():
         assert sizing.sparse_count(Fraction(*w.density), w.numel) == w.k

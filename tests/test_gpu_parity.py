@@ -704,6 +704,23 @@ def test_exactly_repeated_eigenvalues_go_to_the_jacobi_solver():
     ctx.tgrad_destroy()
 
 
+def test_calibration_probes_run_and_report_their_work():
+    import torch
+    sink = torch.zeros(4, dtype=torch.float32, device="cuda:0")
+    for kind, per_instr in ((0, 4096.0), (1, 2048.0)):
+        fl = T.tgrad_calibration_mfma(kind, 100, sink)
+        torch.cuda.synchronize()
+        # 100 iterations round up to 128 (whole unrolled trips); 4 instructions each, 8 wavefronts per compute unit
+        cus = torch.cuda.get_device_properties(0).multi_processor_count
+        assert fl == cus * 8 * 128 * 4 * per_instr
+    assert float(sink.abs().sum()) == 0.0
+    src = torch.arange(1 << 16, dtype=torch.int32, device="cuda:0")
+    dst = torch.zeros_like(src)
+    T.tgrad_calibration_copy(dst, src)
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src)
+
+
 def test_check_counts_non_finite_gradient_entries():
     shape, ranks, k = (16, 16, 8, 5), (8, 8, 4, 3), 103
     g = synth.small_case(shape, 31).copy()
