@@ -2339,18 +2339,19 @@ void launch_core(hipStream_t s, const float2* x, const float2* U, int rn, int K,
 
 // Limits of k_core2: first extent 128 (one 32-row tile per wavefront), ranks within one tile, the second
 // extent within four tiles, and enough column groups (one workgroup each) to occupy the chip: pairs of
-// columns if there are at least 3/4 as many pairs as compute units (the rank of the last mode must then
-// be even: a pair lies inside one row of the mode before it), else single columns if there are at least
-// 3/8 as many columns as compute units.  Below that the three separate kernels, which spread over the
-// chip, are faster.  Returns the columns per workgroup (2 or 1), or 0.
+// columns if there are at least 192 pairs (3/4 of the 256 compute units of the MI355X; the rank of the
+// last mode must then be even: a pair lies inside one row of the mode before it), else single columns if
+// there are at least 96.  Below that the three separate kernels, which spread over the chip, are
+// faster.  Returns the columns per workgroup (2 or 1), or 0.  A function of the shape alone: the
+// workspace layout follows from it, and the size query must not depend on the device that is current.
+constexpr int64_t kCore2MinPairs = 192, kCore2MinColumns = 96;
 int core2_kernel_vec(int I0, int I1, int M0, int M1, int K2, int K) {
   const int64_t Cc = (int64_t)K2 * K;
   if (!(I0 == kCore2Rows && I1 >= 1 && I1 <= 128 && M0 >= 1 && M0 <= 32 && M1 >= 1 && M1 <= 32 &&
         (int64_t)I0 * I1 * Cc < ((int64_t)1 << 28)))
     return 0;
-  const int64_t cus = compute_units();
-  if (K % 2 == 0 && Cc / 2 >= cus * 3 / 4) return 2;
-  if (Cc >= cus * 3 / 8) return 1;
+  if (K % 2 == 0 && Cc / 2 >= kCore2MinPairs) return 2;
+  if (Cc >= kCore2MinColumns) return 1;
   return 0;
 }
 
