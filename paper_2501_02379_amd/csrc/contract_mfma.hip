@@ -9,18 +9,24 @@
 //   re(F X) = Fr Xr - Fi Xi,   im(F X) = Fr Xi + Fi Xr,
 // i.e. 4 real multiply-adds per complex multiply-add on either layout below.
 //
-// Three kernels:
+// The kernels:
 //  k_mid      contracts a mode that is NOT the last one: the tensor is (A, K, B) with B >= 1
 //             contiguous; every lane owns VEC complex columns (a, b) and walks the K rows.
+//  k_core     mode 1 both ways around AdamUpdate on the Tucker core, in one launch.
+//  k_core2    modes 1 and 2 both ways around AdamUpdate on the core, one workgroup per column group:
+//             everything between the two fused end kernels of a four-way tensor, in one launch.
 //  k_lproj    contracts the LAST mode of the gradient itself (first compression stage): a
 //             flat tile of rows is staged in LDS, the entries of the support Omega that fall
 //             in the tile are handed to the sparse branch (gather) and zeroed (this is
 //             G - Sparse(G, Omega) without a second pass over G), then 32 rows per wavefront
-//             go through the matrix cores.  k_lproj_flat is its fused form for odd last extents.
+//             go through the matrix cores.  With FUSE it also contracts mode N-1 (the tile's mode-N
+//             result, still in the accumulators, is the operand of the next contraction);
+//             k_lproj_flat is that fused form for odd last extents.
 //  k_lupdate  the last reconstruction stage fused with everything that touches W: expands the
 //             last mode into an LDS tile, runs AdamUpdate on the sparse values of the tile
 //             and adds lambda N_S into it, then streams W <- W (1 - lr wd) - lr tile with
-//             16-byte accesses.
+//             16-byte accesses.  k_lupdate_fused also expands mode N-1 in front of it.
+//  k_mfma_probe_*  register-resident matrix-core loops (calibration of the reported fractions).
 //
 // Operand layout of v_mfma_f32_32x32x2f32 (D = A B + C, A 32 x 2, B 2 x 32, 64 lanes):
 //   lane l supplies A[l % 32][l / 32] and B[l / 32][l % 32];

@@ -4,9 +4,10 @@
 // mode-n Gram matrix A_n = R_L(n) R_L(n)^H, so the refresh is
 //   (1) A_n for every compressed mode, accumulated in float64 on the f64 matrix cores, with
 //       R_L = G - Sparse(G, Omega) formed on load from the support bitmask, and
-//   (2) a cyclic Jacobi eigen-solve of each A_n in float64 (one workgroup per mode), the
-//       r_n leading eigenvectors written eigenvalue-descending with the phase of every column
-//       fixed (largest-modulus entry real and positive).
+//   (2) an eigen-solve of each A_n in float64 (one workgroup per mode) for its r_n leading
+//       eigenvectors, written eigenvalue-descending with the phase of every column fixed
+//       (largest-modulus entry real and positive): tridiagonalisation + bisection + inverse
+//       iteration for extents up to 128, cyclic Jacobi for clustered spectra and larger extents.
 // float64 is used because Adam in core space is not invariant to the basis inside the subspace:
 // noise-like gradients have relative eigenvalue gaps near 1e-4, and float32 accumulation error
 // divided by such a gap would move the individual eigenvectors far more than the update tolerates.
