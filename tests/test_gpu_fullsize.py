@@ -150,6 +150,32 @@ def test_cfg4_headline_full_tensor_refresh_and_three_steps():
     ctx.tgrad_destroy()
 
 
+def test_cfg4_two_runs_are_bit_identical():
+    """No atomics decide a value or a slot anywhere on the path (ordered compaction, fixed-order
+    reductions of the Gram partials and of the core tiles): two runs of a refresh + 3 steps at the
+    headline size end in the same bits, weights and state."""
+    import torch
+    w = synth.WORKLOADS["cfg4"]
+    grads = [T.to_device_grad(synth.gradient(w, t)) for t in range(2)]
+    W0 = synth.initial_weight(w)
+    results = []
+    for run in range(2):
+        _progress("cfg4 determinism: run %d" % run)
+        ctx = T.Context(T.make_config(w.shape, w.ranks, w.k, **_kw(w)))
+        Wd = T.to_device_weight(W0)
+        for t in range(4):
+            ctx.tgrad_step(Wd, grads[t & 1])
+        torch.cuda.synchronize()
+        items = [T.STATE_INDICES, T.STATE_CORE_M, T.STATE_CORE_V, T.STATE_SPARSE_M, T.STATE_SPARSE_V] + \
+                [T.STATE_FACTOR0 + n for n in range(4)]
+        results.append((T.weight_to_host(Wd), [ctx.tgrad_get_state(it) for it in items]))
+        ctx.tgrad_destroy()
+        del Wd
+    assert np.array_equal(results[0][0], results[1][0])
+    for a, b in zip(results[0][1], results[1][1]):
+        assert np.array_equal(a, b)
+
+
 def test_cfg4_random_support_bit_exact():
     """rand-k at the bench workload's size: 136 M keys, k = 681575, against the oracle's full sort."""
     w = synth.WORKLOADS["cfg4"]
