@@ -136,3 +136,37 @@ def test_static_step_argument_checks_need_no_gpu():
     assert lib.tgrad_step_static(C.byref(small), 256, -1, 512, 1024, None) == T.TGRAD_ERR_INVALID_ARG
     small.refresh_every = 0
     assert lib.tgrad_step_static(C.byref(small), 256, 0, 512, 1024, None) == T.TGRAD_ERR_INVALID_ARG
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build runs on one GPU: the benchmark says so and exits instead of pretending to scale."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode == 2
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_bench_byte_model_of_the_headline_workload():
+    """The algorithmic bytes per launch that the roofline fractions rest on, written out by hand for the
+    128 x 128 x 128 x 65 workload (I elements of 8 bytes, k sparse entries, ranks 32, 32, 32, 16)."""
+    import os
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    sys.path.insert(0, root)
+    import bench
+    w = synth.WORKLOADS["cfg4"]
+    I, k = 128 * 128 * 128 * 65, w.k
+    mid = 128 * 128 * 32 * 16 * 8                      # the tensor between the fused end kernels and the core kernel
+    m = bench.kernel_model(w, True, 8, 2)
+    assert m["project_first"]["bytes"] == 8 * I + mid + 12 * k          # G in, result out, index + value per sparse entry
+    assert m["update"]["bytes"] == 16 * I + mid + 36 * k                # W in and out, operand tensor in, sparse state
+    assert m["core"]["bytes"] == 2 * mid + 32 * (32 * 32 * 32 * 16)     # in, out, moments in and out + core gradient out
+    assert "project" not in m and "backproject" not in m
+    # three separate middle kernels instead: one mode each way, the core kernel one mode
+    m1 = bench.kernel_model(w, True, 8, 1)
+    assert m1["project"]["launches_per_step"] == 1 and m1["backproject"]["launches_per_step"] == 1
+    assert m1["update"]["bytes"] == m["update"]["bytes"]
