@@ -249,6 +249,20 @@ def main():
     ce1.record()
     torch.cuda.synchronize()
     copy_gbs = 2.0 * nb * ncopy / (ce0.elapsed_time(ce1) * 1e-3) / 1e9
+    # ... and what the memory system gives the weight-update kernel's own access pattern (one tile of 32 rows
+    # of the last mode per wavefront, loaded whole and stored back in place; slabs of I_(N-1) / 32 tiles)
+    tile_bytes = 32 * w.shape[-1] * 8
+    tile_gbs = None
+    if len(w.shape) >= 2 and tile_bytes <= 17 * 1024 and w.shape[-2] % 32 == 0:
+        for _ in range(2):
+            T.tgrad_calibration_tile_stream(cdst, tile_bytes, w.shape[-2] // 32)
+        ce0.record()
+        moved = 0
+        for _ in range(10):
+            moved += T.tgrad_calibration_tile_stream(cdst, tile_bytes, w.shape[-2] // 32)
+        ce1.record()
+        torch.cuda.synchronize()
+        tile_gbs = 2.0 * moved / (ce0.elapsed_time(ce1) * 1e-3) / 1e9
     del csrc, cdst
 
     # ---- region A: the timed K steps (no per-kernel events) ----
@@ -376,6 +390,10 @@ def main():
             # what a plain copy kernel reaches on this machine in this run (read + write bytes per second)
             roofline["achievable_peak"] = round(copy_gbs, 1)
             roofline["frac_vs_achievable"] = round(ach / copy_gbs, 4)
+            if dom == "update" and tile_gbs is not None and args.weights == "c64":
+                # the same bytes moved with the update kernel's access pattern and no arithmetic
+                roofline["pattern_ceiling"] = round(tile_gbs, 1)
+                roofline["frac_vs_pattern_ceiling"] = round(ach / tile_gbs, 4)
     # selection as a whole: one read of G is what the method needs (8 or 4 bytes per element)
     sel_ms = sum(v["total_ms"] for n, v in rtimes.items() if n.startswith("select")) / max(1, w.layers)
     gbytes = w.numel * (8 if w.grad_dtype == "c64" else 4)
@@ -409,6 +427,7 @@ def main():
         "ms_per_step_with_kernel_events": round(ms_per_step_profiled, 4),
         "refresh_ms": round(refresh_ms, 4),
         "copy_kernel_GBps": round(copy_gbs, 1),
+        "tile_stream_GBps": round(tile_gbs, 1) if tile_gbs is not None else None,
         "mfma_loop_TFLOPs": {k: round(v, 1) for k, v in mfma_tf.items()},
         "select": select_summary,
         "kernels": kernels,

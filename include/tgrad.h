@@ -269,6 +269,23 @@ int tgrad_get_kernel_times(tgrad_ctx* ctx, const char** names, double* total_ms,
 int tgrad_calibration_copy(void* dst_dev, const void* src_dev, size_t bytes, void* hip_stream);
 
 /*
+ * The memory access pattern of the weight-update kernel without its arithmetic, for calibrating that kernel's
+ * bandwidth fraction: every wavefront owns a tile of `tile_bytes`, loads all of it and then stores it back in
+ * place unchanged; wavefronts take slabs of `tiles_per_slab` consecutive tiles.  (The plain copy above moves
+ * the same bytes with fewer concurrent streams and reaches a higher rate; this is the ceiling of the pattern
+ * that a kernel with one tile per wavefront has.)
+ *  buf_dev         device pointer, 16-byte aligned, `bytes` long; its contents are rewritten with themselves.
+ *  bytes           at least tile_bytes * tiles_per_slab; whole slabs are moved, a remainder is left alone.
+ *  tile_bytes      a multiple of 16, at most 17408 (the update kernel's tile: 32 rows of the last mode).
+ *  tiles_per_slab  >= 1 (the update kernel: extent of mode N-1 / 32).
+ *  hip_stream      stream to enqueue on (NULL = the default stream).  Does not wait.
+ *  bytes_read      host pointer: receives the bytes the launch reads (it writes as many).
+ * Errors: INVALID_ARG, HIP.
+ */
+int tgrad_calibration_tile_stream(void* buf_dev, size_t bytes, int tile_bytes, int tiles_per_slab, void* hip_stream,
+                                  int64_t* bytes_read);
+
+/*
  * Register-resident matrix-core loop over the whole chip, for calibrating the matrix-core fractions that
  * are reported for the projection and Gram kernels: what the hardware delivers with no memory traffic at all.
  *  kind        0 = the float32 instruction of the projection kernels (32 x 32 x 2), 1 = the float64

@@ -411,6 +411,35 @@ __global__ __launch_bounds__(256) void k_copy16(f32x4c* __restrict__ dst, const 
     __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
 
+// The access pattern of the weight-update kernel without its arithmetic: a wavefront owns a tile of
+// `tile_pieces` 16-byte pieces (at most kTilePieces x 64), loads all of it, then stores all of it back in
+// place; wavefronts take slabs of `S` consecutive tiles, slabs dealt round-robin.  What this reaches is
+// what the memory system gives that pattern (fewer, longer requests per wavefront and more concurrent
+// streams than the plain copy above).
+constexpr int kTilePieces = 17;
+__global__ __launch_bounds__(256, 2) void k_tile_stream(f32x4c* __restrict__ w, int64_t ntiles, int tile_pieces, int S) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t nslabs = ntiles / S;
+  const int64_t nw = (int64_t)gridDim.x * 4;
+  for (int64_t slab = (int64_t)blockIdx.x * 4 + wave; slab < nslabs; slab += nw)
+    for (int ts = 0; ts < S; ++ts) {
+      f32x4c* t = w + (slab * S + ts) * tile_pieces;
+      f32x4c v[kTilePieces];
+#pragma unroll
+      for (int i = 0; i < kTilePieces; ++i) {
+        const int q = lane + i * 64;
+        v[i] = __builtin_nontemporal_load(t + (q < tile_pieces ? q : tile_pieces - 1));
+      }
+#pragma unroll
+      for (int i = 0; i < kTilePieces; ++i) asm volatile("" : "+v"(v[i]));   // every load before the first store
+#pragma unroll
+      for (int i = 0; i < kTilePieces; ++i) {
+        const int q = lane + i * 64;
+        if (q < tile_pieces) __builtin_nontemporal_store(v[i], t + q);
+      }
+    }
+}
+
 __global__ void k_zero_u32(uint32_t* p, int64_t n) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = 0u;
@@ -423,6 +452,17 @@ void launch_copy16(hipStream_t s, void* dst, const void* src, int64_t n16) {
   const int64_t want = (n16 + 255) / 256;
   const unsigned grid = (unsigned)(want < 256 * 8 ? want : 256 * 8);
   k_copy16<<<dim3(grid), dim3(256), 0, s>>>(reinterpret_cast<f32x4c*>(dst), reinterpret_cast<const f32x4c*>(src), n16);
+}
+
+// `bytes` of `buf` as tiles of `tile_bytes` (a multiple of 16, at most 17 KB), slabs of `tiles_per_slab`;
+// returns the bytes one launch reads (it writes as many): whole slabs only.
+int64_t launch_tile_stream(hipStream_t s, void* buf, int64_t bytes, int tile_bytes, int tiles_per_slab, int cus) {
+  const int tile_pieces = tile_bytes / 16;
+  const int64_t ntiles = bytes / tile_bytes / tiles_per_slab * tiles_per_slab;
+  if (ntiles <= 0) return 0;
+  k_tile_stream<<<dim3((unsigned)(2 * cus)), dim3(256), 0, s>>>(reinterpret_cast<f32x4c*>(buf), ntiles, tile_pieces,
+                                                            tiles_per_slab);
+  return ntiles * (int64_t)tile_bytes;
 }
 
 void zero_u32(hipStream_t s, uint32_t* p, int64_t n) {

@@ -12,6 +12,7 @@
 namespace tgrad {
 void zero_u32(hipStream_t s, uint32_t* p, int64_t n);
 void launch_copy16(hipStream_t s, void* dst, const void* src, int64_t n16);
+int64_t launch_tile_stream(hipStream_t s, void* buf, int64_t bytes, int tile_bytes, int tiles_per_slab, int cus);
 void launch_eig_batch(hipStream_t s, int njobs, const double* const* gram, double* const* work_a,
                       double* const* work_v, const int* In, const int* r, float* const* U, int* const* status,
                       int max_sweeps);
@@ -1049,6 +1050,20 @@ int tgrad_calibration_copy(void* dst_dev, const void* src_dev, size_t bytes, voi
   const char* b = static_cast<const char*>(src_dev);
   if (a < b + bytes && b < a + bytes) return TGRAD_ERR_INVALID_ARG;
   launch_copy16(static_cast<hipStream_t>(hip_stream), dst_dev, src_dev, (int64_t)(bytes / 16));
+  return check_launch();
+}
+
+int tgrad_calibration_tile_stream(void* buf_dev, size_t bytes, int tile_bytes, int tiles_per_slab, void* hip_stream,
+                                  int64_t* bytes_read) {
+  if (!buf_dev || !bytes_read || ((uintptr_t)buf_dev % 16) || tile_bytes < 16 || (tile_bytes % 16) ||
+      tile_bytes > 17 * 1024 || tiles_per_slab < 1 || bytes < (size_t)tile_bytes * (size_t)tiles_per_slab)
+    return TGRAD_ERR_INVALID_ARG;
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+    return TGRAD_ERR_HIP;
+  *bytes_read = launch_tile_stream(static_cast<hipStream_t>(hip_stream), buf_dev, (int64_t)bytes, tile_bytes,
+                                   tiles_per_slab, cus);
   return check_launch();
 }
 

@@ -36,7 +36,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libtgrad.so
 EXPORTS = (
     "tgrad_query_sizes", "tgrad_init", "tgrad_refresh_factors", "tgrad_step", "tgrad_step_static", "tgrad_get_state", "tgrad_check",
     "tgrad_set_state", "tgrad_set_profiling", "tgrad_get_kernel_times", "tgrad_calibration_copy",
-    "tgrad_calibration_mfma",
+    "tgrad_calibration_mfma", "tgrad_calibration_tile_stream",
     "tgrad_destroy", "tgrad_strerror",
 )
 
@@ -99,6 +99,7 @@ def load():
                                            C.POINTER(C.c_int64), i32]
     lib.tgrad_calibration_copy.argtypes = [vp, vp, sz, vp]
     lib.tgrad_calibration_mfma.argtypes = [C.c_int, C.c_int64, vp, vp, C.POINTER(C.c_double)]
+    lib.tgrad_calibration_tile_stream.argtypes = [vp, sz, C.c_int, C.c_int, vp, C.POINTER(C.c_int64)]
     lib.tgrad_destroy.argtypes = [vp]
     lib.tgrad_strerror.argtypes = [i32]
     lib.tgrad_strerror.restype = C.c_char_p
@@ -288,6 +289,19 @@ def tgrad_calibration_copy(dst, src, stream=None) -> None:
     rc = load().tgrad_calibration_copy(_ptr(dst), _ptr(src), nbytes, C.c_void_p(st.cuda_stream))
     if rc != TGRAD_OK:
         raise TgradError(rc, "tgrad_calibration_copy")
+
+
+def tgrad_calibration_tile_stream(buf, tile_bytes: int, tiles_per_slab: int, stream=None) -> int:
+    """The update kernel's access pattern without arithmetic on `buf` (a torch tensor, rewritten with
+    itself); returns the bytes one launch reads (it writes as many)."""
+    import torch
+    st = stream if stream is not None else torch.cuda.current_stream(buf.device)
+    n = C.c_int64(0)
+    rc = load().tgrad_calibration_tile_stream(_ptr(buf), buf.numel() * buf.element_size(), int(tile_bytes),
+                                              int(tiles_per_slab), C.c_void_p(st.cuda_stream), C.byref(n))
+    if rc != TGRAD_OK:
+        raise TgradError(rc, "tgrad_calibration_tile_stream")
+    return int(n.value)
 
 
 def tgrad_calibration_mfma(kind: int, iterations: int, sink, stream=None) -> float:

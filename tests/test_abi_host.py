@@ -106,6 +106,13 @@ def test_calibration_probes_check_their_arguments_before_the_device():
     assert lib.tgrad_calibration_mfma(0, 16, None, None, C.byref(fl)) == T.TGRAD_ERR_INVALID_ARG
     assert lib.tgrad_calibration_mfma(0, 16, 258, None, C.byref(fl)) == T.TGRAD_ERR_INVALID_ARG     # sink alignment
     assert lib.tgrad_calibration_mfma(1, 16, 256, None, None) == T.TGRAD_ERR_INVALID_ARG
+    n = C.c_int64(0)
+    assert lib.tgrad_calibration_tile_stream(None, 1 << 20, 1024, 4, None, C.byref(n)) == T.TGRAD_ERR_INVALID_ARG
+    assert lib.tgrad_calibration_tile_stream(256, 1 << 20, 1000, 4, None, C.byref(n)) == T.TGRAD_ERR_INVALID_ARG   # not whole pieces
+    assert lib.tgrad_calibration_tile_stream(256, 1 << 20, 18 * 1024, 4, None, C.byref(n)) == T.TGRAD_ERR_INVALID_ARG
+    assert lib.tgrad_calibration_tile_stream(256, 1 << 20, 1024, 0, None, C.byref(n)) == T.TGRAD_ERR_INVALID_ARG
+    assert lib.tgrad_calibration_tile_stream(256, 2048, 1024, 4, None, C.byref(n)) == T.TGRAD_ERR_INVALID_ARG      # less than a slab
+    assert lib.tgrad_calibration_tile_stream(256, 1 << 20, 1024, 4, None, None) == T.TGRAD_ERR_INVALID_ARG
     assert lib.tgrad_calibration_copy(256, 512, 24, None) == T.TGRAD_ERR_INVALID_ARG                # not a multiple of 16
     assert lib.tgrad_calibration_copy(256, 264, 16, None) == T.TGRAD_ERR_INVALID_ARG                # alignment
     assert lib.tgrad_calibration_copy(256, 512, 512, None) == T.TGRAD_ERR_INVALID_ARG               # overlap

@@ -719,6 +719,12 @@ def test_calibration_probes_run_and_report_their_work():
     T.tgrad_calibration_copy(dst, src)
     torch.cuda.synchronize()
     assert torch.equal(dst, src)
+    # the tile stream rewrites its buffer with itself: 17 tiles of 1040 pieces in slabs of 4 -> 16 tiles move
+    buf = torch.arange(17 * 1040 * 4 + 5, dtype=torch.int32, device="cuda:0")
+    keep = buf.clone()
+    assert T.tgrad_calibration_tile_stream(buf, 1040 * 16, 4) == 16 * 1040 * 16
+    torch.cuda.synchronize()
+    assert torch.equal(buf, keep)
 
 
 def test_check_counts_non_finite_gradient_entries():
